@@ -1,0 +1,387 @@
+/*
+ * AutoByte meta-network: plain fp64 CPU oracle.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct statement of what the
+ * meta-network pass computes.  It is used by the test-suite, by the smoke check and by the
+ * benchmark's CPU-baseline leg; the GPU product never calls it and shares no code with it.
+ *
+ * What it follows (arXiv 2112.13509):
+ *   - Table 1 / Section 3.1 "Input runtime metrics": the input record (layer-wise computation
+ *     time and other per-layer statistics, bandwidth, worker count, model / architecture type,
+ *     and the candidate pair <S_p, S_c>).
+ *   - Section 3.1 "Meta network architecture": the four feature groups are concatenated and
+ *     dense layers map the concatenation to the predicted training speed V (Eq. 1).
+ *   - Section 3 (intro) and Eq. 1: the pair with the maximum predicted V is chosen.
+ *   - Eq. 2: L2 loss between predicted and observed speed, used for (online) training.
+ *
+ * Every function takes the steps in that order with no factorisation, blocking or fusion:
+ * for each scenario and each candidate the full input vector is materialised and pushed
+ * through every layer.  Floating point is fp64 throughout.  OpenMP, where present, only
+ * distributes independent scenarios (rows) over threads.
+ *
+ * Pins: see tests/test_oracle_*.py (brute force on tiny grids, library matmul chain,
+ * one-layer closed form, permutation invariance, finite differences, autograd, reference Adam).
+ * Nothing here is pinned against numbers printed in the paper, because the paper prints no
+ * numeric example of the meta-network.
+ */
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#include <stdint.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORC_OK 0
+#define ORC_ERR_ARG (-1)
+#define ORC_ERR_MEM (-2)
+
+/* ---- feature transform: phi(x) = (g(x) - shift) * scale, g = identity (kind 0) or ln (kind 1).
+ * The paper only says the metrics are turned into vector inputs (Section 3.3, "Meta network
+ * optimizer"); the per-feature affine / log-affine normalisation is this build's reading. */
+static double orc_phi(double x, int kind, double shift, double scale)
+{
+    double g = (kind == 1) ? log(x) : x;
+    return (g - shift) * scale;
+}
+
+double orc_encode_value(double x, int kind, double shift, double scale)
+{
+    return orc_phi(x, kind, shift, scale);
+}
+
+int orc_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* y = W x + b, W is [n_out, n_in] row-major; optional ReLU. */
+static void orc_dense(const double *W, const double *b, int n_out, int n_in,
+                      const double *x, double *y, int relu)
+{
+    for (int o = 0; o < n_out; ++o) {
+        double acc = b ? b[o] : 0.0;
+        const double *w = W + (size_t)o * (size_t)n_in;
+        for (int i = 0; i < n_in; ++i)
+            acc += w[i] * x[i];
+        if (relu && !(acc > 0.0))
+            acc = (acc != acc) ? acc : 0.0; /* NaN stays NaN so bad inputs remain visible */
+        y[o] = acc;
+    }
+}
+
+/*
+ * Description of one model, flattened to plain arrays.
+ *
+ *  L, K, Ns          : layers (tensors) per scenario, statistics per layer, scalar features
+ *  stat_* [K]        : transform of each per-layer statistic
+ *  scal_* [Ns]       : transform of each scalar feature
+ *  cfg_*  [2]        : transform of partition size (0) and credit multiple (1)
+ *  tensor_encoder    : 0 -> the L*K statistics are laid side by side (layer-major, stat-minor);
+ *                      1 -> a shared two-layer MLP (K -> te_h0 -> te_h1, ReLU after both) is
+ *                           applied to each layer's K statistics and the results are averaged
+ *                           over the L layers ("embed layer-wise computation time into a fixed
+ *                           dimension feature space", Section 3.1 "Meta network architecture")
+ *  te_W[2], te_b[2]  : tensor-encoder weights ([te_h0,K], [te_h1,te_h0]) and biases
+ *  n_hidden, hidden[]: widths of the scorer's hidden layers (ReLU after each)
+ *  W[n_hidden+1], b[]: scorer weights, W[k] is [out,in] row-major; the last one has out = 1 and
+ *                      is linear (V is a regression target)
+ *
+ * Input vector order: [statistics block | scalars | phi(partition) | phi(credit)].
+ */
+typedef struct {
+    int L, K, Ns;
+    const int *stat_kind; const double *stat_shift; const double *stat_scale;
+    const int *scal_kind; const double *scal_shift; const double *scal_scale;
+    const int *cfg_kind;  const double *cfg_shift;  const double *cfg_scale;
+    int tensor_encoder, te_h0, te_h1;
+    const double *const *te_W; const double *const *te_b;
+    int n_hidden; const int *hidden;
+    const double *const *W; const double *const *b;
+} orc_model;
+
+static int orc_stats_width(const orc_model *m)
+{
+    return (m->tensor_encoder ? m->te_h1 : m->L * m->K) + m->Ns;
+}
+
+int orc_input_width(const orc_model *m) { return orc_stats_width(m) + 2; }
+
+/* Statistics block + scalars of one scenario -> xs[orc_stats_width]. tmp holds te_h0+te_h1+K doubles. */
+static void orc_scenario_features(const orc_model *m, const double *dyn_s, const double *scal_s,
+                                  double *xs, double *tmp)
+{
+    int off;
+    if (!m->tensor_encoder) {
+        for (int l = 0; l < m->L; ++l)
+            for (int k = 0; k < m->K; ++k)
+                xs[l * m->K + k] = orc_phi(dyn_s[l * m->K + k], m->stat_kind[k],
+                                           m->stat_shift[k], m->stat_scale[k]);
+        off = m->L * m->K;
+    } else {
+        double *in = tmp, *h0 = tmp + m->K, *h1 = h0 + m->te_h0;
+        for (int j = 0; j < m->te_h1; ++j) xs[j] = 0.0;
+        for (int l = 0; l < m->L; ++l) {
+            for (int k = 0; k < m->K; ++k)
+                in[k] = orc_phi(dyn_s[l * m->K + k], m->stat_kind[k],
+                                m->stat_shift[k], m->stat_scale[k]);
+            orc_dense(m->te_W[0], m->te_b[0], m->te_h0, m->K, in, h0, 1);
+            orc_dense(m->te_W[1], m->te_b[1], m->te_h1, m->te_h0, h0, h1, 1);
+            for (int j = 0; j < m->te_h1; ++j) xs[j] += h1[j];
+        }
+        for (int j = 0; j < m->te_h1; ++j) xs[j] /= (double)m->L;
+        off = m->te_h1;
+    }
+    for (int j = 0; j < m->Ns; ++j)
+        xs[off + j] = orc_phi(scal_s[j], m->scal_kind[j], m->scal_shift[j], m->scal_scale[j]);
+}
+
+/* Scorer MLP on one full input vector x[F]; buf holds 2*maxwidth doubles. */
+static double orc_mlp_forward(const orc_model *m, const double *x, int F, double *buf, int maxw)
+{
+    const double *cur = x;
+    int n_in = F;
+    double *a = buf, *bb = buf + maxw;
+    for (int k = 0; k < m->n_hidden; ++k) {
+        double *out = (k & 1) ? bb : a;
+        orc_dense(m->W[k], m->b[k], m->hidden[k], n_in, cur, out, 1);
+        cur = out;
+        n_in = m->hidden[k];
+    }
+    double score;
+    orc_dense(m->W[m->n_hidden], m->b[m->n_hidden], 1, n_in, cur, &score, 0);
+    return score;
+}
+
+/*
+ * Score every candidate of every scenario (Eq. 1 evaluated on the whole <S_p,S_c> grid).
+ *   dyn  [S, L, K]   raw per-layer statistics
+ *   scal [S, Ns]     raw scalar features
+ *   part [P], cred [Q]   raw partition sizes and credit multiples; candidate c = p*Q + q
+ *   scores [S, P*Q]  predicted V
+ */
+int orc_score(const orc_model *m, const double *dyn, const double *scal, int64_t S,
+              const double *part, int P, const double *cred, int Q, double *scores)
+{
+    if (!m || !scores || S < 0 || P <= 0 || Q <= 0) return ORC_ERR_ARG;
+    const int Fs = orc_stats_width(m), F = Fs + 2;
+    int maxw = 1;
+    for (int k = 0; k < m->n_hidden; ++k) if (m->hidden[k] > maxw) maxw = m->hidden[k];
+    const int tmpw = m->K + m->te_h0 + m->te_h1 + 1;
+    int err = 0;
+#pragma omp parallel
+    {
+        double *x = (double *)malloc(sizeof(double) * (size_t)(F + 2 * maxw + tmpw));
+        if (!x) {
+#pragma omp atomic write
+            err = 1;
+        } else {
+            double *buf = x + F, *tmp = buf + 2 * maxw;
+#pragma omp for schedule(dynamic, 1)
+            for (int64_t s = 0; s < S; ++s) {
+                orc_scenario_features(m, dyn + (size_t)s * m->L * m->K, scal + (size_t)s * m->Ns, x, tmp);
+                for (int p = 0; p < P; ++p)
+                    for (int q = 0; q < Q; ++q) {
+                        x[Fs]     = orc_phi(part[p], m->cfg_kind[0], m->cfg_shift[0], m->cfg_scale[0]);
+                        x[Fs + 1] = orc_phi(cred[q], m->cfg_kind[1], m->cfg_shift[1], m->cfg_scale[1]);
+                        scores[(size_t)s * P * Q + (size_t)p * Q + q] = orc_mlp_forward(m, x, F, buf, maxw);
+                    }
+            }
+            free(x);
+        }
+    }
+    return err ? ORC_ERR_MEM : ORC_OK;
+}
+
+/* The full input vectors themselves, [S, P*Q, F]: lets tests feed a library matmul chain. */
+int orc_materialise_inputs(const orc_model *m, const double *dyn, const double *scal, int64_t S,
+                           const double *part, int P, const double *cred, int Q, double *X)
+{
+    if (!m || !X || S < 0 || P <= 0 || Q <= 0) return ORC_ERR_ARG;
+    const int Fs = orc_stats_width(m), F = Fs + 2;
+    double *xs = (double *)malloc(sizeof(double) * (size_t)(Fs + m->K + m->te_h0 + m->te_h1 + 1));
+    if (!xs) return ORC_ERR_MEM;
+    for (int64_t s = 0; s < S; ++s) {
+        orc_scenario_features(m, dyn + (size_t)s * m->L * m->K, scal + (size_t)s * m->Ns, xs, xs + Fs);
+        for (int p = 0; p < P; ++p)
+            for (int q = 0; q < Q; ++q) {
+                double *x = X + ((size_t)s * P * Q + (size_t)p * Q + q) * (size_t)F;
+                memcpy(x, xs, sizeof(double) * (size_t)Fs);
+                x[Fs]     = orc_phi(part[p], m->cfg_kind[0], m->cfg_shift[0], m->cfg_scale[0]);
+                x[Fs + 1] = orc_phi(cred[q], m->cfg_kind[1], m->cfg_shift[1], m->cfg_scale[1]);
+            }
+    }
+    free(xs);
+    return ORC_OK;
+}
+
+/*
+ * Pick the candidate with the largest predicted V per scenario (Section 3, "select the optimal
+ * pair with the maximum training speedup").  Sequential scan: the lowest index wins exact ties.
+ * NaN never wins; a scenario whose scores are all NaN gets index -1 and a NaN best score.
+ * second[s] is the runner-up value (-inf if C == 1 or no second non-NaN score).
+ */
+int orc_select(const double *scores, int64_t S, int C, int64_t row_stride,
+               int32_t *best_idx, double *best_score, double *second)
+{
+    if (!scores || !best_idx || S < 0 || C <= 0 || row_stride < C) return ORC_ERR_ARG;
+    for (int64_t s = 0; s < S; ++s) {
+        const double *r = scores + (size_t)s * (size_t)row_stride;
+        int bi = -1;
+        double bv = -INFINITY, sv = -INFINITY;
+        for (int c = 0; c < C; ++c) {
+            double v = r[c];
+            if (v != v) continue;
+            if (bi < 0 || v > bv) { if (bi >= 0) sv = bv; bv = v; bi = c; }
+            else if (v > sv) sv = v;
+        }
+        best_idx[s] = bi;
+        if (best_score) best_score[s] = (bi < 0) ? NAN : bv;
+        if (second) second[s] = sv;
+    }
+    return ORC_OK;
+}
+
+/*
+ * One online-adaptation step of the flat-feature scorer (Section 3.2 "Offline training online
+ * adapting"; loss per Eq. 2 read as the mean squared error over the minibatch).
+ *
+ *   x_raw [B, F]   raw rows: L*K statistics, Ns scalars, partition size, credit multiple
+ *   target [B]     observed speed
+ *   Wf[k]          weights used by forward/backward (pass the master weights, or a rounded copy
+ *                  of them to reproduce a reduced-precision forward); bf[k] biases
+ *   Wm,bm          master parameters updated in place by Adam; mW,vW,mb,vb its moments
+ *   t              1-based step number used for bias correction
+ *   gW,gb          optional outputs: the gradients (may be NULL)
+ *   do_adam        0 -> only loss and gradients
+ *
+ * Backward is exact back-propagation of loss = (1/B) sum_i (yhat_i - y_i)^2:
+ *   d_out_i = 2 (yhat_i - y_i) / B ; dW = d^T h_prev ; db = sum_i d_i ; d_prev = (d W) * [pre > 0].
+ * Adam follows Kingma & Ba, Algorithm 1, with bias correction and epsilon outside the root.
+ */
+int orc_update(const orc_model *m, const double *x_raw, const double *target, int64_t B,
+               const double *const *Wf, const double *const *bf,
+               double *const *Wm, double *const *bm,
+               double *const *mW, double *const *vW, double *const *mb, double *const *vb,
+               int64_t t, double lr, double beta1, double beta2, double eps, int do_adam,
+               double *loss_out, double *const *gW, double *const *gb, double *yhat_out)
+{
+    if (!m || !x_raw || !target || B <= 0 || m->tensor_encoder) return ORC_ERR_ARG;
+    const int nl = m->n_hidden + 1;
+    const int F = m->L * m->K + m->Ns + 2;
+    int width[16];
+    if (nl > 15) return ORC_ERR_ARG;
+    width[0] = F;
+    for (int k = 0; k < m->n_hidden; ++k) width[k + 1] = m->hidden[k];
+    width[nl] = 1;
+
+    /* activations h[k]: [B, width[k]] (h[0] = encoded input), deltas d[k]: [B, width[k]] */
+    double **h = (double **)calloc((size_t)nl + 1, sizeof(double *));
+    double **d = (double **)calloc((size_t)nl + 1, sizeof(double *));
+    double **gWl = (double **)calloc((size_t)nl, sizeof(double *));
+    double **gbl = (double **)calloc((size_t)nl, sizeof(double *));
+    int fail = (!h || !d || !gWl || !gbl);
+    for (int k = 0; !fail && k <= nl; ++k) {
+        h[k] = (double *)malloc(sizeof(double) * (size_t)B * (size_t)width[k]);
+        d[k] = (double *)malloc(sizeof(double) * (size_t)B * (size_t)width[k]);
+        if (!h[k] || !d[k]) fail = 1;
+    }
+    for (int k = 0; !fail && k < nl; ++k) {
+        gWl[k] = (double *)calloc((size_t)width[k + 1] * (size_t)width[k], sizeof(double));
+        gbl[k] = (double *)calloc((size_t)width[k + 1], sizeof(double));
+        if (!gWl[k] || !gbl[k]) fail = 1;
+    }
+    if (fail) goto cleanup;
+
+    /* encode */
+    for (int64_t i = 0; i < B; ++i) {
+        const double *r = x_raw + (size_t)i * F;
+        double *e = h[0] + (size_t)i * F;
+        int nstat = m->L * m->K;
+        for (int j = 0; j < nstat; ++j) {
+            int k = j % m->K;
+            e[j] = orc_phi(r[j], m->stat_kind[k], m->stat_shift[k], m->stat_scale[k]);
+        }
+        for (int j = 0; j < m->Ns; ++j)
+            e[nstat + j] = orc_phi(r[nstat + j], m->scal_kind[j], m->scal_shift[j], m->scal_scale[j]);
+        e[F - 2] = orc_phi(r[F - 2], m->cfg_kind[0], m->cfg_shift[0], m->cfg_scale[0]);
+        e[F - 1] = orc_phi(r[F - 1], m->cfg_kind[1], m->cfg_shift[1], m->cfg_scale[1]);
+    }
+    /* forward: h[k+1] = relu(W_k h[k] + b_k), last layer linear */
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < B; ++i)
+        for (int k = 0; k < nl; ++k)
+            orc_dense(Wf[k], bf[k], width[k + 1], width[k], h[k] + (size_t)i * width[k],
+                      h[k + 1] + (size_t)i * width[k + 1], k < nl - 1);
+    /* loss and output delta */
+    {
+        double loss = 0.0;
+        for (int64_t i = 0; i < B; ++i) {
+            double e = h[nl][i] - target[i];
+            loss += e * e;
+            d[nl][i] = 2.0 * e / (double)B;
+            if (yhat_out) yhat_out[i] = h[nl][i];
+        }
+        if (loss_out) *loss_out = loss / (double)B;
+    }
+    /* backward */
+    for (int k = nl - 1; k >= 0; --k) {
+        const int no = width[k + 1], ni = width[k];
+        /* dW[o,i] = sum_rows d[o] * h_prev[i]; db[o] = sum_rows d[o] */
+#pragma omp parallel for schedule(static)
+        for (int o = 0; o < no; ++o) {
+            double *g = gWl[k] + (size_t)o * ni;
+            double sb = 0.0;
+            for (int64_t r = 0; r < B; ++r) {
+                double dv = d[k + 1][(size_t)r * no + o];
+                const double *hp = h[k] + (size_t)r * ni;
+                sb += dv;
+                for (int i = 0; i < ni; ++i) g[i] += dv * hp[i];
+            }
+            gbl[k][o] = sb;
+        }
+        if (k > 0) {
+#pragma omp parallel for schedule(static)
+            for (int64_t r = 0; r < B; ++r) {
+                const double *dn = d[k + 1] + (size_t)r * no;
+                double *dp = d[k] + (size_t)r * ni;
+                const double *hp = h[k] + (size_t)r * ni;
+                for (int i = 0; i < ni; ++i) {
+                    double acc = 0.0;
+                    for (int o = 0; o < no; ++o) acc += dn[o] * Wf[k][(size_t)o * ni + i];
+                    dp[i] = (hp[i] > 0.0) ? acc : 0.0; /* h = relu(pre): h > 0 <=> pre > 0 */
+                }
+            }
+        }
+    }
+    for (int k = 0; k < nl; ++k) {
+        if (gW && gW[k]) memcpy(gW[k], gWl[k], sizeof(double) * (size_t)width[k + 1] * width[k]);
+        if (gb && gb[k]) memcpy(gb[k], gbl[k], sizeof(double) * (size_t)width[k + 1]);
+    }
+    if (do_adam) {
+        const double c1 = 1.0 - pow(beta1, (double)t), c2 = 1.0 - pow(beta2, (double)t);
+        for (int k = 0; k < nl; ++k) {
+            size_t nw = (size_t)width[k + 1] * width[k], nb = (size_t)width[k + 1];
+            for (size_t j = 0; j < nw + nb; ++j) {
+                int isb = j >= nw;
+                size_t q = isb ? j - nw : j;
+                double g = isb ? gbl[k][q] : gWl[k][q];
+                double *pm = isb ? &mb[k][q] : &mW[k][q];
+                double *pv = isb ? &vb[k][q] : &vW[k][q];
+                double *pw = isb ? &bm[k][q] : &Wm[k][q];
+                *pm = beta1 * *pm + (1.0 - beta1) * g;
+                *pv = beta2 * *pv + (1.0 - beta2) * g * g;
+                *pw -= lr * (*pm / c1) / (sqrt(*pv / c2) + eps);
+            }
+        }
+    }
+cleanup:
+    for (int k = 0; h && d && k <= nl; ++k) { free(h[k]); free(d[k]); }
+    for (int k = 0; gWl && gbl && k < nl; ++k) { free(gWl[k]); free(gbl[k]); }
+    free(h); free(d); free(gWl); free(gbl);
+    return fail ? ORC_ERR_MEM : ORC_OK;
+}
