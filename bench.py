@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark of the AutoByte meta-network hot path on one MI355X.
+
+One *step* = one pass of the whole hot path over one batch of synthetic input, inputs already
+resident in HBM:
+  scoring workloads (cfg2, cfg3, cfg5): ab_score_candidates on all scenarios x all candidates,
+      writing the score matrix (cfg3) and the per-scenario choice  -> candidates scored / s
+  update workload (cfg4): ab_online_update on one 4096-row minibatch             -> samples / s
+The default workload is cfg3 (65536 scenarios x 256 candidates, 390 -> 1024^4 -> 1, bf16).
+
+Prints ONE JSON line with the throughput, the roofline position of the dominant kernel (device
+time per launch from events recorded around each launch on the launching stream) and the CPU
+oracle's rate on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"bf16": 2.5e15, "f32": 157.3e12}     # dense MFMA peaks of MI355X, flop/s
+HBM_PEAK = 8.0e12
+
+
+def oracle_model(orc, np, w):
+    return orc.Model(L=w.L, K=w.K, stat_enc=list(w.stat_enc), scal_enc=list(w.scal_enc),
+                     part_enc=w.part_enc, cred_enc=w.cred_enc, hidden=list(w.hidden),
+                     W=[np.asarray(x, dtype=np.float64) for x in w.W],
+                     b=[np.asarray(x, dtype=np.float64) for x in w.b],
+                     te_W=getattr(w, "te_W", None), te_b=getattr(w, "te_b", None))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--scenarios", type=int, default=None, help="override the scenario count (debugging)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (scenarios are independent, so more GPUs would "
+              "each take a slice with no exchange); run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2112_13509_amd import binding as ab
+    from paper_2112_13509_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    ab.load()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = int(args.workload[3:])
+    t_gen = time.time()
+
+    if cfg == 4:
+        u = wl.make_update()
+        d = ab.desc_from_workload(u)
+        prm = ab.Params(u.W, u.b, u.dtype, dev, trainable=True)
+        ws = ab.alloc_workspace(d, B=u.batch, device=dev)
+        loss = torch.zeros(1, dtype=torch.float32, device=dev)
+        xall, yall = torch.from_numpy(u.x_raw).to(dev), torch.from_numpy(u.target).to(dev)
+        batches = []
+        for s in range(16):
+            idx = torch.from_numpy(u.batch_indices(s)).to(dev)
+            batches.append((xall[idx].contiguous(), yall[idx].contiguous()))
+        counter = [0]
+
+        def step():
+            x, y = batches[counter[0] % 16]
+            counter[0] += 1
+            ab.ab_online_update(d, prm, x, y, loss_out=loss, workspace=ws)
+
+        units_per_step = u.batch
+        metric, unit = "online-update samples/sec", "samples/s"
+        dtype = u.dtype
+        steps = args.steps if args.steps is not None else 1000
+        warmup = args.warmup if args.warmup is not None else 20
+        widths = [u.F] + list(u.hidden) + [1]
+        flops_per_unit = sum(6.0 * widths[i] * widths[i + 1] for i in range(len(widths) - 1)) - 2.0 * widths[0] * widths[1]
+        dominant = None
+        workload_desc = {"workload": "cfg4: online adaptation, minibatch 4096, 390->512->512->512->1, "
+                                     "bf16 GEMMs, fp32 masters, Adam lr 1e-3", "batch": u.batch}
+    else:
+        w = wl.make_config(cfg, S=args.scenarios)
+        d = ab.desc_from_workload(w)
+        prm = ab.Params.from_workload(w, dev)
+        S, Cn = w.S, w.C
+        ws = ab.alloc_workspace(d, S, Cn, device=dev)
+        dyn, scal = torch.from_numpy(w.dyn).to(dev), torch.from_numpy(w.scal).to(dev)
+        part, cred = torch.from_numpy(w.part).to(dev), torch.from_numpy(w.cred).to(dev)
+        want_scores = (cfg == 3)
+        scores = torch.empty(S, Cn, dtype=torch.float32, device=dev) if want_scores else None
+        idx = torch.empty(S, dtype=torch.int32, device=dev)
+        best = torch.empty(S, dtype=torch.float32, device=dev)
+
+        def step():
+            ab.ab_score_candidates(d, prm, dyn, scal, part, cred, scores, idx, best, ws)
+
+        units_per_step = S * Cn
+        metric, unit = "candidate configs scored/sec (meta-net fwd+argmax)", "candidates/s"
+        dtype = w.dtype
+        steps = args.steps if args.steps is not None else (10 if cfg == 3 else 20)
+        warmup = args.warmup if args.warmup is not None else 2
+        H = list(w.hidden)
+        flops_per_unit = H[0] + sum(2.0 * H[i] * H[i + 1] for i in range(len(H) - 1)) + 2.0 * H[-1]
+        workload_desc = {"workload": "%s: %d scenarios x %d candidates, scorer %d->%s->1%s, %s"
+                                     % (args.workload, S, Cn, w.F, "->".join(map(str, H)),
+                                        ", tensor encoder 4->128->128 mean-pooled over %d tensors" % w.L
+                                        if w.te_hidden else "", dtype),
+                         "scenarios": S, "candidates_per_scenario": Cn,
+                         "outputs": "scores+argmax" if want_scores else "argmax"}
+    t_gen = time.time() - t_gen
+
+    # ---- timed region: W warm-up steps, then exactly K steps between two device syncs
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = max(e0.elapsed_time(e1), 0.0) / steps
+    ms_wall = wall * 1e3 / steps
+    value = units_per_step / (ms_per_step * 1e-3)
+
+    # ---- per-kernel device time: events around every launch, on the launching stream
+    trace_steps = 2 if cfg != 4 else 20
+    with ab.KernelTimer() as kt:
+        for _ in range(trace_steps):
+            step()
+        ksum = kt.summary()
+    kernels = {}
+    for name, r in sorted(ksum.items(), key=lambda kv: -kv[1]["total_ms"]):
+        rate = r["work"] / (r["total_ms"] * 1e-3) if r["total_ms"] > 0 else 0.0
+        kernels[name] = {"launches_per_step": r["launches"] / trace_steps, "avg_ms": round(r["avg_ms"], 5),
+                         "ms_per_step": round(r["total_ms"] / trace_steps, 5),
+                         ("GB/s" if r["is_bytes"] else "TFLOP/s"): round(rate / (1e9 if r["is_bytes"] else 1e12), 3)}
+    gemm_names = [n for n in ksum if n.startswith("gemm_hidden") or n.startswith("upd_gemm")]
+    if gemm_names:
+        tot_ms = sum(ksum[n]["total_ms"] for n in gemm_names)
+        tot_work = sum(ksum[n]["work"] for n in gemm_names)
+        launches = sum(ksum[n]["launches"] for n in gemm_names)
+        achieved = tot_work / (tot_ms * 1e-3)
+        roofline = {"bound": "mfma", "kernel": "hidden-layer GEMM launches (" + ", ".join(sorted(gemm_names)) + ")",
+                    "achieved": round(achieved / 1e12, 3), "peak": PEAK[dtype] / 1e12, "unit": "TFLOP/s",
+                    "frac": round(achieved / PEAK[dtype], 4), "traffic": None,
+                    "flop_per_launch": tot_work / launches, "avg_launch_ms": round(tot_ms / launches, 5),
+                    "share_of_step_time": round(tot_ms / trace_steps / ms_per_step, 3)}
+    else:
+        roofline = None
+
+    # ---- CPU oracle on a bounded sample of the same workload, same box
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        if cfg == 4:
+            n_rows = 1024
+            st = orc.TrainState.fresh(u.W, u.b)
+            rows = u.batch_indices(0)[:n_rows]
+            t0 = time.perf_counter()
+            orc.update(oracle_model(orc, np, u), st, u.x_raw[rows], u.target[rows], want_grads=False)
+            dt = time.perf_counter() - t0
+            cpu = {"value": n_rows / dt, "unit": unit, "cores": orc.num_threads(), "kind": "oracle",
+                   "sample": "one fp64 step on the first %d rows of minibatch 0 (%.1f s)" % (n_rows, dt)}
+        else:
+            n_s = {2: 8, 3: 96, 5: 24}[cfg]
+            n_s = min(n_s, w.S)
+            sub = w.subset(np.arange(n_s))
+            t0 = time.perf_counter()
+            ref = orc.score(oracle_model(orc, np, sub), sub.dyn, sub.scal, sub.part, sub.cred)
+            ridx, _, _ = orc.select(ref)
+            dt = time.perf_counter() - t0
+            cpu = {"value": n_s * w.C / dt, "unit": unit, "cores": orc.num_threads(), "kind": "oracle",
+                   "sample": "first %d scenarios x all %d candidates, fp64, unfactorised (%.1f s)" % (n_s, w.C, dt)}
+            if want_scores:
+                got = scores[:n_s].cpu().numpy().astype(np.float64)
+                scale = np.abs(ref).max(axis=1, keepdims=True)
+                cpu["gpu_vs_oracle_max_scaled_err"] = float((np.abs(got - ref) / scale).max())
+
+    out = {"metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": steps, "warmup": warmup,
+           "ms_per_step": ms_per_step, "ms_per_step_wall": ms_wall, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": dtype, "data": "synthetic (seeded, shaped like the paper's workloads)",
+           "config": workload_desc,
+           "algorithmic_flop_per_unit": flops_per_unit,
+           "whole_step_TFLOP/s": round(units_per_step * flops_per_unit / (ms_per_step * 1e-3) / 1e12, 3),
+           "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+           "input_generation_s": round(t_gen, 2)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

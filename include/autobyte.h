@@ -1,0 +1,204 @@
+/*
+ * autobyte.h - C ABI of the MI355X (gfx950) implementation of the AutoByte meta-network hot path.
+ *
+ * AutoByte (arXiv 2112.13509) tunes two ByteScheduler knobs, the partition size S_p and the credit
+ * size S_c, with a meta-network f : (T, B, S_c, S_p) -> V (Eq. 1) that predicts the training speed V
+ * of a job from its runtime statistics (Table 1) for a candidate pair <S_p, S_c>.  The pair with the
+ * largest predicted V is applied (Section 3, introduction; Section 3.3 "Meta network optimizer"),
+ * and the network keeps being adapted online on freshly observed speeds (Section 3.2 "Offline
+ * training online adapting"; loss of Eq. 2).
+ *
+ * This library is that hot path, batched: many scenarios (one scenario = the statistics of one job
+ * at one moment) times a whole grid of candidates.
+ *
+ *   ab_score_candidates  predicted V for every (scenario, candidate), optionally fused with the choice
+ *   ab_select_best       per-scenario argmax over a stored score matrix
+ *   ab_online_update     one forward + backward + Adam step on explicit (statistics, candidate, V) rows
+ *
+ * General rules
+ *   - Every pointer marked DEVICE is HIP device memory on the current device, owned by the caller.  The
+ *     library never allocates, frees or retains device memory and keeps no state between calls.
+ *   - Every pointer marked HOST is ordinary host memory, read during the call only.
+ *   - Work is enqueued on the HIP stream passed as `stream` (a hipStream_t cast to void*, NULL = the
+ *     default stream).  Calls return as soon as the work is enqueued; nothing synchronises.
+ *   - The workspace is DEVICE scratch of at least ab_workspace_bytes(...) bytes, 256-byte aligned, owned
+ *     by the caller; its contents are undefined after the call and two calls that share it must be
+ *     ordered on one stream.
+ *   - Errors are returned as negative ab_status values after host-side checks of the arguments (null
+ *     pointers, sizes, widths, alignment, workspace size) and of the launch status.  Nothing is thrown
+ *     and nothing aborts.  Data-dependent trouble (a non-finite statistic) cannot be seen by the host
+ *     and shows up in the outputs: a NaN score, and best_idx = -1 if a scenario has no non-NaN score.
+ *   - Output buffers must not overlap inputs, weights or the workspace.
+ *
+ * Feature layout (Table 1; Section 3.1 "Meta network architecture": the feature groups are concatenated)
+ *   x = [ statistics block | scalars | phi(S_p) | phi(S_c) ]
+ *   statistics block: L*K transformed per-layer statistics, layer-major / statistic-minor (flat model),
+ *   or the mean over the L layers of a shared two-layer MLP applied to each layer's K transformed
+ *   statistics (tensor-encoder model: "embed layer-wise computation time into a fixed dimension
+ *   feature space").  Every raw value x is transformed as phi(x) = (g(x) - shift) * scale with
+ *   g = identity or natural logarithm; S_c is expressed as a multiple of S_p (Section 2.4).
+ *
+ * Network: hidden dense layers with ReLU, then one linear output unit (V is a regression target).
+ */
+#ifndef AUTOBYTE_H
+#define AUTOBYTE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AB_MAX_STATS   8    /* statistics per layer (K)                    */
+#define AB_MAX_SCALARS 16   /* scalar features per scenario                */
+#define AB_MAX_HIDDEN  8    /* hidden layers of the scorer                 */
+#define AB_MAX_LAYERS  12   /* tensor-encoder (2) + hidden (8) + output (1) rounded up */
+
+typedef int32_t ab_status;
+enum {
+    AB_OK = 0,
+    AB_ERR_NULL = -1,         /* a required pointer is NULL                                   */
+    AB_ERR_SHAPE = -2,        /* a size is non-positive or inconsistent (e.g. C != P*Q)        */
+    AB_ERR_DTYPE = -3,        /* compute_dtype is not AB_F32 / AB_BF16                         */
+    AB_ERR_ALIGN = -4,        /* a pointer misses its required alignment                       */
+    AB_ERR_WORKSPACE = -5,    /* workspace is NULL or smaller than ab_workspace_bytes(...)     */
+    AB_ERR_UNSUPPORTED = -6,  /* valid description that this build has no kernel for           */
+    AB_ERR_DEVICE = -7        /* HIP reported a launch / runtime error                         */
+};
+
+enum { AB_F32 = 0, AB_BF16 = 1 };          /* arithmetic type of weights and activations; accumulation is fp32 */
+enum { AB_ENC_LINEAR = 0, AB_ENC_LOG = 1 };
+
+/* phi(x) = (g(x) - shift) * scale, g(x) = x (AB_ENC_LINEAR) or ln x (AB_ENC_LOG). */
+typedef struct { int32_t kind; float shift; float scale; } ab_enc;
+
+/*
+ * Model description (HOST, plain data, read during the call).
+ *   n_layers, n_stats      L and K of the statistics tensor dyn[S, L, K]
+ *   n_scalars              scalar features per scenario (worker count, bandwidth, type one-hots ...)
+ *   enc_*                  transform of each statistic kind, each scalar, the partition size and the
+ *                          credit multiple
+ *   n_hidden, hidden[]     scorer hidden widths.  Supported: 1 <= n_hidden <= 8, every width a multiple
+ *                          of 64 and <= 4096
+ *   tensor_encoder         0: flat statistics block (width L*K); 1: shared per-layer MLP
+ *                          K -> enc_hidden[0] -> enc_hidden[1] (ReLU after both), mean over the L layers
+ *                          (width enc_hidden[1]).  Supported: enc_hidden = {128, 128}
+ *   compute_dtype          AB_F32: fp32 weights, activations and fp32 MFMA; AB_BF16: bf16 weights and
+ *                          activations with fp32 accumulation
+ * The scorer's input width is F = (L*K or enc_hidden[1]) + n_scalars + 2.
+ */
+typedef struct {
+    int32_t n_layers, n_stats, n_scalars;
+    ab_enc  enc_stat[AB_MAX_STATS];
+    ab_enc  enc_scalar[AB_MAX_SCALARS];
+    ab_enc  enc_partition, enc_credit;
+    int32_t n_hidden;
+    int32_t hidden[AB_MAX_HIDDEN];
+    int32_t tensor_encoder;
+    int32_t enc_hidden[2];
+    int32_t compute_dtype;
+} ab_model_desc;
+
+/*
+ * Parameters (the struct is HOST, every pointer in it is DEVICE).
+ * Layer order: the two tensor-encoder layers first (only if tensor_encoder = 1), then the scorer's
+ * hidden layers, then the output layer (1 x last hidden width).
+ *   W[k]         [out, in] row-major in compute_dtype (bf16 = upper 16 bits of an fp32), 16-byte aligned
+ *   b[k]         [out] fp32
+ * Only ab_online_update uses the rest (flat model, so index k counts scorer layers from 0):
+ *   W_master[k]  fp32 master copy of W[k]; b[k] is its own master
+ *   adam_mW/vW   first / second moment of W[k], fp32; adam_mb/vb the same for b[k]
+ *   step         one int64: number of update steps taken so far (0 before the first step)
+ */
+typedef struct {
+    const void  *W[AB_MAX_LAYERS];
+    float       *b[AB_MAX_LAYERS];
+    float       *W_master[AB_MAX_LAYERS];
+    float       *adam_mW[AB_MAX_LAYERS], *adam_vW[AB_MAX_LAYERS];
+    float       *adam_mb[AB_MAX_LAYERS], *adam_vb[AB_MAX_LAYERS];
+    int64_t     *step;
+} ab_params;
+
+/* Runtime statistics of S scenarios (struct HOST, pointers DEVICE, fp32, densely packed). */
+typedef struct {
+    const float *dyn;       /* [S, L, K] raw per-layer statistics (computation times, tensor bytes ...) */
+    const float *scalars;   /* [S, n_scalars] raw scalars                                                */
+    int64_t      S;
+} ab_stats;
+
+/* Candidate grid shared by all scenarios (struct HOST, pointers DEVICE). Candidate c = p*Q + q. */
+typedef struct {
+    const float *partition_bytes;  int32_t P;   /* [P] partition sizes S_p                    */
+    const float *credit_mult;      int32_t Q;   /* [Q] credit sizes as multiples of S_p       */
+} ab_grid;
+
+/*
+ * Bytes of workspace needed.  Pass S and C = P*Q for ab_score_candidates (B = 0), or B for
+ * ab_online_update (S = C = 0); with all three set the result covers both.  Returns 0 for an
+ * unsupported description.
+ */
+size_t ab_workspace_bytes(const ab_model_desc *desc, int64_t S, int32_t C, int64_t B);
+
+/*
+ * Predicted V of every candidate for every scenario (Eq. 1 over the <S_p, S_c> grid), and / or the
+ * predicted-best candidate per scenario (Section 3: the pair with the maximum predicted speed).
+ *   scores      DEVICE [S, C] fp32, or NULL when only the choice is wanted
+ *   best_idx    DEVICE [S] int32 index c = p*Q+q of the largest score (lowest index on exact ties,
+ *               NaN never wins, -1 if every score of the scenario is NaN), or NULL
+ *   best_score  DEVICE [S] fp32 score of that candidate (NaN where best_idx = -1), or NULL
+ * At least one of scores / best_idx must be given.  S = 0 is a valid no-op.
+ */
+ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params,
+                              const ab_stats *stats, const ab_grid *grid,
+                              float *scores, int32_t *best_idx, float *best_score,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Per-scenario argmax over a stored score matrix (same rules as above).
+ *   scores      DEVICE fp32, row s starts at scores + s*row_stride (row_stride >= C, in elements)
+ *   best_idx    DEVICE [S] int32;  best_score DEVICE [S] fp32 or NULL
+ */
+ab_status ab_select_best(const float *scores, int64_t S, int32_t C, int64_t row_stride,
+                         int32_t *best_idx, float *best_score, void *stream);
+
+/*
+ * One online-adaptation step of the flat model (tensor_encoder = 0) on a minibatch of B observed rows:
+ * forward, loss = mean_i (V_hat_i - V_i)^2 (Eq. 2 as mean squared error), exact back-propagation, Adam
+ * with bias correction (epsilon outside the square root).
+ *   x_raw     DEVICE [B, F] fp32 raw rows: L*K statistics, n_scalars scalars, partition bytes, credit
+ *             multiple (transformed on the device with the description's constants)
+ *   target    DEVICE [B] fp32 observed speed V
+ *   loss_out  DEVICE one fp32 (loss before the step), or NULL
+ * Mutates W_master, b, the Adam moments, *step (incremented by one) and refreshes W[k] (the
+ * compute_dtype copy used by scoring).  With AB_BF16 the GEMMs run on bf16 copies of the masters.
+ */
+ab_status ab_online_update(const ab_model_desc *desc, ab_params *params,
+                           const float *x_raw, const float *target, int64_t B,
+                           float lr, float beta1, float beta2, float eps,
+                           float *loss_out, void *workspace, size_t workspace_bytes, void *stream);
+
+const char *ab_status_string(ab_status status);
+
+/*
+ * Optional launch tracing, for measurement (the paper times computation and communication per
+ * mini-batch, Section 3.1 "Input runtime metrics"; this is the library's counterpart for its own
+ * kernels).  When a callback is installed, every kernel launch made by the entry points above is
+ * bracketed by two calls on the launching host thread: phase 0 just before the launch is enqueued
+ * and phase 1 just after.  A caller that records an event on `stream` in both gets the kernel's
+ * device time.  `kernel` is a static string naming the launch's role, `work` its algorithmic
+ * floating-point operations (matrix products) or bytes moved (streaming kernels), `work_is_bytes`
+ * tells which.  Pass fn = NULL to switch tracing off (the default).  Process-wide, not thread-safe
+ * against concurrent entry-point calls.
+ */
+typedef void (*ab_trace_fn)(const char *kernel, int32_t phase, double work, int32_t work_is_bytes,
+                            void *stream, void *user);
+void ab_set_trace(ab_trace_fn fn, void *user);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int32_t ab_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AUTOBYTE_H */

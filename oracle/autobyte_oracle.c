@@ -45,6 +45,20 @@ static double orc_phi(double x, int kind, double shift, double scale)
     return (g - shift) * scale;
 }
 
+/* Diagnostic only: nearest bfloat16 (ties to even) of a value, via its nearest float.  Used when a
+ * test wants the oracle to round stored activations where a bf16 implementation stores them, so
+ * that implementation bugs can be told apart from rounding noise.  Off by default. */
+static double orc_round_bf16(double v)
+{
+    float f = (float)v;
+    uint32_t u;
+    if (f != f) return v;
+    memcpy(&u, &f, 4);
+    u = (u + 0x7FFFu + ((u >> 16) & 1u)) & 0xFFFF0000u;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
 double orc_encode_value(double x, int kind, double shift, double scale)
 {
     return orc_phi(x, kind, shift, scale);
@@ -102,6 +116,9 @@ typedef struct {
     const double *const *te_W; const double *const *te_b;
     int n_hidden; const int *hidden;
     const double *const *W; const double *const *b;
+    int round_stored_bf16;   /* diagnostic, default 0: round to bf16 the values a bf16 pipeline keeps in
+                                memory (statistics block + scalars, tensor-encoder hidden layer, every
+                                hidden activation except the last) */
 } orc_model;
 
 static int orc_stats_width(const orc_model *m)
@@ -130,6 +147,7 @@ static void orc_scenario_features(const orc_model *m, const double *dyn_s, const
                 in[k] = orc_phi(dyn_s[l * m->K + k], m->stat_kind[k],
                                 m->stat_shift[k], m->stat_scale[k]);
             orc_dense(m->te_W[0], m->te_b[0], m->te_h0, m->K, in, h0, 1);
+            if (m->round_stored_bf16) for (int j = 0; j < m->te_h0; ++j) h0[j] = orc_round_bf16(h0[j]);
             orc_dense(m->te_W[1], m->te_b[1], m->te_h1, m->te_h0, h0, h1, 1);
             for (int j = 0; j < m->te_h1; ++j) xs[j] += h1[j];
         }
@@ -138,6 +156,7 @@ static void orc_scenario_features(const orc_model *m, const double *dyn_s, const
     }
     for (int j = 0; j < m->Ns; ++j)
         xs[off + j] = orc_phi(scal_s[j], m->scal_kind[j], m->scal_shift[j], m->scal_scale[j]);
+    if (m->round_stored_bf16) for (int j = 0; j < off + m->Ns; ++j) xs[j] = orc_round_bf16(xs[j]);
 }
 
 /* Scorer MLP on one full input vector x[F]; buf holds 2*maxwidth doubles. */
@@ -149,6 +168,8 @@ static double orc_mlp_forward(const orc_model *m, const double *x, int F, double
     for (int k = 0; k < m->n_hidden; ++k) {
         double *out = (k & 1) ? bb : a;
         orc_dense(m->W[k], m->b[k], m->hidden[k], n_in, cur, out, 1);
+        if (m->round_stored_bf16 && k < m->n_hidden - 1)
+            for (int j = 0; j < m->hidden[k]; ++j) out[j] = orc_round_bf16(out[j]);
         cur = out;
         n_in = m->hidden[k];
     }

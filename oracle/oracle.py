@@ -60,7 +60,7 @@ class _CModel(C.Structure):
                 ("tensor_encoder", C.c_int), ("te_h0", C.c_int), ("te_h1", C.c_int),
                 ("te_W", _dpp), ("te_b", _dpp),
                 ("n_hidden", C.c_int), ("hidden", _ip),
-                ("W", _dpp), ("b", _dpp)]
+                ("W", _dpp), ("b", _dpp), ("round_stored_bf16", C.c_int)]
 
 
 def _f64(a) -> np.ndarray:
@@ -88,6 +88,7 @@ class Model:
     b: List[np.ndarray]
     te_W: Optional[List[np.ndarray]] = None   # tensor encoder: [[h0,K],[h1,h0]] or None
     te_b: Optional[List[np.ndarray]] = None
+    round_stored_bf16: bool = False          # diagnostic: mimic a bf16 pipeline's stored activations
     _keep: list = field(default_factory=list, repr=False)
 
     @property
@@ -141,6 +142,7 @@ class Model:
         pW, pb = _ptr_array(Ws), _ptr_array(bs)
         keep.extend([hid, pW, pb] + Ws + bs)
         m.W, m.b = C.cast(pW, _dpp), C.cast(pb, _dpp)
+        m.round_stored_bf16 = 1 if self.round_stored_bf16 else 0
         self._keep = keep
         return m
 

@@ -1,0 +1,289 @@
+// C-ABI entry points: host-side argument checks, workspace layout, launch sequences.
+#include "internal.hpp"
+#include <string.h>
+
+namespace ab {
+
+ab_trace_fn g_trace_fn = nullptr;
+void *g_trace_user = nullptr;
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline int round_up(int x, int a) { return (x + a - 1) / a * a; }
+
+static int pick_tile(int64_t M, int N)
+{
+    for (int tile = TILE_BIG; tile > TILE_SMALL; --tile) {
+        const int edge = tile_edge(tile);
+        if (N % edge != 0) continue;
+        if (((M + edge - 1) / edge) * (N / edge) >= 512) return tile;
+    }
+    return TILE_SMALL;
+}
+
+static ab_status check_desc(const ab_model_desc *d)
+{
+    if (!d) return AB_ERR_NULL;
+    if (d->compute_dtype != AB_F32 && d->compute_dtype != AB_BF16) return AB_ERR_DTYPE;
+    if (d->n_layers <= 0 || d->n_stats <= 0 || d->n_stats > AB_MAX_STATS) return AB_ERR_SHAPE;
+    if (d->n_scalars < 0 || d->n_scalars > AB_MAX_SCALARS) return AB_ERR_SHAPE;
+    if (d->n_hidden < 0 || d->n_hidden > AB_MAX_HIDDEN) return AB_ERR_SHAPE;
+    if (d->n_hidden == 0) return AB_ERR_UNSUPPORTED;
+    for (int k = 0; k < d->n_hidden; ++k) {
+        if (d->hidden[k] <= 0) return AB_ERR_SHAPE;
+        if (d->hidden[k] % 64 != 0 || d->hidden[k] > 4096) return AB_ERR_UNSUPPORTED;
+    }
+    for (int k = 0; k < d->n_stats; ++k)
+        if (d->enc_stat[k].kind != AB_ENC_LINEAR && d->enc_stat[k].kind != AB_ENC_LOG) return AB_ERR_SHAPE;
+    for (int k = 0; k < d->n_scalars; ++k)
+        if (d->enc_scalar[k].kind != AB_ENC_LINEAR && d->enc_scalar[k].kind != AB_ENC_LOG) return AB_ERR_SHAPE;
+    if (d->tensor_encoder != 0 && d->tensor_encoder != 1) return AB_ERR_SHAPE;
+    if (d->tensor_encoder) {
+        if (d->enc_hidden[0] <= 0 || d->enc_hidden[1] <= 0) return AB_ERR_SHAPE;
+        if (d->enc_hidden[0] != 128 || d->enc_hidden[1] != 128) return AB_ERR_UNSUPPORTED;
+        if (d->compute_dtype != AB_BF16) return AB_ERR_UNSUPPORTED;
+    } else if ((int64_t)d->n_layers * d->n_stats > (1 << 20)) {
+        return AB_ERR_UNSUPPORTED;
+    }
+    return AB_OK;
+}
+
+struct ScorePlan {
+    int dtype, Fs, F, Kp, D, base;
+    int H[AB_MAX_HIDDEN];
+    int tile[AB_MAX_HIDDEN];      // tile of hidden GEMM k (k >= 1)
+    int tile_a;                   // tile of the scenario-term GEMM
+    int nt_last;
+    int64_t chunk_scen, chunk_rows;
+    size_t off_xs, off_w1s, off_aterm, off_bterm, off_wout, off_partial, off_act0, off_act1, total;
+};
+
+static const int64_t kTargetChunkRows = 1 << 20;
+
+static ab_status plan_scoring(const ab_model_desc *d, int64_t S, int32_t C, ScorePlan *p)
+{
+    memset(p, 0, sizeof(*p));
+    p->dtype = d->compute_dtype;
+    p->base = d->tensor_encoder ? 2 : 0;
+    p->Fs = (d->tensor_encoder ? d->enc_hidden[1] : d->n_layers * d->n_stats) + d->n_scalars;
+    p->F = p->Fs + 2;
+    p->Kp = round_up(p->Fs, 64);
+    p->D = d->n_hidden;
+    int hmax = 0;
+    for (int k = 0; k < p->D; ++k) { p->H[k] = d->hidden[k]; if (p->H[k] > hmax) hmax = p->H[k]; }
+    if ((int64_t)C * p->H[0] >= (1LL << 31)) return AB_ERR_UNSUPPORTED;
+    int64_t cs = kTargetChunkRows / C;
+    if (cs < 1) cs = 1;
+    if (cs > S) cs = S > 0 ? S : 1;
+    const int64_t cap = ((1LL << 31) - 1) / p->H[0];
+    if (cs > cap) cs = cap;
+    p->chunk_scen = cs;
+    p->chunk_rows = cs * C;
+    p->tile_a = pick_tile(S, p->H[0]);
+    for (int k = 1; k < p->D; ++k) p->tile[k] = pick_tile(p->chunk_rows, p->H[k]);
+    p->nt_last = (p->D >= 2) ? p->H[p->D - 1] / tile_edge(p->tile[p->D - 1]) : 1;
+    const size_t es = elem_size(p->dtype);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    p->off_xs = take((size_t)(S > 0 ? S : 1) * p->Kp * es);
+    p->off_w1s = take((size_t)p->H[0] * p->Kp * es);
+    p->off_aterm = take((size_t)(S > 0 ? S : 1) * p->H[0] * 4);
+    p->off_bterm = take((size_t)C * p->H[0] * 4);
+    p->off_wout = take((size_t)p->H[p->D - 1] * 4);
+    p->off_partial = take((size_t)p->chunk_rows * p->nt_last * 4);
+    p->off_act0 = p->off_act1 = 0;
+    if (p->D >= 3) p->off_act0 = take((size_t)p->chunk_rows * hmax * es);
+    if (p->D >= 4) p->off_act1 = take((size_t)p->chunk_rows * hmax * es);
+    p->total = off;
+    return AB_OK;
+}
+
+#define AB_HIP(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return AB_ERR_DEVICE; } while (0)
+
+static inline bool misaligned(const void *p, size_t a) { return ((uintptr_t)p % a) != 0; }
+
+// defined in update.hip
+size_t update_workspace_bytes(const ab_model_desc *d, int64_t B);
+ab_status online_update(const ab_model_desc *d, ab_params *params, const float *x_raw, const float *target,
+                        int64_t B, float lr, float beta1, float beta2, float eps, float *loss_out,
+                        void *workspace, size_t ws_bytes, hipStream_t st);
+
+}  // namespace ab
+
+using namespace ab;
+
+extern "C" {
+
+int32_t ab_version(void) { return 100; }
+
+void ab_set_trace(ab_trace_fn fn, void *user) { g_trace_fn = fn; g_trace_user = user; }
+
+const char *ab_status_string(ab_status s)
+{
+    switch (s) {
+    case AB_OK: return "ok";
+    case AB_ERR_NULL: return "a required pointer is NULL";
+    case AB_ERR_SHAPE: return "a size is non-positive or inconsistent";
+    case AB_ERR_DTYPE: return "unknown compute dtype";
+    case AB_ERR_ALIGN: return "a pointer misses its required alignment";
+    case AB_ERR_WORKSPACE: return "workspace missing or too small";
+    case AB_ERR_UNSUPPORTED: return "description not supported by this build";
+    case AB_ERR_DEVICE: return "HIP reported an error";
+    default: return "unknown status";
+    }
+}
+
+size_t ab_workspace_bytes(const ab_model_desc *desc, int64_t S, int32_t C, int64_t B)
+{
+    if (check_desc(desc) != AB_OK || S < 0 || C < 0 || B < 0) return 0;
+    size_t need = 0;
+    if (C > 0) {
+        ScorePlan p;
+        if (plan_scoring(desc, S, C, &p) != AB_OK) return 0;
+        need = p.total;
+    }
+    if (B > 0) {
+        const size_t u = update_workspace_bytes(desc, B);
+        if (u == 0) return 0;
+        if (u > need) need = u;
+    }
+    return need;
+}
+
+ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params,
+                              const ab_stats *stats, const ab_grid *grid,
+                              float *scores, int32_t *best_idx, float *best_score,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    ab_status rc = check_desc(desc);
+    if (rc != AB_OK) return rc;
+    if (!params || !stats || !grid) return AB_ERR_NULL;
+    if (!scores && !best_idx) return AB_ERR_NULL;
+    if (best_score && !best_idx) return AB_ERR_NULL;
+    if (stats->S < 0 || grid->P <= 0 || grid->Q <= 0) return AB_ERR_SHAPE;
+    if ((int64_t)grid->P * grid->Q > (1 << 24)) return AB_ERR_SHAPE;
+    if (!grid->partition_bytes || !grid->credit_mult) return AB_ERR_NULL;
+    const int64_t S = stats->S;
+    const int32_t C = grid->P * grid->Q;
+    if (S > 0 && (!stats->dyn || (desc->n_scalars > 0 && !stats->scalars))) return AB_ERR_NULL;
+    ScorePlan p;
+    rc = plan_scoring(desc, S, C, &p);
+    if (rc != AB_OK) return rc;
+    const int n_layers_total = p.base + p.D + 1;
+    for (int k = 0; k < n_layers_total; ++k) {
+        if (!params->W[k] || !params->b[k]) return AB_ERR_NULL;
+        if (misaligned(params->W[k], 16) || misaligned(params->b[k], 4)) return AB_ERR_ALIGN;
+    }
+    if (misaligned(stats->dyn, 4) || misaligned(stats->scalars, 4) || misaligned(scores, 4) ||
+        misaligned(best_idx, 4) || misaligned(best_score, 4)) return AB_ERR_ALIGN;
+    if (!workspace || workspace_bytes < p.total) return AB_ERR_WORKSPACE;
+    if (misaligned(workspace, 256)) return AB_ERR_ALIGN;
+    if (S == 0) return AB_OK;
+
+    hipStream_t st = (hipStream_t)stream;
+    unsigned char *ws = (unsigned char *)workspace;
+    void *xs = ws + p.off_xs, *w1s = ws + p.off_w1s;
+    float *a_term = (float *)(ws + p.off_aterm), *b_term = (float *)(ws + p.off_bterm);
+    float *w_out_f = (float *)(ws + p.off_wout), *partial = (float *)(ws + p.off_partial);
+    void *act[2] = {ws + p.off_act0, ws + p.off_act1};
+    const int dt = p.dtype;
+
+    // 1. scenario rows: transformed statistics (or pooled tensor embedding) + scalars, K-padded
+    const double es = (double)elem_size(dt);
+    if (desc->tensor_encoder) {
+        {
+            TraceScope ts("tensor_encoder", (double)S * desc->n_layers * 2.0 * (desc->n_stats * 128.0 + 128.0 * 128.0),
+                          0, st);
+            AB_HIP(launch_tensor_encoder(dt, desc, stats->dyn, params->W[0], params->b[0], params->W[1],
+                                         params->b[1], xs, p.Kp, S, st));
+        }
+        TraceScope ts("encode_stats", (double)S * (desc->n_scalars * 4.0 + (p.Kp - desc->enc_hidden[1]) * es), 1, st);
+        AB_HIP(launch_encode_stats(dt, desc, stats->dyn, stats->scalars, xs, S, p.Kp,
+                                   desc->enc_hidden[1], 0, st));
+    } else {
+        TraceScope ts("encode_stats", (double)S * (p.Fs * 4.0 + p.Kp * es), 1, st);
+        AB_HIP(launch_encode_stats(dt, desc, stats->dyn, stats->scalars, xs, S, p.Kp, 0, 1, st));
+    }
+    // 2. layer-1 split: packed statistics columns of W1, candidate term B[c], fp32 output weights
+    {
+        TraceScope ts("prep_layer1", (double)p.H[0] * (p.F * es + p.Kp * es) + (double)C * p.H[0] * 4.0, 1, st);
+        AB_HIP(launch_prep_layer1(dt, desc, params->W[p.base], params->b[p.base], p.F, p.Fs, p.H[0], p.Kp, w1s,
+                                  grid, b_term, params->W[p.base + p.D], p.H[p.D - 1], w_out_f, st));
+    }
+    // 3. scenario term A[s] = x_s W1_s^T (fp32 out)
+    {
+        GemmArgs g;
+        memset(&g, 0, sizeof(g));
+        g.A = xs; g.lda = p.Kp; g.B = w1s; g.ldb = p.Kp;
+        g.M = S; g.N = p.H[0]; g.K = p.Kp;
+        g.out = a_term; g.ldo = p.H[0]; g.out_f32 = 1;
+        TraceScope ts("gemm_scenario_term", 2.0 * S * p.H[0] * p.Kp, 0, st);
+        AB_HIP(launch_gemm(dt, p.tile_a, AMODE_LOAD, EPI_STORE, g, st));
+    }
+    // 4. candidate rows, a chunk of scenarios at a time
+    for (int64_t s0 = 0; s0 < S; s0 += p.chunk_scen) {
+        const int64_t ns = (S - s0 < p.chunk_scen) ? S - s0 : p.chunk_scen;
+        const int64_t rows = ns * C;
+        const float *a_chunk = a_term + s0 * p.H[0];
+        int nt = 1;
+        if (p.D == 1) {
+            TraceScope ts("score_single_hidden", 3.0 * rows * p.H[0], 0, st);
+            AB_HIP(launch_score_single_hidden(a_chunk, b_term, w_out_f, partial, rows, C, p.H[0], st));
+        } else {
+            for (int k = 1; k < p.D; ++k) {
+                GemmArgs g;
+                memset(&g, 0, sizeof(g));
+                if (k == 1) { g.a_term = a_chunk; g.b_term = b_term; g.ldt = p.H[0]; g.C = C; }
+                else { g.A = act[k & 1]; g.lda = p.H[k - 1]; }
+                g.B = params->W[p.base + k]; g.ldb = p.H[k - 1];
+                g.M = rows; g.N = p.H[k]; g.K = p.H[k - 1];
+                g.bias = params->b[p.base + k]; g.relu = 1;
+                const bool last = (k == p.D - 1);
+                if (last) { g.w_out = w_out_f; g.partial = partial; nt = p.H[k] / tile_edge(p.tile[k]); }
+                else { g.out = act[(k + 1) & 1]; g.ldo = p.H[k]; }
+                TraceScope ts(k == 1 ? (last ? "gemm_hidden_first_last" : "gemm_hidden_first")
+                                     : (last ? "gemm_hidden_last" : "gemm_hidden_mid"),
+                              2.0 * rows * p.H[k] * p.H[k - 1], 0, st);
+                AB_HIP(launch_gemm(dt, p.tile[k], k == 1 ? AMODE_GEN : AMODE_LOAD,
+                                   last ? EPI_SCORE : EPI_STORE, g, st));
+            }
+        }
+        TraceScope ts("finish_select", (double)rows * (nt * 4.0 + (scores ? 4.0 : 0.0)) + ns * 8.0, 1, st);
+        AB_HIP(launch_finish_select(partial, nt, C, params->b[p.base + p.D],
+                                    scores ? scores + s0 * C : nullptr, C,
+                                    best_idx ? best_idx + s0 : nullptr,
+                                    best_score ? best_score + s0 : nullptr, ns, C, st));
+    }
+    return AB_OK;
+}
+
+ab_status ab_select_best(const float *scores, int64_t S, int32_t C, int64_t row_stride,
+                         int32_t *best_idx, float *best_score, void *stream)
+{
+    if (!scores || !best_idx) return AB_ERR_NULL;
+    if (S < 0 || C <= 0 || row_stride < C) return AB_ERR_SHAPE;
+    if (misaligned(scores, 4) || misaligned(best_idx, 4) || misaligned(best_score, 4)) return AB_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    for (int64_t s0 = 0; s0 < S; s0 += (1 << 30)) {
+        const int64_t ns = (S - s0 < (1 << 30)) ? S - s0 : (1 << 30);
+        TraceScope ts("select_best", (double)ns * (C * 4.0 + 8.0), 1, st);
+        AB_HIP(launch_finish_select(scores + s0 * row_stride, 1, row_stride, nullptr, nullptr, 0,
+                                    best_idx + s0, best_score ? best_score + s0 : nullptr, ns, C, st));
+    }
+    return AB_OK;
+}
+
+ab_status ab_online_update(const ab_model_desc *desc, ab_params *params,
+                           const float *x_raw, const float *target, int64_t B,
+                           float lr, float beta1, float beta2, float eps,
+                           float *loss_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    ab_status rc = check_desc(desc);
+    if (rc != AB_OK) return rc;
+    if (desc->tensor_encoder) return AB_ERR_UNSUPPORTED;
+    if (!params || !x_raw || !target) return AB_ERR_NULL;
+    if (B <= 0) return AB_ERR_SHAPE;
+    return online_update(desc, params, x_raw, target, B, lr, beta1, beta2, eps, loss_out,
+                         workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,338 @@
+// Tiled C = A * B^T on the CDNA4 matrix cores, shared by the scoring and the update kernels.
+//
+// Both operands are "K-contiguous": A is [M, K] row-major (activations), B is [N, K] row-major
+// (a dense layer's weight matrix W[out, in]), so a layer h W^T needs no transposition anywhere.
+//
+// Work-group: 256 threads = 4 wavefronts in a 2 x 2 arrangement; each wavefront owns WMB x WNB
+// blocks of 32 x 32 outputs, i.e. the work-group tile is (64*WMB) x (64*WNB).  A K-slab is 128 bytes
+// per row (64 bf16 or 32 fp32) and is kept in LDS as rows of eight 16-byte chunks; chunk c of row r
+// sits at position c ^ ((r >> 1) & 7), which makes both the 16-byte row-wise writes and the
+// 16-byte column-of-rows operand reads spread over all banks.
+//
+// Matrix-core operand convention used here: for the 32x32 instructions lane l supplies row
+// (l & 31) of its operand and the K positions selected by (l >> 5); since both operands use the
+// same K assignment any consistent assignment is valid, so each lane simply takes one 16-byte
+// chunk (8 bf16 -> one 32x32x16 instruction, 4 fp32 -> four 32x32x2 instructions).
+// The 32x32 result holds, in register r of lane l, row 8*(r/4) + 4*(l>>5) + (r&3) and column (l&31).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ab {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+
+struct bf16_t { uint16_t bits; };   // storage type of a bfloat16 value
+
+// ReLU that lets NaN through, so a non-finite statistic stays visible in the scores.
+__device__ __forceinline__ float relu_keep_nan(float v) { return v <= 0.f ? 0.f : v; }
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    f32x2 v = {lo, hi};
+    bf16x2 b = __builtin_convertvector(v, bf16x2);   // round to nearest even
+    return __builtin_bit_cast(uint32_t, b);
+}
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+
+enum { AMODE_LOAD = 0, AMODE_GEN = 1 };
+enum { EPI_STORE = 0, EPI_SCORE = 1, EPI_DRELU = 2, EPI_SPLITK = 3 };
+
+struct GemmArgs {
+    // A operand, AMODE_LOAD: A[M, K] with leading dimension lda (elements of the compute type)
+    const void *A; int64_t lda;
+    // A operand, AMODE_GEN: row r stands for (scenario s = r / C, candidate c = r % C) and
+    // A[r, k] = relu(a_term[s*ldt + k] + b_term[c*ldt + k]) rounded to the compute type
+    const float *a_term; const float *b_term; int32_t ldt; int32_t C;
+    // B operand: B[N, K], leading dimension ldb
+    const void *B; int64_t ldb;
+    int64_t M; int32_t N; int32_t K;          // K is a multiple of the K-slab; N a multiple of the tile width
+    int64_t m_tiles; int32_t n_tiles;
+    // epilogue
+    const float *bias; int32_t relu;          // EPI_STORE: out = act(acc + bias)
+    void *out; int64_t ldo; int32_t out_f32;  // EPI_STORE / EPI_DRELU: compute type or fp32 output
+    void *out_t; int64_t ldo_t;               // optional transposed copy out_t[col, row] (compute type);
+                                              // ldo_t a multiple of 4 and out_t 16-byte aligned
+    const float *w_out; float *partial;       // EPI_SCORE: partial[row*n_tiles + tile_n] = sum_col relu(acc+bias)*w_out
+    const void *mask; int64_t ldmask;         // EPI_DRELU: out = acc * (mask[row, col] > 0)
+    int32_t k_splits; int64_t split_stride;   // EPI_SPLITK: fp32 out + split*split_stride, K range split evenly
+};
+
+template <typename T> struct TileTraits;
+template <> struct TileTraits<bf16_t> { static constexpr int BK = 64, EPC = 8; };
+template <> struct TileTraits<float>  { static constexpr int BK = 32, EPC = 4; };
+
+template <typename T>
+__device__ __forceinline__ void mma_chunk(const i32x4 &a, const i32x4 &b, f32x16 &acc)
+{
+    if constexpr (sizeof(T) == 2) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                      __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+    } else {
+        f32x4 fa = __builtin_bit_cast(f32x4, a), fb = __builtin_bit_cast(f32x4, b);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.x, fb.x, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.y, fb.y, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.z, fb.z, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa.w, fb.w, acc, 0, 0, 0);
+    }
+}
+
+// relu(a + b) for one 16-byte chunk of the generated operand.
+template <typename T>
+__device__ __forceinline__ i32x4 gen_chunk(const float *pa, const float *pb)
+{
+    if constexpr (sizeof(T) == 2) {
+        f32x4 a0 = *(const f32x4 *)pa, a1 = *(const f32x4 *)(pa + 4);
+        f32x4 b0 = *(const f32x4 *)pb, b1 = *(const f32x4 *)(pb + 4);
+        i32x4 r;
+        r.x = (int)pack_bf16x2(relu_keep_nan(a0.x + b0.x), relu_keep_nan(a0.y + b0.y));
+        r.y = (int)pack_bf16x2(relu_keep_nan(a0.z + b0.z), relu_keep_nan(a0.w + b0.w));
+        r.z = (int)pack_bf16x2(relu_keep_nan(a1.x + b1.x), relu_keep_nan(a1.y + b1.y));
+        r.w = (int)pack_bf16x2(relu_keep_nan(a1.z + b1.z), relu_keep_nan(a1.w + b1.w));
+        return r;
+    } else {
+        f32x4 a0 = *(const f32x4 *)pa, b0 = *(const f32x4 *)pb;
+        f32x4 v = {relu_keep_nan(a0.x + b0.x), relu_keep_nan(a0.y + b0.y),
+                   relu_keep_nan(a0.z + b0.z), relu_keep_nan(a0.w + b0.w)};
+        return __builtin_bit_cast(i32x4, v);
+    }
+}
+
+template <typename T>
+__device__ __forceinline__ void store_elem(void *base, int64_t idx, float v, int as_f32)
+{
+    if (sizeof(T) == 4 || as_f32) ((float *)base)[idx] = v;
+    else ((uint16_t *)base)[idx] = (uint16_t)(pack_bf16x2(v, 0.f) & 0xffffu);
+}
+
+template <typename T, int WMB, int WNB, int AMODE, int EPI>
+__global__ __launch_bounds__(256) void gemm_tn_kernel(const GemmArgs g)
+{
+    constexpr int BM = 64 * WMB, BN = 64 * WNB;
+    constexpr int BK = TileTraits<T>::BK, EPC = TileTraits<T>::EPC;
+    constexpr int A_CH = BM / 32, B_CH = BN / 32;        // 16-byte chunks per thread per slab
+    constexpr int STAGE_BYTES = (BM + BN) * 128;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    // Work-group -> tile.  Consecutive work-group ids go to consecutive XCDs, so the n_tiles tiles
+    // that share one panel of A are given ids that land on the same XCD (same L2) back to back.
+    int64_t id = blockIdx.x;
+    int split = 0;
+    if constexpr (EPI == EPI_SPLITK) { split = (int)(id % g.k_splits); id /= g.k_splits; }
+    const int xcd = (int)(id & 7);
+    const int64_t local = id >> 3;
+    const int tn = (int)(local % g.n_tiles);
+    const int64_t tm = (local / g.n_tiles) * 8 + xcd;
+    if (tm >= g.m_tiles) return;
+
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wave_m = wave >> 1, wave_n = wave & 1;
+    const int64_t m0 = tm * BM;
+    const int n0 = tn * BN;
+    const int ld_row = t >> 3, ld_cc = t & 7;
+
+    int kt_begin = 0, kt_end = g.K / BK;
+    if constexpr (EPI == EPI_SPLITK) {
+        const int per = (kt_end + g.k_splits - 1) / g.k_splits;
+        kt_begin = split * per;
+        kt_end = min(kt_end, kt_begin + per);
+    }
+
+    // per-thread source offsets (elements) of its chunks within the A panel / B panel
+    int32_t a_off[A_CH], a2_off[A_CH], b_off[B_CH];
+    const T *Ab = nullptr;
+    if constexpr (AMODE == AMODE_LOAD) {
+        Ab = (const T *)g.A + m0 * g.lda;
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) {
+            int64_t r = min((int64_t)(ld_row + i * 32), g.M - 1 - m0);
+            a_off[i] = (int32_t)(r * g.lda) + ld_cc * EPC;
+            a2_off[i] = 0;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) {
+            int64_t r = min(m0 + ld_row + i * 32, g.M - 1);
+            int64_t s = r / g.C;
+            int32_t c = (int32_t)(r - s * g.C);
+            a_off[i] = (int32_t)s * g.ldt + ld_cc * EPC;
+            a2_off[i] = c * g.ldt + ld_cc * EPC;
+        }
+    }
+    const T *Bb = (const T *)g.B + (int64_t)n0 * g.ldb;
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) b_off[i] = (int32_t)((ld_row + i * 32) * g.ldb) + ld_cc * EPC;
+
+    // LDS positions
+    int32_t st_off[(A_CH > B_CH ? A_CH : B_CH)];
+#pragma unroll
+    for (int i = 0; i < (A_CH > B_CH ? A_CH : B_CH); ++i) {
+        const int r = ld_row + i * 32;
+        st_off[i] = r * 128 + ((ld_cc ^ ((r >> 1) & 7)) << 4);
+    }
+    const int sw = ((lane & 31) >> 1) & 7, half = lane >> 5;
+    int32_t rd_off[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) rd_off[q] = (lane & 31) * 128 + ((((q << 1) | half) ^ sw) << 4);
+    const int a_rd_base = wave_m * (WMB * 32) * 128;
+    const int b_rd_base = BM * 128 + wave_n * (WNB * 32) * 128;
+
+    f32x16 acc[WMB][WNB];
+#pragma unroll
+    for (int i = 0; i < WMB; ++i)
+#pragma unroll
+        for (int j = 0; j < WNB; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    i32x4 ra[A_CH], rb[B_CH];
+
+    auto load_slab = [&](int kt) {
+        const int k0 = kt * BK;
+        if constexpr (AMODE == AMODE_LOAD) {
+#pragma unroll
+            for (int i = 0; i < A_CH; ++i) ra[i] = *(const i32x4 *)(Ab + a_off[i] + k0);
+        } else {
+#pragma unroll
+            for (int i = 0; i < A_CH; ++i)
+                ra[i] = gen_chunk<T>(g.a_term + a_off[i] + k0, g.b_term + a2_off[i] + k0);
+        }
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i) rb[i] = *(const i32x4 *)(Bb + b_off[i] + k0);
+    };
+    auto store_slab = [&](int stage) {
+        unsigned char *sa = smem + stage * STAGE_BYTES, *sb = sa + BM * 128;
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) *(i32x4 *)(sa + st_off[i]) = ra[i];
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i) *(i32x4 *)(sb + st_off[i]) = rb[i];
+    };
+    auto compute_slab = [&](int stage) {
+        const unsigned char *sa = smem + stage * STAGE_BYTES + a_rd_base;
+        const unsigned char *sb = smem + stage * STAGE_BYTES + b_rd_base;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            i32x4 fa[WMB], fb[WNB];
+#pragma unroll
+            for (int i = 0; i < WMB; ++i) fa[i] = *(const i32x4 *)(sa + i * 4096 + rd_off[q]);
+#pragma unroll
+            for (int j = 0; j < WNB; ++j) fb[j] = *(const i32x4 *)(sb + j * 4096 + rd_off[q]);
+#pragma unroll
+            for (int i = 0; i < WMB; ++i)
+#pragma unroll
+                for (int j = 0; j < WNB; ++j) mma_chunk<T>(fa[i], fb[j], acc[i][j]);
+        }
+    };
+
+    if (kt_begin < kt_end) {
+        load_slab(kt_begin);
+        store_slab(0);
+        __syncthreads();
+        for (int kt = kt_begin; kt < kt_end; ++kt) {
+            const int cur = (kt - kt_begin) & 1;
+            if (kt + 1 < kt_end) load_slab(kt + 1);
+            compute_slab(cur);
+            if (kt + 1 < kt_end) store_slab(cur ^ 1);
+            __syncthreads();
+        }
+    }
+
+    // ---------------------------------------------------------------- epilogues
+    const int row_l0 = wave_m * (WMB * 32) + half * 4;        // + i*32 + (r>>2)*8 + (r&3)
+    const int col_l0 = wave_n * (WNB * 32) + (lane & 31);     // + j*32
+    if constexpr (EPI == EPI_STORE || EPI == EPI_DRELU || EPI == EPI_SPLITK) {
+        float *out_split = nullptr;
+        if constexpr (EPI == EPI_SPLITK) out_split = (float *)g.out + (int64_t)split * g.split_stride;
+#pragma unroll
+        for (int j = 0; j < WNB; ++j) {
+            const int col = n0 + col_l0 + j * 32;
+            float bv = 0.f;
+            if constexpr (EPI == EPI_STORE) bv = g.bias ? g.bias[col] : 0.f;
+#pragma unroll
+            for (int i = 0; i < WMB; ++i)
+#pragma unroll
+                for (int rg = 0; rg < 4; ++rg) {
+                    // registers 4*rg .. 4*rg+3 of this block are four consecutive rows of one column
+                    const int64_t row0 = m0 + row_l0 + i * 32 + rg * 8;
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        v[e] = acc[i][j][rg * 4 + e];
+                        const int64_t row = row0 + e;
+                        if constexpr (EPI == EPI_STORE) {
+                            v[e] += bv;
+                            if (g.relu) v[e] = relu_keep_nan(v[e]);
+                        } else if constexpr (EPI == EPI_DRELU) {
+                            if (row < g.M) {
+                                float mk;
+                                if constexpr (sizeof(T) == 2)
+                                    mk = bf16_bits_to_f32(((const uint16_t *)g.mask)[row * g.ldmask + col]);
+                                else
+                                    mk = ((const float *)g.mask)[row * g.ldmask + col];
+                                v[e] = mk > 0.f ? v[e] : 0.f;
+                            }
+                        }
+                        if (row < g.M) {
+                            if constexpr (EPI == EPI_SPLITK) out_split[row * g.ldo + col] = v[e];
+                            else store_elem<T>(g.out, row * g.ldo + col, v[e], g.out_f32);
+                        }
+                    }
+                    if constexpr (EPI != EPI_SPLITK) {
+                        if (g.out_t) {
+                            const int64_t o = (int64_t)col * g.ldo_t + row0;   // four rows are contiguous here
+                            if (row0 + 3 < g.M) {
+                                if constexpr (sizeof(T) == 2) {
+                                    uint2 pk = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+                                    *(uint2 *)((uint16_t *)g.out_t + o) = pk;
+                                } else {
+                                    *(f32x4 *)((float *)g.out_t + o) = f32x4{v[0], v[1], v[2], v[3]};
+                                }
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e)
+                                    if (row0 + e < g.M) store_elem<T>(g.out_t, o + e, v[e], 0);
+                            }
+                        }
+                    }
+                }
+        }
+    } else {   // EPI_SCORE: per-row dot of relu(acc + bias) with w_out over this tile's columns
+        float rs[WMB][16];
+#pragma unroll
+        for (int i = 0; i < WMB; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) rs[i][r] = 0.f;
+#pragma unroll
+        for (int j = 0; j < WNB; ++j) {
+            const int col = n0 + col_l0 + j * 32;
+            const float bv = g.bias[col], wv = g.w_out[col];
+#pragma unroll
+            for (int i = 0; i < WMB; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) rs[i][r] += relu_keep_nan(acc[i][j][r] + bv) * wv;
+        }
+        float *red = (float *)smem;    // [2][BM]; the K loop ended with a barrier, LDS is free
+#pragma unroll
+        for (int i = 0; i < WMB; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float v = rs[i][r];
+                v += __shfl_xor(v, 1, 64);
+                v += __shfl_xor(v, 2, 64);
+                v += __shfl_xor(v, 4, 64);
+                v += __shfl_xor(v, 8, 64);
+                v += __shfl_xor(v, 16, 64);
+                if ((lane & 31) == 0) red[wave_n * BM + row_l0 + i * 32 + (r >> 2) * 8 + (r & 3)] = v;
+            }
+        __syncthreads();
+        if (t < BM && m0 + t < g.M)
+            g.partial[(m0 + t) * g.n_tiles + tn] = red[t] + red[BM + t];
+    }
+}
+
+}  // namespace ab

@@ -1,0 +1,45 @@
+// Internal declarations shared by the translation units of the library (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/autobyte.h"
+#include "gemm_core.hpp"
+
+namespace ab {
+
+// Launch tracing (see ab_set_trace): brackets one launch with the two callback phases.
+extern ab_trace_fn g_trace_fn;
+extern void *g_trace_user;
+struct TraceScope {
+    const char *name; double work; int bytes; hipStream_t st;
+    TraceScope(const char *n, double w, int is_bytes, hipStream_t s) : name(n), work(w), bytes(is_bytes), st(s)
+    { if (g_trace_fn) g_trace_fn(name, 0, work, bytes, (void *)st, g_trace_user); }
+    ~TraceScope() { if (g_trace_fn) g_trace_fn(name, 1, work, bytes, (void *)st, g_trace_user); }
+};
+
+enum { TILE_SMALL = 0, TILE_MID = 1, TILE_BIG = 2 };   // 64x64, 128x128, 256x256 work-group tiles
+
+static inline int tile_edge(int tile) { return 64 << tile; }
+static inline int slab_k(int dtype) { return dtype == AB_BF16 ? 64 : 32; }
+static inline size_t elem_size(int dtype) { return dtype == AB_BF16 ? 2 : 4; }
+
+// Fills m_tiles / n_tiles from M, N and the tile, then launches.  N must be a multiple of the tile edge.
+hipError_t launch_gemm(int dtype, int tile, int amode, int epi, GemmArgs g, hipStream_t st);
+
+hipError_t launch_encode_stats(int dtype, const ab_model_desc *d, const float *dyn, const float *scal,
+                               void *xs, int64_t S, int ld, int col0, int with_stats, hipStream_t st);
+hipError_t launch_encode_rows(int dtype, const ab_model_desc *d, const float *x_raw, void *x, void *x_t,
+                              int64_t B, int64_t ld_t, int F, int ld, hipStream_t st);
+hipError_t launch_prep_layer1(int dtype, const ab_model_desc *d, const void *W1, const float *b1, int F, int Fs,
+                              int H1, int ld, void *w1s, const ab_grid *grid, float *b_term,
+                              const void *Wout, int H_last, float *w_out_f, hipStream_t st);
+hipError_t launch_finish_select(const float *partial, int nt, int64_t row_stride, const float *b_out,
+                                float *scores, int64_t score_stride, int32_t *best_idx, float *best_score,
+                                int64_t S, int C, hipStream_t st);
+hipError_t launch_score_single_hidden(const float *a_term, const float *b_term, const float *w_out_f,
+                                      float *partial, int64_t rows, int C, int H, hipStream_t st);
+hipError_t launch_tensor_encoder(int dtype, const ab_model_desc *d, const float *dyn, const void *Wa,
+                                 const float *ba, const void *Wb, const float *bb, void *xs, int ld,
+                                 int64_t S, hipStream_t st);
+
+}  // namespace ab

@@ -1,0 +1,426 @@
+// Streaming kernels around the matrix-core GEMMs of the scoring path: feature transform, layer-1
+// candidate term, weight packing, the shared per-tensor encoder, score assembly and argmax.
+#include "internal.hpp"
+
+namespace ab {
+
+__device__ __forceinline__ float phi(float x, const ab_enc &e)
+{
+    const float gx = (e.kind == AB_ENC_LOG) ? logf(x) : x;
+    return (gx - e.shift) * e.scale;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Feature transform (Section 3.3 "Meta network optimizer": runtime statistics are turned into the
+// network's input vector).  One thread produces two adjacent columns of one scenario's row.
+//   xs[s, col0 + j]            j in [0, n_stat)            <- phi_stat(dyn[s, j])      (flat model only)
+//   xs[s, col0 + n_stat + j]   j in [0, n_scal)            <- phi_scal(scal[s, j])
+//   xs[s, ...up to ld)                                      <- 0   (K padding for the GEMM)
+// ------------------------------------------------------------------------------------------------
+struct EncodeArgs {
+    const float *dyn; const float *scal;
+    void *xs; int64_t S; int32_t ld;
+    int32_t col0, n_stat, n_stats_per_layer, n_scal;
+    ab_enc enc_stat[AB_MAX_STATS];
+    ab_enc enc_scal[AB_MAX_SCALARS];
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void encode_stats_kernel(const EncodeArgs a)
+{
+    const int pairs = (a.ld - a.col0) >> 1;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t s = gid / pairs;
+    if (s >= a.S) return;
+    const int j0 = (int)(gid - s * pairs) * 2;
+    float v[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int j = j0 + e;
+        float x = 0.f;
+        if (j < a.n_stat) {
+            x = phi(a.dyn[s * a.n_stat + j], a.enc_stat[j % a.n_stats_per_layer]);
+        } else if (j < a.n_stat + a.n_scal) {
+            const int q = j - a.n_stat;
+            x = phi(a.scal[s * a.n_scal + q], a.enc_scal[q]);
+        }
+        v[e] = x;
+    }
+    const int64_t o = s * a.ld + a.col0 + j0;
+    if constexpr (sizeof(T) == 2) ((uint32_t *)a.xs)[o >> 1] = pack_bf16x2(v[0], v[1]);
+    else ((f32x2 *)a.xs)[o >> 1] = f32x2{v[0], v[1]};
+}
+
+// Raw update rows x_raw[B, F] (statistics, scalars, partition, credit) -> transformed x[B, ld]
+// (zero in the padding columns) and, optionally, its transpose x_t[ld, ld_t].
+struct EncodeRowsArgs {
+    const float *x_raw; void *x; void *x_t; int64_t B, ld_t; int32_t F, ld;
+    int32_t n_stat, n_stats_per_layer, n_scal;
+    ab_enc enc_stat[AB_MAX_STATS];
+    ab_enc enc_scal[AB_MAX_SCALARS];
+    ab_enc enc_part, enc_cred;
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void encode_rows_kernel(const EncodeRowsArgs a)
+{
+    const int pairs = a.ld >> 1;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t r = gid / pairs;
+    if (r >= a.B) return;
+    const int j0 = (int)(gid - r * pairs) * 2;
+    float v[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int j = j0 + e;
+        float x = 0.f;
+        if (j < a.F) {
+            const float raw = a.x_raw[r * a.F + j];
+            if (j < a.n_stat) x = phi(raw, a.enc_stat[j % a.n_stats_per_layer]);
+            else if (j < a.n_stat + a.n_scal) x = phi(raw, a.enc_scal[j - a.n_stat]);
+            else if (j == a.F - 2) x = phi(raw, a.enc_part);
+            else x = phi(raw, a.enc_cred);
+        }
+        v[e] = x;
+    }
+    const int64_t o = r * a.ld + j0;
+    if constexpr (sizeof(T) == 2) {
+        ((uint32_t *)a.x)[o >> 1] = pack_bf16x2(v[0], v[1]);
+        if (a.x_t) {
+            uint16_t *xt = (uint16_t *)a.x_t;
+            const uint32_t p = pack_bf16x2(v[0], v[1]);
+            xt[(int64_t)j0 * a.ld_t + r] = (uint16_t)(p & 0xffffu);
+            xt[(int64_t)(j0 + 1) * a.ld_t + r] = (uint16_t)(p >> 16);
+        }
+    } else {
+        ((f32x2 *)a.x)[o >> 1] = f32x2{v[0], v[1]};
+        if (a.x_t) {
+            float *xt = (float *)a.x_t;
+            xt[(int64_t)j0 * a.ld_t + r] = v[0];
+            xt[(int64_t)(j0 + 1) * a.ld_t + r] = v[1];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Layer-1 preparation.  The first dense layer acts on [statistics | S_p | S_c]; its statistics
+// columns are shared by all candidates of a scenario and its two configuration columns by all
+// scenarios, so W1 x = A[s] + B[c].  This kernel packs the statistics columns of W1 into a
+// K-padded matrix for the A[s] GEMM, builds B[c] (bias included) and widens the output weights.
+// ------------------------------------------------------------------------------------------------
+struct PrepArgs {
+    const void *W1; int32_t F, Fs, H1, ld;      // W1[H1, F]; packed copy w1s[H1, ld]
+    void *w1s;
+    const float *b1;
+    const float *part; const float *cred; int32_t P, Q;
+    ab_enc enc_part, enc_cred;
+    float *b_term;                               // [P*Q, H1]
+    const void *Wout; int32_t H_last; float *w_out_f;
+};
+
+template <typename T>
+__device__ __forceinline__ float load_as_f32(const void *p, int64_t i)
+{
+    if constexpr (sizeof(T) == 2) return bf16_bits_to_f32(((const uint16_t *)p)[i]);
+    else return ((const float *)p)[i];
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void prep_layer1_kernel(const PrepArgs a)
+{
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t n_pack = (int64_t)a.H1 * a.ld;
+    const int64_t n_bt = (int64_t)a.P * a.Q * a.H1;
+    if (gid < n_pack) {
+        const int h = (int)(gid / a.ld), k = (int)(gid - (int64_t)h * a.ld);
+        if constexpr (sizeof(T) == 2) {
+            uint16_t v = (k < a.Fs) ? ((const uint16_t *)a.W1)[(int64_t)h * a.F + k] : (uint16_t)0;
+            ((uint16_t *)a.w1s)[gid] = v;
+        } else {
+            ((float *)a.w1s)[gid] = (k < a.Fs) ? ((const float *)a.W1)[(int64_t)h * a.F + k] : 0.f;
+        }
+    } else if (gid < n_pack + n_bt) {
+        const int64_t e = gid - n_pack;
+        const int c = (int)(e / a.H1), h = (int)(e - (int64_t)c * a.H1);
+        const float xp = phi(a.part[c / a.Q], a.enc_part), xc = phi(a.cred[c % a.Q], a.enc_cred);
+        const float wp = load_as_f32<T>(a.W1, (int64_t)h * a.F + a.Fs);
+        const float wc = load_as_f32<T>(a.W1, (int64_t)h * a.F + a.Fs + 1);
+        a.b_term[e] = a.b1[h] + wp * xp + wc * xc;
+    } else if (gid < n_pack + n_bt + a.H_last) {
+        const int h = (int)(gid - n_pack - n_bt);
+        a.w_out_f[h] = load_as_f32<T>(a.Wout, h);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Argmax helpers: (value, index) pairs, larger value wins, lower index wins ties, NaN never wins.
+// "Nothing yet" is (-inf, INT_MAX).
+// ------------------------------------------------------------------------------------------------
+#define AB_NONE 0x7fffffff
+__device__ __forceinline__ void amax_take(float &bv, int &bi, float v, int i)
+{
+    if (!(v != v) && (v > bv || (v == bv && i < bi))) { bv = v; bi = i; }
+}
+__device__ __forceinline__ void amax_wave(float &bv, int &bi)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+        const float ov = __shfl_xor(bv, m, 64);
+        const int oi = __shfl_xor(bi, m, 64);
+        amax_take(bv, bi, ov, oi);
+    }
+}
+
+// One work-group per scenario.  score[c] = b_out + sum_t partial[(row0 + c)*nt + t]  (nt = 1 and
+// b_out = 0 turn this into a plain argmax over stored scores with a row stride).
+struct FinishArgs {
+    const float *partial; int32_t nt; int64_t row_stride;   // elements between scenarios in `partial` (per nt)
+    const float *b_out;                                      // one fp32 or NULL
+    float *scores; int64_t score_stride;                     // NULL: do not store
+    int32_t *best_idx; float *best_score;                    // may be NULL
+    int32_t C;
+};
+
+__global__ __launch_bounds__(256) void finish_select_kernel(const FinishArgs a)
+{
+    const int64_t s = blockIdx.x;
+    const float *p = a.partial + s * a.row_stride * a.nt;
+    const float b = a.b_out ? a.b_out[0] : 0.f;
+    float bv = -INFINITY;
+    int bi = AB_NONE;
+    for (int c = threadIdx.x; c < a.C; c += 256) {
+        float v = p[(int64_t)c * a.nt];
+        for (int t = 1; t < a.nt; ++t) v += p[(int64_t)c * a.nt + t];
+        v += b;
+        if (a.scores) a.scores[s * a.score_stride + c] = v;
+        amax_take(bv, bi, v, c);
+    }
+    if (!a.best_idx) return;
+    amax_wave(bv, bi);
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { sv[wave] = bv; si[wave] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w) amax_take(bv, bi, sv[w], si[w]);
+        a.best_idx[s] = (bi == AB_NONE) ? -1 : bi;
+        if (a.best_score) a.best_score[s] = (bi == AB_NONE) ? __uint_as_float(0x7fc00000u) : bv;
+    }
+}
+
+// Scorer with a single hidden layer: score = w_out . relu(A[s] + B[c]) + b_out, one wavefront per
+// (scenario, candidate) row, written into the same partial buffer layout (nt = 1, no bias yet).
+struct ScoreD1Args { const float *a_term, *b_term, *w_out_f; float *partial; int64_t rows; int32_t C, H; };
+__global__ __launch_bounds__(256) void score_single_hidden_kernel(const ScoreD1Args a)
+{
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= a.rows) return;
+    const int lane = threadIdx.x & 63;
+    const int64_t s = row / a.C;
+    const int c = (int)(row - s * a.C);
+    float acc = 0.f;
+    for (int h = lane; h < a.H; h += 64)
+        acc += relu_keep_nan(a.a_term[s * a.H + h] + a.b_term[(int64_t)c * a.H + h]) * a.w_out_f[h];
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+    if (lane == 0) a.partial[row] = acc;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Shared per-tensor encoder (Section 3.1 "Meta network architecture": the layer-wise statistics are
+// embedded into a fixed-dimension feature space so that models with different layer counts can be
+// handled).  One work-group per scenario:
+//   e[l] = relu(W_b relu(W_a phi(stat[l]) + b_a) + b_b)   (K -> 128 on the vector ALUs, 128 -> 128 on
+//   the matrix cores), pooled[s] = mean_l e[l], written as the first 128 columns of the scenario row.
+// Wave w owns output columns [32w, 32w+32) and keeps its slice of W_b in registers; the 32-row
+// blocks of the first layer's output go through LDS (rows of 256 bytes; 16-byte chunk c of row r
+// sits at position c ^ (r & 15)).  Both layers' products use bf16 operands with fp32 accumulation.
+// ------------------------------------------------------------------------------------------------
+struct TensorEncArgs {
+    const float *dyn; int32_t L, K;
+    const void *Wa; const float *ba;     // [128, K]
+    const void *Wb; const float *bb;     // [128, 128]
+    void *xs; int32_t ld;                // scenario rows; columns [0,128) written here
+    ab_enc enc_stat[AB_MAX_STATS];
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void tensor_encoder_kernel(const TensorEncArgs a)
+{
+    constexpr int H = 128;
+    __shared__ __attribute__((aligned(16))) unsigned char hbuf[32 * 256];   // 32 rows x 128 bf16
+    __shared__ float xin[32 * AB_MAX_STATS];
+    __shared__ float wa_s[H * AB_MAX_STATS];
+    __shared__ float ba_s[H];
+    const int64_t s = blockIdx.x;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, half = lane >> 5;
+    const float *dyn = a.dyn + s * (int64_t)a.L * a.K;
+
+    for (int i = t; i < H * a.K; i += 256) wa_s[i] = load_as_f32<T>(a.Wa, i);
+    if (t < H) ba_s[t] = a.ba[t];
+
+    // this wave's slice of W_b: column n = 32*wave + (lane & 31), 8 chunks of 8 consecutive k
+    // (chunk q covers k = 16*q + 8*half ... +8), as bf16 pairs
+    i32x4 wb[8];
+    {
+        const int n = wave * 32 + (lane & 31);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int k0 = q * 16 + half * 8;
+            if constexpr (sizeof(T) == 2) {
+                wb[q] = *(const i32x4 *)((const uint16_t *)a.Wb + (int64_t)n * H + k0);
+            } else {
+                const float *w = (const float *)a.Wb + (int64_t)n * H + k0;
+                wb[q].x = (int)pack_bf16x2(w[0], w[1]); wb[q].y = (int)pack_bf16x2(w[2], w[3]);
+                wb[q].z = (int)pack_bf16x2(w[4], w[5]); wb[q].w = (int)pack_bf16x2(w[6], w[7]);
+            }
+        }
+    }
+    const float bb = a.bb[wave * 32 + (lane & 31)];
+    float colsum = 0.f;
+    const int sw = lane & 15;
+
+    for (int l0 = 0; l0 < a.L; l0 += 32) {
+        __syncthreads();                       // previous block's readers are done; wa_s is ready
+        for (int i = t; i < 32 * a.K; i += 256) {
+            const int l = l0 + i / a.K, k = i % a.K;
+            xin[i] = (l < a.L) ? phi(dyn[(int64_t)l * a.K + k], a.enc_stat[k]) : 0.f;
+        }
+        __syncthreads();
+        // first layer: thread -> row r = t >> 3, 16 consecutive outputs starting at (t & 7) * 16
+        {
+            const int r = t >> 3, o0 = (t & 7) * 16;
+            float hv[16];
+#pragma unroll
+            for (int o = 0; o < 16; ++o) {
+                float acc = ba_s[o0 + o];
+                for (int k = 0; k < a.K; ++k) acc += wa_s[(o0 + o) * a.K + k] * xin[r * a.K + k];
+                acc = relu_keep_nan(acc);
+                hv[o] = acc;
+            }
+#pragma unroll
+            for (int c2 = 0; c2 < 2; ++c2) {
+                i32x4 v;
+                v.x = (int)pack_bf16x2(hv[c2 * 8 + 0], hv[c2 * 8 + 1]);
+                v.y = (int)pack_bf16x2(hv[c2 * 8 + 2], hv[c2 * 8 + 3]);
+                v.z = (int)pack_bf16x2(hv[c2 * 8 + 4], hv[c2 * 8 + 5]);
+                v.w = (int)pack_bf16x2(hv[c2 * 8 + 6], hv[c2 * 8 + 7]);
+                const int chunk = (t & 7) * 2 + c2;                        // 16 chunks per 256-byte row
+                *(i32x4 *)(hbuf + r * 256 + ((chunk ^ (r & 15)) << 4)) = v;
+            }
+        }
+        __syncthreads();
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int chunk = q * 2 + half;
+            const i32x4 fa = *(const i32x4 *)(hbuf + (lane & 31) * 256 + ((chunk ^ sw) << 4));
+            // operand roles: rows = tensors (from LDS), columns = this wave's outputs (registers)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa),
+                                                          __builtin_bit_cast(bf16x8, wb[q]), acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int l = l0 + (r >> 2) * 8 + half * 4 + (r & 3);
+            if (l < a.L) colsum += relu_keep_nan(acc[r] + bb);
+        }
+    }
+    colsum += __shfl_xor(colsum, 32, 64);
+    if (half == 0) {
+        const float pooled = colsum / (float)a.L;
+        const int64_t o = s * a.ld + wave * 32 + lane;
+        if constexpr (sizeof(T) == 2) ((uint16_t *)a.xs)[o] = (uint16_t)(pack_bf16x2(pooled, 0.f) & 0xffffu);
+        else ((float *)a.xs)[o] = pooled;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// host-side launch wrappers
+// ------------------------------------------------------------------------------------------------
+static inline unsigned blocks_for(int64_t n) { return (unsigned)((n + 255) / 256); }
+
+hipError_t launch_encode_stats(int dtype, const ab_model_desc *d, const float *dyn, const float *scal,
+                               void *xs, int64_t S, int ld, int col0, int with_stats, hipStream_t st)
+{
+    if (S == 0) return hipSuccess;
+    EncodeArgs a;
+    a.dyn = dyn; a.scal = scal; a.xs = xs; a.S = S; a.ld = ld; a.col0 = col0;
+    a.n_stat = with_stats ? d->n_layers * d->n_stats : 0;
+    a.n_stats_per_layer = d->n_stats; a.n_scal = d->n_scalars;
+    for (int i = 0; i < AB_MAX_STATS; ++i) a.enc_stat[i] = d->enc_stat[i];
+    for (int i = 0; i < AB_MAX_SCALARS; ++i) a.enc_scal[i] = d->enc_scalar[i];
+    const int64_t n = S * ((ld - col0) / 2);
+    if (dtype == AB_BF16) encode_stats_kernel<bf16_t><<<blocks_for(n), 256, 0, st>>>(a);
+    else encode_stats_kernel<float><<<blocks_for(n), 256, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_encode_rows(int dtype, const ab_model_desc *d, const float *x_raw, void *x, void *x_t,
+                              int64_t B, int64_t ld_t, int F, int ld, hipStream_t st)
+{
+    EncodeRowsArgs a;
+    a.x_raw = x_raw; a.x = x; a.x_t = x_t; a.B = B; a.ld_t = ld_t; a.F = F; a.ld = ld;
+    a.n_stat = d->n_layers * d->n_stats; a.n_stats_per_layer = d->n_stats; a.n_scal = d->n_scalars;
+    for (int i = 0; i < AB_MAX_STATS; ++i) a.enc_stat[i] = d->enc_stat[i];
+    for (int i = 0; i < AB_MAX_SCALARS; ++i) a.enc_scal[i] = d->enc_scalar[i];
+    a.enc_part = d->enc_partition; a.enc_cred = d->enc_credit;
+    const int64_t n = B * (ld / 2);
+    if (dtype == AB_BF16) encode_rows_kernel<bf16_t><<<blocks_for(n), 256, 0, st>>>(a);
+    else encode_rows_kernel<float><<<blocks_for(n), 256, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_prep_layer1(int dtype, const ab_model_desc *d, const void *W1, const float *b1, int F, int Fs,
+                              int H1, int ld, void *w1s, const ab_grid *grid, float *b_term,
+                              const void *Wout, int H_last, float *w_out_f, hipStream_t st)
+{
+    PrepArgs a;
+    a.W1 = W1; a.F = F; a.Fs = Fs; a.H1 = H1; a.ld = ld; a.w1s = w1s; a.b1 = b1;
+    a.part = grid->partition_bytes; a.cred = grid->credit_mult; a.P = grid->P; a.Q = grid->Q;
+    a.enc_part = d->enc_partition; a.enc_cred = d->enc_credit; a.b_term = b_term;
+    a.Wout = Wout; a.H_last = H_last; a.w_out_f = w_out_f;
+    const int64_t n = (int64_t)H1 * ld + (int64_t)grid->P * grid->Q * H1 + H_last;
+    if (dtype == AB_BF16) prep_layer1_kernel<bf16_t><<<blocks_for(n), 256, 0, st>>>(a);
+    else prep_layer1_kernel<float><<<blocks_for(n), 256, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_finish_select(const float *partial, int nt, int64_t row_stride, const float *b_out,
+                                float *scores, int64_t score_stride, int32_t *best_idx, float *best_score,
+                                int64_t S, int C, hipStream_t st)
+{
+    if (S == 0) return hipSuccess;
+    FinishArgs a;
+    a.partial = partial; a.nt = nt; a.row_stride = row_stride; a.b_out = b_out; a.scores = scores;
+    a.score_stride = score_stride; a.best_idx = best_idx; a.best_score = best_score; a.C = C;
+    finish_select_kernel<<<(unsigned)S, 256, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_score_single_hidden(const float *a_term, const float *b_term, const float *w_out_f,
+                                      float *partial, int64_t rows, int C, int H, hipStream_t st)
+{
+    if (rows == 0) return hipSuccess;
+    ScoreD1Args a{a_term, b_term, w_out_f, partial, rows, C, H};
+    score_single_hidden_kernel<<<(unsigned)((rows + 3) / 4), 256, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_tensor_encoder(int dtype, const ab_model_desc *d, const float *dyn, const void *Wa,
+                                 const float *ba, const void *Wb, const float *bb, void *xs, int ld,
+                                 int64_t S, hipStream_t st)
+{
+    if (S == 0) return hipSuccess;
+    TensorEncArgs a;
+    a.dyn = dyn; a.L = d->n_layers; a.K = d->n_stats; a.Wa = Wa; a.ba = ba; a.Wb = Wb; a.bb = bb;
+    a.xs = xs; a.ld = ld;
+    for (int i = 0; i < AB_MAX_STATS; ++i) a.enc_stat[i] = d->enc_stat[i];
+    if (dtype == AB_BF16) tensor_encoder_kernel<bf16_t><<<(unsigned)S, 256, 0, st>>>(a);
+    else tensor_encoder_kernel<float><<<(unsigned)S, 256, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+}  // namespace ab

@@ -1,0 +1,440 @@
+// Online adaptation step (Section 3.2 "Offline training online adapting"; loss of Eq. 2 as mean
+// squared error): forward with saved activations, exact back-propagation, Adam.
+//
+// Every matrix product is brought to the K-contiguous form of gemm_core.hpp by keeping transposed
+// copies next to the row-major ones (written by the producing kernel's epilogue):
+//   forward   h_k      = relu(h_{k-1} W_k^T + b_k)          A = h_{k-1} [B, in],   B-op = W_k [out, in]
+//   dW_k      = d_k^T h_{k-1}                               A = d_k^T [out, B],    B-op = h_{k-1}^T [in, B]   (split over B)
+//   d_{k-1}   = (d_k W_k) * [h_{k-1} > 0]                   A = d_k [B, out],      B-op = W_k^T [in, out]
+// The batch dimension is padded to a multiple of 64 in the transposed buffers (zero columns).
+#include "internal.hpp"
+#include <string.h>
+
+namespace ab {
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline int round_up(int x, int a) { return (x + a - 1) / a * a; }
+
+#define AB_HIP(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return AB_ERR_DEVICE; } while (0)
+
+struct UpdatePlan {
+    int dtype, F, Kp, D;
+    int H[AB_MAX_HIDDEN];
+    int64_t B, Bp;
+    int in_w[AB_MAX_HIDDEN + 1];        // padded input width of layer k (Kp for k = 0)
+    int splits[AB_MAX_HIDDEN];
+    size_t off_scal, off_x, off_xt, off_w1p, off_yhat, off_dout, off_gwout, off_gbout;
+    size_t off_wt[AB_MAX_HIDDEN], off_h[AB_MAX_HIDDEN], off_ht[AB_MAX_HIDDEN];
+    size_t off_d[AB_MAX_HIDDEN], off_dt[AB_MAX_HIDDEN], off_gw[AB_MAX_HIDDEN], off_gb[AB_MAX_HIDDEN];
+    size_t total;
+};
+
+static int update_tile(int64_t M, int N)
+{
+    if (N % 128 == 0 && ((M + 127) / 128) * (N / 128) >= 256) return TILE_MID;
+    return TILE_SMALL;
+}
+
+static void plan_update(const ab_model_desc *d, int64_t B, UpdatePlan *p)
+{
+    memset(p, 0, sizeof(*p));
+    p->dtype = d->compute_dtype;
+    p->F = d->n_layers * d->n_stats + d->n_scalars + 2;
+    p->Kp = round_up(p->F, 64);
+    p->D = d->n_hidden;
+    p->B = B;
+    p->Bp = (B + 63) / 64 * 64;
+    const size_t es = elem_size(p->dtype);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    p->off_scal = take(64);
+    p->off_x = take((size_t)B * p->Kp * es);
+    p->off_xt = take((size_t)p->Kp * p->Bp * es);
+    p->off_yhat = take((size_t)B * 4);
+    p->off_dout = take((size_t)p->Bp * 4);
+    for (int k = 0; k < p->D; ++k) {
+        p->H[k] = d->hidden[k];
+        p->in_w[k] = (k == 0) ? p->Kp : d->hidden[k - 1];
+        const int tiles = (p->H[k] / 64) * (p->in_w[k] / 64);
+        const int slabs = (int)(p->Bp / slab_k(p->dtype));
+        int s = 512 / tiles;
+        if (s > 8) s = 8;
+        if (s > slabs) s = slabs;
+        if (s < 1) s = 1;
+        p->splits[k] = s;
+        p->off_wt[k] = take((size_t)p->H[k] * p->in_w[k] * es);     // k = 0: padded copy of W_1; else W_k^T
+        p->off_h[k] = take((size_t)B * p->H[k] * es);
+        p->off_ht[k] = take((size_t)p->H[k] * p->Bp * es);
+        p->off_d[k] = take((size_t)B * p->H[k] * es);
+        p->off_dt[k] = take((size_t)p->H[k] * p->Bp * es);
+        p->off_gw[k] = take((size_t)s * p->H[k] * p->in_w[k] * 4);
+        p->off_gb[k] = take((size_t)p->H[k] * 4);
+    }
+    p->off_gwout = take((size_t)p->H[p->D - 1] * 4);
+    p->off_gbout = take(64);
+    p->total = off;
+}
+
+size_t update_workspace_bytes(const ab_model_desc *d, int64_t B)
+{
+    if (d->tensor_encoder || d->n_hidden < 1) return 0;
+    UpdatePlan p;
+    plan_update(d, B, &p);
+    return p.total;
+}
+
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ float ld_f32(const void *p, int64_t i)
+{
+    if constexpr (sizeof(T) == 2) return bf16_bits_to_f32(((const uint16_t *)p)[i]);
+    else return ((const float *)p)[i];
+}
+template <typename T>
+__device__ __forceinline__ void st_T(void *p, int64_t i, float v)
+{
+    if constexpr (sizeof(T) == 2) ((uint16_t *)p)[i] = (uint16_t)(pack_bf16x2(v, 0.f) & 0xffffu);
+    else ((float *)p)[i] = v;
+}
+
+// step counter and Adam bias corrections 1 - beta^t
+__global__ void update_begin_kernel(int64_t *step, float *scal, float beta1, float beta2)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        const int64_t t = *step + 1;
+        *step = t;
+        scal[0] = (float)(1.0 - pow((double)beta1, (double)t));
+        scal[1] = (float)(1.0 - pow((double)beta2, (double)t));
+    }
+}
+
+// Per call: padded copy of W_1, transposes of the other hidden weights, zero padding columns of
+// the transposed batch buffers.
+struct UpdPrepArgs {
+    int n_jobs;
+    struct Job { const void *src; void *dst; int rows, cols, ld_src, ld_dst, kind; int64_t start; } job[2 + 3 * AB_MAX_HIDDEN];
+    int64_t total;
+};
+enum { JOB_PAD_COPY = 0, JOB_TRANSPOSE = 1, JOB_ZERO_COLS = 2 };
+
+template <typename T>
+__global__ __launch_bounds__(256) void update_prep_kernel(const UpdPrepArgs a)
+{
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= a.total) return;
+    int j = 0;
+    while (j + 1 < a.n_jobs && gid >= a.job[j + 1].start) ++j;
+    const UpdPrepArgs::Job &jb = a.job[j];
+    const int64_t e = gid - jb.start;
+    if (jb.kind == JOB_PAD_COPY) {            // dst[rows, ld_dst] <- src[rows, cols], zero padded
+        const int r = (int)(e / jb.ld_dst), c = (int)(e % jb.ld_dst);
+        if constexpr (sizeof(T) == 2)
+            ((uint16_t *)jb.dst)[e] = c < jb.cols ? ((const uint16_t *)jb.src)[(int64_t)r * jb.ld_src + c] : (uint16_t)0;
+        else
+            ((float *)jb.dst)[e] = c < jb.cols ? ((const float *)jb.src)[(int64_t)r * jb.ld_src + c] : 0.f;
+    } else if (jb.kind == JOB_TRANSPOSE) {    // dst[cols, rows] <- src[rows, cols]
+        const int c = (int)(e / jb.rows), r = (int)(e % jb.rows);
+        if constexpr (sizeof(T) == 2)
+            ((uint16_t *)jb.dst)[e] = ((const uint16_t *)jb.src)[(int64_t)r * jb.ld_src + c];
+        else
+            ((float *)jb.dst)[e] = ((const float *)jb.src)[(int64_t)r * jb.ld_src + c];
+    } else {                                  // zero columns [cols, ld_dst) of dst[rows, ld_dst]
+        const int w = jb.ld_dst - jb.cols;
+        const int r = (int)(e / w), c = jb.cols + (int)(e % w);
+        if constexpr (sizeof(T) == 2) ((uint16_t *)jb.dst)[(int64_t)r * jb.ld_dst + c] = 0;
+        else ((float *)jb.dst)[(int64_t)r * jb.ld_dst + c] = 0.f;
+    }
+}
+
+// Output unit forward and its delta: one wavefront per sample.
+//   yhat = w_out . h + b_out ; dout = 2 (yhat - y) / B ; d[r, :] = dout * w_out * [h > 0]
+struct OutFwdArgs {
+    const void *h; const void *w_out; const float *b_out; const float *target;
+    float *yhat; float *dout; void *d; int64_t B; int32_t H;
+};
+template <typename T>
+__global__ __launch_bounds__(256) void output_forward_kernel(const OutFwdArgs a)
+{
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= a.B) return;
+    const int lane = threadIdx.x & 63;
+    float acc = 0.f;
+    for (int c = lane; c < a.H; c += 64) acc += ld_f32<T>(a.h, r * a.H + c) * ld_f32<T>(a.w_out, c);
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+    const float yh = acc + a.b_out[0];
+    const float dout = 2.f * (yh - a.target[r]) / (float)a.B;
+    if (lane == 0) { a.yhat[r] = yh; a.dout[r] = dout; }
+    for (int c = lane; c < a.H; c += 64) {
+        const float hv = ld_f32<T>(a.h, r * a.H + c);
+        st_T<T>(a.d, r * a.H + c, hv > 0.f ? dout * ld_f32<T>(a.w_out, c) : 0.f);
+    }
+}
+
+// Output unit gradients: block c < H handles column c of the last hidden layer:
+//   gw_out[c] = sum_r dout[r] h[r, c]  and  d^T[c, r] = dout[r] w_out[c] [h^T[c, r] > 0];
+// block H reduces the bias gradient sum_r dout[r] and the loss mean_r (yhat - y)^2.
+struct OutGradArgs {
+    const void *ht; const void *w_out; const float *dout; const float *yhat; const float *target;
+    void *dt; float *gw_out; float *gb_out; float *loss_out; int64_t B, Bp; int32_t H;
+};
+__device__ __forceinline__ float block_sum_256(float v, float *sh)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    const float r = (sh[0] + sh[1]) + (sh[2] + sh[3]);
+    __syncthreads();
+    return r;
+}
+template <typename T>
+__global__ __launch_bounds__(256) void output_grad_kernel(const OutGradArgs a)
+{
+    __shared__ float sh[4];
+    const int c = blockIdx.x;
+    if (c < a.H) {
+        const float w = ld_f32<T>(a.w_out, c);
+        float acc = 0.f;
+        for (int64_t r = threadIdx.x; r < a.B; r += 256) {
+            const float hv = ld_f32<T>(a.ht, (int64_t)c * a.Bp + r);
+            const float dv = a.dout[r];
+            acc += dv * hv;
+            st_T<T>(a.dt, (int64_t)c * a.Bp + r, hv > 0.f ? dv * w : 0.f);
+        }
+        const float s = block_sum_256(acc, sh);
+        if (threadIdx.x == 0) a.gw_out[c] = s;
+    } else {
+        float sd = 0.f, sl = 0.f;
+        for (int64_t r = threadIdx.x; r < a.B; r += 256) {
+            sd += a.dout[r];
+            const float e = a.yhat[r] - a.target[r];
+            sl += e * e;
+        }
+        const float s1 = block_sum_256(sd, sh);
+        const float s2 = block_sum_256(sl, sh);
+        if (threadIdx.x == 0) {
+            a.gb_out[0] = s1;
+            if (a.loss_out) a.loss_out[0] = s2 / (float)a.B;
+        }
+    }
+}
+
+// Bias gradients of the hidden layers: gb_k[c] = sum_r d_k^T[c, r], one block per (layer, unit).
+struct BiasGradArgs {
+    int n; struct L { const void *dt; float *gb; int H; int start; } l[AB_MAX_HIDDEN];
+    int64_t B, Bp;
+};
+template <typename T>
+__global__ __launch_bounds__(256) void bias_grad_kernel(const BiasGradArgs a)
+{
+    __shared__ float sh[4];
+    int k = 0;
+    while (k + 1 < a.n && (int)blockIdx.x >= a.l[k + 1].start) ++k;
+    const int c = blockIdx.x - a.l[k].start;
+    float acc = 0.f;
+    for (int64_t r = threadIdx.x; r < a.B; r += 256) acc += ld_f32<T>(a.l[k].dt, (int64_t)c * a.Bp + r);
+    const float s = block_sum_256(acc, sh);
+    if (threadIdx.x == 0) a.l[k].gb[c] = s;
+}
+
+// Adam (Kingma & Ba, Algorithm 1; bias-corrected, epsilon outside the root) over every parameter
+// tensor in one launch; also refreshes the compute-type copy of each weight matrix.
+struct AdamArgs {
+    int n;
+    struct Tn {
+        float *w, *m, *v; void *w_compute;        // master, moments, compute-type copy (NULL for biases)
+        const float *g; int rows, cols, ldg, splits; int64_t split_stride;
+        int64_t start;
+    } tn[2 * (AB_MAX_HIDDEN + 1)];
+    int64_t total;
+    const float *scal;                            // {1 - beta1^t, 1 - beta2^t}
+    float lr, beta1, beta2, eps;
+};
+template <typename T>
+__global__ __launch_bounds__(256) void adam_kernel(const AdamArgs a)
+{
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= a.total) return;
+    int j = 0;
+    while (j + 1 < a.n && gid >= a.tn[j + 1].start) ++j;
+    const AdamArgs::Tn &tn = a.tn[j];
+    const int64_t e = gid - tn.start;
+    const int r = (int)(e / tn.cols), c = (int)(e % tn.cols);
+    float g = 0.f;
+    for (int s = 0; s < tn.splits; ++s) g += tn.g[s * tn.split_stride + (int64_t)r * tn.ldg + c];
+    const float m = a.beta1 * tn.m[e] + (1.f - a.beta1) * g;
+    const float v = a.beta2 * tn.v[e] + (1.f - a.beta2) * g * g;
+    tn.m[e] = m;
+    tn.v[e] = v;
+    const float w = tn.w[e] - a.lr * (m / a.scal[0]) / (sqrtf(v / a.scal[1]) + a.eps);
+    tn.w[e] = w;
+    if (tn.w_compute) st_T<T>(tn.w_compute, e, w);
+}
+
+template <typename T>
+static ab_status run_update(const ab_model_desc *d, ab_params *prm, const UpdatePlan &p, const float *x_raw,
+                            const float *target, float lr, float beta1, float beta2, float eps,
+                            float *loss_out, unsigned char *ws, hipStream_t st)
+{
+    const int dt = p.dtype, D = p.D;
+    const int64_t B = p.B, Bp = p.Bp;
+    float *scal = (float *)(ws + p.off_scal);
+    void *x = ws + p.off_x, *xt = ws + p.off_xt;
+    float *yhat = (float *)(ws + p.off_yhat), *dout = (float *)(ws + p.off_dout);
+    float *gw_out = (float *)(ws + p.off_gwout), *gb_out = (float *)(ws + p.off_gbout);
+
+    const double esz = (double)elem_size(dt);
+    {
+        TraceScope ts("upd_begin", 16.0, 1, st);
+        update_begin_kernel<<<1, 64, 0, st>>>(prm->step, scal, beta1, beta2);
+        AB_HIP(hipGetLastError());
+    }
+    {
+        TraceScope ts("upd_encode_rows", (double)B * (p.F * 4.0 + 2.0 * p.Kp * esz), 1, st);
+        AB_HIP(launch_encode_rows(dt, d, x_raw, x, xt, B, Bp, p.F, p.Kp, st));
+    }
+    {
+        UpdPrepArgs a;
+        memset(&a, 0, sizeof(a));
+        int64_t start = 0;
+        auto add = [&](int kind, const void *src, void *dst, int rows, int cols, int ld_src, int ld_dst, int64_t n) {
+            if (n <= 0) return;
+            UpdPrepArgs::Job &j = a.job[a.n_jobs++];
+            j.src = src; j.dst = dst; j.rows = rows; j.cols = cols; j.ld_src = ld_src; j.ld_dst = ld_dst;
+            j.kind = kind; j.start = start; start += n;
+        };
+        add(JOB_PAD_COPY, prm->W[0], ws + p.off_wt[0], p.H[0], p.F, p.F, p.Kp, (int64_t)p.H[0] * p.Kp);
+        for (int k = 1; k < D; ++k)
+            add(JOB_TRANSPOSE, prm->W[k], ws + p.off_wt[k], p.H[k], p.H[k - 1], p.H[k - 1], p.H[k],
+                (int64_t)p.H[k] * p.H[k - 1]);
+        if (Bp > B) {
+            add(JOB_ZERO_COLS, nullptr, xt, p.Kp, (int)B, 0, (int)Bp, (int64_t)p.Kp * (Bp - B));
+            for (int k = 0; k < D; ++k) {
+                add(JOB_ZERO_COLS, nullptr, ws + p.off_ht[k], p.H[k], (int)B, 0, (int)Bp, (int64_t)p.H[k] * (Bp - B));
+                add(JOB_ZERO_COLS, nullptr, ws + p.off_dt[k], p.H[k], (int)B, 0, (int)Bp, (int64_t)p.H[k] * (Bp - B));
+            }
+        }
+        a.total = start;
+        TraceScope ts("upd_prep_weights", 2.0 * (double)start * esz, 1, st);
+        update_prep_kernel<T><<<(unsigned)((start + 255) / 256), 256, 0, st>>>(a);
+        AB_HIP(hipGetLastError());
+    }
+    // forward
+    for (int k = 0; k < D; ++k) {
+        GemmArgs g;
+        memset(&g, 0, sizeof(g));
+        g.A = (k == 0) ? x : (void *)(ws + p.off_h[k - 1]);
+        g.lda = p.in_w[k];
+        g.B = (k == 0) ? (const void *)(ws + p.off_wt[0]) : prm->W[k];
+        g.ldb = p.in_w[k];
+        g.M = B; g.N = p.H[k]; g.K = p.in_w[k];
+        g.bias = prm->b[k]; g.relu = 1;
+        g.out = ws + p.off_h[k]; g.ldo = p.H[k];
+        g.out_t = ws + p.off_ht[k]; g.ldo_t = Bp;
+        TraceScope ts("upd_gemm_fwd", 2.0 * B * p.H[k] * p.in_w[k], 0, st);
+        AB_HIP(launch_gemm(dt, update_tile(B, p.H[k]), AMODE_LOAD, EPI_STORE, g, st));
+    }
+    {
+        OutFwdArgs a{ws + p.off_h[D - 1], prm->W[D], prm->b[D], target, yhat, dout, ws + p.off_d[D - 1], B, p.H[D - 1]};
+        {
+            TraceScope ts("upd_output_forward", (double)B * p.H[D - 1] * 3.0 * esz, 1, st);
+            output_forward_kernel<T><<<(unsigned)((B + 3) / 4), 256, 0, st>>>(a);
+            AB_HIP(hipGetLastError());
+        }
+        OutGradArgs b{ws + p.off_ht[D - 1], prm->W[D], dout, yhat, target, ws + p.off_dt[D - 1], gw_out, gb_out,
+                      loss_out, B, Bp, p.H[D - 1]};
+        TraceScope ts("upd_output_grad", (double)B * p.H[D - 1] * 2.0 * esz, 1, st);
+        output_grad_kernel<T><<<(unsigned)(p.H[D - 1] + 1), 256, 0, st>>>(b);
+        AB_HIP(hipGetLastError());
+    }
+    // backward
+    for (int k = D - 1; k >= 0; --k) {
+        {   // dW_k = d_k^T h_{k-1}, split over the batch
+            GemmArgs g;
+            memset(&g, 0, sizeof(g));
+            g.A = ws + p.off_dt[k]; g.lda = Bp;
+            g.B = (k == 0) ? xt : (void *)(ws + p.off_ht[k - 1]); g.ldb = Bp;
+            g.M = p.H[k]; g.N = p.in_w[k]; g.K = (int32_t)Bp;
+            g.out = ws + p.off_gw[k]; g.ldo = p.in_w[k];
+            g.k_splits = p.splits[k]; g.split_stride = (int64_t)p.H[k] * p.in_w[k];
+            TraceScope ts("upd_gemm_dw", 2.0 * Bp * p.H[k] * p.in_w[k], 0, st);
+            AB_HIP(launch_gemm(dt, TILE_SMALL, AMODE_LOAD, EPI_SPLITK, g, st));
+        }
+        if (k > 0) {   // d_{k-1} = (d_k W_k) * [h_{k-1} > 0]
+            GemmArgs g;
+            memset(&g, 0, sizeof(g));
+            g.A = ws + p.off_d[k]; g.lda = p.H[k];
+            g.B = ws + p.off_wt[k]; g.ldb = p.H[k];
+            g.M = B; g.N = p.H[k - 1]; g.K = p.H[k];
+            g.mask = ws + p.off_h[k - 1]; g.ldmask = p.H[k - 1];
+            g.out = ws + p.off_d[k - 1]; g.ldo = p.H[k - 1];
+            g.out_t = ws + p.off_dt[k - 1]; g.ldo_t = Bp;
+            TraceScope ts("upd_gemm_dx", 2.0 * B * p.H[k - 1] * p.H[k], 0, st);
+            AB_HIP(launch_gemm(dt, update_tile(B, p.H[k - 1]), AMODE_LOAD, EPI_DRELU, g, st));
+        }
+    }
+    {
+        BiasGradArgs a;
+        memset(&a, 0, sizeof(a));
+        a.n = D; a.B = B; a.Bp = Bp;
+        int start = 0;
+        for (int k = 0; k < D; ++k) {
+            a.l[k].dt = ws + p.off_dt[k]; a.l[k].gb = (float *)(ws + p.off_gb[k]); a.l[k].H = p.H[k];
+            a.l[k].start = start; start += p.H[k];
+        }
+        TraceScope ts("upd_bias_grad", (double)start * Bp * esz, 1, st);
+        bias_grad_kernel<T><<<(unsigned)start, 256, 0, st>>>(a);
+        AB_HIP(hipGetLastError());
+    }
+    {
+        AdamArgs a;
+        memset(&a, 0, sizeof(a));
+        int64_t start = 0;
+        auto add = [&](float *w, float *m, float *v, void *wc, const float *g, int rows, int cols, int ldg,
+                       int splits, int64_t stride) {
+            AdamArgs::Tn &t = a.tn[a.n++];
+            t.w = w; t.m = m; t.v = v; t.w_compute = wc; t.g = g; t.rows = rows; t.cols = cols; t.ldg = ldg;
+            t.splits = splits; t.split_stride = stride; t.start = start; start += (int64_t)rows * cols;
+        };
+        for (int k = 0; k < D; ++k) {
+            const int cols = (k == 0) ? p.F : p.H[k - 1];
+            add(prm->W_master[k], prm->adam_mW[k], prm->adam_vW[k], (void *)prm->W[k], (float *)(ws + p.off_gw[k]),
+                p.H[k], cols, p.in_w[k], p.splits[k], (int64_t)p.H[k] * p.in_w[k]);
+            add(prm->b[k], prm->adam_mb[k], prm->adam_vb[k], nullptr, (float *)(ws + p.off_gb[k]), 1, p.H[k], p.H[k], 1, 0);
+        }
+        add(prm->W_master[D], prm->adam_mW[D], prm->adam_vW[D], (void *)prm->W[D], gw_out, 1, p.H[D - 1], p.H[D - 1], 1, 0);
+        add(prm->b[D], prm->adam_mb[D], prm->adam_vb[D], nullptr, gb_out, 1, 1, 1, 1, 0);
+        a.total = start; a.scal = scal; a.lr = lr; a.beta1 = beta1; a.beta2 = beta2; a.eps = eps;
+        TraceScope ts("upd_adam", (double)start * (28.0 + esz), 1, st);
+        adam_kernel<T><<<(unsigned)((start + 255) / 256), 256, 0, st>>>(a);
+        AB_HIP(hipGetLastError());
+    }
+    return AB_OK;
+}
+
+ab_status online_update(const ab_model_desc *d, ab_params *prm, const float *x_raw, const float *target,
+                        int64_t B, float lr, float beta1, float beta2, float eps, float *loss_out,
+                        void *workspace, size_t ws_bytes, hipStream_t st)
+{
+    if (B > (1 << 24)) return AB_ERR_UNSUPPORTED;
+    UpdatePlan p;
+    plan_update(d, B, &p);
+    if (!prm->step) return AB_ERR_NULL;
+    for (int k = 0; k <= p.D; ++k) {
+        if (!prm->W[k] || !prm->b[k] || !prm->W_master[k] || !prm->adam_mW[k] || !prm->adam_vW[k] ||
+            !prm->adam_mb[k] || !prm->adam_vb[k]) return AB_ERR_NULL;
+        if (((uintptr_t)prm->W[k] % 16) || ((uintptr_t)prm->W_master[k] % 4)) return AB_ERR_ALIGN;
+    }
+    if (((uintptr_t)prm->step % 8) || ((uintptr_t)x_raw % 4) || ((uintptr_t)target % 4) ||
+        ((uintptr_t)loss_out % 4)) return AB_ERR_ALIGN;
+    if (!workspace || ws_bytes < p.total) return AB_ERR_WORKSPACE;
+    if ((uintptr_t)workspace % 256) return AB_ERR_ALIGN;
+    if (!(beta1 >= 0.f && beta1 < 1.f && beta2 >= 0.f && beta2 < 1.f)) return AB_ERR_SHAPE;
+    unsigned char *ws = (unsigned char *)workspace;
+    if (p.dtype == AB_BF16)
+        return run_update<bf16_t>(d, prm, p, x_raw, target, lr, beta1, beta2, eps, loss_out, ws, st);
+    return run_update<float>(d, prm, p, x_raw, target, lr, beta1, beta2, eps, loss_out, ws, st);
+}
+
+}  // namespace ab

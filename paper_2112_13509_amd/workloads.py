@@ -170,7 +170,7 @@ def _draw_transformer_stats(rng: np.random.Generator, S: int, n_blocks=24, per_b
     nbytes = np.exp(math.log(bytes_lo) + span * ub)
     fwd = np.exp(TIME_MU + TIME_SIGMA * rng.standard_normal((S, L)))
     bwd = np.exp(TIME_MU + TIME_SIGMA * rng.standard_normal((S, L)))
-    pos = np.broadcast_to(np.arange(L, dtype=np.float64) / (L - 1), (S, L))
+    pos = np.broadcast_to(np.arange(L, dtype=np.float64) / max(L - 1, 1), (S, L))
     return np.stack([fwd, bwd, nbytes, pos], axis=2).astype(np.float32)
 
 

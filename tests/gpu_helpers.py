@@ -1,0 +1,38 @@
+"""GPU-side glue for the parity tests: move a drawn workload to the device and call the C ABI."""
+import numpy as np
+import torch
+
+from paper_2112_13509_amd import binding as ab
+
+DEV = "cuda:0"
+
+
+def to_dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+class Scorer:
+    """Device copies of one workload's model and grid; ``run`` scores a batch of scenarios."""
+
+    def __init__(self, w):
+        self.w = w
+        self.desc = ab.desc_from_workload(w)
+        self.params = ab.Params.from_workload(w, DEV)
+        self.part, self.cred = to_dev(w.part), to_dev(w.cred)
+
+    def run(self, dyn=None, scal=None, want_scores=True, want_best=True):
+        w = self.w
+        dyn = w.dyn if dyn is None else dyn
+        scal = w.scal if scal is None else scal
+        S, Cn = dyn.shape[0], w.C
+        d_dyn = dyn if isinstance(dyn, torch.Tensor) else to_dev(dyn)
+        d_scal = scal if isinstance(scal, torch.Tensor) else to_dev(scal)
+        scores = torch.full((S, Cn), float("nan"), dtype=torch.float32, device=DEV) if want_scores else None
+        idx = torch.full((S,), -7, dtype=torch.int32, device=DEV) if want_best else None
+        best = torch.full((S,), float("nan"), dtype=torch.float32, device=DEV) if want_best else None
+        ws = ab.alloc_workspace(self.desc, S, Cn, device=DEV)
+        ab.ab_score_candidates(self.desc, self.params, d_dyn, d_scal, self.part, self.cred,
+                               scores, idx, best, ws)
+        torch.cuda.synchronize()
+        out = lambda t: None if t is None else t.cpu().numpy()
+        return out(scores), out(idx), out(best)

@@ -1,0 +1,141 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and rejects bad arguments with the documented status before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2112_13509_amd import binding as ab
+from paper_2112_13509_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(ab.library_path()):
+        import __graft_entry__
+        __graft_entry__.build()
+    return ab.load()
+
+
+def test_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "autobyte.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(ab_[a-z_]+)\s*\(", header))
+    assert {"ab_score_candidates", "ab_select_best", "ab_online_update", "ab_workspace_bytes",
+            "ab_status_string", "ab_version"} <= names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert ab.ab_version() >= 100
+    assert ab.ab_status_string(0) == "ok" and "NULL" in ab.ab_status_string(-1)
+
+
+def test_struct_layout_matches_header_sizes():
+    # ab_enc = 12 bytes; desc = 3 ints + 26 encs + int + 8 ints + int + 2 ints + int
+    assert C.sizeof(ab.ab_enc) == 12
+    assert C.sizeof(ab.ab_model_desc) == 4 * 3 + 12 * (8 + 16 + 2) + 4 + 4 * 8 + 4 + 8 + 4
+    assert C.sizeof(ab.ab_params) == 8 * (12 * 7 + 1)
+    assert C.sizeof(ab.ab_stats) == 24 and C.sizeof(ab.ab_grid) == 32
+
+
+def _desc(cfg=2):
+    return ab.desc_from_workload(wl.make_config(cfg, S=1))
+
+
+def test_workspace_bytes(lib):
+    d = _desc(3)
+    small, big = ab.ab_workspace_bytes(d, 16, 256), ab.ab_workspace_bytes(d, 65536, 256)
+    assert 0 < small < big
+    # cfg3 at full size: scenario rows + two ping-pong activation chunks of 2^20 rows x 1024 bf16
+    assert 2 * (1 << 20) * 1024 * 2 < big < 6 * (1 << 30)
+    assert ab.ab_workspace_bytes(d, 0, 0, 0) == 0
+    d.compute_dtype = 7
+    assert ab.ab_workspace_bytes(d, 16, 256) == 0
+    du = ab.desc_from_workload(wl.make_update(N=64, batch=64, L=2, hidden=(64,)))
+    assert ab.ab_workspace_bytes(du, 0, 0, 64) > 0
+
+
+def _call_score(lib, d, params=None, stats=None, grid=None, scores=0x1000, idx=0x2000, best=None,
+                ws=0x100000, ws_bytes=1 << 40):
+    p = params or ab.ab_params()
+    st = stats or ab.ab_stats(0x3000, 0x4000, 4)
+    gr = grid or ab.ab_grid(0x5000, 2, 0x6000, 2)
+    return lib.ab_score_candidates(C.byref(d), C.byref(p), C.byref(st), C.byref(gr), scores, idx, best,
+                                   ws, ws_bytes, None)
+
+
+def _fake_params(n):
+    p = ab.ab_params()
+    for k in range(n):
+        p.W[k] = 0x10000 * (k + 1)
+        p.b[k] = 0x10000 * (k + 1) + 0x8000
+    return p
+
+
+def test_score_argument_errors(lib):
+    d = _desc(2)
+    p = _fake_params(3)
+    assert lib.ab_score_candidates(None, None, None, None, None, None, None, None, 0, None) == -1
+    assert _call_score(lib, d, p, scores=None, idx=None) == -1                 # no output requested
+    assert _call_score(lib, d, p, idx=None, best=0x7000) == -1                 # best_score without best_idx
+    assert _call_score(lib, d, ab.ab_params()) == -1                           # weights missing
+    assert _call_score(lib, d, p, grid=ab.ab_grid(0x5000, 0, 0x6000, 2)) == -2  # empty grid
+    assert _call_score(lib, d, p, stats=ab.ab_stats(0x3000, 0x4000, -1)) == -2
+    assert _call_score(lib, d, p, ws=None) == -5
+    assert _call_score(lib, d, p, ws_bytes=16) == -5
+    assert _call_score(lib, d, p, ws=0x100010) == -4                           # workspace not 256-aligned
+    bad = _fake_params(3)
+    bad.W[1] = 0x20004
+    assert _call_score(lib, d, bad) == -4                                      # weight not 16-aligned
+    d2 = _desc(2)
+    d2.compute_dtype = 5
+    assert _call_score(lib, d2, p) == -3
+    d3 = _desc(2)
+    d3.hidden[0] = 100
+    assert _call_score(lib, d3, p) == -6                                       # width not a multiple of 64
+    d4 = _desc(2)
+    d4.n_hidden = 0
+    assert _call_score(lib, d4, p) == -6
+    d5 = _desc(2)
+    d5.n_stats = 99
+    assert _call_score(lib, d5, p) == -2
+    # S = 0 is a valid no-op that never touches the device
+    assert _call_score(lib, d, p, stats=ab.ab_stats(None, None, 0)) == 0
+
+
+def test_select_and_update_argument_errors(lib):
+    assert lib.ab_select_best(None, 4, 4, 4, 0x1000, None, None) == -1
+    assert lib.ab_select_best(0x1000, 4, 4, 4, None, None, None) == -1
+    assert lib.ab_select_best(0x1000, 4, 0, 4, 0x2000, None, None) == -2
+    assert lib.ab_select_best(0x1000, 4, 8, 4, 0x2000, None, None) == -2       # stride < C
+    assert lib.ab_select_best(0x1002, 4, 4, 4, 0x2000, None, None) == -4
+    assert lib.ab_select_best(0x1000, 0, 4, 4, 0x2000, None, None) == 0
+    u = wl.make_update(N=64, batch=64, L=2, hidden=(64,))
+    d = ab.desc_from_workload(u)
+    p = ab.ab_params()
+    f = C.c_float
+    call = lambda prm, x=0x1000, y=0x2000, B=64, ws=0x100000, n=1 << 40: lib.ab_online_update(
+        C.byref(d), C.byref(prm), x, y, B, f(1e-3), f(0.9), f(0.999), f(1e-8), None, ws, n, None)
+    assert call(p) == -1
+    full = ab.ab_params()
+    for k in range(2):
+        for name in ("W", "b", "W_master", "adam_mW", "adam_vW", "adam_mb", "adam_vb"):
+            getattr(full, name)[k] = 0x100000 * (k + 1)
+    full.step = 0x900000
+    assert call(full, x=None) == -1
+    assert call(full, B=0) == -2
+    assert call(full, ws=None) == -5
+    assert call(full, n=10) == -5
+    dte = ab.desc_from_workload(wl.make_config(5, S=1))
+    assert lib.ab_online_update(C.byref(dte), C.byref(full), 0x1000, 0x2000, 64, f(1e-3), f(0.9), f(0.999),
+                                f(1e-8), None, 0x100000, 1 << 40, None) == -6
+
+
+def test_binding_refuses_cpu_tensors(lib):
+    import torch
+    w = wl.make_config(1)
+    d = ab.desc_from_workload(w)
+    with pytest.raises(TypeError):
+        ab.ab_select_best(torch.zeros(2, 4), torch.zeros(2, dtype=torch.int32))

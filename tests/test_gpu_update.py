@@ -1,0 +1,197 @@
+"""Parity of ab_online_update (forward + backward + Adam on the GPU) against the fp64 oracle.
+
+Single steps from an identical state are the real parity test (loss, gradients recovered from the
+first moment, updated weights); long trajectories are compared through their loss curves because
+Adam's early sign-like steps make bf16 and fp64 weight trajectories drift apart.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2112_13509_amd import binding as ab
+from paper_2112_13509_amd import workloads as wl
+from helpers import oracle_model, tensor_error
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    ab.load()
+
+
+class GpuTrainer:
+    def __init__(self, u, B):
+        self.u = u
+        self.desc = ab.desc_from_workload(u)
+        self.params = ab.Params(u.W, u.b, u.dtype, DEV, trainable=True)
+        self.ws = ab.alloc_workspace(self.desc, B=B, device=DEV)
+        self.loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+        self.x = torch.from_numpy(u.x_raw).to(DEV)
+        self.y = torch.from_numpy(u.target).to(DEV)
+
+    def load_state(self, st):
+        p = self.params
+        cdt = torch.bfloat16 if self.u.dtype == "bf16" else torch.float32
+        for k in range(len(st.W)):
+            p.W_master[k].copy_(torch.from_numpy(st.W[k].astype(np.float32)))
+            p.W[k].copy_(p.W_master[k].to(cdt))
+            p.b[k].copy_(torch.from_numpy(st.b[k].astype(np.float32)))
+            p.mW[k].copy_(torch.from_numpy(st.mW[k].astype(np.float32)))
+            p.vW[k].copy_(torch.from_numpy(st.vW[k].astype(np.float32)))
+            p.mb[k].copy_(torch.from_numpy(st.mb[k].astype(np.float32)))
+            p.vb[k].copy_(torch.from_numpy(st.vb[k].astype(np.float32)))
+        p.step.fill_(st.t)
+
+    def step(self, rows, **kw):
+        idx = torch.from_numpy(np.asarray(rows)).to(DEV)
+        ab.ab_online_update(self.desc, self.params, self.x[idx].contiguous(), self.y[idx].contiguous(),
+                            loss_out=self.loss, workspace=self.ws, **kw)
+
+    def loss_value(self):
+        torch.cuda.synchronize()
+        return float(self.loss.item())
+
+
+def check_single_step(u, tr, st, rows, tol, lr=1e-3):
+    """One step on GPU and in the oracle from the same state ``st`` (oracle state is advanced)."""
+    tr.load_state(st)
+    before = st.copy()
+    tr.step(rows, lr=lr)
+    gl = tr.loss_value()
+    ref = orc.update(oracle_model(u), st, u.x_raw[rows], u.target[rows], lr=lr)
+    assert abs(gl - ref["loss"]) <= tol * abs(ref["loss"]), (gl, ref["loss"])
+    p = tr.params
+    worst = 0.0
+    for k in range(len(st.W)):
+        # gradients via the first moment: m' = 0.9 m + 0.1 g
+        gW = (p.mW[k].cpu().numpy().astype(np.float64) - 0.9 * before.mW[k]) / 0.1
+        gb = (p.mb[k].cpu().numpy().astype(np.float64) - 0.9 * before.mb[k]) / 0.1
+        eW, eb = tensor_error(gW, ref["gW"][k]), tensor_error(gb, ref["gb"][k])
+        worst = max(worst, eW, eb)
+        assert eW <= tol and eb <= tol, (k, eW, eb)
+        assert tensor_error(p.vW[k].cpu().numpy(), st.vW[k]) <= 2.5 * tol
+        # updated parameters: each moved by at most ~lr, so two paths differ by at most 2 lr
+        assert np.abs(p.W_master[k].cpu().numpy() - st.W[k]).max() <= 2 * lr + 1e-6
+        assert np.abs(p.b[k].cpu().numpy() - st.b[k]).max() <= 2 * lr + 1e-6
+        cdt = torch.bfloat16 if u.dtype == "bf16" else torch.float32
+        assert torch.equal(p.W[k], p.W_master[k].to(cdt))        # compute copy refreshed
+    assert int(p.step.item()) == st.t
+    return worst
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("L,hidden,B", [(2, (64,), 64), (8, (64, 64), 256), (5, (128, 64, 64), 100),
+                                        (20, (192, 128), 333)])
+def test_single_step_small(dtype, L, hidden, B):
+    u = wl.make_update("upd-small", N=max(B, 64), batch=B, L=L, hidden=hidden, dtype=dtype, seed=L * 100 + B,
+                       P=8, Q=8)
+    tr = GpuTrainer(u, B)
+    st = orc.TrainState.fresh(u.W, u.b)
+    rows = np.arange(B)
+    w1 = check_single_step(u, tr, st, rows, TOL[dtype])
+    w2 = check_single_step(u, tr, st, rows[::-1].copy(), TOL[dtype])     # second step, non-zero moments
+    print("single-step worst gradient error: %.3g, %.3g (tol %g)" % (w1, w2, TOL[dtype]))
+
+
+def test_weight_update_exact_against_oracle_fp32():
+    """fp32 path: away from tiny gradients the updated weights match to fp32 rounding."""
+    u = wl.make_update("upd-w", N=128, batch=128, L=4, hidden=(64, 64), dtype="f32", seed=3, P=4, Q=4)
+    tr = GpuTrainer(u, 128)
+    st = orc.TrainState.fresh(u.W, u.b)
+    tr.load_state(st)
+    tr.step(np.arange(128))
+    torch.cuda.synchronize()
+    ref = orc.update(oracle_model(u), st, u.x_raw[:128], u.target[:128])
+    for k in range(len(st.W)):
+        big = np.abs(ref["gW"][k]) > 1e-4 * np.abs(ref["gW"][k]).max()
+        d = np.abs(tr.params.W_master[k].cpu().numpy() - st.W[k])
+        assert d[big].max() <= 2e-6, (k, d[big].max())
+
+
+def test_config4_single_steps_along_oracle_trajectory():
+    """Configuration 4 at its real shape (B = 4096, 390 -> 512 -> 512 -> 512 -> 1, bf16 GEMMs).
+    The oracle advances a trajectory; at steps 1, 2 and 6 the GPU takes the same step from the
+    oracle's state."""
+    u = wl.make_update()
+    tr = GpuTrainer(u, u.batch)
+    st = orc.TrainState.fresh(u.W, u.b)
+    m = oracle_model(u)
+    for step in range(6):
+        rows = u.batch_indices(step)
+        if step in (0, 1, 5):
+            w = check_single_step(u, tr, st, rows, TOL["bf16"])
+            print("cfg4 step %d: worst gradient error %.3g" % (step + 1, w))
+        else:
+            orc.update(m, st, u.x_raw[rows], u.target[rows], want_grads=False)
+
+
+def test_loss_curve_tracks_oracle_and_reaches_noise_floor():
+    u = wl.make_update("upd-curve", N=4096, batch=256, L=8, hidden=(64, 64), dtype="bf16", seed=12, P=8, Q=8)
+    tr = GpuTrainer(u, 256)
+    st = orc.TrainState.fresh(u.W, u.b)
+    m = oracle_model(u)
+    gl, ol = [], []
+    losses = torch.zeros(300, dtype=torch.float32, device=DEV)
+    for step in range(300):
+        rows = u.batch_indices(step)
+        tr.step(rows)
+        losses[step] = tr.loss[0]
+        ol.append(orc.update(m, st, u.x_raw[rows], u.target[rows], want_grads=False)["loss"])
+    torch.cuda.synchronize()
+    gl = losses.cpu().numpy().astype(np.float64)
+    ol = np.asarray(ol)
+    for a in range(0, 300, 50):
+        g, o = gl[a:a + 50].mean(), ol[a:a + 50].mean()
+        assert abs(g - o) <= 0.05 * o, (a, g, o)
+    assert gl[-50:].mean() <= 1.5 * ol[-50:].mean()
+    assert gl[-50:].mean() >= 0.5 * u.noise_var
+    assert gl[-50:].mean() < 0.3 * gl[:5].mean()
+
+
+def test_config4_thousand_steps_reduce_loss():
+    u = wl.make_update()
+    tr = GpuTrainer(u, u.batch)
+    losses = torch.zeros(1000, dtype=torch.float32, device=DEV)
+    order = [torch.from_numpy(u.batch_indices(s)).to(DEV) for s in range(16)]
+    xb = [tr.x[i].contiguous() for i in order]
+    yb = [tr.y[i].contiguous() for i in order]
+    for step in range(1000):
+        ab.ab_online_update(tr.desc, tr.params, xb[step % 16], yb[step % 16], loss_out=tr.loss, workspace=tr.ws)
+        losses[step] = tr.loss[0]
+    torch.cuda.synchronize()
+    ls = losses.cpu().numpy()
+    assert np.isfinite(ls).all()
+    assert int(tr.params.step.item()) == 1000
+    print("cfg4 loss: first %.4f, last-50 mean %.4f (label noise variance %.4f)" % (ls[0], ls[-50:].mean(), u.noise_var))
+    assert ls[-50:].mean() < 0.25 * ls[0]
+    assert ls[-50:].mean() > 0.3 * u.noise_var
+
+
+def test_resume_is_bitwise_identical():
+    """20 steps straight == 10 steps, copy the state to fresh tensors, 10 more: kernels are deterministic."""
+    u = wl.make_update("upd-resume", N=1024, batch=128, L=6, hidden=(128, 64), dtype="bf16", seed=21, P=4, Q=4)
+    a = GpuTrainer(u, 128)
+    for s in range(20):
+        a.step(u.batch_indices(s))
+    b = GpuTrainer(u, 128)
+    for s in range(10):
+        b.step(u.batch_indices(s))
+    torch.cuda.synchronize()
+    c = GpuTrainer(u, 128)
+    for name in ("W", "b", "W_master", "mW", "vW", "mb", "vb"):
+        for dst, src in zip(getattr(c.params, name), getattr(b.params, name)):
+            dst.copy_(src)
+    c.params.step.copy_(b.params.step)
+    for s in range(10, 20):
+        c.step(u.batch_indices(s))
+    torch.cuda.synchronize()
+    for name in ("W", "b", "W_master", "mW", "vW", "mb", "vb"):
+        for x, y in zip(getattr(a.params, name), getattr(c.params, name)):
+            assert torch.equal(x, y), name
+    assert a.loss_value() == c.loss_value()
