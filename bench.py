@@ -189,7 +189,7 @@ def main():
                    "sample": "first %d scenarios x all %d candidates, fp64, unfactorised (%.1f s)" % (n_s, w.C, dt)}
             if want_scores:
                 got = scores[:n_s].cpu().numpy().astype(np.float64)
-                scale = np.abs(ref).max(axis=1, keepdims=True)
+                scale = np.maximum(np.abs(ref).max(axis=1, keepdims=True), np.sqrt(np.mean(ref ** 2)))
                 cpu["gpu_vs_oracle_max_scaled_err"] = float((np.abs(got - ref) / scale).max())
 
     out = {"metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": steps, "warmup": warmup,

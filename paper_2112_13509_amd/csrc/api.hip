@@ -157,6 +157,7 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
     ab_status rc = check_desc(desc);
     if (rc != AB_OK) return rc;
     if (!params || !stats || !grid) return AB_ERR_NULL;
+    if (stats->S == 0) return AB_OK;      // nothing to score: valid no-op, no pointer is looked at
     if (!scores && !best_idx) return AB_ERR_NULL;
     if (best_score && !best_idx) return AB_ERR_NULL;
     if (stats->S < 0 || grid->P <= 0 || grid->Q <= 0) return AB_ERR_SHAPE;

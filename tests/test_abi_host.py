@@ -103,6 +103,7 @@ def test_score_argument_errors(lib):
     assert _call_score(lib, d5, p) == -2
     # S = 0 is a valid no-op that never touches the device
     assert _call_score(lib, d, p, stats=ab.ab_stats(None, None, 0)) == 0
+    assert _call_score(lib, d, p, stats=ab.ab_stats(None, None, 0), scores=None, idx=None, ws=None) == 0
 
 
 def test_select_and_update_argument_errors(lib):
