@@ -51,6 +51,7 @@ struct ScorePlan {
     int dtype, Fs, F, Kp, D, base;
     int H[AB_MAX_HIDDEN];
     int tile[AB_MAX_HIDDEN];      // tile of hidden GEMM k (k >= 1)
+    int big[AB_MAX_HIDDEN];       // hidden GEMM k runs on the 256x256 bf16 kernel
     int tile_a;                   // tile of the scenario-term GEMM
     int nt_last;
     int64_t chunk_scen, chunk_rows;
@@ -79,8 +80,16 @@ static ab_status plan_scoring(const ab_model_desc *d, int64_t S, int32_t C, Scor
     p->chunk_scen = cs;
     p->chunk_rows = cs * C;
     p->tile_a = pick_tile(S, p->H[0]);
-    for (int k = 1; k < p->D; ++k) p->tile[k] = pick_tile(p->chunk_rows, p->H[k]);
-    p->nt_last = (p->D >= 2) ? p->H[p->D - 1] / tile_edge(p->tile[p->D - 1]) : 1;
+    for (int k = 1; k < p->D; ++k) {
+        p->tile[k] = pick_tile(p->chunk_rows, p->H[k]);
+        p->big[k] = p->dtype == AB_BF16 && p->H[k] % 256 == 0 && (k > 1 || C % 256 == 0) &&
+                    ((p->chunk_rows + 255) / 256) * (p->H[k] / 256) >= 256;
+    }
+    p->nt_last = 1;
+    if (p->D >= 2) {
+        const int kl = p->D - 1;
+        p->nt_last = p->big[kl] ? p->H[kl] / 256 : p->H[kl] / tile_edge(p->tile[kl]);
+    }
     const size_t es = elem_size(p->dtype);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -239,13 +248,18 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
                 g.M = rows; g.N = p.H[k]; g.K = p.H[k - 1];
                 g.bias = params->b[p.base + k]; g.relu = 1;
                 const bool last = (k == p.D - 1);
-                if (last) { g.w_out = w_out_f; g.partial = partial; nt = p.H[k] / tile_edge(p.tile[k]); }
+                if (last) { g.w_out = w_out_f; g.partial = partial; nt = p.nt_last; }
                 else { g.out = act[(k + 1) & 1]; g.ldo = p.H[k]; }
                 TraceScope ts(k == 1 ? (last ? "gemm_hidden_first_last" : "gemm_hidden_first")
                                      : (last ? "gemm_hidden_last" : "gemm_hidden_mid"),
                               2.0 * rows * p.H[k] * p.H[k - 1], 0, st);
-                AB_HIP(launch_gemm(dt, p.tile[k], k == 1 ? AMODE_GEN : AMODE_LOAD,
-                                   last ? EPI_SCORE : EPI_STORE, g, st));
+                const int amode = k == 1 ? AMODE_GEN : AMODE_LOAD, epi = last ? EPI_SCORE : EPI_STORE;
+                if (p.big[k] && gemm_big_supported(dt, amode, epi, g))
+                    AB_HIP(launch_gemm_big(amode, epi, g, st));
+                else if (p.big[k])
+                    return AB_ERR_UNSUPPORTED;     // cannot happen: the plan checked the same conditions
+                else
+                    AB_HIP(launch_gemm(dt, p.tile[k], amode, epi, g, st));
             }
         }
         TraceScope ts("finish_select", (double)rows * (nt * 4.0 + (scores ? 4.0 : 0.0)) + ns * 8.0, 1, st);

@@ -1,0 +1,304 @@
+// The bf16 256 x 256 x 64 work-horse of the hidden-layer chain: C = A * B^T with A [M, K] (activations,
+// or generated on the fly as relu(A[s] + B[c])) and B = W [N, K], both K-contiguous.
+//
+// Shape of the kernel
+//   - 512 threads = 8 wavefronts (2 per SIMD, so one wavefront's LDS / global phases overlap the other's
+//     matrix-core phase), arranged 2 (rows) x 4 (columns); each wavefront owns 128 rows x 64 columns.
+//   - Two LDS stages of 64 KB (A slab 256 rows x 128 bytes, then the W slab).  Slabs that come straight
+//     from memory are written by the global->LDS DMA path (no registers, no ds_write); the generated
+//     operand goes through registers.  Rows are eight 16-byte chunks; chunk c of row r sits at position
+//     c ^ ((r >> 1) & 7).
+//   - Operand roles are swapped with respect to the textbook order: the weight fragment is the matrix
+//     instruction's first operand and the activation fragment its second, so in the 32x32 result a
+//     lane holds ONE output row (lane & 31) and 16 output columns (register r -> column
+//     8*(r/4) + 4*(lane>>5) + (r&3)).  Four consecutive registers are four consecutive columns: the
+//     bf16 store packs them into 8 bytes, and the output-unit dot product is a per-lane sum.
+//   - Fragments are double-buffered in registers; the barrier of a slab sits before its last quarter
+//     so that the first fragments of the next slab are fetched under the last quarter's matrix work.
+//   - Stores go through an LDS staging tile (row stride 528 bytes) and leave as 16-byte, fully
+//     coalesced writes.
+#include "internal.hpp"
+
+namespace ab {
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void global_void;
+
+__device__ __forceinline__ void dma16(const void *gsrc, void *lds_uniform_dst)
+{
+    // 64 lanes x 16 bytes; lane l's data lands at lds_uniform_dst + 16*l
+    __builtin_amdgcn_global_load_lds((global_void *)gsrc, (lds_void *)lds_uniform_dst, 16, 0, 0);
+}
+
+template <int AMODE, int EPI>
+__global__ __launch_bounds__(512) void gemm_big_kernel(const GemmArgs g)
+{
+    constexpr int BM = 256, BN = 256, BK = 64;
+    constexpr int A_BYTES = BM * 128, STAGE = (BM + BN) * 128;
+    constexpr int OUT_STRIDE = 528;                       // bytes per staged output row (512 + 16 pad)
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    int64_t id = blockIdx.x;
+    const int xcd = (int)(id & 7);
+    const int64_t local = id >> 3;
+    const int tn = (int)(local % g.n_tiles);
+    const int64_t tm = (local / g.n_tiles) * 8 + xcd;
+    if (tm >= g.m_tiles) return;
+
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wave_m = wave >> 2, wave_n = wave & 3;
+    const int half = lane >> 5, l31 = lane & 31;
+    const int64_t m0 = tm * BM;
+    const int n0 = tn * BN;
+    const int KT = g.K / BK;
+
+    // ---- sources of this wavefront's DMA rows: row groups rg = wave + 8 i (8 rows each), i < 4
+    const int dma_cc = (lane & 7) ^ ((wave & 1) * 4 + (lane >> 4));     // logical chunk this lane fetches
+    const uint16_t *a_src[4];
+    const uint16_t *w_src[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = (wave + 8 * i) * 8 + (lane >> 3);
+        if constexpr (AMODE == AMODE_LOAD) {
+            int64_t gr = m0 + r;
+            if (gr > g.M - 1) gr = g.M - 1;
+            a_src[i] = (const uint16_t *)g.A + gr * g.lda + dma_cc * 8;
+        } else {
+            a_src[i] = nullptr;
+        }
+        w_src[i] = (const uint16_t *)g.B + (int64_t)(n0 + r) * g.ldb + dma_cc * 8;
+    }
+    // ---- generated operand: thread -> chunks (row = t/8 + 64 i, logical chunk t & 7); one scenario per tile
+    const float *gen_a = nullptr;
+    const float *gen_b[4];
+    int gen_st[4];
+    if constexpr (AMODE == AMODE_GEN) {
+        const int64_t s = m0 / g.C;
+        const int c0 = (int)(m0 - s * g.C);
+        const int cc = t & 7;
+        gen_a = g.a_term + s * g.ldt + cc * 8;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = (t >> 3) + 64 * i;
+            gen_b[i] = g.b_term + (int64_t)(c0 + r) * g.ldt + cc * 8;
+            gen_st[i] = r * 128 + ((cc ^ ((r >> 1) & 7)) << 4);
+        }
+    }
+
+    // ---- fragment read offsets
+    const int sw = (l31 >> 1) & 7;
+    int rd[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) rd[q] = l31 * 128 + ((((q << 1) | half) ^ sw) << 4);
+    const int a_rd = wave_m * 128 * 128;                   // + im * 4096
+    const int w_rd = A_BYTES + wave_n * 64 * 128;          // + jn * 4096
+
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+        for (int im = 0; im < 4; ++im)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[jn][im][r] = 0.f;
+
+    f32x4 raw_a[2], raw_b[4][2];
+    auto issue_loads = [&](int kt, int stage) {
+        unsigned char *sb = smem + stage * STAGE;
+        const int k0 = kt * BK;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dma16(w_src[i] + k0, sb + A_BYTES + (wave + 8 * i) * 1024);
+        if constexpr (AMODE == AMODE_LOAD) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dma16(a_src[i] + k0, sb + (wave + 8 * i) * 1024);
+        } else {
+            raw_a[0] = *(const f32x4 *)(gen_a + k0);
+            raw_a[1] = *(const f32x4 *)(gen_a + k0 + 4);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                raw_b[i][0] = *(const f32x4 *)(gen_b[i] + k0);
+                raw_b[i][1] = *(const f32x4 *)(gen_b[i] + k0 + 4);
+            }
+        }
+    };
+    auto write_generated = [&](int stage) {
+        if constexpr (AMODE == AMODE_GEN) {
+            unsigned char *sa = smem + stage * STAGE;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const f32x4 b0 = raw_b[i][0], b1 = raw_b[i][1];
+                i32x4 v;
+                v.x = (int)pack_bf16x2(relu_keep_nan(raw_a[0].x + b0.x), relu_keep_nan(raw_a[0].y + b0.y));
+                v.y = (int)pack_bf16x2(relu_keep_nan(raw_a[0].z + b0.z), relu_keep_nan(raw_a[0].w + b0.w));
+                v.z = (int)pack_bf16x2(relu_keep_nan(raw_a[1].x + b1.x), relu_keep_nan(raw_a[1].y + b1.y));
+                v.w = (int)pack_bf16x2(relu_keep_nan(raw_a[1].z + b1.z), relu_keep_nan(raw_a[1].w + b1.w));
+                *(i32x4 *)(sa + gen_st[i]) = v;
+            }
+        }
+    };
+
+    i32x4 fa[2][4], fw[2][2];
+    auto load_frags = [&](int stage, int q, int set) {
+        const unsigned char *sb = smem + stage * STAGE;
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn) fw[set][jn] = *(const i32x4 *)(sb + w_rd + jn * 4096 + rd[q]);
+#pragma unroll
+        for (int im = 0; im < 4; ++im) fa[set][im] = *(const i32x4 *)(sb + a_rd + im * 4096 + rd[q]);
+    };
+    auto mma = [&](int set) {
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+            for (int im = 0; im < 4; ++im)
+                acc[jn][im] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8, fw[set][jn]), __builtin_bit_cast(bf16x8, fa[set][im]),
+                    acc[jn][im], 0, 0, 0);
+    };
+
+    // Scheduling hints: keep the source order of the phases (fence) and, inside a phase, alternate one
+    // matrix instruction with one LDS fragment read so the reads for the next quarter are issued under
+    // the current quarter's matrix work instead of being sunk in front of their first use.
+#define AB_FENCE() __builtin_amdgcn_sched_barrier(0)
+#define AB_MFMA_DS_PAIR() do { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); \
+                               __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); } while (0)
+#define AB_INTERLEAVE_6() do { AB_MFMA_DS_PAIR(); AB_MFMA_DS_PAIR(); AB_MFMA_DS_PAIR(); AB_MFMA_DS_PAIR(); \
+                               AB_MFMA_DS_PAIR(); AB_MFMA_DS_PAIR(); \
+                               __builtin_amdgcn_sched_group_barrier(0x008, 2, 0); } while (0)
+
+    // ---- prologue: slab 0
+    issue_loads(0, 0);
+    write_generated(0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    load_frags(0, 0, 0);
+
+    for (int kt = 0; kt < KT; ++kt) {
+        const int cur = kt & 1;
+        const bool has_next = kt + 1 < KT;
+        if (has_next) issue_loads(kt + 1, cur ^ 1);
+        AB_FENCE();
+        load_frags(cur, 1, 1);
+        mma(0);
+        AB_INTERLEAVE_6();
+        AB_FENCE();
+        load_frags(cur, 2, 0);
+        mma(1);
+        AB_INTERLEAVE_6();
+        AB_FENCE();
+        load_frags(cur, 3, 1);
+        mma(0);
+        AB_INTERLEAVE_6();
+        AB_FENCE();
+        if (has_next) write_generated(cur ^ 1);
+        // own DMA / generated writes landed and own fragment reads of this slab returned, then meet:
+        // the next slab is complete and visible, and this slab's stage may be overwritten
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        __syncthreads();
+        AB_FENCE();
+        if (has_next) load_frags(cur ^ 1, 0, 0);
+        mma(1);
+        AB_INTERLEAVE_6();
+        AB_FENCE();
+    }
+    __syncthreads();                           // everybody is done with the operand stages
+
+    // ---------------------------------------------------------------- epilogues
+    const int ncol0 = wave_n * 64 + half * 4;              // + jn*32 + rg*8 + e   (column within the tile)
+    const int mrow0 = wave_m * 128 + l31;                  // + im*32              (row within the tile)
+    if constexpr (EPI == EPI_STORE) {
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                const int nc = ncol0 + jn * 32 + rg * 8;
+                f32x4 bv = {0.f, 0.f, 0.f, 0.f};
+                if (g.bias) bv = *(const f32x4 *)(g.bias + n0 + nc);
+#pragma unroll
+                for (int im = 0; im < 4; ++im) {
+                    float v0 = acc[jn][im][rg * 4 + 0] + bv.x, v1 = acc[jn][im][rg * 4 + 1] + bv.y;
+                    float v2 = acc[jn][im][rg * 4 + 2] + bv.z, v3 = acc[jn][im][rg * 4 + 3] + bv.w;
+                    if (g.relu) {
+                        v0 = relu_keep_nan(v0); v1 = relu_keep_nan(v1);
+                        v2 = relu_keep_nan(v2); v3 = relu_keep_nan(v3);
+                    }
+                    uint2 pk = {pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
+                    *(uint2 *)(smem + (mrow0 + im * 32) * OUT_STRIDE + nc * 2) = pk;
+                }
+            }
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+            const int cid = t + 512 * it;
+            const int row = cid >> 5, ch = cid & 31;
+            if (m0 + row < g.M) {
+                const i32x4 v = *(const i32x4 *)(smem + row * OUT_STRIDE + ch * 16);
+                *(i32x4 *)((uint16_t *)g.out + (m0 + row) * g.ldo + n0 + ch * 8) = v;
+            }
+        }
+    } else {   // EPI_SCORE
+        float ps[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                const int nc = n0 + ncol0 + jn * 32 + rg * 8;
+                const f32x4 bv = *(const f32x4 *)(g.bias + nc);
+                const f32x4 wv = *(const f32x4 *)(g.w_out + nc);
+#pragma unroll
+                for (int im = 0; im < 4; ++im) {
+                    ps[im] += relu_keep_nan(acc[jn][im][rg * 4 + 0] + bv.x) * wv.x;
+                    ps[im] += relu_keep_nan(acc[jn][im][rg * 4 + 1] + bv.y) * wv.y;
+                    ps[im] += relu_keep_nan(acc[jn][im][rg * 4 + 2] + bv.z) * wv.z;
+                    ps[im] += relu_keep_nan(acc[jn][im][rg * 4 + 3] + bv.w) * wv.w;
+                }
+            }
+        float *red = (float *)smem;            // [4 column-waves][256 rows]
+#pragma unroll
+        for (int im = 0; im < 4; ++im) {
+            const float v = ps[im] + __shfl_xor(ps[im], 32, 64);
+            if (half == 0) red[wave_n * BM + mrow0 + im * 32] = v;
+        }
+        __syncthreads();
+        if (t < BM && m0 + t < g.M)
+            g.partial[(m0 + t) * g.n_tiles + tn] = (red[t] + red[BM + t]) + (red[2 * BM + t] + red[3 * BM + t]);
+    }
+}
+
+template <int AMODE, int EPI>
+static hipError_t launch_big_one(const GemmArgs &g, hipStream_t st)
+{
+    constexpr int smem = 256 * 528;    // >= 2 operand stages (131072) and the staged output tile (135168)
+    auto kern = gemm_big_kernel<AMODE, EPI>;
+    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    const int64_t blocks = (g.m_tiles + 7) / 8 * 8 * g.n_tiles;
+    if (blocks <= 0) return hipSuccess;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    kern<<<(unsigned)blocks, 512, smem, st>>>(g);
+    return hipGetLastError();
+}
+
+bool gemm_big_supported(int dtype, int amode, int epi, const GemmArgs &g)
+{
+    if (dtype != AB_BF16 || (epi != EPI_STORE && epi != EPI_SCORE)) return false;
+    if (g.N <= 0 || g.N % 256 != 0 || g.K <= 0 || g.K % 64 != 0 || g.M <= 0) return false;
+    if (epi == EPI_STORE && (g.out_f32 || g.out_t || g.ldo % 8 != 0)) return false;
+    if (amode == AMODE_GEN) {
+        if (g.C % 256 != 0 || g.M % g.C != 0 || g.ldt % 4 != 0) return false;
+    } else if (g.lda % 8 != 0) {
+        return false;
+    }
+    return g.ldb % 8 == 0;
+}
+
+hipError_t launch_gemm_big(int amode, int epi, GemmArgs g, hipStream_t st)
+{
+    g.m_tiles = (g.M + 255) / 256;
+    g.n_tiles = g.N / 256;
+    if (amode == AMODE_LOAD)
+        return epi == EPI_STORE ? launch_big_one<AMODE_LOAD, EPI_STORE>(g, st)
+                                : launch_big_one<AMODE_LOAD, EPI_SCORE>(g, st);
+    return epi == EPI_STORE ? launch_big_one<AMODE_GEN, EPI_STORE>(g, st)
+                            : launch_big_one<AMODE_GEN, EPI_SCORE>(g, st);
+}
+
+}  // namespace ab

@@ -26,6 +26,10 @@ static inline size_t elem_size(int dtype) { return dtype == AB_BF16 ? 2 : 4; }
 // Fills m_tiles / n_tiles from M, N and the tile, then launches.  N must be a multiple of the tile edge.
 hipError_t launch_gemm(int dtype, int tile, int amode, int epi, GemmArgs g, hipStream_t st);
 
+// The 256x256 bf16 kernel (gemm_big.hip): EPI_STORE (bf16 out) or EPI_SCORE, AMODE_LOAD or AMODE_GEN.
+bool gemm_big_supported(int dtype, int amode, int epi, const GemmArgs &g);
+hipError_t launch_gemm_big(int amode, int epi, GemmArgs g, hipStream_t st);
+
 hipError_t launch_encode_stats(int dtype, const ab_model_desc *d, const float *dyn, const float *scal,
                                void *xs, int64_t S, int ld, int col0, int with_stats, hipStream_t st);
 hipError_t launch_encode_rows(int dtype, const ab_model_desc *d, const float *x_raw, void *x, void *x_t,
