@@ -4,10 +4,13 @@
 // Shape of the kernel
 //   - 512 threads = 8 wavefronts (2 per SIMD, so one wavefront's LDS / global phases overlap the other's
 //     matrix-core phase), arranged 2 (rows) x 4 (columns); each wavefront owns 128 rows x 64 columns.
-//   - Two LDS stages of 64 KB (A slab 256 rows x 128 bytes, then the W slab).  Slabs that come straight
-//     from memory are written by the global->LDS DMA path (no registers, no ds_write); the generated
-//     operand goes through registers.  Rows are eight 16-byte chunks; chunk c of row r sits at position
-//     c ^ ((r >> 1) & 7).
+//   - LDS holds a ring of three A slabs and a ring of two W slabs (256 rows x 128 bytes = 32 KB each,
+//     160 KB in all).  A slab's stage is refilled right after the barrier that retires it, so W slabs
+//     (L2 hits) are requested one slab ahead and A slabs (HBM / Infinity Cache) two slabs ahead.
+//     Slabs that come straight from memory are written by the global->LDS DMA path (no registers, no
+//     ds_write) in whole 128-byte row segments (64-byte segments halve the DMA rate); the generated
+//     operand goes through registers.  Rows are eight 16-byte chunks; chunk c of row r sits at
+//     position c ^ ((r >> 1) & 7).
 //   - Operand roles are swapped with respect to the textbook order: the weight fragment is the matrix
 //     instruction's first operand and the activation fragment its second, so in the 32x32 result a
 //     lane holds ONE output row (lane & 31) and 16 output columns (register r -> column
@@ -15,6 +18,7 @@
 //     bf16 store packs them into 8 bytes, and the output-unit dot product is a per-lane sum.
 //   - Fragments are double-buffered in registers; the barrier of a slab sits before its last quarter
 //     so that the first fragments of the next slab are fetched under the last quarter's matrix work.
+//     Waits on the DMA use exact vmcnt counts (loads retire in issue order), never a full drain.
 //   - Stores go through an LDS staging tile (row stride 528 bytes) and leave as 16-byte, fully
 //     coalesced writes.
 #include "internal.hpp"
@@ -34,7 +38,8 @@ template <int AMODE, int EPI>
 __global__ __launch_bounds__(512) void gemm_big_kernel(const GemmArgs g)
 {
     constexpr int BM = 256, BN = 256, BK = 64;
-    constexpr int A_BYTES = BM * 128, STAGE = (BM + BN) * 128;
+    constexpr int SLAB = BM * 128;                         // 32 KB; BN == BM
+    constexpr int W_BASE = 3 * SLAB;                       // A ring: stages 0..2, W ring: stages 0..1
     constexpr int OUT_STRIDE = 528;                       // bytes per staged output row (512 + 16 pad)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -90,8 +95,8 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(const GemmArgs g)
     int rd[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) rd[q] = l31 * 128 + ((((q << 1) | half) ^ sw) << 4);
-    const int a_rd = wave_m * 128 * 128;                   // + im * 4096
-    const int w_rd = A_BYTES + wave_n * 64 * 128;          // + jn * 4096
+    const int a_rd = wave_m * 128 * 128;                   // + stage * SLAB + im * 4096
+    const int w_rd = W_BASE + wave_n * 64 * 128;           // + stage * SLAB + jn * 4096
 
     f32x16 acc[2][4];
 #pragma unroll
@@ -102,15 +107,21 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(const GemmArgs g)
             for (int r = 0; r < 16; ++r) acc[jn][im][r] = 0.f;
 
     f32x4 raw_a[2], raw_b[4][2];
-    auto issue_loads = [&](int kt, int stage) {
-        unsigned char *sb = smem + stage * STAGE;
-        const int k0 = kt * BK;
+    auto dma_w = [&](int kt) {
+        unsigned char *sb = smem + W_BASE + (kt & 1) * SLAB;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) dma16(w_src[i] + k0, sb + A_BYTES + (wave + 8 * i) * 1024);
+        for (int i = 0; i < 4; ++i) dma16(w_src[i] + kt * BK, sb + (wave + 8 * i) * 1024);
+    };
+    auto dma_a = [&](int kt) {
         if constexpr (AMODE == AMODE_LOAD) {
+            unsigned char *sb = smem + (kt % 3) * SLAB;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) dma16(a_src[i] + k0, sb + (wave + 8 * i) * 1024);
-        } else {
+            for (int i = 0; i < 4; ++i) dma16(a_src[i] + kt * BK, sb + (wave + 8 * i) * 1024);
+        }
+    };
+    auto issue_raw = [&](int kt) {
+        if constexpr (AMODE == AMODE_GEN) {
+            const int k0 = kt * BK;
             raw_a[0] = *(const f32x4 *)(gen_a + k0);
             raw_a[1] = *(const f32x4 *)(gen_a + k0 + 4);
 #pragma unroll
@@ -120,9 +131,9 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(const GemmArgs g)
             }
         }
     };
-    auto write_generated = [&](int stage) {
+    auto write_generated = [&](int kt) {
         if constexpr (AMODE == AMODE_GEN) {
-            unsigned char *sa = smem + stage * STAGE;
+            unsigned char *sa = smem + (kt % 3) * SLAB;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const f32x4 b0 = raw_b[i][0], b1 = raw_b[i][1];
@@ -137,12 +148,13 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(const GemmArgs g)
     };
 
     i32x4 fa[2][4], fw[2][2];
-    auto load_frags = [&](int stage, int q, int set) {
-        const unsigned char *sb = smem + stage * STAGE;
+    auto load_frags = [&](int kt, int q, int set) {
+        const unsigned char *sa = smem + (kt % 3) * SLAB + a_rd;
+        const unsigned char *sw_ = smem + (kt & 1) * SLAB + w_rd;
 #pragma unroll
-        for (int jn = 0; jn < 2; ++jn) fw[set][jn] = *(const i32x4 *)(sb + w_rd + jn * 4096 + rd[q]);
+        for (int jn = 0; jn < 2; ++jn) fw[set][jn] = *(const i32x4 *)(sw_ + jn * 4096 + rd[q]);
 #pragma unroll
-        for (int im = 0; im < 4; ++im) fa[set][im] = *(const i32x4 *)(sb + a_rd + im * 4096 + rd[q]);
+        for (int im = 0; im < 4; ++im) fa[set][im] = *(const i32x4 *)(sa + im * 4096 + rd[q]);
     };
     auto mma = [&](int set) {
 #pragma unroll
@@ -164,41 +176,64 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(const GemmArgs g)
                                AB_MFMA_DS_PAIR(); AB_MFMA_DS_PAIR(); \
                                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0); } while (0)
 
-    // ---- prologue: slab 0
-    issue_loads(0, 0);
-    write_generated(0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    // ---- prologue.  Issue order fixes what a vmcnt(n) wait leaves outstanding (loads retire in order).
+    if constexpr (AMODE == AMODE_LOAD) {
+        dma_a(0); dma_w(0);
+        if (KT > 1) { dma_a(1); dma_w(1); }
+        if (KT > 2) dma_a(2);
+        if (KT > 2)      asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+        else if (KT > 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else {
+        issue_raw(0);
+        write_generated(0);                                // (the compiler waits for the raw loads it uses)
+        dma_w(0);
+        if (KT > 1) { dma_w(1); issue_raw(1); }
+        if (KT > 1) asm volatile("s_waitcnt vmcnt(14)" ::: "memory");
+        else        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    AB_FENCE();
     load_frags(0, 0, 0);
 
     for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        const bool has_next = kt + 1 < KT;
-        if (has_next) issue_loads(kt + 1, cur ^ 1);
         AB_FENCE();
-        load_frags(cur, 1, 1);
+        load_frags(kt, 1, 1);
         mma(0);
         AB_INTERLEAVE_6();
         AB_FENCE();
-        load_frags(cur, 2, 0);
+        load_frags(kt, 2, 0);
         mma(1);
         AB_INTERLEAVE_6();
         AB_FENCE();
-        load_frags(cur, 3, 1);
+        load_frags(kt, 3, 1);
         mma(0);
         AB_INTERLEAVE_6();
         AB_FENCE();
-        if (has_next) write_generated(cur ^ 1);
-        // own DMA / generated writes landed and own fragment reads of this slab returned, then meet:
-        // the next slab is complete and visible, and this slab's stage may be overwritten
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-        __syncthreads();
+        if constexpr (AMODE == AMODE_GEN) {
+            if (kt + 1 < KT) write_generated(kt + 1);      // raw(kt+1) was requested one slab ago
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        } else {
+            // slab kt+1 (both operands) must have landed; A(kt+2), issued last, may still be in flight
+            if (kt + 2 < KT) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            else             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+        // own fragment reads of this slab returned; then meet: slab kt+1 is complete and visible to
+        // everybody and slab kt's stages may be refilled
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
         AB_FENCE();
-        if (has_next) load_frags(cur ^ 1, 0, 0);
+        if (kt + 2 < KT) dma_w(kt + 2);
+        if constexpr (AMODE == AMODE_LOAD) { if (kt + 3 < KT) dma_a(kt + 3); }
+        else                               { if (kt + 2 < KT) issue_raw(kt + 2); }
+        AB_FENCE();
+        load_frags(kt + 1, 0, 0);                          // (after the last slab: a stale stage, unused)
         mma(1);
         AB_INTERLEAVE_6();
         AB_FENCE();
     }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __syncthreads();                           // everybody is done with the operand stages
 
     // ---------------------------------------------------------------- epilogues
@@ -266,7 +301,7 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(const GemmArgs g)
 template <int AMODE, int EPI>
 static hipError_t launch_big_one(const GemmArgs &g, hipStream_t st)
 {
-    constexpr int smem = 256 * 528;    // >= 2 operand stages (131072) and the staged output tile (135168)
+    constexpr int smem = 5 * 256 * 128;   // 163840: three A slabs + two W slabs; the staged output tile (135168) reuses them
     auto kern = gemm_big_kernel<AMODE, EPI>;
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
