@@ -55,7 +55,7 @@ struct ScorePlan {
     int tile_a;                   // tile of the scenario-term GEMM
     int nt_last;
     int64_t chunk_scen, chunk_rows;
-    size_t off_xs, off_w1s, off_aterm, off_bterm, off_wout, off_partial, off_act0, off_act1, total;
+    size_t off_xs, off_w1s, off_aterm, off_bterm, off_cfgv, off_wout, off_partial, off_act0, off_act1, total;
 };
 
 static const int64_t kTargetChunkRows = 1 << 20;
@@ -97,6 +97,7 @@ static ab_status plan_scoring(const ab_model_desc *d, int64_t S, int32_t C, Scor
     p->off_w1s = take((size_t)p->H[0] * p->Kp * es);
     p->off_aterm = take((size_t)(S > 0 ? S : 1) * p->H[0] * 4);
     p->off_bterm = take((size_t)C * p->H[0] * 4);
+    p->off_cfgv = take(((size_t)2 * p->H[0] + 2 * (size_t)C) * 4);
     p->off_wout = take((size_t)p->H[p->D - 1] * 4);
     p->off_partial = take((size_t)p->chunk_rows * p->nt_last * 4);
     p->off_act0 = p->off_act1 = 0;
@@ -194,6 +195,7 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
     void *xs = ws + p.off_xs, *w1s = ws + p.off_w1s;
     float *a_term = (float *)(ws + p.off_aterm), *b_term = (float *)(ws + p.off_bterm);
     float *w_out_f = (float *)(ws + p.off_wout), *partial = (float *)(ws + p.off_partial);
+    float *cfg_vec = (float *)(ws + p.off_cfgv);
     void *act[2] = {ws + p.off_act0, ws + p.off_act1};
     const int dt = p.dtype;
 
@@ -217,15 +219,16 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
     {
         TraceScope ts("prep_layer1", (double)p.H[0] * (p.F * es + p.Kp * es) + (double)C * p.H[0] * 4.0, 1, st);
         AB_HIP(launch_prep_layer1(dt, desc, params->W[p.base], params->b[p.base], p.F, p.Fs, p.H[0], p.Kp, w1s,
-                                  grid, b_term, params->W[p.base + p.D], p.H[p.D - 1], w_out_f, st));
+                                  grid, b_term, cfg_vec, params->W[p.base + p.D], p.H[p.D - 1], w_out_f, st));
     }
-    // 3. scenario term A[s] = x_s W1_s^T (fp32 out)
+    // 3. scenario term A[s] = x_s W1_s^T + b1 (fp32 out)
     {
         GemmArgs g;
         memset(&g, 0, sizeof(g));
         g.A = xs; g.lda = p.Kp; g.B = w1s; g.ldb = p.Kp;
         g.M = S; g.N = p.H[0]; g.K = p.Kp;
         g.out = a_term; g.ldo = p.H[0]; g.out_f32 = 1;
+        g.bias = params->b[p.base];
         TraceScope ts("gemm_scenario_term", 2.0 * S * p.H[0] * p.Kp, 0, st);
         AB_HIP(launch_gemm(dt, p.tile_a, AMODE_LOAD, EPI_STORE, g, st));
     }
@@ -242,7 +245,10 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
             for (int k = 1; k < p.D; ++k) {
                 GemmArgs g;
                 memset(&g, 0, sizeof(g));
-                if (k == 1) { g.a_term = a_chunk; g.b_term = b_term; g.ldt = p.H[0]; g.C = C; }
+                if (k == 1) {
+                    g.a_term = a_chunk; g.b_term = b_term; g.ldt = p.H[0]; g.C = C;
+                    g.wp = cfg_vec; g.wc = cfg_vec + p.H[0]; g.xp = cfg_vec + 2 * p.H[0]; g.xc = cfg_vec + 2 * p.H[0] + C;
+                }
                 else { g.A = act[k & 1]; g.lda = p.H[k - 1]; }
                 g.B = params->W[p.base + k]; g.ldb = p.H[k - 1];
                 g.M = rows; g.N = p.H[k]; g.K = p.H[k - 1];

@@ -74,18 +74,23 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(const GemmArgs g)
         w_src[i] = (const uint16_t *)g.B + (int64_t)(n0 + r) * g.ldb + dma_cc * 8;
     }
     // ---- generated operand: thread -> chunks (row = t/8 + 64 i, logical chunk t & 7); one scenario per tile
-    const float *gen_a = nullptr;
-    const float *gen_b[4];
+    // A[r, k] = relu(a_term[s, k] + wp[k] * xp[c] + wc[k] * xc[c]): the per-row pair (xp, xc) stays in
+    // registers, the three per-k vectors are fetched per slab (the same 8 values for all of a thread's rows)
+    const float *gen_a = nullptr, *gen_wp = nullptr, *gen_wc = nullptr;
+    float gen_xp[4], gen_xc[4];
     int gen_st[4];
     if constexpr (AMODE == AMODE_GEN) {
         const int64_t s = m0 / g.C;
         const int c0 = (int)(m0 - s * g.C);
         const int cc = t & 7;
         gen_a = g.a_term + s * g.ldt + cc * 8;
+        gen_wp = g.wp + cc * 8;
+        gen_wc = g.wc + cc * 8;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int r = (t >> 3) + 64 * i;
-            gen_b[i] = g.b_term + (int64_t)(c0 + r) * g.ldt + cc * 8;
+            gen_xp[i] = g.xp[c0 + r];
+            gen_xc[i] = g.xc[c0 + r];
             gen_st[i] = r * 128 + ((cc ^ ((r >> 1) & 7)) << 4);
         }
     }
@@ -106,7 +111,7 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(const GemmArgs g)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[jn][im][r] = 0.f;
 
-    f32x4 raw_a[2], raw_b[4][2];
+    f32x4 raw_a[2], raw_p[2], raw_c[2];
     auto dma_w = [&](int kt) {
         unsigned char *sb = smem + W_BASE + (kt & 1) * SLAB;
 #pragma unroll
@@ -124,11 +129,10 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(const GemmArgs g)
             const int k0 = kt * BK;
             raw_a[0] = *(const f32x4 *)(gen_a + k0);
             raw_a[1] = *(const f32x4 *)(gen_a + k0 + 4);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                raw_b[i][0] = *(const f32x4 *)(gen_b[i] + k0);
-                raw_b[i][1] = *(const f32x4 *)(gen_b[i] + k0 + 4);
-            }
+            raw_p[0] = *(const f32x4 *)(gen_wp + k0);
+            raw_p[1] = *(const f32x4 *)(gen_wp + k0 + 4);
+            raw_c[0] = *(const f32x4 *)(gen_wc + k0);
+            raw_c[1] = *(const f32x4 *)(gen_wc + k0 + 4);
         }
     };
     auto write_generated = [&](int kt) {
@@ -136,12 +140,18 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(const GemmArgs g)
             unsigned char *sa = smem + (kt % 3) * SLAB;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const f32x4 b0 = raw_b[i][0], b1 = raw_b[i][1];
+                const float xp = gen_xp[i], xc = gen_xc[i];
+                float h[8];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    h[e] = relu_keep_nan(fmaf(raw_c[0][e], xc, fmaf(raw_p[0][e], xp, raw_a[0][e])));
+                    h[4 + e] = relu_keep_nan(fmaf(raw_c[1][e], xc, fmaf(raw_p[1][e], xp, raw_a[1][e])));
+                }
                 i32x4 v;
-                v.x = (int)pack_bf16x2(relu_keep_nan(raw_a[0].x + b0.x), relu_keep_nan(raw_a[0].y + b0.y));
-                v.y = (int)pack_bf16x2(relu_keep_nan(raw_a[0].z + b0.z), relu_keep_nan(raw_a[0].w + b0.w));
-                v.z = (int)pack_bf16x2(relu_keep_nan(raw_a[1].x + b1.x), relu_keep_nan(raw_a[1].y + b1.y));
-                v.w = (int)pack_bf16x2(relu_keep_nan(raw_a[1].z + b1.z), relu_keep_nan(raw_a[1].w + b1.w));
+                v.x = (int)pack_bf16x2(h[0], h[1]);
+                v.y = (int)pack_bf16x2(h[2], h[3]);
+                v.z = (int)pack_bf16x2(h[4], h[5]);
+                v.w = (int)pack_bf16x2(h[6], h[7]);
                 *(i32x4 *)(sa + gen_st[i]) = v;
             }
         }
@@ -189,7 +199,7 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(const GemmArgs g)
         write_generated(0);                                // (the compiler waits for the raw loads it uses)
         dma_w(0);
         if (KT > 1) { dma_w(1); issue_raw(1); }
-        if (KT > 1) asm volatile("s_waitcnt vmcnt(14)" ::: "memory");
+        if (KT > 1) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");   // W(1): 4 DMA, raw(1): 6 loads
         else        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -318,7 +328,7 @@ bool gemm_big_supported(int dtype, int amode, int epi, const GemmArgs &g)
     if (g.N <= 0 || g.N % 256 != 0 || g.K <= 0 || g.K % 64 != 0 || g.M <= 0) return false;
     if (epi == EPI_STORE && (g.out_f32 || g.out_t || g.ldo % 8 != 0)) return false;
     if (amode == AMODE_GEN) {
-        if (g.C % 256 != 0 || g.M % g.C != 0 || g.ldt % 4 != 0) return false;
+        if (g.C % 256 != 0 || g.M % g.C != 0 || g.ldt % 4 != 0 || !g.wp || !g.wc || !g.xp || !g.xc) return false;
     } else if (g.lda % 8 != 0) {
         return false;
     }

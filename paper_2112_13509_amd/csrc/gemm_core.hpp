@@ -49,6 +49,8 @@ struct GemmArgs {
     // A operand, AMODE_GEN: row r stands for (scenario s = r / C, candidate c = r % C) and
     // A[r, k] = relu(a_term[s*ldt + k] + b_term[c*ldt + k]) rounded to the compute type
     const float *a_term; const float *b_term; int32_t ldt; int32_t C;
+    // the same b_term in factored form, b_term[c*ldt + k] = wp[k]*xp[c] + wc[k]*xc[c] (256x256 kernel)
+    const float *wp, *wc, *xp, *xc;
     // B operand: B[N, K], leading dimension ldb
     const void *B; int64_t ldb;
     int64_t M; int32_t N; int32_t K;          // K is a multiple of the K-slab; N a multiple of the tile width

@@ -105,8 +105,11 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const EncodeRowsArgs a
 // ------------------------------------------------------------------------------------------------
 // Layer-1 preparation.  The first dense layer acts on [statistics | S_p | S_c]; its statistics
 // columns are shared by all candidates of a scenario and its two configuration columns by all
-// scenarios, so W1 x = A[s] + B[c].  This kernel packs the statistics columns of W1 into a
-// K-padded matrix for the A[s] GEMM, builds B[c] (bias included) and widens the output weights.
+// scenarios, so W1 x + b1 = A[s] + B[c] with A[s] = W1_s x_s + b1 (the bias rides in the A[s] GEMM's
+// epilogue) and B[c] = wp * phi(S_p) + wc * phi(S_c).  This kernel packs the statistics columns of W1
+// into a K-padded matrix for the A[s] GEMM, builds B[c] both as a [C, H1] matrix (generic kernels) and
+// as its four generating vectors wp[H1], wc[H1], phi_p[C], phi_c[C] (the 256x256 kernel rebuilds B[c]
+// from them with two FMAs instead of fetching 4 bytes per element), and widens the output weights.
 // ------------------------------------------------------------------------------------------------
 struct PrepArgs {
     const void *W1; int32_t F, Fs, H1, ld;      // W1[H1, F]; packed copy w1s[H1, ld]
@@ -115,6 +118,7 @@ struct PrepArgs {
     const float *part; const float *cred; int32_t P, Q;
     ab_enc enc_part, enc_cred;
     float *b_term;                               // [P*Q, H1]
+    float *wp_f, *wc_f, *xp_f, *xc_f;            // [H1], [H1], [P*Q], [P*Q]
     const void *Wout; int32_t H_last; float *w_out_f;
 };
 
@@ -145,10 +149,18 @@ __global__ __launch_bounds__(256) void prep_layer1_kernel(const PrepArgs a)
         const float xp = phi(a.part[c / a.Q], a.enc_part), xc = phi(a.cred[c % a.Q], a.enc_cred);
         const float wp = load_as_f32<T>(a.W1, (int64_t)h * a.F + a.Fs);
         const float wc = load_as_f32<T>(a.W1, (int64_t)h * a.F + a.Fs + 1);
-        a.b_term[e] = a.b1[h] + wp * xp + wc * xc;
+        a.b_term[e] = wp * xp + wc * xc;
     } else if (gid < n_pack + n_bt + a.H_last) {
         const int h = (int)(gid - n_pack - n_bt);
         a.w_out_f[h] = load_as_f32<T>(a.Wout, h);
+    } else if (gid < n_pack + n_bt + a.H_last + a.H1) {
+        const int h = (int)(gid - n_pack - n_bt - a.H_last);
+        a.wp_f[h] = load_as_f32<T>(a.W1, (int64_t)h * a.F + a.Fs);
+        a.wc_f[h] = load_as_f32<T>(a.W1, (int64_t)h * a.F + a.Fs + 1);
+    } else if (gid < n_pack + n_bt + a.H_last + a.H1 + (int64_t)a.P * a.Q) {
+        const int c = (int)(gid - n_pack - n_bt - a.H_last - a.H1);
+        a.xp_f[c] = phi(a.part[c / a.Q], a.enc_part);
+        a.xc_f[c] = phi(a.cred[c % a.Q], a.enc_cred);
     }
 }
 
@@ -374,15 +386,17 @@ hipError_t launch_encode_rows(int dtype, const ab_model_desc *d, const float *x_
 }
 
 hipError_t launch_prep_layer1(int dtype, const ab_model_desc *d, const void *W1, const float *b1, int F, int Fs,
-                              int H1, int ld, void *w1s, const ab_grid *grid, float *b_term,
+                              int H1, int ld, void *w1s, const ab_grid *grid, float *b_term, float *cfg_vec,
                               const void *Wout, int H_last, float *w_out_f, hipStream_t st)
 {
     PrepArgs a;
     a.W1 = W1; a.F = F; a.Fs = Fs; a.H1 = H1; a.ld = ld; a.w1s = w1s; a.b1 = b1;
     a.part = grid->partition_bytes; a.cred = grid->credit_mult; a.P = grid->P; a.Q = grid->Q;
     a.enc_part = d->enc_partition; a.enc_cred = d->enc_credit; a.b_term = b_term;
+    const int Cn = grid->P * grid->Q;
+    a.wp_f = cfg_vec; a.wc_f = cfg_vec + H1; a.xp_f = cfg_vec + 2 * H1; a.xc_f = cfg_vec + 2 * H1 + Cn;
     a.Wout = Wout; a.H_last = H_last; a.w_out_f = w_out_f;
-    const int64_t n = (int64_t)H1 * ld + (int64_t)grid->P * grid->Q * H1 + H_last;
+    const int64_t n = (int64_t)H1 * ld + (int64_t)Cn * H1 + H_last + H1 + Cn;
     if (dtype == AB_BF16) prep_layer1_kernel<bf16_t><<<blocks_for(n), 256, 0, st>>>(a);
     else prep_layer1_kernel<float><<<blocks_for(n), 256, 0, st>>>(a);
     return hipGetLastError();
