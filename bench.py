@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--scenarios", type=int, default=None, help="override the scenario count (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (a reference dispatch for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (scenarios are independent, so more GPUs would "
@@ -121,6 +123,14 @@ def main():
                          "scenarios": S, "candidates_per_scenario": Cn,
                          "outputs": "scores+argmax" if want_scores else "argmax"}
     t_gen = time.time() - t_gen
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                 # 1 GiB read + 1 GiB written by one elementwise dispatch
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- timed region: W warm-up steps, then exactly K steps between two device syncs
     for _ in range(warmup):
