@@ -23,6 +23,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK = {"bf16": 2.5e15, "f32": 157.3e12}     # dense MFMA peaks of MI355X, flop/s
+# HBM bytes per hidden-GEMM launch from the FETCH_SIZE / WRITE_SIZE counter runs recorded under profiles/,
+# keyed by (workload, library version the counters were taken with); any other version reports null.
+TRAFFIC = {("cfg3", 101): {"read_bytes": 1.475e9, "written_bytes": 1.439e9, "source": "profiles/gemm_big_cfg3.md"}}
 HBM_PEAK = 8.0e12
 
 
@@ -168,7 +171,8 @@ def main():
         achieved = tot_work / (tot_ms * 1e-3)
         roofline = {"bound": "mfma", "kernel": "hidden-layer GEMM launches (" + ", ".join(sorted(gemm_names)) + ")",
                     "achieved": round(achieved / 1e12, 3), "peak": PEAK[dtype] / 1e12, "unit": "TFLOP/s",
-                    "frac": round(achieved / PEAK[dtype], 4), "traffic": None,
+                    "frac": round(achieved / PEAK[dtype], 4),
+                    "traffic": TRAFFIC.get((args.workload, ab.ab_version())),
                     "flop_per_launch": tot_work / launches, "avg_launch_ms": round(tot_ms / launches, 5),
                     "share_of_step_time": round(tot_ms / trace_steps / ms_per_step, 3)}
     else:

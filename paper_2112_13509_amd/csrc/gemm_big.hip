@@ -28,10 +28,13 @@ namespace ab {
 typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void global_void;
 
+// 64 lanes x 16 bytes; lane l's data lands at lds_uniform_dst + 16*l.  STREAM marks the access
+// non-temporal: activation panels and outputs pass through L2 once per XCD and should not push the
+// weight matrix (re-read by every tile) out of it.
+template <bool STREAM>
 __device__ __forceinline__ void dma16(const void *gsrc, void *lds_uniform_dst)
 {
-    // 64 lanes x 16 bytes; lane l's data lands at lds_uniform_dst + 16*l
-    __builtin_amdgcn_global_load_lds((global_void *)gsrc, (lds_void *)lds_uniform_dst, 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((global_void *)gsrc, (lds_void *)lds_uniform_dst, 16, 0, STREAM ? 2 : 0);
 }
 
 template <int AMODE, int EPI>
@@ -115,13 +118,13 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(const GemmArgs g)
     auto dma_w = [&](int kt) {
         unsigned char *sb = smem + W_BASE + (kt & 1) * SLAB;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) dma16(w_src[i] + kt * BK, sb + (wave + 8 * i) * 1024);
+        for (int i = 0; i < 4; ++i) dma16<false>(w_src[i] + kt * BK, sb + (wave + 8 * i) * 1024);
     };
     auto dma_a = [&](int kt) {
         if constexpr (AMODE == AMODE_LOAD) {
             unsigned char *sb = smem + (kt % 3) * SLAB;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) dma16(a_src[i] + kt * BK, sb + (wave + 8 * i) * 1024);
+            for (int i = 0; i < 4; ++i) dma16<true>(a_src[i] + kt * BK, sb + (wave + 8 * i) * 1024);
         }
     };
     auto issue_raw = [&](int kt) {
@@ -276,7 +279,7 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(const GemmArgs g)
             const int row = cid >> 5, ch = cid & 31;
             if (m0 + row < g.M) {
                 const i32x4 v = *(const i32x4 *)(smem + row * OUT_STRIDE + ch * 16);
-                *(i32x4 *)((uint16_t *)g.out + (m0 + row) * g.ldo + n0 + ch * 8) = v;
+                __builtin_nontemporal_store(v, (i32x4 *)((uint16_t *)g.out + (m0 + row) * g.ldo + n0 + ch * 8));
             }
         }
     } else {   // EPI_SCORE
