@@ -245,9 +245,13 @@ __global__ __launch_bounds__(256) void score_single_hidden_kernel(const ScoreD1A
 // handled).  One work-group per scenario:
 //   e[l] = relu(W_b relu(W_a phi(stat[l]) + b_a) + b_b)   (K -> 128 on the vector ALUs, 128 -> 128 on
 //   the matrix cores), pooled[s] = mean_l e[l], written as the first 128 columns of the scenario row.
-// Wave w owns output columns [32w, 32w+32) and keeps its slice of W_b in registers; the 32-row
-// blocks of the first layer's output go through LDS (rows of 256 bytes; 16-byte chunk c of row r
-// sits at position c ^ (r & 15)).  Both layers' products use bf16 operands with fp32 accumulation.
+// W_b (bf16, 32 KB) is staged once per work-group in LDS.  After that the four wavefronts work on
+// their own 32-tensor blocks without meeting: a wavefront transforms its block's statistics, runs
+// the first layer (a lane owns two of the 128 units, weights in registers), parks the bf16 result in
+// its private 8 KB of LDS, multiplies it with W_b (32 matrix instructions) and adds relu(. + b_b) of the
+// valid tensors to per-lane column sums.  One reduction over the wavefronts at the end.
+// LDS rows are 256 bytes; 16-byte chunk c of row r sits at position c ^ (r & 15).
+// Both layers' products use bf16 operands with fp32 accumulation.
 // ------------------------------------------------------------------------------------------------
 struct TensorEncArgs {
     const float *dyn; int32_t L, K;
@@ -261,89 +265,108 @@ template <typename T>
 __global__ __launch_bounds__(256) void tensor_encoder_kernel(const TensorEncArgs a)
 {
     constexpr int H = 128;
-    __shared__ __attribute__((aligned(16))) unsigned char hbuf[32 * 256];   // 32 rows x 128 bf16
-    __shared__ float xin[32 * AB_MAX_STATS];
-    __shared__ float wa_s[H * AB_MAX_STATS];
+    __shared__ __attribute__((aligned(16))) unsigned char wb_s[H * 256];        // W_b, bf16, swizzled rows
+    __shared__ __attribute__((aligned(16))) unsigned char hbuf[4][32 * 256];    // per wavefront: 32 tensors x 128 bf16
+    __shared__ __attribute__((aligned(16))) float xin[4][32 * AB_MAX_STATS];    // per wavefront: transformed statistics
+    __shared__ __attribute__((aligned(16))) float wa_s[H * AB_MAX_STATS];       // [unit][AB_MAX_STATS], zero padded
     __shared__ float ba_s[H];
+    __shared__ float red[4][H];
     const int64_t s = blockIdx.x;
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, half = lane >> 5;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, half = lane >> 5, l31 = lane & 31;
     const float *dyn = a.dyn + s * (int64_t)a.L * a.K;
 
-    for (int i = t; i < H * a.K; i += 256) wa_s[i] = load_as_f32<T>(a.Wa, i);
-    if (t < H) ba_s[t] = a.ba[t];
-
-    // this wave's slice of W_b: column n = 32*wave + (lane & 31), 8 chunks of 8 consecutive k
-    // (chunk q covers k = 16*q + 8*half ... +8), as bf16 pairs
-    i32x4 wb[8];
-    {
-        const int n = wave * 32 + (lane & 31);
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const int k0 = q * 16 + half * 8;
-            if constexpr (sizeof(T) == 2) {
-                wb[q] = *(const i32x4 *)((const uint16_t *)a.Wb + (int64_t)n * H + k0);
-            } else {
-                const float *w = (const float *)a.Wb + (int64_t)n * H + k0;
-                wb[q].x = (int)pack_bf16x2(w[0], w[1]); wb[q].y = (int)pack_bf16x2(w[2], w[3]);
-                wb[q].z = (int)pack_bf16x2(w[4], w[5]); wb[q].w = (int)pack_bf16x2(w[6], w[7]);
-            }
-        }
+    for (int i = t; i < H * AB_MAX_STATS; i += 256) {
+        const int o = i / AB_MAX_STATS, k = i % AB_MAX_STATS;
+        wa_s[i] = (k < a.K) ? load_as_f32<T>(a.Wa, o * a.K + k) : 0.f;
     }
-    const float bb = a.bb[wave * 32 + (lane & 31)];
-    float colsum = 0.f;
-    const int sw = lane & 15;
+    if (t < H) ba_s[t] = a.ba[t];
+    for (int i = t; i < H * 16; i += 256) {                 // 16-byte chunks of W_b
+        const int n = i >> 4, c = i & 15;
+        i32x4 v;
+        if constexpr (sizeof(T) == 2) {
+            v = *(const i32x4 *)((const uint16_t *)a.Wb + n * H + c * 8);
+        } else {
+            const float *w = (const float *)a.Wb + n * H + c * 8;
+            v.x = (int)pack_bf16x2(w[0], w[1]); v.y = (int)pack_bf16x2(w[2], w[3]);
+            v.z = (int)pack_bf16x2(w[4], w[5]); v.w = (int)pack_bf16x2(w[6], w[7]);
+        }
+        *(i32x4 *)(wb_s + n * 256 + ((c ^ (n & 15)) << 4)) = v;
+    }
+    __syncthreads();
 
-    for (int l0 = 0; l0 < a.L; l0 += 32) {
-        __syncthreads();                       // previous block's readers are done; wa_s is ready
-        for (int i = t; i < 32 * a.K; i += 256) {
-            const int l = l0 + i / a.K, k = i % a.K;
-            xin[i] = (l < a.L) ? phi(dyn[(int64_t)l * a.K + k], a.enc_stat[k]) : 0.f;
+    float bb[4], colsum[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int jn = 0; jn < 4; ++jn) bb[jn] = a.bb[jn * 32 + l31];
+    unsigned char *hb = hbuf[wave];
+    float *xw = xin[wave];
+    float wa0[AB_MAX_STATS], wa1[AB_MAX_STATS];             // first layer: rows 2*lane and 2*lane+1 of W_a
+#pragma unroll
+    for (int k = 0; k < AB_MAX_STATS; ++k) {
+        wa0[k] = wa_s[(2 * lane) * AB_MAX_STATS + k];
+        wa1[k] = wa_s[(2 * lane + 1) * AB_MAX_STATS + k];
+    }
+    const float ba0 = ba_s[2 * lane], ba1 = ba_s[2 * lane + 1];
+
+    for (int l0 = wave * 32; l0 < a.L; l0 += 128) {
+        // transformed statistics of the block's 32 tensors (zero rows past the end)
+        for (int i = lane; i < 32 * AB_MAX_STATS; i += 64) {
+            const int r = i / AB_MAX_STATS, k = i % AB_MAX_STATS, l = l0 + r;
+            xw[i] = (l < a.L && k < a.K) ? phi(dyn[(int64_t)l * a.K + k], a.enc_stat[k]) : 0.f;
         }
-        __syncthreads();
-        // first layer: thread -> row r = t >> 3, 16 consecutive outputs starting at (t & 7) * 16
-        {
-            const int r = t >> 3, o0 = (t & 7) * 16;
-            float hv[16];
-#pragma unroll
-            for (int o = 0; o < 16; ++o) {
-                float acc = ba_s[o0 + o];
-                for (int k = 0; k < a.K; ++k) acc += wa_s[(o0 + o) * a.K + k] * xin[r * a.K + k];
-                acc = relu_keep_nan(acc);
-                hv[o] = acc;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // same wavefront: LDS ops are in order
+        // first layer: this lane owns units 2*lane and 2*lane+1 (weights in registers) for all 32 tensors;
+        // a tensor's statistics are one broadcast LDS read, its two results one packed 4-byte write
+#pragma unroll 8
+        for (int r = 0; r < 32; ++r) {
+            const f32x4 x0 = *(const f32x4 *)(xw + r * AB_MAX_STATS);
+            float h0 = fmaf(wa0[3], x0.w, fmaf(wa0[2], x0.z, fmaf(wa0[1], x0.y, fmaf(wa0[0], x0.x, ba0))));
+            float h1 = fmaf(wa1[3], x0.w, fmaf(wa1[2], x0.z, fmaf(wa1[1], x0.y, fmaf(wa1[0], x0.x, ba1))));
+            if (a.K > 4) {
+                const f32x4 x1 = *(const f32x4 *)(xw + r * AB_MAX_STATS + 4);
+                h0 = fmaf(wa0[7], x1.w, fmaf(wa0[6], x1.z, fmaf(wa0[5], x1.y, fmaf(wa0[4], x1.x, h0))));
+                h1 = fmaf(wa1[7], x1.w, fmaf(wa1[6], x1.z, fmaf(wa1[5], x1.y, fmaf(wa1[4], x1.x, h1))));
             }
-#pragma unroll
-            for (int c2 = 0; c2 < 2; ++c2) {
-                i32x4 v;
-                v.x = (int)pack_bf16x2(hv[c2 * 8 + 0], hv[c2 * 8 + 1]);
-                v.y = (int)pack_bf16x2(hv[c2 * 8 + 2], hv[c2 * 8 + 3]);
-                v.z = (int)pack_bf16x2(hv[c2 * 8 + 4], hv[c2 * 8 + 5]);
-                v.w = (int)pack_bf16x2(hv[c2 * 8 + 6], hv[c2 * 8 + 7]);
-                const int chunk = (t & 7) * 2 + c2;                        // 16 chunks per 256-byte row
-                *(i32x4 *)(hbuf + r * 256 + ((chunk ^ (r & 15)) << 4)) = v;
-            }
+            const uint32_t pk = pack_bf16x2(relu_keep_nan(h0), relu_keep_nan(h1));
+            *(uint32_t *)(hb + r * 256 + (((lane >> 2) ^ (r & 15)) << 4) + (lane & 3) * 4) = pk;
         }
-        __syncthreads();
-        f32x16 acc;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        f32x16 acc[4];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+        for (int jn = 0; jn < 4; ++jn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[jn][r] = 0.f;
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             const int chunk = q * 2 + half;
-            const i32x4 fa = *(const i32x4 *)(hbuf + (lane & 31) * 256 + ((chunk ^ sw) << 4));
-            // operand roles: rows = tensors (from LDS), columns = this wave's outputs (registers)
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa),
-                                                          __builtin_bit_cast(bf16x8, wb[q]), acc, 0, 0, 0);
+            const i32x4 fa = *(const i32x4 *)(hb + l31 * 256 + ((chunk ^ (l31 & 15)) << 4));
+#pragma unroll
+            for (int jn = 0; jn < 4; ++jn) {
+                const int n = jn * 32 + l31;
+                const i32x4 fb = *(const i32x4 *)(wb_s + n * 256 + ((chunk ^ (n & 15)) << 4));
+                // rows = tensors (first operand), columns = units (second operand)
+                acc[jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa),
+                                                                  __builtin_bit_cast(bf16x8, fb), acc[jn], 0, 0, 0);
+            }
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int l = l0 + (r >> 2) * 8 + half * 4 + (r & 3);
-            if (l < a.L) colsum += relu_keep_nan(acc[r] + bb);
+            if (l < a.L) {
+#pragma unroll
+                for (int jn = 0; jn < 4; ++jn) colsum[jn] += relu_keep_nan(acc[jn][r] + bb[jn]);
+            }
         }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // fragment reads done before the block buffer is reused
     }
-    colsum += __shfl_xor(colsum, 32, 64);
-    if (half == 0) {
-        const float pooled = colsum / (float)a.L;
-        const int64_t o = s * a.ld + wave * 32 + lane;
+#pragma unroll
+    for (int jn = 0; jn < 4; ++jn) {
+        const float v = colsum[jn] + __shfl_xor(colsum[jn], 32, 64);
+        if (half == 0) red[wave][jn * 32 + l31] = v;
+    }
+    __syncthreads();
+    if (t < H) {
+        const float pooled = ((red[0][t] + red[1][t]) + (red[2][t] + red[3][t])) / (float)a.L;
+        const int64_t o = s * a.ld + t;
         if constexpr (sizeof(T) == 2) ((uint16_t *)a.xs)[o] = (uint16_t)(pack_bf16x2(pooled, 0.f) & 0xffffu);
         else ((float *)a.xs)[o] = pooled;
     }
