@@ -42,7 +42,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--scenarios", type=int, default=None, help="override the scenario count (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -104,7 +104,7 @@ def main():
         ws = ab.alloc_workspace(d, S, Cn, device=dev)
         dyn, scal = torch.from_numpy(w.dyn).to(dev), torch.from_numpy(w.scal).to(dev)
         part, cred = torch.from_numpy(w.part).to(dev), torch.from_numpy(w.cred).to(dev)
-        want_scores = (cfg == 3)
+        want_scores = cfg in (1, 3)
         scores = torch.empty(S, Cn, dtype=torch.float32, device=dev) if want_scores else None
         idx = torch.empty(S, dtype=torch.int32, device=dev)
         best = torch.empty(S, dtype=torch.float32, device=dev)
@@ -115,7 +115,7 @@ def main():
         units_per_step = S * Cn
         metric, unit = "candidate configs scored/sec (meta-net fwd+argmax)", "candidates/s"
         dtype = w.dtype
-        steps = args.steps if args.steps is not None else (10 if cfg == 3 else 20)
+        steps = args.steps if args.steps is not None else {1: 500, 3: 10}.get(cfg, 20)
         warmup = args.warmup if args.warmup is not None else 2
         H = list(w.hidden)
         flops_per_unit = H[0] + sum(2.0 * H[i] * H[i + 1] for i in range(len(H) - 1)) + 2.0 * H[-1]
@@ -211,7 +211,7 @@ def main():
             cpu = {"value": n_rows / dt, "unit": unit, "cores": orc.num_threads(), "kind": "oracle",
                    "sample": "one fp64 step on the first %d rows of minibatch 0 (%.1f s)" % (n_rows, dt)}
         else:
-            n_s = {2: 8, 3: 96, 5: 24}[cfg]
+            n_s = {1: 1, 2: 8, 3: 96, 5: 24}[cfg]
             n_s = min(n_s, w.S)
             sub = w.subset(np.arange(n_s))
             t0 = time.perf_counter()
