@@ -273,13 +273,21 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(const GemmArgs g)
                 }
             }
         __syncthreads();
+        // thread -> 16-byte chunk (t & 31) of rows (t >> 5) + 16 it: all LDS reads first, then the stores
+        {
+            const unsigned char *src = smem + (t >> 5) * OUT_STRIDE + (t & 31) * 16;
+            uint16_t *dst = (uint16_t *)g.out + (m0 + (t >> 5)) * g.ldo + n0 + (t & 31) * 8;
+            const int64_t step = 16 * g.ldo;
+            i32x4 v[16];
 #pragma unroll
-        for (int it = 0; it < 16; ++it) {
-            const int cid = t + 512 * it;
-            const int row = cid >> 5, ch = cid & 31;
-            if (m0 + row < g.M) {
-                const i32x4 v = *(const i32x4 *)(smem + row * OUT_STRIDE + ch * 16);
-                __builtin_nontemporal_store(v, (i32x4 *)((uint16_t *)g.out + (m0 + row) * g.ldo + n0 + ch * 8));
+            for (int it = 0; it < 16; ++it) v[it] = *(const i32x4 *)(src + it * 16 * OUT_STRIDE);
+            if (m0 + BM <= g.M) {
+#pragma unroll
+                for (int it = 0; it < 16; ++it) __builtin_nontemporal_store(v[it], (i32x4 *)(dst + it * step));
+            } else {
+#pragma unroll
+                for (int it = 0; it < 16; ++it)
+                    if (m0 + (t >> 5) + 16 * it < g.M) __builtin_nontemporal_store(v[it], (i32x4 *)(dst + it * step));
             }
         }
     } else {   // EPI_SCORE
