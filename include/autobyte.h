@@ -14,6 +14,7 @@
  *   ab_score_candidates  predicted V for every (scenario, candidate), optionally fused with the choice
  *   ab_select_best       per-scenario argmax over a stored score matrix
  *   ab_online_update     one forward + backward + Adam step on explicit (statistics, candidate, V) rows
+ *   ab_trigger           the choice plus the two threshold tests of the Optimization Trigger
  *
  * General rules
  *   - Every pointer marked DEVICE is HIP device memory on the current device, owned by the caller.  The
@@ -161,6 +162,25 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
  */
 ab_status ab_select_best(const float *scores, int64_t S, int32_t C, int64_t row_stride,
                          int32_t *best_idx, float *best_score, void *stream);
+
+/*
+ * Optimization Trigger (Section 3.3 "Optimization trigger"), fused with the choice, on a stored score matrix.
+ * Per scenario s, with V_cur = scores[s, current_idx[s]] and V_best the largest non-NaN score:
+ *   best_idx[s]     as ab_select_best
+ *   gain[s]         (V_best - V_cur) / |V_cur|                      (optional)
+ *   reconfigure[s]  1 if gain >= gain_threshold, else 0             (the paper skips attempts below 5 %)
+ *   adapt[s]        1 if |V_cur - observed[s]| / |observed[s]| > error_threshold, else 0 (the paper starts
+ *                   online adaptation above 10 %); optional, needs `observed`
+ * All arithmetic is IEEE single precision.  No valid best candidate, or current_idx[s] outside [0, C):
+ * gain = NaN, reconfigure = 0, adapt = 0.
+ *   scores DEVICE fp32 (row s at scores + s*row_stride), current_idx DEVICE [S] int32, observed DEVICE [S] fp32
+ *   or NULL, best_idx DEVICE [S] int32, gain DEVICE [S] fp32 or NULL, reconfigure DEVICE [S] uint8,
+ *   adapt DEVICE [S] uint8 or NULL (must be NULL when observed is NULL).
+ */
+ab_status ab_trigger(const float *scores, int64_t S, int32_t C, int64_t row_stride,
+                     const int32_t *current_idx, const float *observed,
+                     float gain_threshold, float error_threshold,
+                     int32_t *best_idx, float *gain, uint8_t *reconfigure, uint8_t *adapt, void *stream);
 
 /*
  * One online-adaptation step of the flat model (tensor_encoder = 0) on a minibatch of B observed rows:

@@ -268,6 +268,49 @@ int orc_select(const double *scores, int64_t S, int C, int64_t row_stride,
 }
 
 /*
+ * Optimization Trigger (Section 3.3 "Optimization trigger") on a stored score matrix:
+ *   best    = candidate with the largest predicted V (rules of orc_select)
+ *   gain    = (V_best - V_cur) / |V_cur|, V_cur = score of the configuration the job runs now
+ *   reconf  = 1 if gain >= gain_threshold (the paper skips the attempt when the gain is below 5 %)
+ *   adapt   = 1 if |V_cur - V_obs| / |V_obs| > error_threshold (the paper starts online adaptation when
+ *             prediction and observed speed differ by more than 10 %)
+ * The two decisions are taken in single precision on single-precision scores, the precision in which
+ * the scores are stored, so that an implementation can agree bit for bit.  A scenario without a valid
+ * best candidate, or whose current index is outside [0, C), gets gain = NaN and reconf = 0; adapt is 0
+ * when its ratio is NaN.
+ */
+int orc_trigger(const float *scores, int64_t S, int C, int64_t row_stride, const int32_t *cur_idx,
+                const float *observed, float gain_threshold, float error_threshold,
+                int32_t *best_idx, float *gain, uint8_t *reconf, uint8_t *adapt)
+{
+    if (!scores || !cur_idx || !best_idx || !reconf || S < 0 || C <= 0 || row_stride < C) return ORC_ERR_ARG;
+    for (int64_t s = 0; s < S; ++s) {
+        const float *r = scores + (size_t)s * (size_t)row_stride;
+        int bi = -1;
+        float bv = -INFINITY;
+        for (int c = 0; c < C; ++c) {
+            float v = r[c];
+            if (v != v) continue;
+            if (bi < 0 || v > bv) { bv = v; bi = c; }
+        }
+        best_idx[s] = bi;
+        const int ci = cur_idx[s];
+        const int cur_ok = ci >= 0 && ci < C;
+        const float vc = cur_ok ? r[ci] : NAN;
+        float g = NAN;
+        if (bi >= 0 && cur_ok) g = (bv - vc) / fabsf(vc);
+        if (gain) gain[s] = g;
+        reconf[s] = (uint8_t)(g >= gain_threshold);          /* false for NaN */
+        if (adapt) {
+            float e = NAN;
+            if (observed && cur_ok) e = fabsf(vc - observed[s]) / fabsf(observed[s]);
+            adapt[s] = (uint8_t)(e > error_threshold);
+        }
+    }
+    return ORC_OK;
+}
+
+/*
  * One online-adaptation step of the flat-feature scorer (Section 3.2 "Offline training online
  * adapting"; loss per Eq. 2 read as the mean squared error over the minibatch).
  *

@@ -206,6 +206,30 @@ def select(scores, row_stride: Optional[int] = None):
     return idx, best, second
 
 
+def trigger(scores, cur_idx, observed=None, gain_threshold=0.05, error_threshold=0.10, row_stride=None):
+    """Optimization Trigger on float32 scores [S, C]: returns (best_idx, gain, reconfigure, adapt)."""
+    lib = _load()
+    scores = np.ascontiguousarray(np.asarray(scores, dtype=np.float32))
+    S, Cn = scores.shape
+    stride = Cn if row_stride is None else int(row_stride)
+    Cn = Cn if row_stride is None else Cn
+    cur = np.ascontiguousarray(np.asarray(cur_idx, dtype=np.int32))
+    obs = None if observed is None else np.ascontiguousarray(np.asarray(observed, dtype=np.float32))
+    best = np.empty(S, dtype=np.int32)
+    gain = np.empty(S, dtype=np.float32)
+    reconf = np.empty(S, dtype=np.uint8)
+    adapt = np.empty(S, dtype=np.uint8)
+    fp = C.POINTER(C.c_float)
+    _check(lib.orc_trigger(scores.ctypes.data_as(fp), C.c_int64(S), C.c_int(Cn), C.c_int64(stride),
+                           cur.ctypes.data_as(C.POINTER(C.c_int32)),
+                           obs.ctypes.data_as(fp) if obs is not None else None,
+                           C.c_float(gain_threshold), C.c_float(error_threshold),
+                           best.ctypes.data_as(C.POINTER(C.c_int32)), gain.ctypes.data_as(fp),
+                           reconf.ctypes.data_as(C.POINTER(C.c_uint8)),
+                           adapt.ctypes.data_as(C.POINTER(C.c_uint8))), "trigger")
+    return best, gain, reconf.astype(bool), adapt.astype(bool)
+
+
 @dataclass
 class TrainState:
     """Master parameters and Adam moments (float64), updated in place by :func:`update`."""

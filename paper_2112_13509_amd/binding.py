@@ -81,6 +81,9 @@ def load():
                                             _vp, _vp, _vp, _vp, C.c_size_t, _vp]
         lib.ab_select_best.restype = C.c_int32
         lib.ab_select_best.argtypes = [_vp, C.c_int64, C.c_int32, C.c_int64, _vp, _vp, _vp]
+        lib.ab_trigger.restype = C.c_int32
+        lib.ab_trigger.argtypes = [_vp, C.c_int64, C.c_int32, C.c_int64, _vp, _vp, C.c_float, C.c_float,
+                                   _vp, _vp, _vp, _vp, _vp]
         lib.ab_online_update.restype = C.c_int32
         lib.ab_online_update.argtypes = [C.POINTER(ab_model_desc), C.POINTER(ab_params), _vp, _vp,
                                          C.c_int64, C.c_float, C.c_float, C.c_float, C.c_float,
@@ -300,6 +303,32 @@ def ab_select_best(scores: torch.Tensor, best_idx: torch.Tensor, best_score: Opt
                             _ptr(best_score, torch.float32, "best_score"), _stream_handle(stream))
     if check and rc != 0:
         raise AutoByteError(rc, "ab_select_best")
+    return rc
+
+
+def ab_trigger(scores: torch.Tensor, current_idx: torch.Tensor, best_idx: torch.Tensor,
+               reconfigure: torch.Tensor, observed: Optional[torch.Tensor] = None,
+               gain: Optional[torch.Tensor] = None, adapt: Optional[torch.Tensor] = None,
+               gain_threshold: float = 0.05, error_threshold: float = 0.10, C_: Optional[int] = None,
+               row_stride: Optional[int] = None, stream=None, check: bool = True) -> int:
+    """Choice plus the Optimization Trigger's two threshold tests on ``scores`` [S, row_stride]."""
+    lib = load()
+    if scores.dim() != 2:
+        raise ValueError("scores must be 2-D")
+    S = int(scores.shape[0])
+    row_stride = int(scores.shape[1]) if row_stride is None else int(row_stride)
+    C_ = row_stride if C_ is None else int(C_)
+    for t, what in ((current_idx, "current_idx"), (best_idx, "best_idx"), (reconfigure, "reconfigure"),
+                    (observed, "observed"), (gain, "gain"), (adapt, "adapt")):
+        if t is not None and t.numel() != S:
+            raise ValueError("%s must have one element per row" % what)
+    rc = lib.ab_trigger(_ptr(scores, torch.float32, "scores"), S, C_, row_stride,
+                        _ptr(current_idx, torch.int32, "current_idx"), _ptr(observed, torch.float32, "observed"),
+                        gain_threshold, error_threshold, _ptr(best_idx, torch.int32, "best_idx"),
+                        _ptr(gain, torch.float32, "gain"), _ptr(reconfigure, torch.uint8, "reconfigure"),
+                        _ptr(adapt, torch.uint8, "adapt"), _stream_handle(stream))
+    if check and rc != 0:
+        raise AutoByteError(rc, "ab_trigger")
     return rc
 
 

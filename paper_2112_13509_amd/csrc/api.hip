@@ -293,6 +293,28 @@ ab_status ab_select_best(const float *scores, int64_t S, int32_t C, int64_t row_
     return AB_OK;
 }
 
+ab_status ab_trigger(const float *scores, int64_t S, int32_t C, int64_t row_stride,
+                     const int32_t *current_idx, const float *observed,
+                     float gain_threshold, float error_threshold,
+                     int32_t *best_idx, float *gain, uint8_t *reconfigure, uint8_t *adapt, void *stream)
+{
+    if (!scores || !current_idx || !best_idx || !reconfigure) return AB_ERR_NULL;
+    if (adapt && !observed) return AB_ERR_NULL;
+    if (S < 0 || C <= 0 || row_stride < C) return AB_ERR_SHAPE;
+    if (misaligned(scores, 4) || misaligned(current_idx, 4) || misaligned(observed, 4) ||
+        misaligned(best_idx, 4) || misaligned(gain, 4)) return AB_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    for (int64_t s0 = 0; s0 < S; s0 += (1 << 30)) {
+        const int64_t ns = (S - s0 < (1 << 30)) ? S - s0 : (1 << 30);
+        TraceScope ts("trigger", (double)ns * (C * 4.0 + 16.0), 1, st);
+        AB_HIP(launch_trigger(scores + s0 * row_stride, ns, C, row_stride, current_idx + s0,
+                              observed ? observed + s0 : nullptr, gain_threshold, error_threshold,
+                              best_idx + s0, gain ? gain + s0 : nullptr, reconfigure + s0,
+                              adapt ? adapt + s0 : nullptr, st));
+    }
+    return AB_OK;
+}
+
 ab_status ab_online_update(const ab_model_desc *desc, ab_params *params,
                            const float *x_raw, const float *target, int64_t B,
                            float lr, float beta1, float beta2, float eps,

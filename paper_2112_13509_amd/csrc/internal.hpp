@@ -40,6 +40,9 @@ hipError_t launch_prep_layer1(int dtype, const ab_model_desc *d, const void *W1,
 hipError_t launch_finish_select(const float *partial, int nt, int64_t row_stride, const float *b_out,
                                 float *scores, int64_t score_stride, int32_t *best_idx, float *best_score,
                                 int64_t S, int C, hipStream_t st);
+hipError_t launch_trigger(const float *scores, int64_t S, int C, int64_t row_stride, const int32_t *cur_idx,
+                          const float *observed, float gain_threshold, float error_threshold, int32_t *best_idx,
+                          float *gain, uint8_t *reconf, uint8_t *adapt, hipStream_t st);
 hipError_t launch_score_single_hidden(const float *a_term, const float *b_term, const float *w_out_f,
                                       float *partial, int64_t rows, int C, int H, hipStream_t st);
 hipError_t launch_tensor_encoder(int dtype, const ab_model_desc *d, const float *dyn, const void *Wa,

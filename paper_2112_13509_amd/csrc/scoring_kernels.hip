@@ -221,6 +221,48 @@ __global__ __launch_bounds__(256) void finish_select_kernel(const FinishArgs a)
     }
 }
 
+// Optimization Trigger (Section 3.3): argmax of a stored score row, relative gain over the configuration in
+// use, and the two threshold tests.  One work-group per scenario; IEEE single precision throughout.
+struct TriggerArgs {
+    const float *scores; int64_t row_stride; int32_t C;
+    const int32_t *cur_idx; const float *observed;
+    float gain_threshold, error_threshold;
+    int32_t *best_idx; float *gain; uint8_t *reconf; uint8_t *adapt;
+};
+
+__global__ __launch_bounds__(256) void trigger_kernel(const TriggerArgs a)
+{
+    const int64_t s = blockIdx.x;
+    const float *p = a.scores + s * a.row_stride;
+    float bv = -INFINITY;
+    int bi = AB_NONE;
+    for (int c = threadIdx.x; c < a.C; c += 256) amax_take(bv, bi, p[c], c);
+    amax_wave(bv, bi);
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { sv[wave] = bv; si[wave] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w) amax_take(bv, bi, sv[w], si[w]);
+        const bool has_best = bi != AB_NONE;
+        a.best_idx[s] = has_best ? bi : -1;
+        const int ci = a.cur_idx[s];
+        const bool cur_ok = ci >= 0 && ci < a.C;
+        const float nan = __uint_as_float(0x7fc00000u);
+        const float vc = cur_ok ? p[ci] : nan;
+        float g = nan;
+        if (has_best && cur_ok) g = (bv - vc) / fabsf(vc);
+        if (a.gain) a.gain[s] = g;
+        a.reconf[s] = (uint8_t)(g >= a.gain_threshold);
+        if (a.adapt) {
+            float e = nan;
+            if (a.observed && cur_ok) e = fabsf(vc - a.observed[s]) / fabsf(a.observed[s]);
+            a.adapt[s] = (uint8_t)(e > a.error_threshold);
+        }
+    }
+}
+
 // Scorer with a single hidden layer: score = w_out . relu(A[s] + B[c]) + b_out, one wavefront per
 // (scenario, candidate) row, written into the same partial buffer layout (nt = 1, no bias yet).
 struct ScoreD1Args { const float *a_term, *b_term, *w_out_f; float *partial; int64_t rows; int32_t C, H; };
@@ -434,6 +476,16 @@ hipError_t launch_finish_select(const float *partial, int nt, int64_t row_stride
     a.partial = partial; a.nt = nt; a.row_stride = row_stride; a.b_out = b_out; a.scores = scores;
     a.score_stride = score_stride; a.best_idx = best_idx; a.best_score = best_score; a.C = C;
     finish_select_kernel<<<(unsigned)S, 256, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_trigger(const float *scores, int64_t S, int C, int64_t row_stride, const int32_t *cur_idx,
+                          const float *observed, float gain_threshold, float error_threshold, int32_t *best_idx,
+                          float *gain, uint8_t *reconf, uint8_t *adapt, hipStream_t st)
+{
+    if (S == 0) return hipSuccess;
+    TriggerArgs a{scores, row_stride, C, cur_idx, observed, gain_threshold, error_threshold, best_idx, gain, reconf, adapt};
+    trigger_kernel<<<(unsigned)S, 256, 0, st>>>(a);
     return hipGetLastError();
 }
 

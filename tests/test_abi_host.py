@@ -25,7 +25,7 @@ def test_exports_every_declared_symbol(lib):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(ab_[a-z_]+)\s*\(", header))
     assert {"ab_score_candidates", "ab_select_best", "ab_online_update", "ab_workspace_bytes",
-            "ab_status_string", "ab_version"} <= names
+            "ab_status_string", "ab_version", "ab_trigger", "ab_set_trace"} <= names
     for n in names:
         assert hasattr(lib, n), n
     assert ab.ab_version() >= 100
@@ -113,10 +113,17 @@ def test_select_and_update_argument_errors(lib):
     assert lib.ab_select_best(0x1000, 4, 8, 4, 0x2000, None, None) == -2       # stride < C
     assert lib.ab_select_best(0x1002, 4, 4, 4, 0x2000, None, None) == -4
     assert lib.ab_select_best(0x1000, 0, 4, 4, 0x2000, None, None) == 0
+    f = C.c_float
+    trig = lambda sc=0x1000, S=4, Cn=4, st=4, cur=0x2000, obs=0x3000, best=0x4000, gain=None, rec=0x5000, ad=None: \
+        lib.ab_trigger(sc, S, Cn, st, cur, obs, f(0.05), f(0.1), best, gain, rec, ad, None)
+    assert trig(sc=None) == -1 and trig(cur=None) == -1 and trig(best=None) == -1 and trig(rec=None) == -1
+    assert trig(obs=None, ad=0x6000) == -1                                     # adapt needs observations
+    assert trig(Cn=0) == -2 and trig(Cn=8, st=4) == -2 and trig(S=-1) == -2
+    assert trig(sc=0x1001) == -4
+    assert trig(S=0) == 0
     u = wl.make_update(N=64, batch=64, L=2, hidden=(64,))
     d = ab.desc_from_workload(u)
     p = ab.ab_params()
-    f = C.c_float
     call = lambda prm, x=0x1000, y=0x2000, B=64, ws=0x100000, n=1 << 40: lib.ab_online_update(
         C.byref(d), C.byref(prm), x, y, B, f(1e-3), f(0.9), f(0.999), f(1e-8), None, ws, n, None)
     assert call(p) == -1

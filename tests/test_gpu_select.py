@@ -54,3 +54,34 @@ def test_large_matrix_matches_oracle():
     idx, best = run_select(sc)
     ridx, rbest, _ = orc.select(sc)
     assert (idx == ridx).all() and (best == rbest.astype(np.float32)).all()
+
+
+def test_trigger_matches_oracle_bit_for_bit():
+    rng = np.random.default_rng(9)
+    for S, Cn, stride in [(1, 1, 1), (257, 64, 64), (1000, 300, 320), (4096, 4096, 4096)]:
+        sc = (1.0 + 0.2 * rng.standard_normal((S, stride))).astype(np.float32)
+        sc[rng.random(sc.shape) < 0.01] = np.nan
+        if S > 3:
+            sc[3, :] = np.nan
+        cur = rng.integers(-1, Cn + 1, S).astype(np.int32)           # a few out-of-range indices
+        obs = (1.0 + 0.2 * rng.standard_normal(S)).astype(np.float32)
+        obs[rng.random(S) < 0.02] = 0.0
+        t = lambda a: torch.from_numpy(a).to(DEV)
+        best = torch.full((S,), -9, dtype=torch.int32, device=DEV)
+        gain = torch.zeros(S, dtype=torch.float32, device=DEV)
+        rec = torch.full((S,), 7, dtype=torch.uint8, device=DEV)
+        ad = torch.full((S,), 7, dtype=torch.uint8, device=DEV)
+        ab.ab_trigger(t(sc), t(cur), best, rec, observed=t(obs), gain=gain, adapt=ad, C_=Cn, row_stride=stride)
+        torch.cuda.synchronize()
+        rb, rg, rr, ra = orc.trigger(sc[:, :Cn].copy(), cur, obs)
+        assert (best.cpu().numpy() == rb).all()
+        g = gain.cpu().numpy()
+        assert ((g == rg) | (np.isnan(g) & np.isnan(rg))).all()
+        assert (rec.cpu().numpy().astype(bool) == rr).all() and (ad.cpu().numpy().astype(bool) == ra).all()
+    # optional outputs may be left out
+    best = torch.zeros(4, dtype=torch.int32, device=DEV)
+    rec = torch.zeros(4, dtype=torch.uint8, device=DEV)
+    sc = torch.tensor([[1.0, 1.06], [1.0, 1.04], [2.0, 1.0], [1.0, 1.0]], device=DEV)
+    ab.ab_trigger(sc, torch.zeros(4, dtype=torch.int32, device=DEV), best, rec)
+    torch.cuda.synchronize()
+    assert best.tolist() == [1, 1, 0, 0] and rec.tolist() == [1, 0, 0, 0]
