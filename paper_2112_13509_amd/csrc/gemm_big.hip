@@ -27,6 +27,15 @@ namespace ab {
 
 typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void global_void;
+typedef float f32x8_unaligned __attribute__((ext_vector_type(8), aligned(4)));
+typedef __attribute__((address_space(4))) f32x8_unaligned const_f32x8;   // read-only for the whole launch: scalar loads
+// Eight consecutive floats at a wave-uniform address, fetched through the scalar cache into scalar registers.
+__device__ __forceinline__ f32x8_unaligned scalar_load8(const float *p)
+{
+    f32x8_unaligned v = *(const const_f32x8 *)(uintptr_t)p;
+    asm volatile("" : "+s"(v));
+    return v;
+}
 
 // 64 lanes x 16 bytes; lane l's data lands at lds_uniform_dst + 16*l.  STREAM marks the access
 // non-temporal: activation panels and outputs pass through L2 once per XCD and should not push the
@@ -319,6 +328,339 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(const GemmArgs g)
     }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// Streaming form of the same tile for operands that are read from memory: a grid of one work-group
+// per compute unit, each walking its tiles in the order the one-tile-per-work-group launch would have
+// handed them out (id = block + q * grid; id & 7 = XCD).  The slab rings run on across tile borders, so
+// the first three slabs of the next tile are already under way while the current tile finishes, and
+// the stores of a tile drain under the next tile's matrix work:
+//   - at the last slab of a tile the W stage is refilled as usual, the A stage that was just retired
+//     serves as staging room for the output (4 KB private to each wavefront: 32 rows x 64 columns per
+//     pass, four passes, no work-group barrier in between) and is refilled after the epilogue;
+//   - every slab fetch is issued unconditionally (past the end of the stream the last tile is
+//     fetched again into stages nobody reads), so the number of memory operations between any two
+//     points is fixed and every wait can name exactly how many younger operations may stay in
+//     flight: 4 (the A slab two ahead) in a tile, plus the stores of the epilogue and the next tile's
+//     bias fetch at the first slab after it.  Loads and stores retire in issue order.
+//   - bias (and output weights) are read through the scalar cache in the epilogue, so no ordinary
+//     vector load has to be waited for while slab fetches are in flight.
+//
+// LDS stores the compiler does not see as such: it orders every LDS store it knows of behind all
+// global->LDS DMA in flight (a full vmcnt drain), which the staging writes of the epilogue must not do;
+// the stage they go to has been retired by the barrier before.  LDS operations of a wavefront execute
+// in order, so the reads that follow see the data.
+__device__ __forceinline__ void lds_write8(void *p, uint2 v)
+{
+    asm volatile("ds_write_b64 %0, %1" ::"v"((uint32_t)(uintptr_t)(lds_void *)p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_write4(void *p, float v)
+{
+    asm volatile("ds_write_b32 %0, %1" ::"v"((uint32_t)(uintptr_t)(lds_void *)p), "v"(v) : "memory");
+}
+
+template <int EPI>
+__global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
+{
+    constexpr int BM = 256, BK = 64;
+    constexpr int SLAB = BM * 128;
+    constexpr int W_BASE = 3 * SLAB;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);           // (scalar: addresses and branches on it stay scalar)
+    const int wave_m = wave >> 2, wave_n = wave & 3;
+    const int half = lane >> 5, l31 = lane & 31;
+    const int KT = g.K / BK;
+    // Values that are only needed once per tile are derived from an opaque copy of the lane id at the
+    // place of use, so that they do not occupy registers during the matrix loop.
+    auto opaque_lane = [&]() { int v = lane; asm volatile("" : "+v"(v)); return v; };
+
+    // ---- this work-group's tiles: local index l0 + q * G8 on XCD xcd, q < n_my
+    const unsigned G8 = gridDim.x >> 3, xcd = blockIdx.x & 7, l0 = blockIdx.x >> 3;
+    const unsigned n_tiles = (unsigned)g.n_tiles;
+    const unsigned panels = (unsigned)g.m_tiles > xcd ? ((unsigned)g.m_tiles - xcd + 7) / 8 : 0;
+    const unsigned n_local = panels * n_tiles;
+    if (l0 >= n_local) return;
+    const unsigned n_my = (n_local - l0 + G8 - 1) / G8;
+
+    // ---- DMA sources: a wave-uniform byte pointer per operand (advanced per slab on the scalar unit) plus
+    // four 32-bit per-lane byte offsets (row dma_r0 + 64 i, chunk dma_cc)
+    // lane l of wavefront w fetches logical chunk (l & 7) ^ ((w & 1) * 4 + (l >> 4)) of row w * 8 + (l >> 3) + 64 i
+    const unsigned char *a_base, *w_base;
+    uint32_t a_off[4], w_off[4];
+    auto set_w = [&](unsigned q) {
+        const unsigned local = l0 + q * G8;
+        w_base = (const unsigned char *)g.B + (int64_t)(local % n_tiles) * 256 * g.ldb * 2;
+        const int ln = opaque_lane();
+        const int dma_cc = (ln & 7) ^ ((wave & 1) * 4 + (ln >> 4)), dma_r0 = wave * 8 + (ln >> 3);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w_off[i] = (uint32_t)(dma_r0 + 64 * i) * (uint32_t)g.ldb * 2u + dma_cc * 16;
+    };
+    auto set_a = [&](unsigned q) {
+        const unsigned local = l0 + q * G8;
+        const int64_t m0 = ((int64_t)(local / n_tiles) * 8 + xcd) * BM;
+        a_base = (const unsigned char *)g.A + m0 * g.lda * 2;
+        const int64_t rows_left = g.M - m0;                 // >= 1; rows past the end re-read the last row
+        const int ln = opaque_lane();
+        const int dma_cc = (ln & 7) ^ ((wave & 1) * 4 + (ln >> 4)), dma_r0 = wave * 8 + (ln >> 3);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int r = dma_r0 + 64 * i;
+            if (r > rows_left - 1) r = (int)(rows_left - 1);
+            a_off[i] = (uint32_t)r * (uint32_t)g.lda * 2u + dma_cc * 16;
+        }
+    };
+    unsigned wq = 0, aq = 0;
+    int wkt = 0, akt = 0;
+    auto fetch_w = [&](int slot) {
+        unsigned char *sb = smem + W_BASE + slot * SLAB;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dma16<false>(w_base + w_off[i], sb + (wave + 8 * i) * 1024);
+        w_base += BK * 2;
+        if (++wkt == KT) { wkt = 0; if (wq + 1 < n_my) ++wq; set_w(wq); }
+    };
+    auto fetch_a = [&](int slot) {
+        unsigned char *sb = smem + slot * SLAB;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dma16<true>(a_base + a_off[i], sb + (wave + 8 * i) * 1024);
+        a_base += BK * 2;
+        if (++akt == KT) { akt = 0; if (aq + 1 < n_my) ++aq; set_a(aq); }
+    };
+
+    // ---- fragment read offsets
+    const int sw = (l31 >> 1) & 7;
+    int rd[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) rd[q] = l31 * 128 + ((((q << 1) | half) ^ sw) << 4);
+    const int a_rd = wave_m * 128 * 128;
+    const int w_rd = W_BASE + wave_n * 64 * 128;
+
+    f32x16 acc[2][4];
+    auto zero_acc = [&]() {
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+            for (int im = 0; im < 4; ++im)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[jn][im][r] = 0.f;
+    };
+    zero_acc();
+
+    i32x4 fa[2][4], fw[2][2];
+    auto load_frags = [&](int a_slot, int w_slot, int q, int set) {
+        const unsigned char *sa = smem + a_slot * SLAB + a_rd;
+        const unsigned char *sw_ = smem + w_slot * SLAB + w_rd;
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn) fw[set][jn] = *(const i32x4 *)(sw_ + jn * 4096 + rd[q]);
+#pragma unroll
+        for (int im = 0; im < 4; ++im) fa[set][im] = *(const i32x4 *)(sa + im * 4096 + rd[q]);
+    };
+    auto mma = [&](int set) {
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+            for (int im = 0; im < 4; ++im)
+                acc[jn][im] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8, fw[set][jn]), __builtin_bit_cast(bf16x8, fa[set][im]),
+                    acc[jn][im], 0, 0, 0);
+    };
+
+    // per-tile state of the computing side
+    int64_t m0 = 0;
+    int n0 = 0;
+    unsigned tn = 0;
+    auto begin_tile = [&](unsigned q) {
+        const unsigned local = l0 + q * G8;
+        tn = local % n_tiles;
+        n0 = (int)tn * 256;
+        m0 = ((int64_t)(local / n_tiles) * 8 + xcd) * BM;
+    };
+
+    // vmcnt immediates in use: in a tile 4; at the first slab after an epilogue 4 + its stores.
+    // A stricter wait than needed is always safe.
+    constexpr int EPI_OPS_LOW = EPI == EPI_STORE ? 16 : 1;              // wavefronts 0..3
+    constexpr int EPI_OPS_HIGH = EPI == EPI_STORE ? 16 : 0;             // wavefronts 4..7 (no partial store)
+
+    // ---- prologue
+    begin_tile(0);
+    set_w(0); set_a(0);
+    fetch_a(0); fetch_w(0); fetch_a(1); fetch_w(1); fetch_a(2);
+    asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    AB_FENCE();
+    load_frags(0, 0, 0, 0);
+
+    int a_slot = 0, w_slot = 0, kt = 0;
+    unsigned q = 0;
+    bool after_epilogue = false;
+    while (true) {
+        AB_FENCE();
+        load_frags(a_slot, w_slot, 1, 1);
+        mma(0);
+        AB_INTERLEAVE_6();
+        AB_FENCE();
+        load_frags(a_slot, w_slot, 2, 0);
+        mma(1);
+        AB_INTERLEAVE_6();
+        AB_FENCE();
+        load_frags(a_slot, w_slot, 3, 1);
+        mma(0);
+        AB_INTERLEAVE_6();
+        AB_FENCE();
+        // the next slab (both operands) must have landed; younger operations may stay in flight
+        if (!after_epilogue) {
+            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        } else if (wave < 4) {
+            if constexpr (EPI == EPI_STORE) asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
+            else                            asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+        } else {
+            if constexpr (EPI == EPI_STORE) asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
+            else                            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        }
+        static_assert(EPI_OPS_LOW + 4 == (EPI == EPI_STORE ? 20 : 5) && EPI_OPS_HIGH + 4 == (EPI == EPI_STORE ? 20 : 4), "");
+        after_epilogue = false;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        AB_FENCE();
+        const bool last = kt == KT - 1;
+        fetch_w(w_slot);
+        if (!last) fetch_a(a_slot);
+        AB_FENCE();
+        const int na = a_slot == 2 ? 0 : a_slot + 1, nw = w_slot ^ 1;
+        load_frags(na, nw, 0, 0);
+        mma(1);
+        AB_INTERLEAVE_6();
+        AB_FENCE();
+        if (last) {
+            // ------------------------------------------------------------ epilogue of tile q
+            unsigned char *stage = smem + a_slot * SLAB;
+            const bool ragged = m0 + BM > g.M;
+            const int ln = opaque_lane();
+            const int half = ln >> 5, l31 = ln & 31, sw = (l31 >> 1) & 7;
+            // bias (and output weights) of this wavefront's 64 columns arrive through the scalar cache:
+            // no vector-memory traffic, so nothing here has to wait for the slab fetches in flight
+            const float *bias_s = g.bias + n0 + wave_n * 64;
+            if constexpr (EPI == EPI_STORE) {
+                unsigned char *mine = stage + wave * 4096;
+                const int rrow = ln >> 3, rch = ln & 7;
+                uint16_t *dst = (uint16_t *)g.out + (m0 + wave_m * 128 + rrow) * g.ldo + n0 + wave_n * 64 + rch * 8;
+                float bq[2][4][4];
+#pragma unroll
+                for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+                    for (int rg = 0; rg < 4; ++rg) {
+                        const f32x8_unaligned b8 = scalar_load8(bias_s + jn * 32 + rg * 8);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) bq[jn][rg][e] = half ? b8[4 + e] : b8[e];
+                    }
+#pragma unroll
+                for (int im = 0; im < 4; ++im) {
+#pragma unroll
+                    for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+                        for (int rg = 0; rg < 4; ++rg) {
+                            float v[4];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                v[e] = acc[jn][im][rg * 4 + e] + bq[jn][rg][e];
+                                if (g.relu) v[e] = relu_keep_nan(v[e]);
+                            }
+                            uint2 pk = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+                            lds_write8(mine + l31 * 128 + (((jn * 4 + rg) ^ sw) << 4) + half * 8, pk);
+                        }
+                    i32x4 o[4];
+#pragma unroll
+                    for (int it = 0; it < 4; ++it) {
+                        const int row = rrow + 8 * it;
+                        o[it] = *(const i32x4 *)(mine + row * 128 + ((rch ^ ((row >> 1) & 7)) << 4));
+                    }
+                    uint16_t *d = dst + (int64_t)(im * 32) * g.ldo;
+                    if (!ragged) {
+#pragma unroll
+                        for (int it = 0; it < 4; ++it)
+                            __builtin_nontemporal_store(o[it], (i32x4 *)(d + (int64_t)(8 * it) * g.ldo));
+                    } else {
+#pragma unroll
+                        for (int it = 0; it < 4; ++it)
+                            if (m0 + wave_m * 128 + im * 32 + rrow + 8 * it < g.M)
+                                __builtin_nontemporal_store(o[it], (i32x4 *)(d + (int64_t)(8 * it) * g.ldo));
+                    }
+                }
+            } else {   // EPI_SCORE
+                float ps[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+                    for (int rg = 0; rg < 4; ++rg) {
+                        const f32x8_unaligned b8 = scalar_load8(bias_s + jn * 32 + rg * 8);
+                        const f32x8_unaligned w8 = scalar_load8(g.w_out + n0 + wave_n * 64 + jn * 32 + rg * 8);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float bv = half ? b8[4 + e] : b8[e];
+                            const float wv = half ? w8[4 + e] : w8[e];
+#pragma unroll
+                            for (int im = 0; im < 4; ++im)
+                                ps[im] += relu_keep_nan(acc[jn][im][rg * 4 + e] + bv) * wv;
+                        }
+                    }
+                float *red = (float *)stage;               // [4 column-waves][256 rows]
+#pragma unroll
+                for (int im = 0; im < 4; ++im) {
+                    const float v = ps[im] + __shfl_xor(ps[im], 32, 64);
+                    if (half == 0) lds_write4(red + wave_n * BM + wave_m * 128 + l31 + im * 32, v);
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                if (wave < 4) {
+                    const float v = (red[wave * 64 + ln] + red[BM + wave * 64 + ln]) + (red[2 * BM + wave * 64 + ln] + red[3 * BM + wave * 64 + ln]);
+                    const int tt = wave * 64 + ln;
+                    if (!ragged) g.partial[(m0 + tt) * g.n_tiles + tn] = v;
+                    else if (m0 + tt < g.M) g.partial[(m0 + tt) * g.n_tiles + tn] = v;
+                }
+            }
+            // a ragged tile may have issued fewer stores than the counts assume: drain instead
+            if (ragged) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (q + 1 == n_my) break;
+            ++q;
+            kt = 0;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();                  // everybody has read the staging room back
+            AB_FENCE();
+            begin_tile(q);
+            fetch_a(a_slot);
+            zero_acc();
+            after_epilogue = true;
+        } else {
+            ++kt;
+        }
+        a_slot = na;
+        w_slot = nw;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // no DMA may still target LDS when the group ends
+}
+
+template <int EPI>
+static hipError_t launch_stream_one(const GemmArgs &g, hipStream_t st)
+{
+    constexpr int smem = 5 * 256 * 128;
+    auto kern = gemm_stream_kernel<EPI>;
+    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    int dev = 0, cus = 0;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+    const int64_t ids = (g.m_tiles + 7) / 8 * 8 * g.n_tiles;
+    if (ids <= 0) return hipSuccess;
+    if (ids > 0x7fffffffLL) return hipErrorInvalidValue;
+    int64_t grid = ids < cus ? ids : cus;
+    grid = grid / 8 * 8;
+    if (grid < 8) grid = 8;
+    kern<<<(unsigned)grid, 512, smem, st>>>(g);
+    return hipGetLastError();
+}
+
 template <int AMODE, int EPI>
 static hipError_t launch_big_one(const GemmArgs &g, hipStream_t st)
 {
@@ -340,19 +682,22 @@ bool gemm_big_supported(int dtype, int amode, int epi, const GemmArgs &g)
     if (epi == EPI_STORE && (g.out_f32 || g.out_t || g.ldo % 8 != 0)) return false;
     if (amode == AMODE_GEN) {
         if (g.C % 256 != 0 || g.M % g.C != 0 || g.ldt % 4 != 0 || !g.wp || !g.wc || !g.xp || !g.xc) return false;
-    } else if (g.lda % 8 != 0) {
+    } else if (g.lda % 8 != 0 || g.lda > (1 << 22)) {     // (row offsets inside a tile are kept in 32 bits)
         return false;
     }
-    return g.ldb % 8 == 0;
+    return g.ldb % 8 == 0 && g.ldb <= (1 << 22);
 }
 
 hipError_t launch_gemm_big(int amode, int epi, GemmArgs g, hipStream_t st)
 {
     g.m_tiles = (g.M + 255) / 256;
     g.n_tiles = g.N / 256;
-    if (amode == AMODE_LOAD)
+    if (amode == AMODE_LOAD) {
+        if (g.bias)
+            return epi == EPI_STORE ? launch_stream_one<EPI_STORE>(g, st) : launch_stream_one<EPI_SCORE>(g, st);
         return epi == EPI_STORE ? launch_big_one<AMODE_LOAD, EPI_STORE>(g, st)
                                 : launch_big_one<AMODE_LOAD, EPI_SCORE>(g, st);
+    }
     return epi == EPI_STORE ? launch_big_one<AMODE_GEN, EPI_STORE>(g, st)
                             : launch_big_one<AMODE_GEN, EPI_SCORE>(g, st);
 }
