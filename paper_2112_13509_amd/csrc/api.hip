@@ -123,7 +123,7 @@ using namespace ab;
 
 extern "C" {
 
-int32_t ab_version(void) { return 101; }
+int32_t ab_version(void) { return 102; }
 
 void ab_set_trace(ab_trace_fn fn, void *user) { g_trace_fn = fn; g_trace_user = user; }
 

@@ -22,6 +22,7 @@
 //   - Stores go through an LDS staging tile (row stride 528 bytes) and leave as 16-byte, fully
 //     coalesced writes.
 #include "internal.hpp"
+#include <type_traits>
 
 namespace ab {
 
@@ -413,17 +414,23 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
     };
     unsigned wq = 0, aq = 0;
     int wkt = 0, akt = 0;
-    auto fetch_w = [&](int slot) {
+    // A slab is fetched as two halves (row groups i0, i0 + 1 of four) so that the requests can be spread
+    // over the quarters of a slab's matrix work instead of queueing up behind the barrier.
+    auto dma_w_rows = [&](int slot, int i0) {
         unsigned char *sb = smem + W_BASE + slot * SLAB;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) dma16<false>(w_base + w_off[i], sb + (wave + 8 * i) * 1024);
+        dma16<false>(w_base + w_off[i0], sb + (wave + 8 * i0) * 1024);
+        dma16<false>(w_base + w_off[i0 + 1], sb + (wave + 8 * (i0 + 1)) * 1024);
+    };
+    auto dma_a_rows = [&](int slot, int i0) {
+        unsigned char *sb = smem + slot * SLAB;
+        dma16<true>(a_base + a_off[i0], sb + (wave + 8 * i0) * 1024);
+        dma16<true>(a_base + a_off[i0 + 1], sb + (wave + 8 * (i0 + 1)) * 1024);
+    };
+    auto advance_w = [&]() {
         w_base += BK * 2;
         if (++wkt == KT) { wkt = 0; if (wq + 1 < n_my) ++wq; set_w(wq); }
     };
-    auto fetch_a = [&](int slot) {
-        unsigned char *sb = smem + slot * SLAB;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) dma16<true>(a_base + a_off[i], sb + (wave + 8 * i) * 1024);
+    auto advance_a = [&]() {
         a_base += BK * 2;
         if (++akt == KT) { akt = 0; if (aq + 1 < n_my) ++aq; set_a(aq); }
     };
@@ -437,16 +444,371 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
     const int w_rd = W_BASE + wave_n * 64 * 128;
 
     f32x16 acc[2][4];
-    auto zero_acc = [&]() {
+    i32x4 fa[2][4], fw[2][2];
+    auto load_frags = [&](int a_slot, int w_slot, int q, int set) {
+        const unsigned char *sa = smem + a_slot * SLAB + a_rd;
+        const unsigned char *sw_ = smem + w_slot * SLAB + w_rd;
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn) fw[set][jn] = *(const i32x4 *)(sw_ + jn * 4096 + rd[q]);
+#pragma unroll
+        for (int im = 0; im < 4; ++im) fa[set][im] = *(const i32x4 *)(sa + im * 4096 + rd[q]);
+    };
+    auto mma = [&](int set) {
 #pragma unroll
         for (int jn = 0; jn < 2; ++jn)
 #pragma unroll
             for (int im = 0; im < 4; ++im)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[jn][im][r] = 0.f;
+                acc[jn][im] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8, fw[set][jn]), __builtin_bit_cast(bf16x8, fa[set][im]),
+                    acc[jn][im], 0, 0, 0);
     };
-    zero_acc();
+    // per-tile state of the computing side
+    int64_t m0 = 0;
+    int n0 = 0;
+    unsigned tn = 0;
+    // bias (and output weights) of this wavefront's 64 columns arrive through the scalar cache: no
+    // vector-memory traffic, so nothing has to wait for the slab fetches in flight.  The bias is the
+    // accumulators' starting value, in their layout: register rg*4+e of column block jn is column
+    // jn*32 + rg*8 + (lane>>5)*4 + e.
+    auto begin_tile = [&](unsigned q) {
+        const unsigned local = l0 + q * G8;
+        tn = local % n_tiles;
+        n0 = (int)tn * 256;
+        m0 = ((int64_t)(local / n_tiles) * 8 + xcd) * BM;
+        const int hf = opaque_lane() >> 5;
+        f32x16 cinit[2];                                   // bias in accumulator layout (the same for all four row blocks)
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                const f32x8_unaligned b8 = scalar_load8(g.bias + n0 + wave_n * 64 + jn * 32 + rg * 8);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) cinit[jn][rg * 4 + e] = hf ? b8[4 + e] : b8[e];
+            }
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+            for (int im = 0; im < 4; ++im) acc[jn][im] = cinit[jn];
+    };
 
+    // Scheduling inside a quarter that also issues slab fetches: 8 matrix instructions, 6 fragment reads and
+    // 2 (or 4) DMA requests, spread evenly.
+#define AB_MFMA_VMEM_PAIR() do { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); \
+                                 __builtin_amdgcn_sched_group_barrier(0x010, 1, 0); } while (0)
+#define AB_INTERLEAVE_6_V2() do { AB_MFMA_DS_PAIR(); AB_MFMA_DS_PAIR(); AB_MFMA_VMEM_PAIR(); AB_MFMA_DS_PAIR(); \
+                                  AB_MFMA_DS_PAIR(); AB_MFMA_VMEM_PAIR(); AB_MFMA_DS_PAIR(); AB_MFMA_DS_PAIR(); } while (0)
+#define AB_INTERLEAVE_6_V4() do { __builtin_amdgcn_sched_group_barrier(0x100, 2, 0); \
+                                  AB_MFMA_VMEM_PAIR(); AB_MFMA_DS_PAIR(); AB_MFMA_VMEM_PAIR(); AB_MFMA_DS_PAIR(); \
+                                  AB_MFMA_VMEM_PAIR(); AB_MFMA_DS_PAIR(); AB_MFMA_VMEM_PAIR(); AB_MFMA_DS_PAIR(); } while (0)
+
+    // Order of the memory operations of a wavefront (loads and stores retire in order).  The quarters are
+    // straight-line code on purpose: a branch around matrix instructions makes the compiler copy accumulators.
+    //   quarter 3 of slab j-1 (after its barrier): W(j+1), into the stage just retired (at a tile's last slab
+    //                                              the epilogue's stores follow)
+    //   quarters 0, 1 of slab j:                   A(j+2), into the stage retired one slab ago
+    //   wait before the barrier of slab j:         slab j+1 must be complete -> only A(j+2) (4 operations) and,
+    //                                              at a tile's first slab, the previous tile's stores in front
+    //                                              of it may still be in flight.
+    // A stricter wait than needed is always safe.
+    constexpr int EPI_OPS_LOW = EPI == EPI_STORE ? 16 : 1;              // wavefronts 0..3
+    constexpr int EPI_OPS_HIGH = EPI == EPI_STORE ? 16 : 0;             // wavefronts 4..7 (no partial store)
+    static_assert(EPI_OPS_LOW + 4 == (EPI == EPI_STORE ? 20 : 5) && EPI_OPS_HIGH + 4 == (EPI == EPI_STORE ? 20 : 4), "");
+
+    // ---- prologue: slabs 0 and 1 whole
+    set_w(0); set_a(0);
+    dma_a_rows(0, 0); dma_a_rows(0, 2); advance_a();
+    dma_w_rows(0, 0); dma_w_rows(0, 2); advance_w();
+    dma_a_rows(1, 0); dma_a_rows(1, 2); advance_a();
+    dma_w_rows(1, 0); dma_w_rows(1, 2); advance_w();
+    begin_tile(0);
+    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    AB_FENCE();
+    load_frags(0, 0, 0, 0);
+
+    int a_slot = 0, w_slot = 0, kt = 0;
+    unsigned q = 0;
+    while (true) {
+        const int pa = a_slot == 0 ? 2 : a_slot - 1;       // the A stage retired one slab ago
+        AB_FENCE();
+        load_frags(a_slot, w_slot, 1, 1);
+        dma_a_rows(pa, 0);
+        mma(0);
+        AB_INTERLEAVE_6_V2();
+        AB_FENCE();
+        load_frags(a_slot, w_slot, 2, 0);
+        dma_a_rows(pa, 2);
+        mma(1);
+        AB_INTERLEAVE_6_V2();
+        AB_FENCE();
+        advance_a();
+        AB_FENCE();
+        load_frags(a_slot, w_slot, 3, 1);
+        mma(0);
+        AB_INTERLEAVE_6();
+        AB_FENCE();
+        if (kt != 0 || q == 0) {
+            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        } else if (wave < 4) {
+            if constexpr (EPI == EPI_STORE) asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
+            else                            asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+        } else {
+            if constexpr (EPI == EPI_STORE) asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
+            else                            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        }
+        // own fragment reads of this slab returned; then meet: slab j+1 is complete and visible to
+        // everybody and slab j's stages may be refilled
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        AB_FENCE();
+        const int na = a_slot == 2 ? 0 : a_slot + 1, nw = w_slot ^ 1;
+        load_frags(na, nw, 0, 0);
+        dma_w_rows(w_slot, 0);
+        dma_w_rows(w_slot, 2);
+        mma(1);
+        AB_INTERLEAVE_6_V4();
+        AB_FENCE();
+        advance_w();
+        if (kt != KT - 1) {
+            ++kt;
+        } else {
+            // ------------------------------------------------------------ epilogue of tile q
+            unsigned char *stage = smem + a_slot * SLAB;   // retired by the barrier above; A(j+3) goes there later
+            const bool ragged = m0 + BM > g.M;
+            const int ln = opaque_lane();
+            const int half = ln >> 5, l31 = ln & 31, sw = (l31 >> 1) & 7;
+            if constexpr (EPI == EPI_STORE) {
+                unsigned char *mine = stage + wave * 4096;
+                const int rrow = ln >> 3, rch = ln & 7;
+                uint16_t *dst = (uint16_t *)g.out + (m0 + wave_m * 128 + rrow) * g.ldo + n0 + wave_n * 64 + rch * 8;
+                auto store_tile = [&](auto relu_tag) {
+#pragma unroll
+                    for (int im = 0; im < 4; ++im) {
+#pragma unroll
+                        for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+                            for (int rg = 0; rg < 4; ++rg) {
+                                float v[4];
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) {
+                                    v[e] = acc[jn][im][rg * 4 + e];
+                                    if constexpr (decltype(relu_tag)::value) v[e] = relu_keep_nan(v[e]);
+                                }
+                                uint2 pk = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+                                lds_write8(mine + l31 * 128 + (((jn * 4 + rg) ^ sw) << 4) + half * 8, pk);
+                            }
+                        i32x4 o[4];
+#pragma unroll
+                        for (int it = 0; it < 4; ++it) {
+                            const int row = rrow + 8 * it;
+                            o[it] = *(const i32x4 *)(mine + row * 128 + ((rch ^ ((row >> 1) & 7)) << 4));
+                        }
+                        uint16_t *d = dst + (int64_t)(im * 32) * g.ldo;
+                        if (!ragged) {
+#pragma unroll
+                            for (int it = 0; it < 4; ++it)
+                                __builtin_nontemporal_store(o[it], (i32x4 *)(d + (int64_t)(8 * it) * g.ldo));
+                        } else {
+#pragma unroll
+                            for (int it = 0; it < 4; ++it)
+                                if (m0 + wave_m * 128 + im * 32 + rrow + 8 * it < g.M)
+                                    __builtin_nontemporal_store(o[it], (i32x4 *)(d + (int64_t)(8 * it) * g.ldo));
+                        }
+                    }
+                };
+                if (g.relu) store_tile(std::true_type{});
+                else        store_tile(std::false_type{});
+            } else {   // EPI_SCORE
+                float ps[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+                    for (int rg = 0; rg < 4; ++rg) {
+                        const f32x8_unaligned w8 = scalar_load8(g.w_out + n0 + wave_n * 64 + jn * 32 + rg * 8);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float wv = half ? w8[4 + e] : w8[e];
+#pragma unroll
+                            for (int im = 0; im < 4; ++im)
+                                ps[im] += relu_keep_nan(acc[jn][im][rg * 4 + e]) * wv;
+                        }
+                    }
+                float *red = (float *)stage;               // [4 column-waves][256 rows]
+#pragma unroll
+                for (int im = 0; im < 4; ++im) {
+                    const float v = ps[im] + __shfl_xor(ps[im], 32, 64);
+                    if (half == 0) lds_write4(red + wave_n * BM + wave_m * 128 + l31 + im * 32, v);
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                if (wave < 4) {
+                    const int tt = wave * 64 + ln;
+                    const float v = (red[tt] + red[BM + tt]) + (red[2 * BM + tt] + red[3 * BM + tt]);
+                    if (!ragged) g.partial[(m0 + tt) * g.n_tiles + tn] = v;
+                    else if (m0 + tt < g.M) g.partial[(m0 + tt) * g.n_tiles + tn] = v;
+                }
+            }
+            // a ragged tile may have issued fewer stores than the counts assume: drain instead
+            if (ragged) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (q + 1 == n_my) break;
+            ++q;
+            kt = 0;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();                  // everybody has read the staging room back
+            AB_FENCE();
+            begin_tile(q);
+        }
+        a_slot = na;
+        w_slot = nw;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // no DMA may still target LDS when the group ends
+}
+
+
+// ------------------------------------------------------------------------------------------------
+// Streaming kernel for the first hidden layer: the activation operand is not read but generated,
+// A[r, k] = relu(a_term[s, k] + wp[k] * xp[c] + wc[k] * xc[c]) for row r = (scenario s, candidate c), one
+// scenario per 256-row tile.  Same walk over the tiles and same W ring as gemm_stream_kernel; differences:
+//   - the A ring has two stages; while slab j is multiplied, slab j+1 is generated into the other
+//     stage by the vector ALUs (a thread owns one 8-wide k chunk of four rows: two row chunks in the
+//     first quarter, one in each of the next two), next to the matrix instructions;
+//   - everything the generation reads comes from LDS: wp and wc (whole, fetched once), the scenario's
+//     a_term row and the tile's xp / xc slices (double-buffered per tile, fetched one tile ahead by
+//     DMA, 3 requests per wavefront), 20 KB behind the rings.  No ordinary vector load is in flight
+//     next to the DMA, so no wait ever has to drain the queue.
+//   - memory operations of a wavefront: W(j+2) x4 in the last quarter of slab j; at a tile border
+//     the stores x16 and the vector fetch x3 follow.  Inside a tile the wait before a slab's barrier
+//     is therefore for everything, at a tile's first slab 19 operations may stay in flight.
+// Needs K <= 1024 (vector area) and at least two slabs.
+__device__ __forceinline__ void lds_write16(void *p, i32x4 v)
+{
+    asm volatile("ds_write_b128 %0, %1" ::"v"((uint32_t)(uintptr_t)(lds_void *)p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void dma4(const void *gsrc, void *lds_uniform_dst)   // 64 lanes x 4 bytes
+{
+    __builtin_amdgcn_global_load_lds((global_void *)gsrc, (lds_void *)lds_uniform_dst, 4, 0, 0);
+}
+
+__global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
+{
+    constexpr int BM = 256, BK = 64;
+    constexpr int SLAB = BM * 128;
+    constexpr int W_BASE = 2 * SLAB;
+    constexpr int V_WP = 4 * SLAB, V_WC = V_WP + 4096, V_AT = V_WC + 4096, V_XP = V_AT + 8192;   // + 4096: 151552
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int wave_m = wave >> 2, wave_n = wave & 3;
+    const int half = lane >> 5, l31 = lane & 31;
+    const int KT = g.K / BK;
+    auto opaque_lane = [&]() { int v = lane; asm volatile("" : "+v"(v)); return v; };
+
+    const unsigned G8 = gridDim.x >> 3, xcd = blockIdx.x & 7, l0 = blockIdx.x >> 3;
+    const unsigned n_tiles = (unsigned)g.n_tiles;
+    const unsigned panels = (unsigned)g.m_tiles > xcd ? ((unsigned)g.m_tiles - xcd + 7) / 8 : 0;
+    const unsigned n_local = panels * n_tiles;
+    if (l0 >= n_local) return;
+    const unsigned n_my = (n_local - l0 + G8 - 1) / G8;
+
+    // ---- W slabs by DMA
+    const unsigned char *w_base;
+    uint32_t w_off[4];
+    auto set_w = [&](unsigned q) {
+        const unsigned local = l0 + q * G8;
+        w_base = (const unsigned char *)g.B + (int64_t)(local % n_tiles) * 256 * g.ldb * 2;
+        const int ln = opaque_lane();
+        const int dma_cc = (ln & 7) ^ ((wave & 1) * 4 + (ln >> 4)), dma_r0 = wave * 8 + (ln >> 3);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w_off[i] = (uint32_t)(dma_r0 + 64 * i) * (uint32_t)g.ldb * 2u + dma_cc * 16;
+    };
+    unsigned wq = 0;
+    int wkt = 0;
+    auto dma_w_rows = [&](int slot, int i0) {
+        unsigned char *sb = smem + W_BASE + slot * SLAB;
+        dma16<false>(w_base + w_off[i0], sb + (wave + 8 * i0) * 1024);
+        dma16<false>(w_base + w_off[i0 + 1], sb + (wave + 8 * (i0 + 1)) * 1024);
+    };
+    auto advance_w = [&]() {
+        w_base += BK * 2;
+        if (++wkt == KT) { wkt = 0; if (wq + 1 < n_my) ++wq; set_w(wq); }
+    };
+
+    // ---- what the generation reads, by DMA: 3 requests per wavefront and tile (past the end the last tile again)
+    auto fetch_vec = [&](unsigned qq) {
+        const int b = (int)(qq & 1);
+        if (qq > n_my - 1) qq = n_my - 1;
+        const unsigned local = l0 + qq * G8;
+        const unsigned m0u = ((local / n_tiles) * 8 + xcd) * BM;
+        const unsigned s = m0u / (unsigned)g.C, c0 = m0u - s * (unsigned)g.C;
+        const int ln = opaque_lane();
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            int i = wave + 8 * h;
+            if (i > KT - 1) i = KT - 1;
+            dma4(g.a_term + (int64_t)s * g.ldt + i * 64 + ln, smem + V_AT + b * 4096 + i * 256);
+        }
+        dma4((wave < 4 ? g.xp : g.xc) + c0 + (wave & 3) * 64 + ln,
+             smem + V_XP + b * 2048 + (wave >> 2) * 1024 + (wave & 3) * 256);
+    };
+    auto fetch_wp_wc = [&]() {                              // 4 requests per wavefront, once
+        const int ln = opaque_lane();
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            int i = wave + 8 * h;
+            if (i > KT - 1) i = KT - 1;
+            dma4(g.wp + i * 64 + ln, smem + V_WP + i * 256);
+            dma4(g.wc + i * 64 + ln, smem + V_WC + i * 256);
+        }
+    };
+
+    // ---- generation: thread -> k chunk t & 7 of rows (t >> 3) + 64 i
+    const int gcc = t & 7, grow = t >> 3;
+    const int gen_st0 = grow * 128 + ((gcc ^ ((grow >> 1) & 7)) << 4);       // (+ 64 i rows: same swizzle)
+    float gxp[4], gxc[4];
+    auto load_xpc = [&](int b) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            gxp[i] = *(const float *)(smem + V_XP + b * 2048 + (grow + 64 * i) * 4);
+            gxc[i] = *(const float *)(smem + V_XP + b * 2048 + 1024 + (grow + 64 * i) * 4);
+        }
+    };
+    f32x4 va[2], vp[2], vc[2];
+    auto load_slices = [&](int b, int gk) {
+        const int o = (gk * 64 + gcc * 8) * 4;
+        va[0] = *(const f32x4 *)(smem + V_AT + b * 4096 + o);
+        va[1] = *(const f32x4 *)(smem + V_AT + b * 4096 + o + 16);
+        vp[0] = *(const f32x4 *)(smem + V_WP + o);
+        vp[1] = *(const f32x4 *)(smem + V_WP + o + 16);
+        vc[0] = *(const f32x4 *)(smem + V_WC + o);
+        vc[1] = *(const f32x4 *)(smem + V_WC + o + 16);
+    };
+    auto gen_chunk = [&](int slot, int i) {
+        const float xp = gxp[i], xc = gxc[i];
+        float h[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            h[e] = relu_keep_nan(fmaf(vc[0][e], xc, fmaf(vp[0][e], xp, va[0][e])));
+            h[4 + e] = relu_keep_nan(fmaf(vc[1][e], xc, fmaf(vp[1][e], xp, va[1][e])));
+        }
+        i32x4 v;
+        v.x = (int)pack_bf16x2(h[0], h[1]);
+        v.y = (int)pack_bf16x2(h[2], h[3]);
+        v.z = (int)pack_bf16x2(h[4], h[5]);
+        v.w = (int)pack_bf16x2(h[6], h[7]);
+        lds_write16(smem + slot * SLAB + gen_st0 + i * 8192, v);
+    };
+
+    // ---- fragment read offsets
+    const int sw = (l31 >> 1) & 7;
+    int rd[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) rd[q] = l31 * 128 + ((((q << 1) | half) ^ sw) << 4);
+    const int a_rd = wave_m * 128 * 128;
+    const int w_rd = W_BASE + wave_n * 64 * 128;
+
+    f32x16 acc[2][4];
     i32x4 fa[2][4], fw[2][2];
     auto load_frags = [&](int a_slot, int w_slot, int q, int set) {
         const unsigned char *sa = smem + a_slot * SLAB + a_rd;
@@ -466,95 +828,97 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
                     acc[jn][im], 0, 0, 0);
     };
 
-    // per-tile state of the computing side
     int64_t m0 = 0;
     int n0 = 0;
-    unsigned tn = 0;
-    auto begin_tile = [&](unsigned q) {
+    auto begin_tile = [&](unsigned q) {                     // accumulators start at the bias
         const unsigned local = l0 + q * G8;
-        tn = local % n_tiles;
-        n0 = (int)tn * 256;
+        n0 = (int)(local % n_tiles) * 256;
         m0 = ((int64_t)(local / n_tiles) * 8 + xcd) * BM;
+        const int hf = opaque_lane() >> 5;
+        f32x16 cinit[2];
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                const f32x8_unaligned b8 = scalar_load8(g.bias + n0 + wave_n * 64 + jn * 32 + rg * 8);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) cinit[jn][rg * 4 + e] = hf ? b8[4 + e] : b8[e];
+            }
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+            for (int im = 0; im < 4; ++im) acc[jn][im] = cinit[jn];
     };
 
-    // vmcnt immediates in use: in a tile 4; at the first slab after an epilogue 4 + its stores.
-    // A stricter wait than needed is always safe.
-    constexpr int EPI_OPS_LOW = EPI == EPI_STORE ? 16 : 1;              // wavefronts 0..3
-    constexpr int EPI_OPS_HIGH = EPI == EPI_STORE ? 16 : 0;             // wavefronts 4..7 (no partial store)
-
     // ---- prologue
+    set_w(0);
+    fetch_wp_wc();
+    fetch_vec(0);
+    fetch_vec(1);
+    dma_w_rows(0, 0); dma_w_rows(0, 2); advance_w();
+    dma_w_rows(1, 0); dma_w_rows(1, 2); advance_w();
     begin_tile(0);
-    set_w(0); set_a(0);
-    fetch_a(0); fetch_w(0); fetch_a(1); fetch_w(1); fetch_a(2);
-    asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_s_barrier();                          // vectors and W(0) are in LDS for everybody
+    AB_FENCE();
+    load_xpc(0);
+    load_slices(0, 0);
+    gen_chunk(0, 0); gen_chunk(0, 1); gen_chunk(0, 2); gen_chunk(0, 3);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();                          // A(0) is complete
     AB_FENCE();
     load_frags(0, 0, 0, 0);
 
-    int a_slot = 0, w_slot = 0, kt = 0;
+    int a_slot = 0, w_slot = 0, kt = 0, gpar = 0;
     unsigned q = 0;
-    bool after_epilogue = false;
     while (true) {
+        const int nxt = a_slot ^ 1;                        // retired one slab ago: slab j+1 is generated there
+        int gk = kt + 1;                                   // its place in its tile
+        if (gk == KT) { gk = 0; gpar ^= 1; load_xpc(gpar); }
+        load_slices(gpar, gk);
         AB_FENCE();
         load_frags(a_slot, w_slot, 1, 1);
+        gen_chunk(nxt, 0);
+        gen_chunk(nxt, 1);
         mma(0);
         AB_INTERLEAVE_6();
         AB_FENCE();
         load_frags(a_slot, w_slot, 2, 0);
+        gen_chunk(nxt, 2);
         mma(1);
         AB_INTERLEAVE_6();
         AB_FENCE();
         load_frags(a_slot, w_slot, 3, 1);
+        gen_chunk(nxt, 3);
         mma(0);
         AB_INTERLEAVE_6();
         AB_FENCE();
-        // the next slab (both operands) must have landed; younger operations may stay in flight
-        if (!after_epilogue) {
-            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        } else if (wave < 4) {
-            if constexpr (EPI == EPI_STORE) asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
-            else                            asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
-        } else {
-            if constexpr (EPI == EPI_STORE) asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
-            else                            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        }
-        static_assert(EPI_OPS_LOW + 4 == (EPI == EPI_STORE ? 20 : 5) && EPI_OPS_HIGH + 4 == (EPI == EPI_STORE ? 20 : 4), "");
-        after_epilogue = false;
+        if (kt != 0 || q == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else                   asm volatile("s_waitcnt vmcnt(19)" ::: "memory");
+        // own LDS traffic of this slab is done (fragment reads, generated chunks); then meet: slab j+1 is
+        // complete and visible to everybody and slab j's stages may be refilled
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         AB_FENCE();
-        const bool last = kt == KT - 1;
-        fetch_w(w_slot);
-        if (!last) fetch_a(a_slot);
-        AB_FENCE();
-        const int na = a_slot == 2 ? 0 : a_slot + 1, nw = w_slot ^ 1;
-        load_frags(na, nw, 0, 0);
+        const int nw = w_slot ^ 1;
+        load_frags(nxt, nw, 0, 0);
+        dma_w_rows(w_slot, 0);
+        dma_w_rows(w_slot, 2);
         mma(1);
-        AB_INTERLEAVE_6();
+        AB_INTERLEAVE_6_V4();
         AB_FENCE();
-        if (last) {
-            // ------------------------------------------------------------ epilogue of tile q
-            unsigned char *stage = smem + a_slot * SLAB;
-            const bool ragged = m0 + BM > g.M;
+        advance_w();
+        if (kt != KT - 1) {
+            ++kt;
+        } else {
+            // ------------------------------------------------------------ epilogue of tile q (never ragged)
+            unsigned char *mine = smem + a_slot * SLAB + wave * 4096;     // retired by the barrier above
             const int ln = opaque_lane();
             const int half = ln >> 5, l31 = ln & 31, sw = (l31 >> 1) & 7;
-            // bias (and output weights) of this wavefront's 64 columns arrive through the scalar cache:
-            // no vector-memory traffic, so nothing here has to wait for the slab fetches in flight
-            const float *bias_s = g.bias + n0 + wave_n * 64;
-            if constexpr (EPI == EPI_STORE) {
-                unsigned char *mine = stage + wave * 4096;
-                const int rrow = ln >> 3, rch = ln & 7;
-                uint16_t *dst = (uint16_t *)g.out + (m0 + wave_m * 128 + rrow) * g.ldo + n0 + wave_n * 64 + rch * 8;
-                float bq[2][4][4];
-#pragma unroll
-                for (int jn = 0; jn < 2; ++jn)
-#pragma unroll
-                    for (int rg = 0; rg < 4; ++rg) {
-                        const f32x8_unaligned b8 = scalar_load8(bias_s + jn * 32 + rg * 8);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) bq[jn][rg][e] = half ? b8[4 + e] : b8[e];
-                    }
+            const int rrow = ln >> 3, rch = ln & 7;
+            uint16_t *dst = (uint16_t *)g.out + (m0 + wave_m * 128 + rrow) * g.ldo + n0 + wave_n * 64 + rch * 8;
+            auto store_tile = [&](auto relu_tag) {
 #pragma unroll
                 for (int im = 0; im < 4; ++im) {
 #pragma unroll
@@ -564,8 +928,8 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
                             float v[4];
 #pragma unroll
                             for (int e = 0; e < 4; ++e) {
-                                v[e] = acc[jn][im][rg * 4 + e] + bq[jn][rg][e];
-                                if (g.relu) v[e] = relu_keep_nan(v[e]);
+                                v[e] = acc[jn][im][rg * 4 + e];
+                                if constexpr (decltype(relu_tag)::value) v[e] = relu_keep_nan(v[e]);
                             }
                             uint2 pk = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
                             lds_write8(mine + l31 * 128 + (((jn * 4 + rg) ^ sw) << 4) + half * 8, pk);
@@ -577,51 +941,13 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
                         o[it] = *(const i32x4 *)(mine + row * 128 + ((rch ^ ((row >> 1) & 7)) << 4));
                     }
                     uint16_t *d = dst + (int64_t)(im * 32) * g.ldo;
-                    if (!ragged) {
 #pragma unroll
-                        for (int it = 0; it < 4; ++it)
-                            __builtin_nontemporal_store(o[it], (i32x4 *)(d + (int64_t)(8 * it) * g.ldo));
-                    } else {
-#pragma unroll
-                        for (int it = 0; it < 4; ++it)
-                            if (m0 + wave_m * 128 + im * 32 + rrow + 8 * it < g.M)
-                                __builtin_nontemporal_store(o[it], (i32x4 *)(d + (int64_t)(8 * it) * g.ldo));
-                    }
+                    for (int it = 0; it < 4; ++it)
+                        __builtin_nontemporal_store(o[it], (i32x4 *)(d + (int64_t)(8 * it) * g.ldo));
                 }
-            } else {   // EPI_SCORE
-                float ps[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int jn = 0; jn < 2; ++jn)
-#pragma unroll
-                    for (int rg = 0; rg < 4; ++rg) {
-                        const f32x8_unaligned b8 = scalar_load8(bias_s + jn * 32 + rg * 8);
-                        const f32x8_unaligned w8 = scalar_load8(g.w_out + n0 + wave_n * 64 + jn * 32 + rg * 8);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const float bv = half ? b8[4 + e] : b8[e];
-                            const float wv = half ? w8[4 + e] : w8[e];
-#pragma unroll
-                            for (int im = 0; im < 4; ++im)
-                                ps[im] += relu_keep_nan(acc[jn][im][rg * 4 + e] + bv) * wv;
-                        }
-                    }
-                float *red = (float *)stage;               // [4 column-waves][256 rows]
-#pragma unroll
-                for (int im = 0; im < 4; ++im) {
-                    const float v = ps[im] + __shfl_xor(ps[im], 32, 64);
-                    if (half == 0) lds_write4(red + wave_n * BM + wave_m * 128 + l31 + im * 32, v);
-                }
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                __builtin_amdgcn_s_barrier();
-                if (wave < 4) {
-                    const float v = (red[wave * 64 + ln] + red[BM + wave * 64 + ln]) + (red[2 * BM + wave * 64 + ln] + red[3 * BM + wave * 64 + ln]);
-                    const int tt = wave * 64 + ln;
-                    if (!ragged) g.partial[(m0 + tt) * g.n_tiles + tn] = v;
-                    else if (m0 + tt < g.M) g.partial[(m0 + tt) * g.n_tiles + tn] = v;
-                }
-            }
-            // a ragged tile may have issued fewer stores than the counts assume: drain instead
-            if (ragged) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            };
+            if (g.relu) store_tile(std::true_type{});
+            else        store_tile(std::false_type{});
             if (q + 1 == n_my) break;
             ++q;
             kt = 0;
@@ -629,16 +955,31 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
             __builtin_amdgcn_s_barrier();                  // everybody has read the staging room back
             AB_FENCE();
             begin_tile(q);
-            fetch_a(a_slot);
-            zero_acc();
-            after_epilogue = true;
-        } else {
-            ++kt;
+            fetch_vec(q + 1);
         }
-        a_slot = na;
+        a_slot = nxt;
         w_slot = nw;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // no DMA may still target LDS when the group ends
+}
+
+static hipError_t launch_stream_gen(const GemmArgs &g, hipStream_t st)
+{
+    constexpr int smem = 4 * 256 * 128 + 20480;
+    auto kern = gemm_stream_gen_kernel;
+    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    int dev = 0, cus = 0;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+    const int64_t ids = (g.m_tiles + 7) / 8 * 8 * g.n_tiles;
+    if (ids <= 0) return hipSuccess;
+    if (ids > 0x7fffffffLL) return hipErrorInvalidValue;
+    int64_t grid = ids < cus ? ids : cus;
+    grid = grid / 8 * 8;
+    if (grid < 8) grid = 8;
+    kern<<<(unsigned)grid, 512, smem, st>>>(g);
+    return hipGetLastError();
 }
 
 template <int EPI>
@@ -698,6 +1039,10 @@ hipError_t launch_gemm_big(int amode, int epi, GemmArgs g, hipStream_t st)
         return epi == EPI_STORE ? launch_big_one<AMODE_LOAD, EPI_STORE>(g, st)
                                 : launch_big_one<AMODE_LOAD, EPI_SCORE>(g, st);
     }
+    // generated operand: the streaming kernel needs the bias, the vector area bounds K, two slabs at least,
+    // 32-bit row arithmetic and 4-byte DMA sources
+    if (epi == EPI_STORE && g.bias && g.K <= 1024 && g.K >= 128 && g.M < (1LL << 31))
+        return launch_stream_gen(g, st);
     return epi == EPI_STORE ? launch_big_one<AMODE_GEN, EPI_STORE>(g, st)
                             : launch_big_one<AMODE_GEN, EPI_SCORE>(g, st);
 }
