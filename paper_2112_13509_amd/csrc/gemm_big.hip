@@ -29,6 +29,7 @@ namespace ab {
 typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void global_void;
 typedef float f32x8_unaligned __attribute__((ext_vector_type(8), aligned(4)));
+
 typedef __attribute__((address_space(4))) f32x8_unaligned const_f32x8;   // read-only for the whole launch: scalar loads
 // Eight consecutive floats at a wave-uniform address, fetched through the scalar cache into scalar registers.
 __device__ __forceinline__ f32x8_unaligned scalar_load8(const float *p)
@@ -505,7 +506,8 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
     // straight-line code on purpose: a branch around matrix instructions makes the compiler copy accumulators.
     //   quarter 3 of slab j-1 (after its barrier): W(j+1), into the stage just retired (at a tile's last slab
     //                                              the epilogue's stores follow)
-    //   quarters 0, 1 of slab j:                   A(j+2), into the stage retired one slab ago
+    //   quarter 0 of slab j:                       A(j+2), into the stage retired one slab ago (as early as the
+    //                                              epilogue's use of that stage allows: measured best)
     //   wait before the barrier of slab j:         slab j+1 must be complete -> only A(j+2) (4 operations) and,
     //                                              at a tile's first slab, the previous tile's stores in front
     //                                              of it may still be in flight.
@@ -534,15 +536,15 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
         AB_FENCE();
         load_frags(a_slot, w_slot, 1, 1);
         dma_a_rows(pa, 0);
-        mma(0);
-        AB_INTERLEAVE_6_V2();
-        AB_FENCE();
-        load_frags(a_slot, w_slot, 2, 0);
         dma_a_rows(pa, 2);
-        mma(1);
-        AB_INTERLEAVE_6_V2();
+        mma(0);
+        AB_INTERLEAVE_6_V4();
         AB_FENCE();
         advance_a();
+        AB_FENCE();
+        load_frags(a_slot, w_slot, 2, 0);
+        mma(1);
+        AB_INTERLEAVE_6();
         AB_FENCE();
         load_frags(a_slot, w_slot, 3, 1);
         mma(0);

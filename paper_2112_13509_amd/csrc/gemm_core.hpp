@@ -30,7 +30,8 @@ typedef __attribute__((ext_vector_type(4))) int i32x4;
 struct bf16_t { uint16_t bits; };   // storage type of a bfloat16 value
 
 // ReLU that lets NaN through, so a non-finite statistic stays visible in the scores.
-__device__ __forceinline__ float relu_keep_nan(float v) { return v <= 0.f ? 0.f : v; }
+// max(v, 0) that hands a NaN on (IEEE 754-2019 maximum; one v_maximum3_f32 on this target)
+__device__ __forceinline__ float relu_keep_nan(float v) { return __builtin_elementwise_maximum(v, 0.f); }
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
