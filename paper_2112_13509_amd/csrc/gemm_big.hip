@@ -445,6 +445,7 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
     const int w_rd = W_BASE + wave_n * 64 * 128;
 
     f32x16 acc[2][4];
+    f32x16 cinit[2];                                       // the tile's bias in accumulator layout (same for all four row blocks)
     i32x4 fa[2][4], fw[2][2];
     auto load_frags = [&](int a_slot, int w_slot, int q, int set) {
         const unsigned char *sa = smem + a_slot * SLAB + a_rd;
@@ -463,6 +464,16 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
                     __builtin_bit_cast(bf16x8, fw[set][jn]), __builtin_bit_cast(bf16x8, fa[set][im]),
                     acc[jn][im], 0, 0, 0);
     };
+    auto mma_first = [&](int set) {                        // a tile's first quarter: the accumulators start at the bias
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+            for (int im = 0; im < 4; ++im)
+                acc[jn][im] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8, fw[set][jn]), __builtin_bit_cast(bf16x8, fa[set][im]),
+                    cinit[jn], 0, 0, 0);
+    };
+
     // per-tile state of the computing side
     int64_t m0 = 0;
     int n0 = 0;
@@ -477,7 +488,6 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
         n0 = (int)tn * 256;
         m0 = ((int64_t)(local / n_tiles) * 8 + xcd) * BM;
         const int hf = opaque_lane() >> 5;
-        f32x16 cinit[2];                                   // bias in accumulator layout (the same for all four row blocks)
 #pragma unroll
         for (int jn = 0; jn < 2; ++jn)
 #pragma unroll
@@ -486,10 +496,6 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) cinit[jn][rg * 4 + e] = hf ? b8[4 + e] : b8[e];
             }
-#pragma unroll
-        for (int jn = 0; jn < 2; ++jn)
-#pragma unroll
-            for (int im = 0; im < 4; ++im) acc[jn][im] = cinit[jn];
     };
 
     // Scheduling inside a quarter that also issues slab fetches: 8 matrix instructions, 6 fragment reads and
@@ -529,15 +535,18 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
     AB_FENCE();
     load_frags(0, 0, 0, 0);
 
-    int a_slot = 0, w_slot = 0, kt = 0;
+    int a_slot = 0, w_slot = 0;
     unsigned q = 0;
-    while (true) {
+    // One slab.  A tile's first slab is its own copy of the code (its first matrix instructions take the bias
+    // as their addend, its wait knows of the stores in front), so that no branch sits inside a quarter.
+    auto slab = [&](auto first_tag) {
+        constexpr bool FIRST = decltype(first_tag)::value;
         const int pa = a_slot == 0 ? 2 : a_slot - 1;       // the A stage retired one slab ago
         AB_FENCE();
         load_frags(a_slot, w_slot, 1, 1);
         dma_a_rows(pa, 0);
         dma_a_rows(pa, 2);
-        mma(0);
+        if constexpr (FIRST) mma_first(0); else mma(0);
         AB_INTERLEAVE_6_V4();
         AB_FENCE();
         advance_a();
@@ -550,7 +559,7 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
         mma(0);
         AB_INTERLEAVE_6();
         AB_FENCE();
-        if (kt != 0 || q == 0) {
+        if (!FIRST || q == 0) {
             asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
         } else if (wave < 4) {
             if constexpr (EPI == EPI_STORE) asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
@@ -572,11 +581,16 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
         AB_INTERLEAVE_6_V4();
         AB_FENCE();
         advance_w();
-        if (kt != KT - 1) {
-            ++kt;
-        } else {
+        a_slot = na;
+        w_slot = nw;
+    };
+    while (true) {
+        slab(std::true_type{});
+        for (int kt = 1; kt < KT; ++kt) slab(std::false_type{});
+        {
             // ------------------------------------------------------------ epilogue of tile q
-            unsigned char *stage = smem + a_slot * SLAB;   // retired by the barrier above; A(j+3) goes there later
+            // staging room: the A stage retired by the last barrier; A(j+3) goes there later
+            unsigned char *stage = smem + (a_slot == 0 ? 2 : a_slot - 1) * SLAB;
             const bool ragged = m0 + BM > g.M;
             const int ln = opaque_lane();
             const int half = ln >> 5, l31 = ln & 31, sw = (l31 >> 1) & 7;
@@ -655,14 +669,11 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
             if (ragged) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             if (q + 1 == n_my) break;
             ++q;
-            kt = 0;
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             __builtin_amdgcn_s_barrier();                  // everybody has read the staging room back
             AB_FENCE();
             begin_tile(q);
         }
-        a_slot = na;
-        w_slot = nw;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // no DMA may still target LDS when the group ends
 }
@@ -811,6 +822,7 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
     const int w_rd = W_BASE + wave_n * 64 * 128;
 
     f32x16 acc[2][4];
+    f32x16 cinit[2];                                       // the tile's bias in accumulator layout
     i32x4 fa[2][4], fw[2][2];
     auto load_frags = [&](int a_slot, int w_slot, int q, int set) {
         const unsigned char *sa = smem + a_slot * SLAB + a_rd;
@@ -830,14 +842,23 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
                     acc[jn][im], 0, 0, 0);
     };
 
+    auto mma_first = [&](int set) {                        // a tile's first quarter: the accumulators start at the bias
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+            for (int im = 0; im < 4; ++im)
+                acc[jn][im] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8, fw[set][jn]), __builtin_bit_cast(bf16x8, fa[set][im]),
+                    cinit[jn], 0, 0, 0);
+    };
+
     int64_t m0 = 0;
     int n0 = 0;
-    auto begin_tile = [&](unsigned q) {                     // accumulators start at the bias
+    auto begin_tile = [&](unsigned q) {
         const unsigned local = l0 + q * G8;
         n0 = (int)(local % n_tiles) * 256;
         m0 = ((int64_t)(local / n_tiles) * 8 + xcd) * BM;
         const int hf = opaque_lane() >> 5;
-        f32x16 cinit[2];
 #pragma unroll
         for (int jn = 0; jn < 2; ++jn)
 #pragma unroll
@@ -846,10 +867,6 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) cinit[jn][rg * 4 + e] = hf ? b8[4 + e] : b8[e];
             }
-#pragma unroll
-        for (int jn = 0; jn < 2; ++jn)
-#pragma unroll
-            for (int im = 0; im < 4; ++im) acc[jn][im] = cinit[jn];
     };
 
     // ---- prologue
@@ -872,9 +889,12 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
     AB_FENCE();
     load_frags(0, 0, 0, 0);
 
-    int a_slot = 0, w_slot = 0, kt = 0, gpar = 0;
+    int a_slot = 0, w_slot = 0, gpar = 0;
     unsigned q = 0;
-    while (true) {
+    // One slab (kt = its place in the tile).  A tile's first slab is its own copy of the code, so that no
+    // branch sits inside a quarter.
+    auto slab = [&](auto first_tag, int kt) {
+        constexpr bool FIRST = decltype(first_tag)::value;
         const int nxt = a_slot ^ 1;                        // retired one slab ago: slab j+1 is generated there
         int gk = kt + 1;                                   // its place in its tile
         if (gk == KT) { gk = 0; gpar ^= 1; load_xpc(gpar); }
@@ -883,7 +903,7 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
         load_frags(a_slot, w_slot, 1, 1);
         gen_chunk(nxt, 0);
         gen_chunk(nxt, 1);
-        mma(0);
+        if constexpr (FIRST) mma_first(0); else mma(0);
         AB_INTERLEAVE_6();
         AB_FENCE();
         load_frags(a_slot, w_slot, 2, 0);
@@ -896,8 +916,8 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
         mma(0);
         AB_INTERLEAVE_6();
         AB_FENCE();
-        if (kt != 0 || q == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        else                   asm volatile("s_waitcnt vmcnt(19)" ::: "memory");
+        if (!FIRST || q == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else                  asm volatile("s_waitcnt vmcnt(19)" ::: "memory");
         // own LDS traffic of this slab is done (fragment reads, generated chunks); then meet: slab j+1 is
         // complete and visible to everybody and slab j's stages may be refilled
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -911,11 +931,15 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
         AB_INTERLEAVE_6_V4();
         AB_FENCE();
         advance_w();
-        if (kt != KT - 1) {
-            ++kt;
-        } else {
+        a_slot = nxt;
+        w_slot = nw;
+    };
+    while (true) {
+        slab(std::true_type{}, 0);
+        for (int kt = 1; kt < KT; ++kt) slab(std::false_type{}, kt);
+        {
             // ------------------------------------------------------------ epilogue of tile q (never ragged)
-            unsigned char *mine = smem + a_slot * SLAB + wave * 4096;     // retired by the barrier above
+            unsigned char *mine = smem + (a_slot ^ 1) * SLAB + wave * 4096;   // the A stage retired by the last barrier
             const int ln = opaque_lane();
             const int half = ln >> 5, l31 = ln & 31, sw = (l31 >> 1) & 7;
             const int rrow = ln >> 3, rch = ln & 7;
@@ -952,15 +976,12 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
             else        store_tile(std::false_type{});
             if (q + 1 == n_my) break;
             ++q;
-            kt = 0;
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             __builtin_amdgcn_s_barrier();                  // everybody has read the staging room back
             AB_FENCE();
             begin_tile(q);
             fetch_vec(q + 1);
         }
-        a_slot = nxt;
-        w_slot = nw;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // no DMA may still target LDS when the group ends
 }
