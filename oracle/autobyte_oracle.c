@@ -100,7 +100,16 @@ static void orc_dense(const double *W, const double *b, int n_out, int n_in,
  *                           applied to each layer's K statistics and the results are averaged
  *                           over the L layers ("embed layer-wise computation time into a fixed
  *                           dimension feature space", Section 3.1 "Meta network architecture")
- *  te_W[2], te_b[2]  : tensor-encoder weights ([te_h0,K], [te_h1,te_h0]) and biases
+ *                      2 -> each layer's K statistics are embedded linearly into te_h0 values and a
+ *                           two-layer LSTM of te_h1 units per layer runs over the L layers in order;
+ *                           the second layer's last hidden state is the statistics block
+ *                           ("we apply two-layer LSTM to extract the sequential features in T",
+ *                           Section 3.1 "Meta network architecture")
+ *  te_W[2], te_b[2]  : tensor-encoder weights ([te_h0,K], [te_h1,te_h0]) and biases; for the LSTM
+ *                      te_W[3] = {[te_h0,K], [4*te_h1, te_h0+te_h1], [4*te_h1, 2*te_h1]} and te_b[3]
+ *                      = {[te_h0], [4*te_h1], [4*te_h1]}: the recurrent matrices act on
+ *                      [input ; previous hidden state], gate blocks in the order input, forget,
+ *                      candidate, output
  *  n_hidden, hidden[]: widths of the scorer's hidden layers (ReLU after each)
  *  W[n_hidden+1], b[]: scorer weights, W[k] is [out,in] row-major; the last one has out = 1 and
  *                      is linear (V is a regression target)
@@ -128,7 +137,67 @@ static int orc_stats_width(const orc_model *m)
 
 int orc_input_width(const orc_model *m) { return orc_stats_width(m) + 2; }
 
-/* Statistics block + scalars of one scenario -> xs[orc_stats_width]. tmp holds te_h0+te_h1+K doubles. */
+static double orc_sigmoid(double x) { return 1.0 / (1.0 + exp(-x)); }
+
+/*
+ * One LSTM cell step (Hochreiter & Schmidhuber's cell with forget gate, the form every library uses):
+ *   z = W [x ; h] + b,  i = s(z[0:H]), f = s(z[H:2H]), g = tanh(z[2H:3H]), o = s(z[3H:4H]),
+ *   c <- f*c + i*g,  h <- o*tanh(c).
+ * xh holds [x (nx values) ; h (H values)], z is scratch of 4H values.
+ */
+static void orc_lstm_step(const double *W, const double *b, int nx, int H, const double *xh,
+                          double *c, double *h_out, double *z)
+{
+    orc_dense(W, b, 4 * H, nx + H, xh, z, 0);
+    for (int u = 0; u < H; ++u) {
+        const double i = orc_sigmoid(z[u]), f = orc_sigmoid(z[H + u]);
+        const double g = tanh(z[2 * H + u]), o = orc_sigmoid(z[3 * H + u]);
+        c[u] = f * c[u] + i * g;
+        h_out[u] = o * tanh(c[u]);
+    }
+}
+
+/*
+ * The temporal encoder of Section 3.1: linear embedding of each layer's statistics, two stacked LSTM
+ * layers over the L layers (zero initial state), last hidden state of the second layer -> out[te_h1].
+ * tmp holds K + te_h0 + 11*te_h1 doubles.
+ */
+static void orc_lstm_encode_one(const orc_model *m, const double *dyn_s, double *out, double *tmp)
+{
+    const int E = m->te_h0, H = m->te_h1;
+    double *in = tmp, *xh1 = in + m->K, *xh2 = xh1 + E + H, *c1 = xh2 + 2 * H, *c2 = c1 + H, *z = c2 + H;
+    double *h1 = xh1 + E, *h2 = xh2 + H;                 /* the recurrent halves of the two inputs */
+    for (int u = 0; u < H; ++u) h1[u] = h2[u] = c1[u] = c2[u] = 0.0;
+    for (int l = 0; l < m->L; ++l) {
+        for (int k = 0; k < m->K; ++k)
+            in[k] = orc_phi(dyn_s[l * m->K + k], m->stat_kind[k], m->stat_shift[k], m->stat_scale[k]);
+        orc_dense(m->te_W[0], m->te_b[0], E, m->K, in, xh1, 0);
+        if (m->round_stored_bf16) for (int j = 0; j < E; ++j) xh1[j] = orc_round_bf16(xh1[j]);
+        orc_lstm_step(m->te_W[1], m->te_b[1], E, H, xh1, c1, h1, z);
+        if (m->round_stored_bf16) for (int u = 0; u < H; ++u) h1[u] = orc_round_bf16(h1[u]);
+        for (int u = 0; u < H; ++u) xh2[u] = h1[u];
+        orc_lstm_step(m->te_W[2], m->te_b[2], H, H, xh2, c2, h2, z);
+        if (m->round_stored_bf16) for (int u = 0; u < H; ++u) h2[u] = orc_round_bf16(h2[u]);
+    }
+    for (int u = 0; u < H; ++u) out[u] = h2[u];
+}
+
+/* Scratch doubles orc_scenario_features needs behind xs. */
+static int orc_feature_scratch(const orc_model *m) { return m->K + m->te_h0 + 11 * m->te_h1 + 8; }
+
+/* The LSTM encoder alone: out[S, te_h1] (lets tests hold it against a library LSTM). */
+int orc_lstm_encode(const orc_model *m, const double *dyn, int64_t S, double *out)
+{
+    if (!m || m->tensor_encoder != 2 || !out || S < 0) return ORC_ERR_ARG;
+    double *tmp = (double *)malloc(sizeof(double) * (size_t)orc_feature_scratch(m));
+    if (!tmp) return ORC_ERR_MEM;
+    for (int64_t s = 0; s < S; ++s)
+        orc_lstm_encode_one(m, dyn + (size_t)s * m->L * m->K, out + (size_t)s * m->te_h1, tmp);
+    free(tmp);
+    return ORC_OK;
+}
+
+/* Statistics block + scalars of one scenario -> xs[orc_stats_width]. tmp holds orc_feature_scratch doubles. */
 static void orc_scenario_features(const orc_model *m, const double *dyn_s, const double *scal_s,
                                   double *xs, double *tmp)
 {
@@ -139,6 +208,9 @@ static void orc_scenario_features(const orc_model *m, const double *dyn_s, const
                 xs[l * m->K + k] = orc_phi(dyn_s[l * m->K + k], m->stat_kind[k],
                                            m->stat_shift[k], m->stat_scale[k]);
         off = m->L * m->K;
+    } else if (m->tensor_encoder == 2) {
+        orc_lstm_encode_one(m, dyn_s, xs, tmp);
+        off = m->te_h1;
     } else {
         double *in = tmp, *h0 = tmp + m->K, *h1 = h0 + m->te_h0;
         for (int j = 0; j < m->te_h1; ++j) xs[j] = 0.0;
@@ -192,7 +264,7 @@ int orc_score(const orc_model *m, const double *dyn, const double *scal, int64_t
     const int Fs = orc_stats_width(m), F = Fs + 2;
     int maxw = 1;
     for (int k = 0; k < m->n_hidden; ++k) if (m->hidden[k] > maxw) maxw = m->hidden[k];
-    const int tmpw = m->K + m->te_h0 + m->te_h1 + 1;
+    const int tmpw = orc_feature_scratch(m);
     int err = 0;
 #pragma omp parallel
     {
@@ -224,7 +296,7 @@ int orc_materialise_inputs(const orc_model *m, const double *dyn, const double *
 {
     if (!m || !X || S < 0 || P <= 0 || Q <= 0) return ORC_ERR_ARG;
     const int Fs = orc_stats_width(m), F = Fs + 2;
-    double *xs = (double *)malloc(sizeof(double) * (size_t)(Fs + m->K + m->te_h0 + m->te_h1 + 1));
+    double *xs = (double *)malloc(sizeof(double) * (size_t)(Fs + orc_feature_scratch(m)));
     if (!xs) return ORC_ERR_MEM;
     for (int64_t s = 0; s < S; ++s) {
         orc_scenario_features(m, dyn + (size_t)s * m->L * m->K, scal + (size_t)s * m->Ns, xs, xs + Fs);

@@ -88,6 +88,8 @@ class Model:
     b: List[np.ndarray]
     te_W: Optional[List[np.ndarray]] = None   # tensor encoder: [[h0,K],[h1,h0]] or None
     te_b: Optional[List[np.ndarray]] = None
+    te_kind: str = "mlp"                     # "mlp": shared per-layer MLP + mean; "lstm": embedding + 2-layer LSTM,
+                                             #   te_W = [[E,K], [4H,E+H], [4H,2H]], te_b = [[E], [4H], [4H]]
     round_stored_bf16: bool = False          # diagnostic: mimic a bf16 pipeline's stored activations
     _keep: list = field(default_factory=list, repr=False)
 
@@ -97,7 +99,9 @@ class Model:
 
     @property
     def stats_width(self) -> int:
-        return (self.te_W[1].shape[0] if self.te_W is not None else self.L * self.K) + self.Ns
+        if self.te_W is None:
+            return self.L * self.K + self.Ns
+        return (self.te_W[1].shape[0] // 4 if self.te_kind == "lstm" else self.te_W[1].shape[0]) + self.Ns
 
     @property
     def F(self) -> int:
@@ -122,8 +126,14 @@ class Model:
         if self.te_W is not None:
             tw = [_f64(w) for w in self.te_W]
             tb = [_f64(x) for x in self.te_b]
-            assert tw[0].shape[1] == self.K and tw[1].shape[1] == tw[0].shape[0]
-            m.tensor_encoder, m.te_h0, m.te_h1 = 1, tw[0].shape[0], tw[1].shape[0]
+            if self.te_kind == "lstm":
+                E, H = tw[0].shape[0], tw[1].shape[0] // 4
+                assert tw[0].shape == (E, self.K) and tw[1].shape == (4 * H, E + H) and tw[2].shape == (4 * H, 2 * H)
+                assert tb[0].shape == (E,) and tb[1].shape == (4 * H,) and tb[2].shape == (4 * H,)
+                m.tensor_encoder, m.te_h0, m.te_h1 = 2, E, H
+            else:
+                assert tw[0].shape[1] == self.K and tw[1].shape[1] == tw[0].shape[0]
+                m.tensor_encoder, m.te_h0, m.te_h1 = 1, tw[0].shape[0], tw[1].shape[0]
             pw, pb = _ptr_array(tw), _ptr_array(tb)
             keep.extend(tw + tb + [pw, pb])
             m.te_W, m.te_b = C.cast(pw, _dpp), C.cast(pb, _dpp)
@@ -172,6 +182,19 @@ def score(model: Model, dyn, scal, part, cred) -> np.ndarray:
     _check(lib.orc_score(C.byref(cm), dyn.ctypes.data_as(_dp), scal.ctypes.data_as(_dp),
                          C.c_int64(S), part.ctypes.data_as(_dp), C.c_int(P),
                          cred.ctypes.data_as(_dp), C.c_int(Q), out.ctypes.data_as(_dp)), "score")
+    return out
+
+
+def lstm_encode(model: Model, dyn) -> np.ndarray:
+    """The LSTM temporal encoder alone (Section 3.1): last hidden state of the second layer, float64 [S, H]."""
+    lib = _load()
+    dyn = _f64(dyn)
+    S = dyn.shape[0]
+    assert model.te_kind == "lstm" and dyn.shape == (S, model.L, model.K)
+    out = np.empty((S, model.te_W[1].shape[0] // 4), dtype=np.float64)
+    cm = model._c()
+    _check(lib.orc_lstm_encode(C.byref(cm), dyn.ctypes.data_as(_dp), C.c_int64(S), out.ctypes.data_as(_dp)),
+           "lstm_encode")
     return out
 
 
