@@ -34,7 +34,7 @@ def oracle_model(orc, np, w):
                      part_enc=w.part_enc, cred_enc=w.cred_enc, hidden=list(w.hidden),
                      W=[np.asarray(x, dtype=np.float64) for x in w.W],
                      b=[np.asarray(x, dtype=np.float64) for x in w.b],
-                     te_W=getattr(w, "te_W", None), te_b=getattr(w, "te_b", None))
+                     te_W=getattr(w, "te_W", None), te_b=getattr(w, "te_b", None), te_kind=getattr(w, "te_kind", "mlp"))
 
 
 def main():
@@ -42,7 +42,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "lstm"])
     ap.add_argument("--scenarios", type=int, default=None, help="override the scenario count (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -65,7 +65,7 @@ def main():
     ab.load()
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    cfg = int(args.workload[3:])
+    cfg = 6 if args.workload == "lstm" else int(args.workload[3:])   # "lstm": cfg5's shape behind the LSTM encoder
     t_gen = time.time()
 
     if cfg == 4:
@@ -121,7 +121,9 @@ def main():
         flops_per_unit = H[0] + sum(2.0 * H[i] * H[i + 1] for i in range(len(H) - 1)) + 2.0 * H[-1]
         workload_desc = {"workload": "%s: %d scenarios x %d candidates, scorer %d->%s->1%s, %s"
                                      % (args.workload, S, Cn, w.F, "->".join(map(str, H)),
-                                        ", tensor encoder 4->128->128 mean-pooled over %d tensors" % w.L
+                                        (", embedding 4->32 + two-layer LSTM (64 units) over %d tensors" % w.L
+                                         if w.te_kind == "lstm" else
+                                         ", tensor encoder 4->128->128 mean-pooled over %d tensors" % w.L)
                                         if w.te_hidden else "", dtype),
                          "scenarios": S, "candidates_per_scenario": Cn,
                          "outputs": "scores+argmax" if want_scores else "argmax"}
@@ -178,6 +180,20 @@ def main():
     else:
         roofline = None
 
+    # ---- the temporal encoder is bound by the vector ALUs: lane-operation slots (a transcendental takes four)
+    encoder_roofline = None
+    if cfg == 6 and "lstm_encoder" in ksum:
+        # per unit and step: 5 exp2 + 5 reciprocals (4 slots each) and 16 plain operations (scalings, sums,
+        # cell update, packing); 128 units (two layers of 64) per scenario and step
+        slots = float(S) * w.L * 128 * (10 * 4 + 16)
+        t_ms = ksum["lstm_encoder"]["avg_ms"]
+        peak = 256 * 4 * 16 * 2.4e9            # CUs x SIMDs x lanes per clock x clock: non-packed fp32 issue slots
+        encoder_roofline = {"bound": "alu", "kernel": "lstm_encoder", "achieved": round(slots / (t_ms * 1e-3) / 1e12, 3),
+                            "peak": round(peak / 1e12, 3), "unit": "T lane-operations/s",
+                            "frac": round(slots / (t_ms * 1e-3) / peak, 4), "traffic": None,
+                            "avg_launch_ms": round(t_ms, 5),
+                            "scenario_steps_per_s": round(float(S) * w.L / (t_ms * 1e-3), 1)}
+
     # ---- launch floor of the update step: the same number of back-to-back trivial dependent launches
     launch_floor = None
     if cfg == 4:
@@ -211,7 +227,7 @@ def main():
             cpu = {"value": n_rows / dt, "unit": unit, "cores": orc.num_threads(), "kind": "oracle",
                    "sample": "one fp64 step on the first %d rows of minibatch 0 (%.1f s)" % (n_rows, dt)}
         else:
-            n_s = {1: 1, 2: 8, 3: 96, 5: 24}[cfg]
+            n_s = {1: 1, 2: 8, 3: 96, 5: 24, 6: 24}[cfg]
             n_s = min(n_s, w.S)
             sub = w.subset(np.arange(n_s))
             t0 = time.perf_counter()
@@ -231,7 +247,7 @@ def main():
            "config": workload_desc,
            "algorithmic_flop_per_unit": flops_per_unit,
            "whole_step_TFLOP/s": round(units_per_step * flops_per_unit / (ms_per_step * 1e-3) / 1e12, 3),
-           "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "launch_floor": launch_floor,
+           "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "launch_floor": launch_floor, "encoder_roofline": encoder_roofline,
            "input_generation_s": round(t_gen, 2)}
     print(json.dumps(out))
 

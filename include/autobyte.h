@@ -54,7 +54,7 @@ extern "C" {
 #define AB_MAX_STATS   8    /* statistics per layer (K)                    */
 #define AB_MAX_SCALARS 16   /* scalar features per scenario                */
 #define AB_MAX_HIDDEN  8    /* hidden layers of the scorer                 */
-#define AB_MAX_LAYERS  12   /* tensor-encoder (2) + hidden (8) + output (1) rounded up */
+#define AB_MAX_LAYERS  12   /* encoder (up to 3) + hidden (8) + output (1)                */
 
 typedef int32_t ab_status;
 enum {
@@ -84,7 +84,13 @@ typedef struct { int32_t kind; float shift; float scale; } ab_enc;
  *                          of 64 and <= 4096
  *   tensor_encoder         0: flat statistics block (width L*K); 1: shared per-layer MLP
  *                          K -> enc_hidden[0] -> enc_hidden[1] (ReLU after both), mean over the L layers
- *                          (width enc_hidden[1]).  Supported: enc_hidden = {128, 128}
+ *                          (width enc_hidden[1]).  Supported: enc_hidden = {128, 128};
+ *                          2: the temporal encoder of Section 3.1 "Meta network architecture": each layer's
+ *                          K statistics are embedded linearly into enc_hidden[0] values and a two-layer
+ *                          LSTM of enc_hidden[1] units per layer runs over the L layers in order (zero
+ *                          initial state); the second layer's last hidden state is the statistics block
+ *                          (width enc_hidden[1]).  Supported: enc_hidden = {32, 64}.
+ *                          Both encoders need compute_dtype = AB_BF16
  *   compute_dtype          AB_F32: fp32 weights, activations and fp32 MFMA; AB_BF16: bf16 weights and
  *                          activations with fp32 accumulation
  * The scorer's input width is F = (L*K or enc_hidden[1]) + n_scalars + 2.
@@ -103,8 +109,11 @@ typedef struct {
 
 /*
  * Parameters (the struct is HOST, every pointer in it is DEVICE).
- * Layer order: the two tensor-encoder layers first (only if tensor_encoder = 1), then the scorer's
- * hidden layers, then the output layer (1 x last hidden width).
+ * Layer order: the encoder's layers first (two if tensor_encoder = 1; three if tensor_encoder = 2: the
+ * embedding [E, K], then per LSTM layer one matrix [4H, n_in + H] = [W_ih | W_hh] acting on
+ * [input ; previous hidden state] with gate blocks in the order input, forget, candidate, output and one
+ * bias [4H], n_in = E for the first and H for the second layer), then the scorer's hidden layers, then
+ * the output layer (1 x last hidden width).
  *   W[k]         [out, in] row-major in compute_dtype (bf16 = upper 16 bits of an fp32), 16-byte aligned
  *   b[k]         [out] fp32
  * Only ab_online_update uses the rest (flat model, so index k counts scorer layers from 0):

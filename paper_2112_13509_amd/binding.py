@@ -162,7 +162,8 @@ def ab_status_string(status: int) -> str:
 # ---------------------------------------------------------------------------------------------
 def make_desc(L: int, K: int, stat_enc: Sequence[Tuple[int, float, float]],
               scal_enc: Sequence[Tuple[int, float, float]], part_enc, cred_enc,
-              hidden: Sequence[int], dtype: str, te_hidden: Optional[Sequence[int]] = None) -> ab_model_desc:
+              hidden: Sequence[int], dtype: str, te_hidden: Optional[Sequence[int]] = None,
+              te_kind: str = "mlp") -> ab_model_desc:
     d = ab_model_desc()
     d.n_layers, d.n_stats, d.n_scalars = int(L), int(K), len(scal_enc)
     if K > AB_MAX_STATS or len(scal_enc) > AB_MAX_SCALARS or len(hidden) > AB_MAX_HIDDEN:
@@ -176,7 +177,7 @@ def make_desc(L: int, K: int, stat_enc: Sequence[Tuple[int, float, float]],
     d.n_hidden = len(hidden)
     for i, h in enumerate(hidden):
         d.hidden[i] = int(h)
-    d.tensor_encoder = 1 if te_hidden else 0
+    d.tensor_encoder = (2 if te_kind == "lstm" else 1) if te_hidden else 0
     if te_hidden:
         d.enc_hidden[0], d.enc_hidden[1] = int(te_hidden[0]), int(te_hidden[1])
     d.compute_dtype = {"f32": AB_F32, "bf16": AB_BF16}[dtype]
@@ -185,7 +186,7 @@ def make_desc(L: int, K: int, stat_enc: Sequence[Tuple[int, float, float]],
 
 def desc_from_workload(wl) -> ab_model_desc:
     return make_desc(wl.L, wl.K, wl.stat_enc, wl.scal_enc, wl.part_enc, wl.cred_enc, wl.hidden,
-                     wl.dtype, getattr(wl, "te_hidden", None))
+                     wl.dtype, getattr(wl, "te_hidden", None), getattr(wl, "te_kind", "mlp"))
 
 
 def _ptr(t: Optional[torch.Tensor], dtype, what: str) -> Optional[int]:

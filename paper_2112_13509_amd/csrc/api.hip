@@ -36,10 +36,11 @@ static ab_status check_desc(const ab_model_desc *d)
         if (d->enc_stat[k].kind != AB_ENC_LINEAR && d->enc_stat[k].kind != AB_ENC_LOG) return AB_ERR_SHAPE;
     for (int k = 0; k < d->n_scalars; ++k)
         if (d->enc_scalar[k].kind != AB_ENC_LINEAR && d->enc_scalar[k].kind != AB_ENC_LOG) return AB_ERR_SHAPE;
-    if (d->tensor_encoder != 0 && d->tensor_encoder != 1) return AB_ERR_SHAPE;
+    if (d->tensor_encoder < 0 || d->tensor_encoder > 2) return AB_ERR_SHAPE;
     if (d->tensor_encoder) {
         if (d->enc_hidden[0] <= 0 || d->enc_hidden[1] <= 0) return AB_ERR_SHAPE;
-        if (d->enc_hidden[0] != 128 || d->enc_hidden[1] != 128) return AB_ERR_UNSUPPORTED;
+        if (d->tensor_encoder == 1 && (d->enc_hidden[0] != 128 || d->enc_hidden[1] != 128)) return AB_ERR_UNSUPPORTED;
+        if (d->tensor_encoder == 2 && (d->enc_hidden[0] != 32 || d->enc_hidden[1] != 64)) return AB_ERR_UNSUPPORTED;
         if (d->compute_dtype != AB_BF16) return AB_ERR_UNSUPPORTED;
     } else if ((int64_t)d->n_layers * d->n_stats > (1 << 20)) {
         return AB_ERR_UNSUPPORTED;
@@ -64,7 +65,7 @@ static ab_status plan_scoring(const ab_model_desc *d, int64_t S, int32_t C, Scor
 {
     memset(p, 0, sizeof(*p));
     p->dtype = d->compute_dtype;
-    p->base = d->tensor_encoder ? 2 : 0;
+    p->base = d->tensor_encoder == 2 ? 3 : d->tensor_encoder ? 2 : 0;
     p->Fs = (d->tensor_encoder ? d->enc_hidden[1] : d->n_layers * d->n_stats) + d->n_scalars;
     p->F = p->Fs + 2;
     p->Kp = round_up(p->Fs, 64);
@@ -201,7 +202,17 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
 
     // 1. scenario rows: transformed statistics (or pooled tensor embedding) + scalars, K-padded
     const double es = (double)elem_size(dt);
-    if (desc->tensor_encoder) {
+    if (desc->tensor_encoder == 2) {
+        {
+            // per scenario and layer: two gate products (256 x 96 and 256 x 128) and the K -> 32 embedding
+            TraceScope ts("lstm_encoder", (double)S * desc->n_layers * 2.0 * (256.0 * 224.0 + 32.0 * desc->n_stats), 0, st);
+            AB_HIP(launch_lstm_encoder(desc, stats->dyn, params->W[0], params->b[0], params->W[1], params->b[1],
+                                       params->W[2], params->b[2], xs, p.Kp, S, st));
+        }
+        TraceScope ts("encode_stats", (double)S * (desc->n_scalars * 4.0 + (p.Kp - desc->enc_hidden[1]) * es), 1, st);
+        AB_HIP(launch_encode_stats(dt, desc, stats->dyn, stats->scalars, xs, S, p.Kp,
+                                   desc->enc_hidden[1], 0, st));
+    } else if (desc->tensor_encoder) {
         {
             TraceScope ts("tensor_encoder", (double)S * desc->n_layers * 2.0 * (desc->n_stats * 128.0 + 128.0 * 128.0),
                           0, st);

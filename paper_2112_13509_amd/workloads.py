@@ -81,6 +81,7 @@ class Workload:
     part: np.ndarray                # [P] float32 partition sizes in bytes
     cred: np.ndarray                # [Q] float32 credit multiples
     seed: int = 0
+    te_kind: str = "mlp"            # "mlp": per-layer MLP + mean; "lstm": embedding + two-layer LSTM over the layers
 
     @property
     def S(self) -> int:
@@ -96,7 +97,7 @@ class Workload:
 
     @property
     def F(self) -> int:
-        return (self.te_hidden[1] if self.te_hidden else self.L * self.K) + self.Ns + 2
+        return (self.te_hidden[1] if self.te_hidden else self.L * self.K) + self.Ns + 2   # (te_hidden = [E, H] for "lstm")
 
     def subset(self, idx) -> "Workload":
         """Same model and grid, scenarios restricted to ``idx``."""
@@ -104,7 +105,7 @@ class Workload:
         return Workload(self.name, self.dtype, self.L, self.K, self.stat_enc, self.scal_enc,
                         self.part_enc, self.cred_enc, self.hidden, self.W, self.b, self.te_hidden,
                         self.te_W, self.te_b, np.ascontiguousarray(self.dyn[idx]),
-                        np.ascontiguousarray(self.scal[idx]), self.part, self.cred, self.seed)
+                        np.ascontiguousarray(self.scal[idx]), self.part, self.cred, self.seed, self.te_kind)
 
 
 # --------------------------------------------------------------------------------------------
@@ -228,6 +229,26 @@ def make_tensor_encoder(name: str, S: int, hidden: List[int], te_hidden: List[in
                     log_spaced(part_lo, part_hi, P), log_spaced(cred_lo, cred_hi, Q), seed)
 
 
+def make_lstm_encoder(name: str, S: int, hidden: List[int], P: int, Q: int, dtype: str, seed: int,
+                      n_blocks=24, per_block=16, extra=16, E: int = 32, H: int = 64) -> Workload:
+    """The tensor-encoder problem with the temporal encoder in front: per-tensor statistics embedded into E
+    values, two LSTM layers of H units over the tensor sequence (te_W = [[E,4], [4H,E+H], [4H,2H]])."""
+    rng = np.random.default_rng(seed)
+    W_e, b_e = _draw_dense(rng, E, 4, dtype)
+    W_1, b_1 = _draw_dense(rng, 4 * H, E + H, dtype)
+    W_2, b_2 = _draw_dense(rng, 4 * H, 2 * H, dtype)
+    Ws, bs = _draw_mlp(rng, [H + 6 + 2] + list(hidden) + [1], dtype)
+    dyn = _draw_transformer_stats(rng, S, n_blocks, per_block, extra)
+    scal, _ = _draw_scalars(rng, S, 2)
+    part_lo, part_hi, cred_lo, cred_hi = 16.0 * KIB, 64.0 * MIB, 1.0, 64.0
+    stat_enc = [_time_enc(), _time_enc(), _log_uniform_enc(1.0 * KIB, 256.0 * MIB),
+                (ENC_LINEAR, 0.5, math.sqrt(12.0))]
+    return Workload(name, dtype, dyn.shape[1], 4, stat_enc, _scalar_encs(2),
+                    _log_uniform_enc(part_lo, part_hi), _log_uniform_enc(cred_lo, cred_hi),
+                    list(hidden), Ws, bs, [E, H], [W_e, W_1, W_2], [b_e, b_1, b_2], dyn, scal,
+                    log_spaced(part_lo, part_hi, P), log_spaced(cred_lo, cred_hi, Q), seed, "lstm")
+
+
 def make_config(cfg: int, S: Optional[int] = None, seed: Optional[int] = None) -> Workload:
     """The four scoring configurations (1, 2, 3, 5).  ``S`` overrides the scenario count (the
     distributions, model and grid stay those of the configuration)."""
@@ -244,7 +265,9 @@ def make_config(cfg: int, S: Optional[int] = None, seed: Optional[int] = None) -
     if cfg == 5:
         return make_tensor_encoder("cfg5-tensor-encoder-bf16", S or 8192, [512, 512], [128, 128],
                                    32, 32, "bf16", seed)
-    raise ValueError("scoring configurations are 1, 2, 3 and 5 (4 is the update workload)")
+    if cfg == 6:     # not one of the five baseline configurations: configuration 5's shape with the paper's LSTM encoder
+        return make_lstm_encoder("lstm-encoder-bf16", S or 8192, [512, 512], 32, 32, "bf16", seed)
+    raise ValueError("scoring configurations are 1, 2, 3, 5 and 6 (4 is the update workload)")
 
 
 # --------------------------------------------------------------------------------------------
