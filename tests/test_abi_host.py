@@ -57,6 +57,24 @@ def test_workspace_bytes(lib):
     assert ab.ab_workspace_bytes(du, 0, 0, 64) > 0
 
 
+def test_encoder_options_in_the_descriptor(lib):
+    # the temporal encoder (embedding + two-layer LSTM): widths {32, 64}, bf16 only, three parameter layers in front
+    w = wl.make_lstm_encoder("lstm-host", 2, [64, 64], 2, 2, "bf16", 1, n_blocks=1, per_block=2, extra=0)
+    d = ab.desc_from_workload(w)
+    assert d.tensor_encoder == 2 and list(d.enc_hidden) == [32, 64]
+    assert ab.ab_workspace_bytes(d, 16, 4) > 0
+    p = _fake_params(3 + 2)                                   # the output layer's pointers are missing
+    assert _call_score(lib, d, params=p) == -1
+    d.enc_hidden[1] = 128
+    assert ab.ab_workspace_bytes(d, 16, 4) == 0 and _call_score(lib, d, params=_fake_params(6)) == -6
+    d.enc_hidden[1] = 64
+    d.compute_dtype = 0
+    assert _call_score(lib, d, params=_fake_params(6)) == -6
+    d.compute_dtype = 1
+    d.tensor_encoder = 3
+    assert _call_score(lib, d, params=_fake_params(6)) == -2
+
+
 def _call_score(lib, d, params=None, stats=None, grid=None, scores=0x1000, idx=0x2000, best=None,
                 ws=0x100000, ws_bytes=1 << 40):
     p = params or ab.ab_params()
