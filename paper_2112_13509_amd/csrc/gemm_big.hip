@@ -703,6 +703,7 @@ __device__ __forceinline__ void dma4(const void *gsrc, void *lds_uniform_dst)   
     __builtin_amdgcn_global_load_lds((global_void *)gsrc, (lds_void *)lds_uniform_dst, 4, 0, 0);
 }
 
+template <int EPI>
 __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
 {
     constexpr int BM = 256, BK = 64;
@@ -854,9 +855,11 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
 
     int64_t m0 = 0;
     int n0 = 0;
+    unsigned tn = 0;
     auto begin_tile = [&](unsigned q) {
         const unsigned local = l0 + q * G8;
-        n0 = (int)(local % n_tiles) * 256;
+        tn = local % n_tiles;
+        n0 = (int)tn * 256;
         m0 = ((int64_t)(local / n_tiles) * 8 + xcd) * BM;
         const int hf = opaque_lane() >> 5;
 #pragma unroll
@@ -916,8 +919,14 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
         mma(0);
         AB_INTERLEAVE_6();
         AB_FENCE();
-        if (!FIRST || q == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        else                  asm volatile("s_waitcnt vmcnt(19)" ::: "memory");
+        if (!FIRST || q == 0) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        } else if constexpr (EPI == EPI_STORE) {
+            asm volatile("s_waitcnt vmcnt(19)" ::: "memory");          // 16 stores + 3 vector fetches
+        } else {
+            if (wave < 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");   // 1 store of partial sums + 3
+            else          asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+        }
         // own LDS traffic of this slab is done (fragment reads, generated chunks); then meet: slab j+1 is
         // complete and visible to everybody and slab j's stages may be refilled
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -939,41 +948,72 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
         for (int kt = 1; kt < KT; ++kt) slab(std::false_type{}, kt);
         {
             // ------------------------------------------------------------ epilogue of tile q (never ragged)
-            unsigned char *mine = smem + (a_slot ^ 1) * SLAB + wave * 4096;   // the A stage retired by the last barrier
+            unsigned char *stage = smem + (a_slot ^ 1) * SLAB;            // the A stage retired by the last barrier
             const int ln = opaque_lane();
             const int half = ln >> 5, l31 = ln & 31, sw = (l31 >> 1) & 7;
-            const int rrow = ln >> 3, rch = ln & 7;
-            uint16_t *dst = (uint16_t *)g.out + (m0 + wave_m * 128 + rrow) * g.ldo + n0 + wave_n * 64 + rch * 8;
-            auto store_tile = [&](auto relu_tag) {
+            if constexpr (EPI == EPI_STORE) {
+                unsigned char *mine = stage + wave * 4096;
+                const int rrow = ln >> 3, rch = ln & 7;
+                uint16_t *dst = (uint16_t *)g.out + (m0 + wave_m * 128 + rrow) * g.ldo + n0 + wave_n * 64 + rch * 8;
+                auto store_tile = [&](auto relu_tag) {
+    #pragma unroll
+                    for (int im = 0; im < 4; ++im) {
+    #pragma unroll
+                        for (int jn = 0; jn < 2; ++jn)
+    #pragma unroll
+                            for (int rg = 0; rg < 4; ++rg) {
+                                float v[4];
+    #pragma unroll
+                                for (int e = 0; e < 4; ++e) {
+                                    v[e] = acc[jn][im][rg * 4 + e];
+                                    if constexpr (decltype(relu_tag)::value) v[e] = relu_keep_nan(v[e]);
+                                }
+                                uint2 pk = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+                                lds_write8(mine + l31 * 128 + (((jn * 4 + rg) ^ sw) << 4) + half * 8, pk);
+                            }
+                        i32x4 o[4];
+    #pragma unroll
+                        for (int it = 0; it < 4; ++it) {
+                            const int row = rrow + 8 * it;
+                            o[it] = *(const i32x4 *)(mine + row * 128 + ((rch ^ ((row >> 1) & 7)) << 4));
+                        }
+                        uint16_t *d = dst + (int64_t)(im * 32) * g.ldo;
+    #pragma unroll
+                        for (int it = 0; it < 4; ++it)
+                            __builtin_nontemporal_store(o[it], (i32x4 *)(d + (int64_t)(8 * it) * g.ldo));
+                    }
+                };
+                if (g.relu) store_tile(std::true_type{});
+                else        store_tile(std::false_type{});
+            } else {   // EPI_SCORE: the output unit as a per-lane dot product, reduced over the four column wavefronts
+                float ps[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+                    for (int rg = 0; rg < 4; ++rg) {
+                        const f32x8_unaligned w8 = scalar_load8(g.w_out + n0 + wave_n * 64 + jn * 32 + rg * 8);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float wv = half ? w8[4 + e] : w8[e];
+#pragma unroll
+                            for (int im = 0; im < 4; ++im)
+                                ps[im] += relu_keep_nan(acc[jn][im][rg * 4 + e]) * wv;
+                        }
+                    }
+                float *red = (float *)stage;               // [4 column-waves][256 rows]
 #pragma unroll
                 for (int im = 0; im < 4; ++im) {
-#pragma unroll
-                    for (int jn = 0; jn < 2; ++jn)
-#pragma unroll
-                        for (int rg = 0; rg < 4; ++rg) {
-                            float v[4];
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                v[e] = acc[jn][im][rg * 4 + e];
-                                if constexpr (decltype(relu_tag)::value) v[e] = relu_keep_nan(v[e]);
-                            }
-                            uint2 pk = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-                            lds_write8(mine + l31 * 128 + (((jn * 4 + rg) ^ sw) << 4) + half * 8, pk);
-                        }
-                    i32x4 o[4];
-#pragma unroll
-                    for (int it = 0; it < 4; ++it) {
-                        const int row = rrow + 8 * it;
-                        o[it] = *(const i32x4 *)(mine + row * 128 + ((rch ^ ((row >> 1) & 7)) << 4));
-                    }
-                    uint16_t *d = dst + (int64_t)(im * 32) * g.ldo;
-#pragma unroll
-                    for (int it = 0; it < 4; ++it)
-                        __builtin_nontemporal_store(o[it], (i32x4 *)(d + (int64_t)(8 * it) * g.ldo));
+                    const float v = ps[im] + __shfl_xor(ps[im], 32, 64);
+                    if (half == 0) lds_write4(red + wave_n * BM + wave_m * 128 + l31 + im * 32, v);
                 }
-            };
-            if (g.relu) store_tile(std::true_type{});
-            else        store_tile(std::false_type{});
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                if (wave < 4) {
+                    const int tt = wave * 64 + ln;
+                    const float v = (red[tt] + red[BM + tt]) + (red[2 * BM + tt] + red[3 * BM + tt]);
+                    g.partial[(m0 + tt) * g.n_tiles + tn] = v;
+                }
+            }
             if (q + 1 == n_my) break;
             ++q;
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -986,10 +1026,11 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // no DMA may still target LDS when the group ends
 }
 
+template <int EPI>
 static hipError_t launch_stream_gen(const GemmArgs &g, hipStream_t st)
 {
     constexpr int smem = 4 * 256 * 128 + 20480;
-    auto kern = gemm_stream_gen_kernel;
+    auto kern = gemm_stream_gen_kernel<EPI>;
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     int dev = 0, cus = 0;
@@ -1064,8 +1105,8 @@ hipError_t launch_gemm_big(int amode, int epi, GemmArgs g, hipStream_t st)
     }
     // generated operand: the streaming kernel needs the bias, the vector area bounds K, two slabs at least,
     // 32-bit row arithmetic and 4-byte DMA sources
-    if (epi == EPI_STORE && g.bias && g.K <= 1024 && g.K >= 128 && g.M < (1LL << 31))
-        return launch_stream_gen(g, st);
+    if (g.bias && g.K <= 1024 && g.K >= 128 && g.M < (1LL << 31))
+        return epi == EPI_STORE ? launch_stream_gen<EPI_STORE>(g, st) : launch_stream_gen<EPI_SCORE>(g, st);
     return epi == EPI_STORE ? launch_big_one<AMODE_GEN, EPI_STORE>(g, st)
                             : launch_big_one<AMODE_GEN, EPI_SCORE>(g, st);
 }
