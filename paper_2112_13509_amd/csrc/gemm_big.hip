@@ -956,14 +956,14 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
                 const int rrow = ln >> 3, rch = ln & 7;
                 uint16_t *dst = (uint16_t *)g.out + (m0 + wave_m * 128 + rrow) * g.ldo + n0 + wave_n * 64 + rch * 8;
                 auto store_tile = [&](auto relu_tag) {
-    #pragma unroll
+#pragma unroll
                     for (int im = 0; im < 4; ++im) {
-    #pragma unroll
+#pragma unroll
                         for (int jn = 0; jn < 2; ++jn)
-    #pragma unroll
+#pragma unroll
                             for (int rg = 0; rg < 4; ++rg) {
                                 float v[4];
-    #pragma unroll
+#pragma unroll
                                 for (int e = 0; e < 4; ++e) {
                                     v[e] = acc[jn][im][rg * 4 + e];
                                     if constexpr (decltype(relu_tag)::value) v[e] = relu_keep_nan(v[e]);
@@ -972,13 +972,13 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
                                 lds_write8(mine + l31 * 128 + (((jn * 4 + rg) ^ sw) << 4) + half * 8, pk);
                             }
                         i32x4 o[4];
-    #pragma unroll
+#pragma unroll
                         for (int it = 0; it < 4; ++it) {
                             const int row = rrow + 8 * it;
                             o[it] = *(const i32x4 *)(mine + row * 128 + ((rch ^ ((row >> 1) & 7)) << 4));
                         }
                         uint16_t *d = dst + (int64_t)(im * 32) * g.ldo;
-    #pragma unroll
+#pragma unroll
                         for (int it = 0; it < 4; ++it)
                             __builtin_nontemporal_store(o[it], (i32x4 *)(d + (int64_t)(8 * it) * g.ldo));
                     }
