@@ -398,15 +398,23 @@ int orc_trigger(const float *scores, int64_t S, int C, int64_t row_stride, const
  * Backward is exact back-propagation of loss = (1/B) sum_i (yhat_i - y_i)^2:
  *   d_out_i = 2 (yhat_i - y_i) / B ; dW = d^T h_prev ; db = sum_i d_i ; d_prev = (d W) * [pre > 0].
  * Adam follows Kingma & Ba, Algorithm 1, with bias correction and epsilon outside the root.
+ *
+ * Transfer-learning form ("use transfer learning to update the offline trained model", Section 3.2; the
+ * workflow of Section 3.3 adapts the trained network online): layers below first_trainable keep their
+ * parameters and moments; back-propagation stops at the first trainable layer.  first_trainable = 0 is
+ * the full update, first_trainable = n_hidden updates the output layer alone.  Frozen layers report
+ * zero gradients.
  */
-int orc_update(const orc_model *m, const double *x_raw, const double *target, int64_t B,
-               const double *const *Wf, const double *const *bf,
-               double *const *Wm, double *const *bm,
-               double *const *mW, double *const *vW, double *const *mb, double *const *vb,
-               int64_t t, double lr, double beta1, double beta2, double eps, int do_adam,
-               double *loss_out, double *const *gW, double *const *gb, double *yhat_out)
+int orc_update_tail(const orc_model *m, const double *x_raw, const double *target, int64_t B,
+                    const double *const *Wf, const double *const *bf,
+                    double *const *Wm, double *const *bm,
+                    double *const *mW, double *const *vW, double *const *mb, double *const *vb,
+                    int64_t t, double lr, double beta1, double beta2, double eps, int do_adam,
+                    double *loss_out, double *const *gW, double *const *gb, double *yhat_out,
+                    int first_trainable)
 {
     if (!m || !x_raw || !target || B <= 0 || m->tensor_encoder) return ORC_ERR_ARG;
+    if (first_trainable < 0 || first_trainable > m->n_hidden) return ORC_ERR_ARG;
     const int nl = m->n_hidden + 1;
     const int F = m->L * m->K + m->Ns + 2;
     int width[16];
@@ -465,7 +473,7 @@ int orc_update(const orc_model *m, const double *x_raw, const double *target, in
         if (loss_out) *loss_out = loss / (double)B;
     }
     /* backward */
-    for (int k = nl - 1; k >= 0; --k) {
+    for (int k = nl - 1; k >= first_trainable; --k) {
         const int no = width[k + 1], ni = width[k];
         /* dW[o,i] = sum_rows d[o] * h_prev[i]; db[o] = sum_rows d[o] */
 #pragma omp parallel for schedule(static)
@@ -480,7 +488,7 @@ int orc_update(const orc_model *m, const double *x_raw, const double *target, in
             }
             gbl[k][o] = sb;
         }
-        if (k > 0) {
+        if (k > first_trainable) {
 #pragma omp parallel for schedule(static)
             for (int64_t r = 0; r < B; ++r) {
                 const double *dn = d[k + 1] + (size_t)r * no;
@@ -500,7 +508,7 @@ int orc_update(const orc_model *m, const double *x_raw, const double *target, in
     }
     if (do_adam) {
         const double c1 = 1.0 - pow(beta1, (double)t), c2 = 1.0 - pow(beta2, (double)t);
-        for (int k = 0; k < nl; ++k) {
+        for (int k = first_trainable; k < nl; ++k) {
             size_t nw = (size_t)width[k + 1] * width[k], nb = (size_t)width[k + 1];
             for (size_t j = 0; j < nw + nb; ++j) {
                 int isb = j >= nw;
@@ -520,4 +528,15 @@ cleanup:
     for (int k = 0; gWl && gbl && k < nl; ++k) { free(gWl[k]); free(gbl[k]); }
     free(h); free(d); free(gWl); free(gbl);
     return fail ? ORC_ERR_MEM : ORC_OK;
+}
+
+int orc_update(const orc_model *m, const double *x_raw, const double *target, int64_t B,
+               const double *const *Wf, const double *const *bf,
+               double *const *Wm, double *const *bm,
+               double *const *mW, double *const *vW, double *const *mb, double *const *vb,
+               int64_t t, double lr, double beta1, double beta2, double eps, int do_adam,
+               double *loss_out, double *const *gW, double *const *gb, double *yhat_out)
+{
+    return orc_update_tail(m, x_raw, target, B, Wf, bf, Wm, bm, mW, vW, mb, vb, t, lr, beta1, beta2, eps,
+                           do_adam, loss_out, gW, gb, yhat_out, 0);
 }

@@ -277,12 +277,13 @@ class TrainState:
 
 
 def update(model: Model, state: TrainState, x_raw, target, lr=1e-3, beta1=0.9, beta2=0.999,
-           eps=1e-8, do_adam=True, forward_weights=None, want_grads=True):
+           eps=1e-8, do_adam=True, forward_weights=None, want_grads=True, first_trainable=0):
     """One online-adaptation step (forward, MSE loss, back-propagation, Adam) on ``state``.
 
     ``model`` supplies the feature layout and widths; its own W/b are ignored in favour of
     ``state``.  ``forward_weights`` optionally replaces the weights used by forward/backward
     (e.g. a bf16-rounded copy) while Adam still updates the fp64 masters.
+    ``first_trainable`` > 0 is the transfer-learning form: scorer layers below it stay frozen.
     Returns dict(loss, gW, gb, yhat)."""
     lib = _load()
     x_raw, target = _f64(x_raw), _f64(target)
@@ -301,14 +302,32 @@ def update(model: Model, state: TrainState, x_raw, target, lr=1e-3, beta1=0.9, b
         for a in lst:
             assert a.dtype == np.float64 and a.flags.c_contiguous
     t = state.t + 1
-    _check(lib.orc_update(C.byref(cm), x_raw.ctypes.data_as(_dp), target.ctypes.data_as(_dp),
+    _check(lib.orc_update_tail(C.byref(cm), x_raw.ctypes.data_as(_dp), target.ctypes.data_as(_dp),
                           C.c_int64(B), _ptr_array(Wf), _ptr_array(state.b),
                           _ptr_array(state.W), _ptr_array(state.b),
                           _ptr_array(state.mW), _ptr_array(state.vW),
                           _ptr_array(state.mb), _ptr_array(state.vb),
                           C.c_int64(t), C.c_double(lr), C.c_double(beta1), C.c_double(beta2),
                           C.c_double(eps), C.c_int(1 if do_adam else 0), C.byref(loss),
-                          _ptr_array(gW), _ptr_array(gb), yhat.ctypes.data_as(_dp)), "update")
+                          _ptr_array(gW), _ptr_array(gb), yhat.ctypes.data_as(_dp),
+                          C.c_int(int(first_trainable))), "update")
     if do_adam:
         state.t = t
     return {"loss": float(loss.value), "gW": gW, "gb": gb, "yhat": yhat}
+
+
+def replay_mix(x_new, t_new, x_old, t_old, pick):
+    """Minibatch assembled from freshly observed rows and the offline set ("update the offline trained model
+    and also update the dataset", Section 3.2): entry i of ``pick`` >= 0 takes new row pick[i], entry < 0 takes
+    old row -pick[i] - 1; an index outside its pool gives a NaN row.  Returns (x [B, F], target [B])."""
+    x_new, t_new, x_old, t_old = _f64(x_new), _f64(t_new), _f64(x_old), _f64(t_old)
+    pick = np.asarray(pick, dtype=np.int64)
+    F = x_new.shape[1] if x_new.size else x_old.shape[1]
+    x = np.full((pick.shape[0], F), np.nan)
+    t = np.full(pick.shape[0], np.nan)
+    for i, p in enumerate(pick):
+        if 0 <= p < x_new.shape[0]:
+            x[i], t[i] = x_new[p], t_new[p]
+        elif p < 0 and -p - 1 < x_old.shape[0]:
+            x[i], t[i] = x_old[-p - 1], t_old[-p - 1]
+    return x, t
