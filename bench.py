@@ -180,6 +180,39 @@ def main():
     else:
         roofline = None
 
+    # ---- transfer-learning form of the update and the minibatch assembly, timed next to the full step (cfg4 only)
+    transfer = None
+    if cfg == 4:
+        transfer = {}
+        D = len(u.hidden)
+        for k0 in (D - 1, D):
+            for _ in range(20):
+                ab.ab_online_update_tail(d, prm, batches[0][0], batches[0][1], k0, loss_out=loss, workspace=ws)
+            torch.cuda.synchronize()
+            f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            f0.record()
+            for i in range(200):
+                ab.ab_online_update_tail(d, prm, batches[i % 16][0], batches[i % 16][1], k0, loss_out=loss, workspace=ws)
+            f1.record()
+            torch.cuda.synchronize()
+            transfer["first_trainable_%d_us_per_step" % k0] = round(f0.elapsed_time(f1) * 1e3 / 200, 2)
+        pick = torch.randint(-u.x_raw.shape[0], 4096, (u.batch,), dtype=torch.int32, device=dev)
+        xo, to = torch.empty_like(batches[0][0]), torch.empty_like(batches[0][1])
+        for _ in range(10):
+            ab.ab_replay_mix(batches[1][0], batches[1][1], xall, yall, pick, xo, to)
+        torch.cuda.synchronize()
+        f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        f0.record()
+        for _ in range(200):
+            ab.ab_replay_mix(batches[1][0], batches[1][1], xall, yall, pick, xo, to)
+        f1.record()
+        torch.cuda.synchronize()
+        us = f0.elapsed_time(f1) * 1e3 / 200
+        transfer["replay_mix_us"] = round(us, 2)
+        transfer["replay_mix_GB/s"] = round(u.batch * (u.F + 1) * 8.0 / (us * 1e-6) / 1e9, 1)
+        transfer["note"] = ("first_trainable = D-1 trains the last hidden layer and the output unit, D the output "
+                            "unit alone; replay_mix gathers one 4096-row minibatch from a 4096-row and a 65536-row pool")
+
     # ---- the temporal encoder is bound by the vector ALUs: lane-operation slots (a transcendental takes four)
     encoder_roofline = None
     if cfg == 6 and "lstm_encoder" in ksum:
@@ -247,7 +280,7 @@ def main():
            "config": workload_desc,
            "algorithmic_flop_per_unit": flops_per_unit,
            "whole_step_TFLOP/s": round(units_per_step * flops_per_unit / (ms_per_step * 1e-3) / 1e12, 3),
-           "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "launch_floor": launch_floor, "encoder_roofline": encoder_roofline,
+           "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "launch_floor": launch_floor, "encoder_roofline": encoder_roofline, "transfer_learning": transfer,
            "input_generation_s": round(t_gen, 2)}
     print(json.dumps(out))
 

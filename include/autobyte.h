@@ -14,6 +14,7 @@
  *   ab_score_candidates  predicted V for every (scenario, candidate), optionally fused with the choice
  *   ab_select_best       per-scenario argmax over a stored score matrix
  *   ab_online_update     one forward + backward + Adam step on explicit (statistics, candidate, V) rows
+ *   ab_online_update_tail, ab_replay_mix   the same step with frozen lower layers; minibatch from two pools
  *   ab_trigger           the choice plus the two threshold tests of the Optimization Trigger
  *
  * General rules
@@ -206,6 +207,33 @@ ab_status ab_online_update(const ab_model_desc *desc, ab_params *params,
                            const float *x_raw, const float *target, int64_t B,
                            float lr, float beta1, float beta2, float eps,
                            float *loss_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Transfer-learning form of the online step (Section 3.2 "Offline training online adapting": the offline
+ * trained model is updated by transfer learning): scorer layers below first_trainable are frozen: they are
+ * only run forward, their parameters, master copies and moments are not touched (and need not be given,
+ * beyond W[k] and b[k]); back-propagation stops at layer first_trainable.  0 <= first_trainable <= n_hidden;
+ * 0 is ab_online_update, n_hidden trains the output layer alone.  Everything else as ab_online_update
+ * (same workspace size).
+ */
+ab_status ab_online_update_tail(const ab_model_desc *desc, ab_params *params,
+                                const float *x_raw, const float *target, int64_t B, int32_t first_trainable,
+                                float lr, float beta1, float beta2, float eps,
+                                float *loss_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Minibatch assembly for online adaptation (Section 3.2: the newly observed samples also extend the
+ * dataset the model was trained on, so a step mixes both): output row i is row pick[i] of the new pool
+ * if pick[i] >= 0, else row -pick[i] - 1 of the old pool; the targets follow.  Which rows to mix is the
+ * caller's draw.  An index outside its pool yields a NaN row and a NaN target (no memory is read).
+ *   x_new [n_new, F], target_new [n_new], x_old [n_old, F], target_old [n_old]   DEVICE fp32 raw rows
+ *   pick [B] DEVICE int32;  x_out [B, F], target_out [B] DEVICE fp32 (must not overlap the pools)
+ * A pool of size 0 may be NULL.
+ */
+ab_status ab_replay_mix(const float *x_new, const float *target_new, int64_t n_new,
+                        const float *x_old, const float *target_old, int64_t n_old,
+                        const int32_t *pick, int64_t B, int32_t F,
+                        float *x_out, float *target_out, void *stream);
 
 const char *ab_status_string(ab_status status);
 

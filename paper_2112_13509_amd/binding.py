@@ -88,6 +88,13 @@ def load():
         lib.ab_online_update.argtypes = [C.POINTER(ab_model_desc), C.POINTER(ab_params), _vp, _vp,
                                          C.c_int64, C.c_float, C.c_float, C.c_float, C.c_float,
                                          _vp, _vp, C.c_size_t, _vp]
+        lib.ab_online_update_tail.restype = C.c_int32
+        lib.ab_online_update_tail.argtypes = [C.POINTER(ab_model_desc), C.POINTER(ab_params), _vp, _vp,
+                                              C.c_int64, C.c_int32, C.c_float, C.c_float, C.c_float, C.c_float,
+                                              _vp, _vp, C.c_size_t, _vp]
+        lib.ab_replay_mix.restype = C.c_int32
+        lib.ab_replay_mix.argtypes = [_vp, _vp, C.c_int64, _vp, _vp, C.c_int64, _vp, C.c_int64, C.c_int32,
+                                      _vp, _vp, _vp]
         _lib = lib
     return _lib
 
@@ -352,4 +359,48 @@ def ab_online_update(desc: ab_model_desc, params: Params, x_raw: torch.Tensor, t
                               0 if workspace is None else workspace.numel(), _stream_handle(stream))
     if check and rc != 0:
         raise AutoByteError(rc, "ab_online_update")
+    return rc
+
+
+def ab_online_update_tail(desc: ab_model_desc, params: Params, x_raw: torch.Tensor, target: torch.Tensor,
+                          first_trainable: int, lr: float = 1e-3, beta1: float = 0.9, beta2: float = 0.999,
+                          eps: float = 1e-8, loss_out: Optional[torch.Tensor] = None,
+                          workspace: Optional[torch.Tensor] = None, stream=None, check: bool = True) -> int:
+    """The online step with scorer layers below ``first_trainable`` frozen."""
+    lib = load()
+    B = int(x_raw.shape[0])
+    F = desc.n_layers * desc.n_stats + desc.n_scalars + 2
+    if x_raw.numel() != B * F or target.numel() != B:
+        raise ValueError("x_raw must be [B, %d] and target [B]" % F)
+    if params.step is None:
+        raise ValueError("params were not created with trainable=True")
+    rc = lib.ab_online_update_tail(C.byref(desc), C.byref(params.c), _ptr(x_raw, torch.float32, "x_raw"),
+                                   _ptr(target, torch.float32, "target"), B, int(first_trainable),
+                                   lr, beta1, beta2, eps, _ptr(loss_out, torch.float32, "loss_out"),
+                                   _ptr(workspace, torch.uint8, "workspace"),
+                                   0 if workspace is None else workspace.numel(), _stream_handle(stream))
+    if check and rc != 0:
+        raise AutoByteError(rc, "ab_online_update_tail")
+    return rc
+
+
+def ab_replay_mix(x_new: Optional[torch.Tensor], target_new: Optional[torch.Tensor], x_old: Optional[torch.Tensor],
+                  target_old: Optional[torch.Tensor], pick: torch.Tensor, x_out: torch.Tensor,
+                  target_out: torch.Tensor, stream=None, check: bool = True) -> int:
+    """Gather a minibatch from a pool of new rows (pick >= 0) and a pool of old rows (pick < 0: row -pick-1)."""
+    lib = load()
+    B, F = int(x_out.shape[0]), int(x_out.shape[1])
+    n_new = 0 if x_new is None else int(x_new.shape[0])
+    n_old = 0 if x_old is None else int(x_old.shape[0])
+    for t_ in (x_new, x_old):
+        if t_ is not None and int(t_.shape[1]) != F:
+            raise ValueError("pools and output must have the same row width")
+    if pick.numel() != B or target_out.numel() != B:
+        raise ValueError("pick and target_out must have one entry per output row")
+    rc = lib.ab_replay_mix(_ptr(x_new, torch.float32, "x_new"), _ptr(target_new, torch.float32, "target_new"), n_new,
+                           _ptr(x_old, torch.float32, "x_old"), _ptr(target_old, torch.float32, "target_old"), n_old,
+                           _ptr(pick, torch.int32, "pick"), B, F, _ptr(x_out, torch.float32, "x_out"),
+                           _ptr(target_out, torch.float32, "target_out"), _stream_handle(stream))
+    if check and rc != 0:
+        raise AutoByteError(rc, "ab_replay_mix")
     return rc

@@ -114,9 +114,12 @@ static inline bool misaligned(const void *p, size_t a) { return ((uintptr_t)p % 
 
 // defined in update.hip
 size_t update_workspace_bytes(const ab_model_desc *d, int64_t B);
+hipError_t launch_replay_mix(const float *x_new, const float *t_new, int64_t n_new, const float *x_old,
+                             const float *t_old, int64_t n_old, const int32_t *pick, int64_t B, int32_t F,
+                             float *x_out, float *t_out, hipStream_t st);
 ab_status online_update(const ab_model_desc *d, ab_params *params, const float *x_raw, const float *target,
                         int64_t B, float lr, float beta1, float beta2, float eps, float *loss_out,
-                        void *workspace, size_t ws_bytes, hipStream_t st);
+                        void *workspace, size_t ws_bytes, int first_trainable, hipStream_t st);
 
 }  // namespace ab
 
@@ -337,7 +340,39 @@ ab_status ab_online_update(const ab_model_desc *desc, ab_params *params,
     if (!params || !x_raw || !target) return AB_ERR_NULL;
     if (B <= 0) return AB_ERR_SHAPE;
     return online_update(desc, params, x_raw, target, B, lr, beta1, beta2, eps, loss_out,
-                         workspace, workspace_bytes, (hipStream_t)stream);
+                         workspace, workspace_bytes, 0, (hipStream_t)stream);
+}
+
+ab_status ab_online_update_tail(const ab_model_desc *desc, ab_params *params,
+                                const float *x_raw, const float *target, int64_t B, int32_t first_trainable,
+                                float lr, float beta1, float beta2, float eps,
+                                float *loss_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    ab_status rc = check_desc(desc);
+    if (rc != AB_OK) return rc;
+    if (desc->tensor_encoder) return AB_ERR_UNSUPPORTED;
+    if (!params || !x_raw || !target) return AB_ERR_NULL;
+    if (B <= 0 || first_trainable < 0 || first_trainable > desc->n_hidden) return AB_ERR_SHAPE;
+    return online_update(desc, params, x_raw, target, B, lr, beta1, beta2, eps, loss_out,
+                         workspace, workspace_bytes, first_trainable, (hipStream_t)stream);
+}
+
+ab_status ab_replay_mix(const float *x_new, const float *target_new, int64_t n_new,
+                        const float *x_old, const float *target_old, int64_t n_old,
+                        const int32_t *pick, int64_t B, int32_t F,
+                        float *x_out, float *target_out, void *stream)
+{
+    if (n_new < 0 || n_old < 0 || B < 0 || F <= 0) return AB_ERR_SHAPE;
+    if (B == 0) return AB_OK;
+    if (!pick || !x_out || !target_out) return AB_ERR_NULL;
+    if ((n_new > 0 && (!x_new || !target_new)) || (n_old > 0 && (!x_old || !target_old))) return AB_ERR_NULL;
+    if (n_new > 0x7fffffffLL || n_old > 0x7fffffffLL || (B + 3) / 4 > 0x7fffffffLL) return AB_ERR_UNSUPPORTED;
+    if (misaligned(x_new, 4) || misaligned(x_old, 4) || misaligned(x_out, 4) || misaligned(pick, 4) ||
+        misaligned(target_new, 4) || misaligned(target_old, 4) || misaligned(target_out, 4)) return AB_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    TraceScope ts("replay_mix", (double)B * (F + 1) * 8.0 + (double)B * 4.0, 1, st);
+    AB_HIP(launch_replay_mix(x_new, target_new, n_new, x_old, target_old, n_old, pick, B, F, x_out, target_out, st));
+    return AB_OK;
 }
 
 }  // extern "C"

@@ -275,8 +275,9 @@ __global__ __launch_bounds__(256) void adam_kernel(const AdamArgs a)
 template <typename T>
 static ab_status run_update(const ab_model_desc *d, ab_params *prm, const UpdatePlan &p, const float *x_raw,
                             const float *target, float lr, float beta1, float beta2, float eps,
-                            float *loss_out, unsigned char *ws, hipStream_t st)
+                            float *loss_out, unsigned char *ws, int k0, hipStream_t st)
 {
+    // k0 = first trainable scorer layer (0: all; D: the output layer alone): layers below it are only run forward
     const int dt = p.dtype, D = p.D;
     const int64_t B = p.B, Bp = p.Bp;
     float *scal = (float *)(ws + p.off_scal);
@@ -305,7 +306,7 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
             j.kind = kind; j.start = start; start += n;
         };
         add(JOB_PAD_COPY, prm->W[0], ws + p.off_wt[0], p.H[0], p.F, p.F, p.Kp, (int64_t)p.H[0] * p.Kp);
-        for (int k = 1; k < D; ++k)
+        for (int k = (k0 > 0 ? k0 + 1 : 1); k < D; ++k)      // W_k^T is the operand of the delta of layer k - 1
             add(JOB_TRANSPOSE, prm->W[k], ws + p.off_wt[k], p.H[k], p.H[k - 1], p.H[k - 1], p.H[k],
                 (int64_t)p.H[k] * p.H[k - 1]);
         if (Bp > B) {
@@ -349,7 +350,7 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
         AB_HIP(hipGetLastError());
     }
     // backward
-    for (int k = D - 1; k >= 0; --k) {
+    for (int k = D - 1; k >= k0; --k) {
         {   // dW_k = d_k^T h_{k-1}, split over the batch
             GemmArgs g;
             memset(&g, 0, sizeof(g));
@@ -361,7 +362,7 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
             TraceScope ts("upd_gemm_dw", 2.0 * Bp * p.H[k] * p.in_w[k], 0, st);
             AB_HIP(launch_gemm(dt, TILE_SMALL, AMODE_LOAD, EPI_SPLITK, g, st));
         }
-        if (k > 0) {   // d_{k-1} = (d_k W_k) * [h_{k-1} > 0]
+        if (k > k0) {   // d_{k-1} = (d_k W_k) * [h_{k-1} > 0]
             GemmArgs g;
             memset(&g, 0, sizeof(g));
             g.A = ws + p.off_d[k]; g.lda = p.H[k];
@@ -374,14 +375,14 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
             AB_HIP(launch_gemm(dt, update_tile(B, p.H[k - 1]), AMODE_LOAD, EPI_DRELU, g, st));
         }
     }
-    {
+    if (k0 < D) {
         BiasGradArgs a;
         memset(&a, 0, sizeof(a));
-        a.n = D; a.B = B; a.Bp = Bp;
+        a.n = D - k0; a.B = B; a.Bp = Bp;
         int start = 0;
-        for (int k = 0; k < D; ++k) {
-            a.l[k].dt = ws + p.off_dt[k]; a.l[k].gb = (float *)(ws + p.off_gb[k]); a.l[k].H = p.H[k];
-            a.l[k].start = start; start += p.H[k];
+        for (int k = k0; k < D; ++k) {
+            a.l[k - k0].dt = ws + p.off_dt[k]; a.l[k - k0].gb = (float *)(ws + p.off_gb[k]); a.l[k - k0].H = p.H[k];
+            a.l[k - k0].start = start; start += p.H[k];
         }
         TraceScope ts("upd_bias_grad", (double)start * Bp * esz, 1, st);
         bias_grad_kernel<T><<<(unsigned)start, 256, 0, st>>>(a);
@@ -397,7 +398,7 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
             t.w = w; t.m = m; t.v = v; t.w_compute = wc; t.g = g; t.rows = rows; t.cols = cols; t.ldg = ldg;
             t.splits = splits; t.split_stride = stride; t.start = start; start += (int64_t)rows * cols;
         };
-        for (int k = 0; k < D; ++k) {
+        for (int k = k0; k < D; ++k) {
             const int cols = (k == 0) ? p.F : p.H[k - 1];
             add(prm->W_master[k], prm->adam_mW[k], prm->adam_vW[k], (void *)prm->W[k], (float *)(ws + p.off_gw[k]),
                 p.H[k], cols, p.in_w[k], p.splits[k], (int64_t)p.H[k] * p.in_w[k]);
@@ -413,18 +414,57 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
     return AB_OK;
 }
 
+// Minibatch assembled from two pools of raw rows (fresh observations and the offline set): one wavefront per
+// output row, 16-byte pieces where the row width allows.  An index outside its pool gives a NaN row.
+struct ReplayMixArgs {
+    const float *x_new, *t_new, *x_old, *t_old; const int32_t *pick;
+    float *x_out, *t_out; int64_t n_new, n_old, B; int32_t F;
+};
+__global__ __launch_bounds__(256) void replay_mix_kernel(const ReplayMixArgs a)
+{
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= a.B) return;
+    const int lane = threadIdx.x & 63;
+    const int64_t pk = a.pick[row];
+    const float *src = nullptr, *ts = nullptr;
+    if (pk >= 0) { if (pk < a.n_new) { src = a.x_new + pk * a.F; ts = a.t_new + pk; } }
+    else { const int64_t o = -pk - 1; if (o < a.n_old) { src = a.x_old + o * a.F; ts = a.t_old + o; } }
+    float *dst = a.x_out + row * a.F;
+    const float nanv = __uint_as_float(0x7fc00000u);
+    if ((a.F & 3) == 0 && src && (((uintptr_t)src | (uintptr_t)dst) & 15) == 0) {
+        for (int j = lane; j < a.F / 4; j += 64) ((f32x4 *)dst)[j] = ((const f32x4 *)src)[j];
+    } else {
+        for (int j = lane; j < a.F; j += 64) dst[j] = src ? src[j] : nanv;
+    }
+    if (lane == 0) a.t_out[row] = ts ? *ts : nanv;
+}
+
+hipError_t launch_replay_mix(const float *x_new, const float *t_new, int64_t n_new, const float *x_old,
+                             const float *t_old, int64_t n_old, const int32_t *pick, int64_t B, int32_t F,
+                             float *x_out, float *t_out, hipStream_t st)
+{
+    if (B == 0) return hipSuccess;
+    ReplayMixArgs a{x_new, t_new, x_old, t_old, pick, x_out, t_out, n_new, n_old, B, F};
+    replay_mix_kernel<<<(unsigned)((B + 3) / 4), 256, 0, st>>>(a);
+    return hipGetLastError();
+}
+
 ab_status online_update(const ab_model_desc *d, ab_params *prm, const float *x_raw, const float *target,
                         int64_t B, float lr, float beta1, float beta2, float eps, float *loss_out,
-                        void *workspace, size_t ws_bytes, hipStream_t st)
+                        void *workspace, size_t ws_bytes, int first_trainable, hipStream_t st)
 {
     if (B > (1 << 24)) return AB_ERR_UNSUPPORTED;
     UpdatePlan p;
     plan_update(d, B, &p);
+    if (first_trainable < 0 || first_trainable > p.D) return AB_ERR_SHAPE;
     if (!prm->step) return AB_ERR_NULL;
     for (int k = 0; k <= p.D; ++k) {
-        if (!prm->W[k] || !prm->b[k] || !prm->W_master[k] || !prm->adam_mW[k] || !prm->adam_vW[k] ||
-            !prm->adam_mb[k] || !prm->adam_vb[k]) return AB_ERR_NULL;
-        if (((uintptr_t)prm->W[k] % 16) || ((uintptr_t)prm->W_master[k] % 4)) return AB_ERR_ALIGN;
+        if (!prm->W[k] || !prm->b[k]) return AB_ERR_NULL;
+        if ((uintptr_t)prm->W[k] % 16) return AB_ERR_ALIGN;
+        if (k < first_trainable) continue;                 // frozen layers need no master copy and no moments
+        if (!prm->W_master[k] || !prm->adam_mW[k] || !prm->adam_vW[k] || !prm->adam_mb[k] || !prm->adam_vb[k])
+            return AB_ERR_NULL;
+        if ((uintptr_t)prm->W_master[k] % 4) return AB_ERR_ALIGN;
     }
     if (((uintptr_t)prm->step % 8) || ((uintptr_t)x_raw % 4) || ((uintptr_t)target % 4) ||
         ((uintptr_t)loss_out % 4)) return AB_ERR_ALIGN;
@@ -433,8 +473,8 @@ ab_status online_update(const ab_model_desc *d, ab_params *prm, const float *x_r
     if (!(beta1 >= 0.f && beta1 < 1.f && beta2 >= 0.f && beta2 < 1.f)) return AB_ERR_SHAPE;
     unsigned char *ws = (unsigned char *)workspace;
     if (p.dtype == AB_BF16)
-        return run_update<bf16_t>(d, prm, p, x_raw, target, lr, beta1, beta2, eps, loss_out, ws, st);
-    return run_update<float>(d, prm, p, x_raw, target, lr, beta1, beta2, eps, loss_out, ws, st);
+        return run_update<bf16_t>(d, prm, p, x_raw, target, lr, beta1, beta2, eps, loss_out, ws, first_trainable, st);
+    return run_update<float>(d, prm, p, x_raw, target, lr, beta1, beta2, eps, loss_out, ws, first_trainable, st);
 }
 
 }  // namespace ab

@@ -25,7 +25,8 @@ def test_exports_every_declared_symbol(lib):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(ab_[a-z_]+)\s*\(", header))
     assert {"ab_score_candidates", "ab_select_best", "ab_online_update", "ab_workspace_bytes",
-            "ab_status_string", "ab_version", "ab_trigger", "ab_set_trace"} <= names
+            "ab_status_string", "ab_version", "ab_trigger", "ab_set_trace", "ab_online_update_tail",
+            "ab_replay_mix"} <= names
     for n in names:
         assert hasattr(lib, n), n
     assert ab.ab_version() >= 100
@@ -157,6 +158,32 @@ def test_select_and_update_argument_errors(lib):
     dte = ab.desc_from_workload(wl.make_config(5, S=1))
     assert lib.ab_online_update(C.byref(dte), C.byref(full), 0x1000, 0x2000, 64, f(1e-3), f(0.9), f(0.999),
                                 f(1e-8), None, 0x100000, 1 << 40, None) == -6
+
+
+def test_transfer_learning_argument_errors(lib):
+    f = C.c_float
+    u = wl.make_update(N=64, batch=64, L=2, hidden=(64, 64))
+    d = ab.desc_from_workload(u)
+    p = ab.ab_params()
+    tail = lambda k0, B=64, prm=p: lib.ab_online_update_tail(C.byref(d), C.byref(prm), 0x1000, 0x2000, B, k0, f(1e-3), f(0.9),
+                                                             f(0.999), f(1e-8), None, 0x100000, 1 << 40, None)
+    assert tail(-1) == -2 and tail(3) == -2 and tail(0, B=0) == -2
+    assert tail(2) == -1                                       # parameter pointers missing
+    # frozen layers need W and b only
+    q = ab.ab_params()
+    for k in range(3):
+        q.W[k], q.b[k] = 0x10000 * (k + 1), 0x10000 * (k + 1) + 0x8000
+    q.step = 0x90000
+    assert tail(2, prm=q) == -1                                # the output layer's master copy and moments are missing
+    q.W_master[2] = q.adam_mW[2] = q.adam_vW[2] = q.adam_mb[2] = q.adam_vb[2] = 0xa0000
+    assert lib.ab_online_update_tail(C.byref(d), C.byref(q), 0x1000, 0x2000, 64, 2, f(1e-3), f(0.9), f(0.999), f(1e-8),
+                                     None, 0x100000, 16, None) == -5     # everything present: the workspace is too small
+    mix = lambda xn=0x1000, tn=0x2000, nn=4, xo=0x3000, to=0x4000, no=4, pick=0x5000, B=8, F=6, xout=0x6000, tout=0x7000: \
+        lib.ab_replay_mix(xn, tn, nn, xo, to, no, pick, B, F, xout, tout, None)
+    assert mix(F=0) == -2 and mix(nn=-1) == -2 and mix(B=-1) == -2
+    assert mix(pick=None) == -1 and mix(xout=None) == -1 and mix(xn=None) == -1 and mix(to=None) == -1
+    assert mix(xout=0x6001) == -4
+    assert mix(B=0) == 0
 
 
 def test_binding_refuses_cpu_tensors(lib):

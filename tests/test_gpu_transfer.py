@@ -1,0 +1,117 @@
+"""GPU parity of the transfer-learning form of the online step (ab_online_update_tail: frozen lower layers) and of
+the minibatch assembly from two pools (ab_replay_mix) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2112_13509_amd import binding as ab
+from paper_2112_13509_amd import workloads as wl
+from helpers import oracle_model, tensor_error
+from test_gpu_update import GpuTrainer, TOL
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    ab.load()
+
+
+def snapshot(p):
+    return [[t.clone() for t in lst] for lst in (p.W, p.W_master, p.b, p.mW, p.vW, p.mb, p.vb)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_tail_step_freezes_below_and_matches_the_oracle_above(dtype):
+    B = 256
+    u = wl.make_update("upd-tail", N=B, batch=B, L=6, hidden=(128, 64, 64), dtype=dtype, seed=21, P=8, Q=8)
+    rows = np.arange(B)
+    fw = [wl.bf16_round(w.astype(np.float32)).astype(np.float64) for w in u.W] if dtype == "bf16" else None
+    tol_g = TOL[dtype] if dtype == "f32" else 0.15          # (small bf16 problems: ReLU mask flips, as in the full step)
+    for k0 in (0, 1, 2, 3):
+        tr = GpuTrainer(u, B)
+        st = orc.TrainState.fresh(u.W, u.b)
+        tr.load_state(st)
+        before = snapshot(tr.params)
+        ab.ab_online_update_tail(tr.desc, tr.params, tr.x[:B].contiguous(), tr.y[:B].contiguous(), k0,
+                                 loss_out=tr.loss, workspace=tr.ws)
+        gl = tr.loss_value()
+        ref = orc.update(oracle_model(u), st, u.x_raw[rows], u.target[rows], forward_weights=fw, first_trainable=k0)
+        assert abs(gl - ref["loss"]) <= TOL[dtype] * abs(ref["loss"])
+        after = snapshot(tr.params)
+        for k in range(4):
+            if k < k0:
+                for a, b in zip(before, after):
+                    assert torch.equal(a[k], b[k]), ("frozen layer changed", k0, k)
+            else:
+                gW = after[3][k].cpu().numpy().astype(np.float64) / 0.1        # first moment from zero: m = 0.1 g
+                gb = after[5][k].cpu().numpy().astype(np.float64) / 0.1
+                assert tensor_error(gW, ref["gW"][k]) <= tol_g and tensor_error(gb, ref["gb"][k]) <= tol_g, (k0, k)
+                assert np.abs(after[1][k].cpu().numpy() - st.W[k]).max() <= 2e-3 + 1e-6
+                cdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+                assert torch.equal(after[0][k], after[1][k].to(cdt))
+        assert int(tr.params.step.item()) == 1
+
+
+def test_tail_equals_full_step_bit_for_bit_when_nothing_is_frozen():
+    B = 128
+    u = wl.make_update("upd-tail0", N=B, batch=B, L=4, hidden=(64, 64), dtype="bf16", seed=22, P=4, Q=4)
+    a, b = GpuTrainer(u, B), GpuTrainer(u, B)
+    st = orc.TrainState.fresh(u.W, u.b)
+    a.load_state(st)
+    b.load_state(st)
+    for _ in range(3):
+        a.step(np.arange(B))
+        ab.ab_online_update_tail(b.desc, b.params, b.x[:B].contiguous(), b.y[:B].contiguous(), 0,
+                                 loss_out=b.loss, workspace=b.ws)
+    torch.cuda.synchronize()
+    for la, lb in zip(snapshot(a.params), snapshot(b.params)):
+        for ta, tb in zip(la, lb):
+            assert torch.equal(ta, tb)
+    assert a.loss_value() == b.loss_value()
+
+
+def test_output_layer_only_training_at_configuration_4_shape_lowers_the_loss():
+    u = wl.make_update("cfg4-tail", dtype="bf16")            # B = 4096, 390 -> 512^3 -> 1
+    B = u.batch
+    tr = GpuTrainer(u, B)
+    st = orc.TrainState.fresh(u.W, u.b)
+    tr.load_state(st)
+    rows = u.batch_indices(0)
+    idx = torch.from_numpy(rows).to(DEV)
+    x, y = tr.x[idx].contiguous(), (tr.y[idx] * 1.2 + 0.1).contiguous()      # the speeds drifted
+    k0 = len(u.hidden)
+    ab.ab_online_update_tail(tr.desc, tr.params, x, y, k0, lr=0.0, loss_out=tr.loss, workspace=tr.ws)
+    first = tr.loss_value()
+    fw = [wl.bf16_round(w.astype(np.float32)).astype(np.float64) for w in u.W]
+    ref = orc.update(oracle_model(u), st, u.x_raw[rows], u.target[rows].astype(np.float64) * 1.2 + 0.1, lr=0.0,
+                     forward_weights=fw, first_trainable=k0)
+    assert abs(first - ref["loss"]) <= 2e-2 * ref["loss"]
+    for _ in range(200):
+        ab.ab_online_update_tail(tr.desc, tr.params, x, y, k0, lr=3e-3, loss_out=tr.loss, workspace=tr.ws)
+    assert tr.loss_value() < 0.7 * first
+    for k in range(k0):
+        assert torch.equal(tr.params.W_master[k].cpu(), torch.from_numpy(u.W[k]))
+
+
+def test_replay_mix_matches_the_oracle_bit_for_bit():
+    rng = np.random.default_rng(3)
+    for F, n_new, n_old, B in ((392, 300, 5000, 4096), (7, 5, 3, 40), (64, 0, 10, 33), (12, 9, 0, 17)):
+        xn, tn = rng.standard_normal((n_new, F)).astype(np.float32), rng.standard_normal(n_new).astype(np.float32)
+        xo, to = rng.standard_normal((n_old, F)).astype(np.float32), rng.standard_normal(n_old).astype(np.float32)
+        pick = rng.integers(-n_old - 1, n_new + 1, B).astype(np.int32)        # a few entries outside both pools
+        t = lambda a: torch.from_numpy(a).to(DEV) if a.shape[0] else None
+        x_out = torch.full((B, F), 7.0, dtype=torch.float32, device=DEV)
+        t_out = torch.full((B,), 7.0, dtype=torch.float32, device=DEV)
+        ab.ab_replay_mix(t(xn), t(tn), t(xo), t(to), torch.from_numpy(pick).to(DEV), x_out, t_out)
+        torch.cuda.synchronize()
+        rx, rt = orc.replay_mix(xn, tn, xo, to, pick)
+        gx, gt = x_out.cpu().numpy(), t_out.cpu().numpy()
+        assert np.array_equal(np.isnan(gx), np.isnan(rx)) and np.array_equal(np.isnan(gt), np.isnan(rt))
+        ok = ~np.isnan(rt)
+        assert np.array_equal(gx[ok], rx[ok].astype(np.float32)) and np.array_equal(gt[ok], rt[ok].astype(np.float32))
+        assert (~ok).sum() > 0 or B == 0
