@@ -162,13 +162,13 @@ static void orc_lstm_step(const double *W, const double *b, int nx, int H, const
  * layers over the L layers (zero initial state), last hidden state of the second layer -> out[te_h1].
  * tmp holds K + te_h0 + 11*te_h1 doubles.
  */
-static void orc_lstm_encode_one(const orc_model *m, const double *dyn_s, double *out, double *tmp)
+static void orc_lstm_encode_one(const orc_model *m, const double *dyn_s, int Ls, double *out, double *tmp)
 {
     const int E = m->te_h0, H = m->te_h1;
     double *in = tmp, *xh1 = in + m->K, *xh2 = xh1 + E + H, *c1 = xh2 + 2 * H, *c2 = c1 + H, *z = c2 + H;
     double *h1 = xh1 + E, *h2 = xh2 + H;                 /* the recurrent halves of the two inputs */
     for (int u = 0; u < H; ++u) h1[u] = h2[u] = c1[u] = c2[u] = 0.0;
-    for (int l = 0; l < m->L; ++l) {
+    for (int l = 0; l < Ls; ++l) {
         for (int k = 0; k < m->K; ++k)
             in[k] = orc_phi(dyn_s[l * m->K + k], m->stat_kind[k], m->stat_shift[k], m->stat_scale[k]);
         orc_dense(m->te_W[0], m->te_b[0], E, m->K, in, xh1, 0);
@@ -185,22 +185,35 @@ static void orc_lstm_encode_one(const orc_model *m, const double *dyn_s, double 
 /* Scratch doubles orc_scenario_features needs behind xs. */
 static int orc_feature_scratch(const orc_model *m) { return m->K + m->te_h0 + 11 * m->te_h1 + 8; }
 
+/*
+ * Layers a scenario really has: jobs differ in their number of layers (Section 3.1 "Meta network
+ * architecture": "different training tasks usually result in different number of layers"), the statistics
+ * tensor is padded to L.  layers_of == NULL: all L; values are clamped to [1, L].
+ */
+static int orc_layers_of(const orc_model *m, const int32_t *layers_of, int64_t s)
+{
+    if (!layers_of) return m->L;
+    int n = layers_of[s];
+    return n < 1 ? 1 : (n > m->L ? m->L : n);
+}
+
 /* The LSTM encoder alone: out[S, te_h1] (lets tests hold it against a library LSTM). */
-int orc_lstm_encode(const orc_model *m, const double *dyn, int64_t S, double *out)
+int orc_lstm_encode(const orc_model *m, const double *dyn, int64_t S, const int32_t *layers_of, double *out)
 {
     if (!m || m->tensor_encoder != 2 || !out || S < 0) return ORC_ERR_ARG;
     double *tmp = (double *)malloc(sizeof(double) * (size_t)orc_feature_scratch(m));
     if (!tmp) return ORC_ERR_MEM;
     for (int64_t s = 0; s < S; ++s)
-        orc_lstm_encode_one(m, dyn + (size_t)s * m->L * m->K, out + (size_t)s * m->te_h1, tmp);
+        orc_lstm_encode_one(m, dyn + (size_t)s * m->L * m->K, orc_layers_of(m, layers_of, s),
+                            out + (size_t)s * m->te_h1, tmp);
     free(tmp);
     return ORC_OK;
 }
 
 /* Statistics block + scalars of one scenario -> xs[orc_stats_width]. tmp holds orc_feature_scratch doubles. */
-static void orc_scenario_features(const orc_model *m, const double *dyn_s, const double *scal_s,
+static void orc_scenario_features(const orc_model *m, const double *dyn_s, const double *scal_s, int Ls,
                                   double *xs, double *tmp)
-{
+{   /* Ls = layers of this scenario (<= L; only the encoders can take fewer than L) */
     int off;
     if (!m->tensor_encoder) {
         for (int l = 0; l < m->L; ++l)
@@ -209,12 +222,12 @@ static void orc_scenario_features(const orc_model *m, const double *dyn_s, const
                                            m->stat_shift[k], m->stat_scale[k]);
         off = m->L * m->K;
     } else if (m->tensor_encoder == 2) {
-        orc_lstm_encode_one(m, dyn_s, xs, tmp);
+        orc_lstm_encode_one(m, dyn_s, Ls, xs, tmp);
         off = m->te_h1;
     } else {
         double *in = tmp, *h0 = tmp + m->K, *h1 = h0 + m->te_h0;
         for (int j = 0; j < m->te_h1; ++j) xs[j] = 0.0;
-        for (int l = 0; l < m->L; ++l) {
+        for (int l = 0; l < Ls; ++l) {
             for (int k = 0; k < m->K; ++k)
                 in[k] = orc_phi(dyn_s[l * m->K + k], m->stat_kind[k],
                                 m->stat_shift[k], m->stat_scale[k]);
@@ -223,7 +236,7 @@ static void orc_scenario_features(const orc_model *m, const double *dyn_s, const
             orc_dense(m->te_W[1], m->te_b[1], m->te_h1, m->te_h0, h0, h1, 1);
             for (int j = 0; j < m->te_h1; ++j) xs[j] += h1[j];
         }
-        for (int j = 0; j < m->te_h1; ++j) xs[j] /= (double)m->L;
+        for (int j = 0; j < m->te_h1; ++j) xs[j] /= (double)Ls;
         off = m->te_h1;
     }
     for (int j = 0; j < m->Ns; ++j)
@@ -257,10 +270,11 @@ static double orc_mlp_forward(const orc_model *m, const double *x, int F, double
  *   part [P], cred [Q]   raw partition sizes and credit multiples; candidate c = p*Q + q
  *   scores [S, P*Q]  predicted V
  */
-int orc_score(const orc_model *m, const double *dyn, const double *scal, int64_t S,
-              const double *part, int P, const double *cred, int Q, double *scores)
+int orc_score_layers(const orc_model *m, const double *dyn, const double *scal, int64_t S,
+                     const int32_t *layers_of, const double *part, int P, const double *cred, int Q, double *scores)
 {
     if (!m || !scores || S < 0 || P <= 0 || Q <= 0) return ORC_ERR_ARG;
+    if (layers_of && !m->tensor_encoder) return ORC_ERR_ARG;      /* the flat layout has one width */
     const int Fs = orc_stats_width(m), F = Fs + 2;
     int maxw = 1;
     for (int k = 0; k < m->n_hidden; ++k) if (m->hidden[k] > maxw) maxw = m->hidden[k];
@@ -276,7 +290,8 @@ int orc_score(const orc_model *m, const double *dyn, const double *scal, int64_t
             double *buf = x + F, *tmp = buf + 2 * maxw;
 #pragma omp for schedule(dynamic, 1)
             for (int64_t s = 0; s < S; ++s) {
-                orc_scenario_features(m, dyn + (size_t)s * m->L * m->K, scal + (size_t)s * m->Ns, x, tmp);
+                orc_scenario_features(m, dyn + (size_t)s * m->L * m->K, scal + (size_t)s * m->Ns,
+                                      orc_layers_of(m, layers_of, s), x, tmp);
                 for (int p = 0; p < P; ++p)
                     for (int q = 0; q < Q; ++q) {
                         x[Fs]     = orc_phi(part[p], m->cfg_kind[0], m->cfg_shift[0], m->cfg_scale[0]);
@@ -290,6 +305,12 @@ int orc_score(const orc_model *m, const double *dyn, const double *scal, int64_t
     return err ? ORC_ERR_MEM : ORC_OK;
 }
 
+int orc_score(const orc_model *m, const double *dyn, const double *scal, int64_t S,
+              const double *part, int P, const double *cred, int Q, double *scores)
+{
+    return orc_score_layers(m, dyn, scal, S, NULL, part, P, cred, Q, scores);
+}
+
 /* The full input vectors themselves, [S, P*Q, F]: lets tests feed a library matmul chain. */
 int orc_materialise_inputs(const orc_model *m, const double *dyn, const double *scal, int64_t S,
                            const double *part, int P, const double *cred, int Q, double *X)
@@ -299,7 +320,7 @@ int orc_materialise_inputs(const orc_model *m, const double *dyn, const double *
     double *xs = (double *)malloc(sizeof(double) * (size_t)(Fs + orc_feature_scratch(m)));
     if (!xs) return ORC_ERR_MEM;
     for (int64_t s = 0; s < S; ++s) {
-        orc_scenario_features(m, dyn + (size_t)s * m->L * m->K, scal + (size_t)s * m->Ns, xs, xs + Fs);
+        orc_scenario_features(m, dyn + (size_t)s * m->L * m->K, scal + (size_t)s * m->Ns, m->L, xs, xs + Fs);
         for (int p = 0; p < P; ++p)
             for (int q = 0; q < Q; ++q) {
                 double *x = X + ((size_t)s * P * Q + (size_t)p * Q + q) * (size_t)F;

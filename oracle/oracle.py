@@ -170,8 +170,9 @@ def _check(rc: int, what: str):
         raise RuntimeError("oracle %s failed with code %d" % (what, rc))
 
 
-def score(model: Model, dyn, scal, part, cred) -> np.ndarray:
-    """Predicted V for every scenario and candidate: returns float64 [S, P*Q], c = p*Q + q."""
+def score(model: Model, dyn, scal, part, cred, layers_of=None) -> np.ndarray:
+    """Predicted V for every scenario and candidate: returns float64 [S, P*Q], c = p*Q + q.
+    ``layers_of`` [S] (encoder models only): how many of the L padded layers each scenario really has."""
     lib = _load()
     dyn, scal, part, cred = _f64(dyn), _f64(scal), _f64(part), _f64(cred)
     S = dyn.shape[0]
@@ -179,13 +180,16 @@ def score(model: Model, dyn, scal, part, cred) -> np.ndarray:
     P, Q = part.shape[0], cred.shape[0]
     out = np.empty((S, P * Q), dtype=np.float64)
     cm = model._c()
-    _check(lib.orc_score(C.byref(cm), dyn.ctypes.data_as(_dp), scal.ctypes.data_as(_dp),
-                         C.c_int64(S), part.ctypes.data_as(_dp), C.c_int(P),
-                         cred.ctypes.data_as(_dp), C.c_int(Q), out.ctypes.data_as(_dp)), "score")
+    lo = None if layers_of is None else np.ascontiguousarray(layers_of, dtype=np.int32)
+    assert lo is None or lo.shape == (S,)
+    _check(lib.orc_score_layers(C.byref(cm), dyn.ctypes.data_as(_dp), scal.ctypes.data_as(_dp),
+                                C.c_int64(S), None if lo is None else lo.ctypes.data_as(_ip),
+                                part.ctypes.data_as(_dp), C.c_int(P),
+                                cred.ctypes.data_as(_dp), C.c_int(Q), out.ctypes.data_as(_dp)), "score")
     return out
 
 
-def lstm_encode(model: Model, dyn) -> np.ndarray:
+def lstm_encode(model: Model, dyn, layers_of=None) -> np.ndarray:
     """The LSTM temporal encoder alone (Section 3.1): last hidden state of the second layer, float64 [S, H]."""
     lib = _load()
     dyn = _f64(dyn)
@@ -193,7 +197,9 @@ def lstm_encode(model: Model, dyn) -> np.ndarray:
     assert model.te_kind == "lstm" and dyn.shape == (S, model.L, model.K)
     out = np.empty((S, model.te_W[1].shape[0] // 4), dtype=np.float64)
     cm = model._c()
-    _check(lib.orc_lstm_encode(C.byref(cm), dyn.ctypes.data_as(_dp), C.c_int64(S), out.ctypes.data_as(_dp)),
+    lo = None if layers_of is None else np.ascontiguousarray(layers_of, dtype=np.int32)
+    _check(lib.orc_lstm_encode(C.byref(cm), dyn.ctypes.data_as(_dp), C.c_int64(S),
+                               None if lo is None else lo.ctypes.data_as(_ip), out.ctypes.data_as(_dp)),
            "lstm_encode")
     return out
 
