@@ -136,6 +136,11 @@ typedef struct {
     const float *dyn;       /* [S, L, K] raw per-layer statistics (computation times, tensor bytes ...) */
     const float *scalars;   /* [S, n_scalars] raw scalars                                                */
     int64_t      S;
+    const int32_t *layers_of; /* [S] or NULL: how many of the L layers scenario s really has (jobs differ in
+                                 their number of layers, Section 3.1 "Meta network architecture"); rows of dyn
+                                 past that count never influence a result; values are clamped to [1, L].  Needs an
+                                 encoder (tensor_encoder = 1: mean over the scenario's own layers; 2: the LSTM
+                                 stops after them); must be NULL for the flat layout                       */
 } ab_stats;
 
 /* Candidate grid shared by all scenarios (struct HOST, pointers DEVICE). Candidate c = p*Q + q. */

@@ -45,7 +45,7 @@ class ab_params(C.Structure):
 
 
 class ab_stats(C.Structure):
-    _fields_ = [("dyn", _vp), ("scalars", _vp), ("S", C.c_int64)]
+    _fields_ = [("dyn", _vp), ("scalars", _vp), ("S", C.c_int64), ("layers_of", _vp)]
 
 
 class ab_grid(C.Structure):
@@ -271,11 +271,15 @@ def ab_score_candidates(desc: ab_model_desc, params: Params, dyn: torch.Tensor, 
                         partition_bytes: torch.Tensor, credit_mult: torch.Tensor,
                         scores: Optional[torch.Tensor] = None, best_idx: Optional[torch.Tensor] = None,
                         best_score: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                        stream=None, check: bool = True) -> int:
-    """Enqueue scoring of every (scenario, candidate); outputs are written into the given tensors."""
+                        stream=None, check: bool = True, layers_of: Optional[torch.Tensor] = None) -> int:
+    """Enqueue scoring of every (scenario, candidate); outputs are written into the given tensors.
+    ``layers_of`` (int32 [S], encoder models only): how many of the L padded layers each scenario really has."""
     lib = load()
     S = int(dyn.shape[0])
-    st = ab_stats(_ptr(dyn, torch.float32, "dyn"), _ptr(scalars, torch.float32, "scalars"), S)
+    if layers_of is not None and layers_of.numel() != S:
+        raise ValueError("layers_of must have one entry per scenario")
+    st = ab_stats(_ptr(dyn, torch.float32, "dyn"), _ptr(scalars, torch.float32, "scalars"), S,
+                  _ptr(layers_of, torch.int32, "layers_of"))
     P, Q = int(partition_bytes.numel()), int(credit_mult.numel())
     gr = ab_grid(_ptr(partition_bytes, torch.float32, "partition_bytes"), P,
                  _ptr(credit_mult, torch.float32, "credit_mult"), Q)

@@ -180,6 +180,8 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
     const int64_t S = stats->S;
     const int32_t C = grid->P * grid->Q;
     if (S > 0 && (!stats->dyn || (desc->n_scalars > 0 && !stats->scalars))) return AB_ERR_NULL;
+    if (stats->layers_of && !desc->tensor_encoder) return AB_ERR_UNSUPPORTED;   // the flat layout has one width
+    if (misaligned(stats->layers_of, 4)) return AB_ERR_ALIGN;
     ScorePlan p;
     rc = plan_scoring(desc, S, C, &p);
     if (rc != AB_OK) return rc;
@@ -210,7 +212,7 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
             // per scenario and layer: two gate products (256 x 96 and 256 x 128) and the K -> 32 embedding
             TraceScope ts("lstm_encoder", (double)S * desc->n_layers * 2.0 * (256.0 * 224.0 + 32.0 * desc->n_stats), 0, st);
             AB_HIP(launch_lstm_encoder(desc, stats->dyn, params->W[0], params->b[0], params->W[1], params->b[1],
-                                       params->W[2], params->b[2], xs, p.Kp, S, st));
+                                       params->W[2], params->b[2], xs, p.Kp, S, stats->layers_of, st));
         }
         TraceScope ts("encode_stats", (double)S * (desc->n_scalars * 4.0 + (p.Kp - desc->enc_hidden[1]) * es), 1, st);
         AB_HIP(launch_encode_stats(dt, desc, stats->dyn, stats->scalars, xs, S, p.Kp,
@@ -220,7 +222,7 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
             TraceScope ts("tensor_encoder", (double)S * desc->n_layers * 2.0 * (desc->n_stats * 128.0 + 128.0 * 128.0),
                           0, st);
             AB_HIP(launch_tensor_encoder(dt, desc, stats->dyn, params->W[0], params->b[0], params->W[1],
-                                         params->b[1], xs, p.Kp, S, st));
+                                         params->b[1], xs, p.Kp, S, stats->layers_of, st));
         }
         TraceScope ts("encode_stats", (double)S * (desc->n_scalars * 4.0 + (p.Kp - desc->enc_hidden[1]) * es), 1, st);
         AB_HIP(launch_encode_stats(dt, desc, stats->dyn, stats->scalars, xs, S, p.Kp,

@@ -47,9 +47,9 @@ hipError_t launch_score_single_hidden(const float *a_term, const float *b_term, 
                                       float *partial, int64_t rows, int C, int H, hipStream_t st);
 hipError_t launch_lstm_encoder(const ab_model_desc *d, const float *dyn, const void *We, const float *be,
                                const void *W1, const float *b1, const void *W2, const float *b2, void *xs,
-                               int ld, int64_t S, hipStream_t st);
+                               int ld, int64_t S, const int32_t *layers_of, hipStream_t st);
 hipError_t launch_tensor_encoder(int dtype, const ab_model_desc *d, const float *dyn, const void *Wa,
                                  const float *ba, const void *Wb, const float *bb, void *xs, int ld,
-                                 int64_t S, hipStream_t st);
+                                 int64_t S, const int32_t *layers_of, hipStream_t st);
 
 }  // namespace ab

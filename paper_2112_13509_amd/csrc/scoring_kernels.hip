@@ -300,6 +300,7 @@ struct TensorEncArgs {
     const void *Wa; const float *ba;     // [128, K]
     const void *Wb; const float *bb;     // [128, 128]
     void *xs; int32_t ld;                // scenario rows; columns [0,128) written here
+    const int32_t *layers_of;            // [S] or NULL: layers the scenario really has (clamped to [1, L])
     ab_enc enc_stat[AB_MAX_STATS];
 };
 
@@ -316,6 +317,8 @@ __global__ __launch_bounds__(256) void tensor_encoder_kernel(const TensorEncArgs
     const int64_t s = blockIdx.x;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, half = lane >> 5, l31 = lane & 31;
     const float *dyn = a.dyn + s * (int64_t)a.L * a.K;
+    int Ls = a.L;                                           // this scenario's own layer count
+    if (a.layers_of) { Ls = a.layers_of[s]; Ls = Ls < 1 ? 1 : (Ls > a.L ? a.L : Ls); }
 
     for (int i = t; i < H * AB_MAX_STATS; i += 256) {
         const int o = i / AB_MAX_STATS, k = i % AB_MAX_STATS;
@@ -349,11 +352,11 @@ __global__ __launch_bounds__(256) void tensor_encoder_kernel(const TensorEncArgs
     }
     const float ba0 = ba_s[2 * lane], ba1 = ba_s[2 * lane + 1];
 
-    for (int l0 = wave * 32; l0 < a.L; l0 += 128) {
+    for (int l0 = wave * 32; l0 < Ls; l0 += 128) {
         // transformed statistics of the block's 32 tensors (zero rows past the end)
         for (int i = lane; i < 32 * AB_MAX_STATS; i += 64) {
             const int r = i / AB_MAX_STATS, k = i % AB_MAX_STATS, l = l0 + r;
-            xw[i] = (l < a.L && k < a.K) ? phi(dyn[(int64_t)l * a.K + k], a.enc_stat[k]) : 0.f;
+            xw[i] = (l < Ls && k < a.K) ? phi(dyn[(int64_t)l * a.K + k], a.enc_stat[k]) : 0.f;
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // same wavefront: LDS ops are in order
         // first layer: this lane owns units 2*lane and 2*lane+1 (weights in registers) for all 32 tensors;
@@ -393,7 +396,7 @@ __global__ __launch_bounds__(256) void tensor_encoder_kernel(const TensorEncArgs
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int l = l0 + (r >> 2) * 8 + half * 4 + (r & 3);
-            if (l < a.L) {
+            if (l < Ls) {
 #pragma unroll
                 for (int jn = 0; jn < 4; ++jn) colsum[jn] += relu_keep_nan(acc[jn][r] + bb[jn]);
             }
@@ -407,7 +410,7 @@ __global__ __launch_bounds__(256) void tensor_encoder_kernel(const TensorEncArgs
     }
     __syncthreads();
     if (t < H) {
-        const float pooled = ((red[0][t] + red[1][t]) + (red[2][t] + red[3][t])) / (float)a.L;
+        const float pooled = ((red[0][t] + red[1][t]) + (red[2][t] + red[3][t])) / (float)Ls;
         const int64_t o = s * a.ld + t;
         if constexpr (sizeof(T) == 2) ((uint16_t *)a.xs)[o] = (uint16_t)(pack_bf16x2(pooled, 0.f) & 0xffffu);
         else ((float *)a.xs)[o] = pooled;
@@ -523,6 +526,7 @@ struct LstmEncArgs {
     const void *W1; const float *b1;      // [256, 32 + 64]
     const void *W2; const float *b2;      // [256, 64 + 64]
     void *xs; int32_t ld;                 // scenario rows; columns [0, 64) written here
+    const int32_t *layers_of;             // [S] or NULL: layers the scenario really has (clamped to [1, L])
     ab_enc enc_stat[AB_MAX_STATS];
 };
 
@@ -632,11 +636,20 @@ __global__ __launch_bounds__(256) void lstm_encoder_kernel(const LstmEncArgs a)
     __syncthreads();
     embed_step(0, 0);
 
-    float c1[2][4], c2[2][4], h2v[2][4];
+    float c1[2][4], c2[2][4], h2v[2][4], hlast[2][4];
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) c1[b][j] = c2[b][j] = h2v[b][j] = 0.f;
+        for (int j = 0; j < 4; ++j) c1[b][j] = c2[b][j] = h2v[b][j] = hlast[b][j] = 0.f;
+    // this lane's scenario (row l31) may have fewer layers than the block runs for: its result is the second
+    // layer's hidden state after its own last layer; what the recurrence does to that row afterwards is unused
+    int my_len = L;
+    if (a.layers_of) {
+        int64_t sc = s0 + l31;
+        if (sc > a.S - 1) sc = a.S - 1;
+        my_len = a.layers_of[sc];
+        my_len = my_len < 1 ? 1 : (my_len > L ? L : my_len);
+    }
 
     const int frag_rd = l31 * STRIDE + 16 * hf;          // + column * 2
     const int h_wr = l31 * STRIDE + (16 * wave + 4 * hf) * 2;   // + (field column + 8 b) * 2
@@ -692,6 +705,10 @@ __global__ __launch_bounds__(256) void lstm_encoder_kernel(const LstmEncArgs a)
             cell(z[b], c2[b], h2v[b]);
             uint2 pk = {pack_bf16x2(h2v[b][0], h2v[b][1]), pack_bf16x2(h2v[b][2], h2v[b][3])};
             *(uint2 *)(&act[p ^ 1][h_wr + (COL_H2 + 8 * b) * 2]) = pk;
+            if (step + 1 == my_len) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) hlast[b][j] = h2v[b][j];
+            }
         }
     }
     // ---- last hidden state of the second layer -> columns 16 w + 8 b + 4 hf .. + 3 of the scenario row
@@ -699,7 +716,7 @@ __global__ __launch_bounds__(256) void lstm_encoder_kernel(const LstmEncArgs a)
         uint16_t *row = (uint16_t *)a.xs + (s0 + l31) * (int64_t)a.ld + 16 * wave + 4 * hf;
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
-            uint2 pk = {pack_bf16x2(h2v[b][0], h2v[b][1]), pack_bf16x2(h2v[b][2], h2v[b][3])};
+            uint2 pk = {pack_bf16x2(hlast[b][0], hlast[b][1]), pack_bf16x2(hlast[b][2], hlast[b][3])};
             *(uint2 *)(row + 8 * b) = pk;
         }
     }
@@ -707,10 +724,11 @@ __global__ __launch_bounds__(256) void lstm_encoder_kernel(const LstmEncArgs a)
 
 hipError_t launch_lstm_encoder(const ab_model_desc *d, const float *dyn, const void *We, const float *be,
                                const void *W1, const float *b1, const void *W2, const float *b2, void *xs,
-                               int ld, int64_t S, hipStream_t st)
+                               int ld, int64_t S, const int32_t *layers_of, hipStream_t st)
 {
     if (S == 0) return hipSuccess;
     LstmEncArgs a;
+    a.layers_of = layers_of;
     a.dyn = dyn; a.L = d->n_layers; a.K = d->n_stats; a.S = S;
     a.We = We; a.be = be; a.W1 = W1; a.b1 = b1; a.W2 = W2; a.b2 = b2; a.xs = xs; a.ld = ld;
     for (int i = 0; i < AB_MAX_STATS; ++i) a.enc_stat[i] = d->enc_stat[i];
@@ -722,10 +740,11 @@ hipError_t launch_lstm_encoder(const ab_model_desc *d, const float *dyn, const v
 
 hipError_t launch_tensor_encoder(int dtype, const ab_model_desc *d, const float *dyn, const void *Wa,
                                  const float *ba, const void *Wb, const float *bb, void *xs, int ld,
-                                 int64_t S, hipStream_t st)
+                                 int64_t S, const int32_t *layers_of, hipStream_t st)
 {
     if (S == 0) return hipSuccess;
     TensorEncArgs a;
+    a.layers_of = layers_of;
     a.dyn = dyn; a.L = d->n_layers; a.K = d->n_stats; a.Wa = Wa; a.ba = ba; a.Wb = Wb; a.bb = bb;
     a.xs = xs; a.ld = ld;
     for (int i = 0; i < AB_MAX_STATS; ++i) a.enc_stat[i] = d->enc_stat[i];

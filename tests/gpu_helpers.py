@@ -20,7 +20,7 @@ class Scorer:
         self.params = ab.Params.from_workload(w, DEV)
         self.part, self.cred = to_dev(w.part), to_dev(w.cred)
 
-    def run(self, dyn=None, scal=None, want_scores=True, want_best=True):
+    def run(self, dyn=None, scal=None, want_scores=True, want_best=True, layers_of=None):
         w = self.w
         dyn = w.dyn if dyn is None else dyn
         scal = w.scal if scal is None else scal
@@ -31,8 +31,9 @@ class Scorer:
         idx = torch.full((S,), -7, dtype=torch.int32, device=DEV) if want_best else None
         best = torch.full((S,), float("nan"), dtype=torch.float32, device=DEV) if want_best else None
         ws = ab.alloc_workspace(self.desc, S, Cn, device=DEV)
+        lo = None if layers_of is None else to_dev(np.asarray(layers_of, dtype=np.int32))
         ab.ab_score_candidates(self.desc, self.params, d_dyn, d_scal, self.part, self.cred,
-                               scores, idx, best, ws)
+                               scores, idx, best, ws, layers_of=lo)
         torch.cuda.synchronize()
         out = lambda t: None if t is None else t.cpu().numpy()
         return out(scores), out(idx), out(best)

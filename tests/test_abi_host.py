@@ -38,7 +38,7 @@ def test_struct_layout_matches_header_sizes():
     assert C.sizeof(ab.ab_enc) == 12
     assert C.sizeof(ab.ab_model_desc) == 4 * 3 + 12 * (8 + 16 + 2) + 4 + 4 * 8 + 4 + 8 + 4
     assert C.sizeof(ab.ab_params) == 8 * (12 * 7 + 1)
-    assert C.sizeof(ab.ab_stats) == 24 and C.sizeof(ab.ab_grid) == 32
+    assert C.sizeof(ab.ab_stats) == 32 and C.sizeof(ab.ab_grid) == 32
 
 
 def _desc(cfg=2):
@@ -66,6 +66,10 @@ def test_encoder_options_in_the_descriptor(lib):
     assert ab.ab_workspace_bytes(d, 16, 4) > 0
     p = _fake_params(3 + 2)                                   # the output layer's pointers are missing
     assert _call_score(lib, d, params=p) == -1
+    # per-scenario layer counts: encoders only, 4-byte aligned
+    assert _call_score(lib, d, params=_fake_params(6), stats=ab.ab_stats(0x3000, 0x4000, 4, 0x7002)) == -4
+    flat = _desc(1)
+    assert _call_score(lib, flat, params=_fake_params(3), stats=ab.ab_stats(0x3000, 0x4000, 4, 0x7000)) == -6
     d.enc_hidden[1] = 128
     assert ab.ab_workspace_bytes(d, 16, 4) == 0 and _call_score(lib, d, params=_fake_params(6)) == -6
     d.enc_hidden[1] = 64

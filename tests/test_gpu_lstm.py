@@ -77,3 +77,33 @@ def test_lstm_encoder_nan_statistic_poisons_only_its_scenario():
     ref = orc.score(oracle_model(w), w.dyn, w.scal, w.part, w.cred)
     assert np.isfinite(scores[ok]).all()
     assert tensor_scaled_error(scores[ok], ref[ok]) <= TOL
+
+
+@pytest.mark.parametrize("kind", ["mlp", "lstm"])
+def test_scenarios_with_fewer_layers_than_the_padded_tensor(kind):
+    """Per-scenario layer counts: mean over / recurrence through a scenario's own layers only; whatever sits in
+    the padding (NaN here) must not reach the result."""
+    from gpu_helpers import Scorer
+    S = 70
+    if kind == "mlp":
+        w = wl.make_tensor_encoder("te-len", S, [64, 64], [128, 128], 3, 3, "bf16", 41, n_blocks=3, per_block=16, extra=2)
+    else:
+        w = wl.make_lstm_encoder("lstm-len", S, [64, 64], 3, 3, "bf16", 41, n_blocks=3, per_block=16, extra=2)
+    rng = np.random.default_rng(8)
+    lens = rng.integers(1, w.L + 1, S).astype(np.int32)
+    lens[:4] = [1, w.L, 17, 33]
+    for s in range(S):
+        w.dyn[s, lens[s]:] = np.nan
+    scores, idx, best = Scorer(w).run(layers_of=lens)
+    ref = orc.score(oracle_model(w), w.dyn, w.scal, w.part, w.cred, layers_of=lens)
+    assert np.isfinite(scores).all() and np.isfinite(ref).all()
+    err, strict = tensor_scaled_error(scores, ref), scaled_error(scores, ref)
+    print("%s with own layer counts: rel err %.3g strict %.3g" % (kind, err, strict))
+    assert err <= TOL and strict <= 5e-2
+    check_selection(idx, ref, TOL, per_scenario=False)
+    # out-of-range counts are clamped to [1, L]
+    lens2 = lens.copy()
+    lens2[lens == w.L] = w.L + 50
+    lens2[lens == 1] = -3
+    s2, _, _ = Scorer(w).run(layers_of=lens2)
+    assert np.array_equal(s2, scores)
