@@ -507,14 +507,15 @@ hipError_t launch_score_single_hidden(const float *a_term, const float *b_term, 
 // (K -> 32), two stacked LSTM layers of 64 units over t = 0..L-1 with zero initial state, gate blocks in
 // the order input, forget, candidate, output; the second layer's last hidden state becomes the first 64
 // columns of the scenario row.
-// One work-group of four wavefronts per 32 scenarios, the whole sequence in one launch:
-//   - a wavefront owns 16 units of both layers and keeps their rows of [W_ih | W_hh] (bf16) in registers
+// One work-group of eight wavefronts per 32 scenarios, the whole sequence in one launch; four wavefronts run
+// the first layer, four the second one step behind (two wavefronts per SIMD hide each other's latencies):
+//   - a wavefront owns 16 units of its layer and keeps their rows of [W_ih | W_hh] (bf16) in registers
 //     as matrix-instruction operands, permuted so that the four gates of a unit land in one lane:
 //     column 8g + 4h + j of output block b is gate g of unit 16w + 8b + 4h + j;  the bias is the
 //     addend of the first matrix instruction;
-//   - the recurrent operands live in LDS as rows [e | h1 | h2] (bf16), double-buffered by step parity:
-//     layer 1 of step t reads (e_t, h1_{t-1}) from buffer t&1 and writes h1_t to the other buffer, layer 2
-//     reads h1_t there and h2_{t-1} here: two barriers per step;
+//   - the recurrent operands live in LDS as rows [e | h1 | h2] (bf16), double-buffered by iteration parity:
+//     in iteration t layer 1 makes h1_t from (e_t, h1_{t-1}) and layer 2 makes h2_{t-1} from (h1_{t-1},
+//     h2_{t-2}), all read from buffer t&1 and written to the other one: one barrier per iteration;
 //   - cell states stay in fp32 registers; sigmoid and tanh through exp2 and reciprocal;
 //   - the statistics come in chunks of 16 steps (transformed once, one chunk ahead in registers).
 // The step is bound by the transcendental rate of the vector ALUs (10 per unit and step), not by the
@@ -539,7 +540,7 @@ __device__ __forceinline__ float fast_tanh(float x)
     return 1.f - 2.f * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(2.88539008177793f * x));
 }
 
-__global__ __launch_bounds__(256) void lstm_encoder_kernel(const LstmEncArgs a)
+__global__ __launch_bounds__(512) void lstm_encoder_kernel(const LstmEncArgs a)
 {
     constexpr int E = 32, H = 64, R = 32, TC = 16;
     constexpr int STRIDE = 336;                    // bytes per row: (32 + 64 + 64) bf16 + 16 (bank spread)
@@ -549,50 +550,51 @@ __global__ __launch_bounds__(256) void lstm_encoder_kernel(const LstmEncArgs a)
 
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int role = wave >> 2, wu = wave & 3;     // role 0: first LSTM layer, 1: second; wu: which 16 units
     const int l31 = lane & 31, hf = lane >> 5;
     const int64_t s0 = (int64_t)blockIdx.x * R;
     const int L = a.L, K = a.K;
 
-    // ---- weights as first operands: lane -> row (l31 = output column) and 8 k values (hf)
-    i32x4 w1f[2][6], w2f[2][8];
-    f32x16 bias1[2], bias2[2];
+    // ---- this wavefront's weights as first operands: lane -> row (l31 = output column) and 8 k values (hf);
+    // layer 1 has 6 k steps (32 + 64 inputs), layer 2 has 8 (64 + 64)
+    i32x4 wf[2][8];
+    f32x16 bias[2];
     {
         const int g = l31 >> 3, hp = (l31 >> 2) & 1, j = l31 & 3;
+        const uint16_t *W = (const uint16_t *)(role ? a.W2 : a.W1);
+        const float *bsrc = role ? a.b2 : a.b1;
+        const int kin = role ? 2 * H : E + H;
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
-            const int wrow = g * H + 16 * wave + 8 * b + 4 * hp + j;
+            const int wrow = g * H + 16 * wu + 8 * b + 4 * hp + j;
 #pragma unroll
-            for (int ks = 0; ks < 6; ++ks)
-                w1f[b][ks] = *(const i32x4 *)((const uint16_t *)a.W1 + (size_t)wrow * (E + H) + ks * 16 + 8 * hf);
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
-                w2f[b][ks] = *(const i32x4 *)((const uint16_t *)a.W2 + (size_t)wrow * (2 * H) + ks * 16 + 8 * hf);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {          // register r of the result: gate r / 4, unit offset r & 3 (+ 4 hf)
-                const int col = (r >> 2) * H + 16 * wave + 8 * b + 4 * hf + (r & 3);
-                bias1[b][r] = a.b1[col];
-                bias2[b][r] = a.b2[col];
+            for (int ks = 0; ks < 8; ++ks) {
+                wf[b][ks] = i32x4{0, 0, 0, 0};
+                if (ks * 16 < kin) wf[b][ks] = *(const i32x4 *)(W + (size_t)wrow * kin + ks * 16 + 8 * hf);
             }
+#pragma unroll
+            for (int r = 0; r < 16; ++r)          // register r of the result: gate r / 4, unit offset r & 3 (+ 4 hf)
+                bias[b][r] = bsrc[(r >> 2) * H + 16 * wu + 8 * b + 4 * hf + (r & 3)];
         }
     }
-    // ---- embedding: thread -> row t >> 3, outputs 4 (t & 7) .. + 3
-    const int erow = t >> 3, ej = (t & 7) * 4;
-    float we[4][AB_MAX_STATS], be4[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        be4[i] = a.be[ej + i];
-#pragma unroll
-        for (int k = 0; k < AB_MAX_STATS; ++k)
-            we[i][k] = k < K ? bf16_bits_to_f32(((const uint16_t *)a.We)[(ej + i) * K + k]) : 0.f;
+    // ---- embedding (the second layer's wavefronts do it): thread -> row te >> 3, outputs 4 (te & 7) .. + 3
+    // (W_e and b_e sit in LDS: 33 values per output would crowd the registers that hold the gate weights)
+    __shared__ __attribute__((aligned(16))) float we_s[E][AB_MAX_STATS];
+    __shared__ float be_s[E];
+    const int te = t & 255, erow = te >> 3, ej = (te & 7) * 4;
+    if (t < E * AB_MAX_STATS) {
+        const int o = t / AB_MAX_STATS, k = t % AB_MAX_STATS;
+        we_s[o][k] = k < K ? bf16_bits_to_f32(((const uint16_t *)a.We)[o * K + k]) : 0.f;
     }
-    // ---- statistics chunks: 32 rows x TC steps x K values, element idx = t + 256 i
-    constexpr int PRE = R * TC * AB_MAX_STATS / 256;     // 16 registers at K = 8
+    if (t < E) be_s[t] = a.be[t];
+    // ---- statistics chunks: 32 rows x TC steps x K values, element idx = t + 512 i
+    constexpr int PRE = R * TC * AB_MAX_STATS / 512;     // 8 registers at K = 8
     float pre[PRE];
     const int per_row = TC * K;
     auto fetch_chunk = [&](int n) {
 #pragma unroll
         for (int i = 0; i < PRE; ++i) {
-            const int idx = t + 256 * i;
+            const int idx = t + 512 * i;
             pre[i] = 0.f;
             if (idx < R * per_row) {
                 const int row = idx / per_row, o = idx - row * per_row;
@@ -608,7 +610,7 @@ __global__ __launch_bounds__(256) void lstm_encoder_kernel(const LstmEncArgs a)
     auto put_chunk = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < PRE; ++i) {
-            const int idx = t + 256 * i;
+            const int idx = t + 512 * i;
             if (idx < R * per_row) {
                 const int row = idx / per_row, o = idx - row * per_row;
                 stat[buf][row][o / K][o % K] = pre[i];
@@ -617,30 +619,30 @@ __global__ __launch_bounds__(256) void lstm_encoder_kernel(const LstmEncArgs a)
     };
     auto embed_step = [&](int step, int buf) {           // e_step -> act[buf], columns [0, 32)
         const float *sp = &stat[(step / TC) & 1][erow][step % TC][0];
-        float e[4] = {be4[0], be4[1], be4[2], be4[3]};
+        float e[4] = {be_s[ej], be_s[ej + 1], be_s[ej + 2], be_s[ej + 3]};
 #pragma unroll
         for (int k = 0; k < AB_MAX_STATS; ++k)
             if (k < K) {
                 const float x = sp[k];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) e[i] = fmaf(we[i][k], x, e[i]);
+                for (int i = 0; i < 4; ++i) e[i] = fmaf(we_s[ej + i][k], x, e[i]);
             }
         uint2 pk = {pack_bf16x2(e[0], e[1]), pack_bf16x2(e[2], e[3])};
         *(uint2 *)(&act[buf][erow * STRIDE + ej * 2]) = pk;
     };
 
     // ---- start: zero state, first chunk, e_0
-    for (int i = t; i < 2 * R * STRIDE / 4; i += 256) ((uint32_t *)&act[0][0])[i] = 0u;
+    for (int i = t; i < 2 * R * STRIDE / 4; i += 512) ((uint32_t *)&act[0][0])[i] = 0u;
     fetch_chunk(0);
     put_chunk(0);
     __syncthreads();
-    embed_step(0, 0);
+    if (role == 1) embed_step(0, 0);
 
-    float c1[2][4], c2[2][4], h2v[2][4], hlast[2][4];
+    float c[2][4], hv[2][4], hlast[2][4];
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) c1[b][j] = c2[b][j] = h2v[b][j] = hlast[b][j] = 0.f;
+        for (int j = 0; j < 4; ++j) c[b][j] = hv[b][j] = hlast[b][j] = 0.f;
     // this lane's scenario (row l31) may have fewer layers than the block runs for: its result is the second
     // layer's hidden state after its own last layer; what the recurrence does to that row afterwards is unused
     int my_len = L;
@@ -652,68 +654,73 @@ __global__ __launch_bounds__(256) void lstm_encoder_kernel(const LstmEncArgs a)
     }
 
     const int frag_rd = l31 * STRIDE + 16 * hf;          // + column * 2
-    const int h_wr = l31 * STRIDE + (16 * wave + 4 * hf) * 2;   // + (field column + 8 b) * 2
-    auto cell = [&](const f32x16 &z, float (&c)[4], float (&h)[4]) {
+    const int h_wr = l31 * STRIDE + (16 * wu + 4 * hf) * 2;     // + (field column + 8 b) * 2
+    auto cell = [&](const f32x16 &z, float (&cs)[4], float (&h)[4]) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const float ig = fast_sigmoid(z[j]), fg = fast_sigmoid(z[4 + j]);
             const float gg = fast_tanh(z[8 + j]), og = fast_sigmoid(z[12 + j]);
-            c[j] = fmaf(fg, c[j], ig * gg);
-            h[j] = og * fast_tanh(c[j]);
+            cs[j] = fmaf(fg, cs[j], ig * gg);
+            h[j] = og * fast_tanh(cs[j]);
         }
     };
 
-    for (int step = 0; step < L; ++step) {
-        const int p = step & 1;
-        __syncthreads();                                   // act[p] holds e_step, h1_{step-1}, h2_{step-1}
-        const int tc = step % TC, n = step / TC;
+    // Iteration tau: the first layer makes h1_tau from (e_tau, h1_{tau-1}) while the second layer makes
+    // h2_{tau-1} from (h1_{tau-1}, h2_{tau-2}); all of these sit in buffer tau & 1 and every result (with
+    // e_{tau+1}) goes to the other buffer, so one barrier per iteration orders everything.
+    for (int tau = 0; tau <= L; ++tau) {
+        const int p = tau & 1;
+        __syncthreads();
+        const int tc = tau % TC, n = tau / TC;
         if (tc == 0 && (n + 1) * TC < L) fetch_chunk(n + 1);
         if (tc == TC - 2 && (n + 1) * TC < L) put_chunk((n + 1) & 1);
-        if (step + 1 < L) embed_step(step + 1, p ^ 1);
-        // layer 1
         f32x16 z[2];
+        if (role == 0) {
+            if (tau < L) {
 #pragma unroll
-        for (int ks = 0; ks < 6; ++ks) {
-            const i32x4 xf = *(const i32x4 *)(&act[p][frag_rd + ks * 32]);
+                for (int ks = 0; ks < 6; ++ks) {
+                    const i32x4 xf = *(const i32x4 *)(&act[p][frag_rd + ks * 32]);
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
-                z[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w1f[b][ks]),
-                                                               __builtin_bit_cast(bf16x8, xf),
-                                                               ks == 0 ? bias1[b] : z[b], 0, 0, 0);
-        }
+                    for (int b = 0; b < 2; ++b)
+                        z[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf[b][ks]),
+                                                                       __builtin_bit_cast(bf16x8, xf),
+                                                                       ks == 0 ? bias[b] : z[b], 0, 0, 0);
+                }
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            float h[4];
-            cell(z[b], c1[b], h);
-            uint2 pk = {pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3])};
-            *(uint2 *)(&act[p ^ 1][h_wr + (COL_H1 + 8 * b) * 2]) = pk;
-        }
-        __syncthreads();                                   // h1_step is in act[p ^ 1]
-        // layer 2: [h1_step (other buffer) | h2_{step-1} (this buffer)]
+                for (int b = 0; b < 2; ++b) {
+                    cell(z[b], c[b], hv[b]);
+                    uint2 pk = {pack_bf16x2(hv[b][0], hv[b][1]), pack_bf16x2(hv[b][2], hv[b][3])};
+                    *(uint2 *)(&act[p ^ 1][h_wr + (COL_H1 + 8 * b) * 2]) = pk;
+                }
+            }
+        } else {
+            if (tau + 1 < L) embed_step(tau + 1, p ^ 1);
+            if (tau >= 1) {
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            const i32x4 xf = ks < 4 ? *(const i32x4 *)(&act[p ^ 1][frag_rd + (COL_H1 + ks * 16) * 2])
-                                    : *(const i32x4 *)(&act[p][frag_rd + (COL_H2 + (ks - 4) * 16) * 2]);
+                for (int ks = 0; ks < 8; ++ks) {
+                    const i32x4 xf = *(const i32x4 *)(&act[p][frag_rd + (COL_H1 + ks * 16) * 2]);
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
-                z[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w2f[b][ks]),
-                                                               __builtin_bit_cast(bf16x8, xf),
-                                                               ks == 0 ? bias2[b] : z[b], 0, 0, 0);
-        }
+                    for (int b = 0; b < 2; ++b)
+                        z[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf[b][ks]),
+                                                                       __builtin_bit_cast(bf16x8, xf),
+                                                                       ks == 0 ? bias[b] : z[b], 0, 0, 0);
+                }
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            cell(z[b], c2[b], h2v[b]);
-            uint2 pk = {pack_bf16x2(h2v[b][0], h2v[b][1]), pack_bf16x2(h2v[b][2], h2v[b][3])};
-            *(uint2 *)(&act[p ^ 1][h_wr + (COL_H2 + 8 * b) * 2]) = pk;
-            if (step + 1 == my_len) {
+                for (int b = 0; b < 2; ++b) {
+                    cell(z[b], c[b], hv[b]);
+                    uint2 pk = {pack_bf16x2(hv[b][0], hv[b][1]), pack_bf16x2(hv[b][2], hv[b][3])};
+                    *(uint2 *)(&act[p ^ 1][h_wr + (COL_H2 + 8 * b) * 2]) = pk;
+                    if (tau == my_len) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) hlast[b][j] = h2v[b][j];
+                        for (int j = 0; j < 4; ++j) hlast[b][j] = hv[b][j];
+                    }
+                }
             }
         }
     }
-    // ---- last hidden state of the second layer -> columns 16 w + 8 b + 4 hf .. + 3 of the scenario row
-    if (s0 + l31 < a.S) {
-        uint16_t *row = (uint16_t *)a.xs + (s0 + l31) * (int64_t)a.ld + 16 * wave + 4 * hf;
+    // ---- second layer's hidden state after the scenario's last layer -> columns 16 wu + 8 b + 4 hf .. + 3
+    if (role == 1 && s0 + l31 < a.S) {
+        uint16_t *row = (uint16_t *)a.xs + (s0 + l31) * (int64_t)a.ld + 16 * wu + 4 * hf;
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
             uint2 pk = {pack_bf16x2(hlast[b][0], hlast[b][1]), pack_bf16x2(hlast[b][2], hlast[b][3])};
@@ -734,7 +741,7 @@ hipError_t launch_lstm_encoder(const ab_model_desc *d, const float *dyn, const v
     for (int i = 0; i < AB_MAX_STATS; ++i) a.enc_stat[i] = d->enc_stat[i];
     const int64_t blocks = (S + 31) / 32;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    lstm_encoder_kernel<<<(unsigned)blocks, 256, 0, st>>>(a);
+    lstm_encoder_kernel<<<(unsigned)blocks, 512, 0, st>>>(a);
     return hipGetLastError();
 }
 
