@@ -97,20 +97,10 @@ __device__ __forceinline__ void st_T(void *p, int64_t i, float v)
     else ((float *)p)[i] = v;
 }
 
-// step counter and Adam bias corrections 1 - beta^t
-__global__ void update_begin_kernel(int64_t *step, float *scal, float beta1, float beta2)
-{
-    if (threadIdx.x == 0 && blockIdx.x == 0) {
-        const int64_t t = *step + 1;
-        *step = t;
-        scal[0] = (float)(1.0 - pow((double)beta1, (double)t));
-        scal[1] = (float)(1.0 - pow((double)beta2, (double)t));
-    }
-}
-
 // Per call: padded copy of W_1, transposes of the other hidden weights, zero padding columns of
 // the transposed batch buffers.
 struct UpdPrepArgs {
+    int64_t *step; float *scal; float beta1, beta2;      // the step counter and Adam's bias corrections ride along
     int n_jobs;
     struct Job { const void *src; void *dst; int rows, cols, ld_src, ld_dst, kind; int64_t start; } job[2 + 3 * AB_MAX_HIDDEN];
     int64_t total;
@@ -121,6 +111,12 @@ template <typename T>
 __global__ __launch_bounds__(256) void update_prep_kernel(const UpdPrepArgs a)
 {
     const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid == 0) {                            // step counter and Adam bias corrections 1 - beta^t
+        const int64_t t = *a.step + 1;
+        *a.step = t;
+        a.scal[0] = (float)(1.0 - pow((double)a.beta1, (double)t));
+        a.scal[1] = (float)(1.0 - pow((double)a.beta2, (double)t));
+    }
     if (gid >= a.total) return;
     int j = 0;
     while (j + 1 < a.n_jobs && gid >= a.job[j + 1].start) ++j;
@@ -287,11 +283,6 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
 
     const double esz = (double)elem_size(dt);
     {
-        TraceScope ts("upd_begin", 16.0, 1, st);
-        update_begin_kernel<<<1, 64, 0, st>>>(prm->step, scal, beta1, beta2);
-        AB_HIP(hipGetLastError());
-    }
-    {
         TraceScope ts("upd_encode_rows", (double)B * (p.F * 4.0 + 2.0 * p.Kp * esz), 1, st);
         AB_HIP(launch_encode_rows(dt, d, x_raw, x, xt, B, Bp, p.F, p.Kp, st));
     }
@@ -317,8 +308,9 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
             }
         }
         a.total = start;
+        a.step = prm->step; a.scal = scal; a.beta1 = beta1; a.beta2 = beta2;
         TraceScope ts("upd_prep_weights", 2.0 * (double)start * esz, 1, st);
-        update_prep_kernel<T><<<(unsigned)((start + 255) / 256), 256, 0, st>>>(a);
+        update_prep_kernel<T><<<(unsigned)((start + 255) / 256 > 0 ? (start + 255) / 256 : 1), 256, 0, st>>>(a);
         AB_HIP(hipGetLastError());
     }
     // forward
