@@ -197,6 +197,15 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
     if (S == 0) return AB_OK;
 
     hipStream_t st = (hipStream_t)stream;
+    if (score_tiny_supported(desc, S, C)) {
+        // the paper's own operating point (a job, tens of candidates, a small scorer): one launch does everything
+        double fl = (double)p.H[0] * p.Fs * 2.0 * S;
+        for (int k = 0; k < p.D; ++k) fl += 2.0 * S * C * p.H[k] * (k ? p.H[k - 1] : 3);
+        TraceScope ts("score_tiny", fl, 0, st);
+        AB_HIP(launch_score_tiny(p.dtype, desc, params, stats->dyn, stats->scalars, grid->partition_bytes,
+                                 grid->credit_mult, grid->P, grid->Q, S, scores, best_idx, best_score, st));
+        return AB_OK;
+    }
     unsigned char *ws = (unsigned char *)workspace;
     void *xs = ws + p.off_xs, *w1s = ws + p.off_w1s;
     float *a_term = (float *)(ws + p.off_aterm), *b_term = (float *)(ws + p.off_bterm);

@@ -221,6 +221,180 @@ __global__ __launch_bounds__(256) void finish_select_kernel(const FinishArgs a)
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// The whole pass in one launch for the size the paper runs it at (one job, tens of candidates, a small
+// scorer; Section 3.3 "Meta network optimizer"): at that size the chain of launches of the batched path
+// costs more than the arithmetic.  One work-group per scenario:
+//   transformed features -> LDS; scenario term A[j] = W1[j, :Fs] x + b1[j] (a wavefront per output,
+//   lanes over the inputs); then 64 candidates at a time, a candidate per lane and a quarter of a layer's
+//   outputs per wavefront: h1 = relu(A + wp phi(S_p) + wc phi(S_c)), the further layers as dot products
+//   whose weights are staged in LDS (wave-uniform broadcast reads) against the candidate's activations
+//   (read once per layer into registers from LDS rows of stride H + 4 floats: no bank conflicts), the output unit, and
+//   the running argmax.  With bf16 as compute type the values the batched path keeps in memory in bf16 (the
+//   scenario's features, every hidden activation but the last layer's) are rounded to bf16 here too, so a
+//   model scores the same whichever path a call takes.
+// ------------------------------------------------------------------------------------------------
+struct TinyArgs {
+    const float *dyn, *scal, *part, *cred;
+    int32_t L, K, Ns, Q, C, F, Fs, D;
+    int32_t H[AB_MAX_HIDDEN];
+    const void *W[AB_MAX_HIDDEN + 1];
+    const float *b[AB_MAX_HIDDEN + 1];
+    ab_enc enc_stat[AB_MAX_STATS], enc_scalar[AB_MAX_SCALARS], enc_part, enc_cred;
+    float *scores; int32_t *best_idx; float *best_score;
+};
+
+// One dense layer for 64 candidates (one per lane): this wavefront's outputs [j0, j0 + nj) from the
+// candidate's HIN inputs held in registers and the layer's weights staged in LDS as fp32 (every lane of a
+// wavefront reads the same weight: broadcast reads).  f(j, value) consumes an output.
+template <int HIN, typename F>
+__device__ __forceinline__ void tiny_dense(const float *w_lds, const float *bias, int j0, int nj, const float (&h)[HIN], F &&f)
+{
+    for (int jj = 0; jj < nj; ++jj) {
+        const int j = j0 + jj;
+        const float *wr = w_lds + j * HIN;
+        float acc = bias[j];
+#pragma unroll
+        for (int i = 0; i < HIN; i += 4) {
+            const f32x4 w = *(const f32x4 *)(wr + i);
+            acc = fmaf(w.w, h[i + 3], fmaf(w.z, h[i + 2], fmaf(w.y, h[i + 1], fmaf(w.x, h[i], acc))));
+        }
+        f(j, acc);
+    }
+}
+
+template <typename T>
+__device__ __forceinline__ float as_stored(float v)        // what a value becomes when kept in the compute type
+{
+    if constexpr (sizeof(T) == 2) return bf16_bits_to_f32(pack_bf16x2(v, 0.f) & 0xffffu);
+    else return v;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void score_tiny_kernel(const TinyArgs a)
+{
+    constexpr int HM = 128, G = 64, STR = HM + 4, FS_MAX = 2048;
+    __shared__ float xs[FS_MAX];
+    __shared__ float A1[HM], wp[HM], wc[HM];
+    __shared__ float red[4][G];
+    extern __shared__ __attribute__((aligned(16))) float tiny_dyn[];      // two activation buffers, one weight matrix
+    float (*hb)[G * STR] = (float (*)[G * STR])tiny_dyn;
+    float *w_lds = tiny_dyn + 2 * G * STR;
+    const int64_t s = blockIdx.x;
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+
+    // transformed statistics and scalars of the scenario
+    const int n_stat = a.L * a.K;
+    for (int i = t; i < a.Fs; i += 256)
+        xs[i] = as_stored<T>(i < n_stat ? phi(a.dyn[s * n_stat + i], a.enc_stat[i % a.K])
+                                        : phi(a.scal[s * a.Ns + (i - n_stat)], a.enc_scalar[i - n_stat]));
+    __syncthreads();
+    // scenario term of layer 1 and its two configuration columns
+    const int H1 = a.H[0];
+    for (int j0 = wave * 4; j0 < H1; j0 += 16) {           // four outputs at a time: four loads in flight
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int i = lane; i < a.Fs; i += 64) {
+            const float x = xs[i];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc[u] = fmaf(load_as_f32<T>(a.W[0], (int64_t)(j0 + u) * a.F + i), x, acc[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) acc[u] += __shfl_xor(acc[u], m, 64);
+        }
+        if (lane < 4) {
+            const int j = j0 + lane;
+            const float av = lane == 0 ? acc[0] : lane == 1 ? acc[1] : lane == 2 ? acc[2] : acc[3];
+            A1[j] = av + a.b[0][j];
+            wp[j] = load_as_f32<T>(a.W[0], (int64_t)j * a.F + a.Fs);
+            wc[j] = load_as_f32<T>(a.W[0], (int64_t)j * a.F + a.Fs + 1);
+        }
+    }
+    __syncthreads();
+
+    float bv = -INFINITY;
+    int bi = AB_NONE;
+    for (int c0 = 0; c0 < a.C; c0 += G) {
+        const int c = c0 + lane;
+        const int cc = c < a.C ? c : a.C - 1;
+        const float xp = phi(a.part[cc / a.Q], a.enc_part), xc = phi(a.cred[cc % a.Q], a.enc_cred);
+        float *mine = &hb[0][lane * STR];
+        {
+            const int hq = H1 >> 2;
+            for (int jj = 0; jj < hq; ++jj) {
+                const int j = wave * hq + jj;
+                const float h = relu_keep_nan(fmaf(wc[j], xc, fmaf(wp[j], xp, A1[j])));
+                mine[j] = a.D > 1 ? as_stored<T>(h) : h;
+            }
+        }
+        __syncthreads();
+        int cur = 0;
+        for (int k = 1; k < a.D; ++k) {
+            const int hin = a.H[k - 1], hq = a.H[k] >> 2;
+            // the layer's weights -> LDS as fp32 (the previous layer's readers are past the barrier above)
+            for (int e = t * 4; e < a.H[k] * hin; e += 1024) {
+                f32x4 w;
+                if constexpr (sizeof(T) == 2) {
+                    const uint2 r = *(const uint2 *)((const uint16_t *)a.W[k] + e);
+                    w = f32x4{__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xffff0000u),
+                              __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xffff0000u)};
+                } else {
+                    w = *(const f32x4 *)((const float *)a.W[k] + e);
+                }
+                *(f32x4 *)(w_lds + e) = w;
+            }
+            const float *src = &hb[cur][lane * STR];
+            float *dst = &hb[cur ^ 1][lane * STR];
+            const bool keep = k == a.D - 1;                 // the last hidden layer is not kept in the compute type
+            auto put = [&](int j, float v) { v = relu_keep_nan(v); dst[j] = keep ? v : as_stored<T>(v); };
+            if (hin == 64) {
+                float h[64];
+#pragma unroll
+                for (int i = 0; i < 64; i += 4) *(f32x4 *)&h[i] = *(const f32x4 *)(src + i);
+                __syncthreads();
+                tiny_dense<64>(w_lds, a.b[k], wave * hq, hq, h, put);
+            } else {
+                float h[128];
+#pragma unroll
+                for (int i = 0; i < 128; i += 4) *(f32x4 *)&h[i] = *(const f32x4 *)(src + i);
+                __syncthreads();
+                tiny_dense<128>(w_lds, a.b[k], wave * hq, hq, h, put);
+            }
+            __syncthreads();
+            cur ^= 1;
+        }
+        {   // output unit: a quarter of the dot product per wavefront
+            const int hl = a.H[a.D - 1], hq = hl >> 2;
+            const float *src = &hb[cur][lane * STR + wave * hq];
+            float acc = 0.f;
+            for (int i = 0; i < hq; i += 4) {
+                const f32x4 h = *(const f32x4 *)(src + i);
+                acc = fmaf(load_as_f32<T>(a.W[a.D], wave * hq + i + 3), h.w,
+                           fmaf(load_as_f32<T>(a.W[a.D], wave * hq + i + 2), h.z,
+                                fmaf(load_as_f32<T>(a.W[a.D], wave * hq + i + 1), h.y,
+                                     fmaf(load_as_f32<T>(a.W[a.D], wave * hq + i), h.x, acc))));
+            }
+            red[wave][lane] = acc;
+        }
+        __syncthreads();
+        if (wave == 0 && c < a.C) {
+            const float v = ((red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane])) + a.b[a.D][0];
+            if (a.scores) a.scores[s * a.C + c] = v;
+            amax_take(bv, bi, v, c);
+        }
+        __syncthreads();                                    // red and the activation buffers are reused
+    }
+    if (wave == 0 && a.best_idx) {
+        amax_wave(bv, bi);
+        if (lane == 0) {
+            a.best_idx[s] = (bi == AB_NONE) ? -1 : bi;
+            if (a.best_score) a.best_score[s] = (bi == AB_NONE) ? __uint_as_float(0x7fc00000u) : bv;
+        }
+    }
+}
+
 // Optimization Trigger (Section 3.3): argmax of a stored score row, relative gain over the configuration in
 // use, and the two threshold tests.  One work-group per scenario; IEEE single precision throughout.
 struct TriggerArgs {
@@ -479,6 +653,42 @@ hipError_t launch_finish_select(const float *partial, int nt, int64_t row_stride
     a.partial = partial; a.nt = nt; a.row_stride = row_stride; a.b_out = b_out; a.scores = scores;
     a.score_stride = score_stride; a.best_idx = best_idx; a.best_score = best_score; a.C = C;
     finish_select_kernel<<<(unsigned)S, 256, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+bool score_tiny_supported(const ab_model_desc *d, int64_t S, int32_t C)
+{
+    if (d->tensor_encoder || d->n_hidden < 1) return false;
+    for (int k = 0; k < d->n_hidden; ++k) if (d->hidden[k] > 128) return false;     // (multiples of 64 already)
+    const int64_t Fs = (int64_t)d->n_layers * d->n_stats + d->n_scalars;
+    return Fs <= 2048 && C <= 256 && S >= 1 && S * C <= 16384;
+}
+
+hipError_t launch_score_tiny(int dtype, const ab_model_desc *d, const ab_params *prm, const float *dyn,
+                             const float *scal, const float *part, const float *cred, int32_t P, int32_t Q,
+                             int64_t S, float *scores, int32_t *best_idx, float *best_score, hipStream_t st)
+{
+    TinyArgs a = {};
+    a.dyn = dyn; a.scal = scal; a.part = part; a.cred = cred;
+    a.L = d->n_layers; a.K = d->n_stats; a.Ns = d->n_scalars; a.Q = Q; a.C = P * Q;
+    a.Fs = d->n_layers * d->n_stats + d->n_scalars; a.F = a.Fs + 2; a.D = d->n_hidden;
+    for (int k = 0; k < d->n_hidden; ++k) a.H[k] = d->hidden[k];
+    for (int k = 0; k <= d->n_hidden; ++k) { a.W[k] = prm->W[k]; a.b[k] = prm->b[k]; }
+    for (int i = 0; i < AB_MAX_STATS; ++i) a.enc_stat[i] = d->enc_stat[i];
+    for (int i = 0; i < AB_MAX_SCALARS; ++i) a.enc_scalar[i] = d->enc_scalar[i];
+    a.enc_part = d->enc_partition; a.enc_cred = d->enc_credit;
+    a.scores = scores; a.best_idx = best_idx; a.best_score = best_score;
+    constexpr int smem = (2 * 64 * 132 + 128 * 128) * 4;       // activation buffers + one weight matrix as fp32
+    hipError_t e;
+    if (dtype == AB_BF16) {
+        e = hipFuncSetAttribute((const void *)score_tiny_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        score_tiny_kernel<bf16_t><<<(unsigned)S, 256, smem, st>>>(a);
+    } else {
+        e = hipFuncSetAttribute((const void *)score_tiny_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        score_tiny_kernel<float><<<(unsigned)S, 256, smem, st>>>(a);
+    }
     return hipGetLastError();
 }
 
