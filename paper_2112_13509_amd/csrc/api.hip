@@ -84,7 +84,7 @@ static ab_status plan_scoring(const ab_model_desc *d, int64_t S, int32_t C, Scor
     for (int k = 1; k < p->D; ++k) {
         p->tile[k] = pick_tile(p->chunk_rows, p->H[k]);
         p->big[k] = p->dtype == AB_BF16 && p->H[k] % 256 == 0 && (k > 1 || C % 256 == 0) &&
-                    ((p->chunk_rows + 255) / 256) * (p->H[k] / 256) >= 256;
+                    ((p->chunk_rows + 255) / 256) * (p->H[k] / 256) >= 64;   // (measured crossover against the generic tiles)
     }
     p->nt_last = 1;
     if (p->D >= 2) {

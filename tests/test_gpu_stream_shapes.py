@@ -29,7 +29,7 @@ def run_and_compare(w, label):
     assert np.array_equal(idx, np.argmax(scores, axis=1)) and np.array_equal(best, scores[np.arange(w.S), idx])
 
 
-# The 256 x 256 kernels take a hidden GEMM from 256 tiles per launch on; every case below has at least that many.
+# The 256 x 256 kernels take a hidden GEMM from 64 tiles per launch on; every case below has at least that many.
 @pytest.mark.parametrize("S,P,Q,hidden,label", [
     (600, 16, 16, [256, 256], "600 row tiles over 256 work-groups (2 or 3 each), generated operand + fused output"),
     (257, 16, 16, [256, 256, 256], "257 row tiles: one work-group walks two tiles, the others one"),
