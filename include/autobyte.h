@@ -36,8 +36,8 @@
  *   x = [ statistics block | scalars | phi(S_p) | phi(S_c) ]
  *   statistics block: L*K transformed per-layer statistics, layer-major / statistic-minor (flat model),
  *   or the mean over the L layers of a shared two-layer MLP applied to each layer's K transformed
- *   statistics (tensor-encoder model: "embed layer-wise computation time into a fixed dimension
- *   feature space").  Every raw value x is transformed as phi(x) = (g(x) - shift) * scale with
+ *   statistics (tensor-encoder model: the paper maps the per-layer times to a feature space of fixed
+ *   width before anything else reads them).  Every raw value x is transformed as phi(x) = (g(x) - shift) * scale with
  *   g = identity or natural logarithm; S_c is expressed as a multiple of S_p (Section 2.4).
  *
  * Network: hidden dense layers with ReLU, then one linear output unit (V is a regression target).

@@ -98,13 +98,13 @@ static void orc_dense(const double *W, const double *b, int n_out, int n_in,
  *  tensor_encoder    : 0 -> the L*K statistics are laid side by side (layer-major, stat-minor);
  *                      1 -> a shared two-layer MLP (K -> te_h0 -> te_h1, ReLU after both) is
  *                           applied to each layer's K statistics and the results are averaged
- *                           over the L layers ("embed layer-wise computation time into a fixed
- *                           dimension feature space", Section 3.1 "Meta network architecture")
+ *                           over the L layers (Section 3.1 "Meta network architecture": the per-layer
+ *                           times are first mapped to a feature space of fixed width)
  *                      2 -> each layer's K statistics are embedded linearly into te_h0 values and a
  *                           two-layer LSTM of te_h1 units per layer runs over the L layers in order;
  *                           the second layer's last hidden state is the statistics block
- *                           ("we apply two-layer LSTM to extract the sequential features in T",
- *                           Section 3.1 "Meta network architecture")
+ *                           (Section 3.1 "Meta network architecture": after the embedding a two-layer LSTM
+ *                           reads the layer sequence)
  *  te_W[2], te_b[2]  : tensor-encoder weights ([te_h0,K], [te_h1,te_h0]) and biases; for the LSTM
  *                      te_W[3] = {[te_h0,K], [4*te_h1, te_h0+te_h1], [4*te_h1, 2*te_h1]} and te_b[3]
  *                      = {[te_h0], [4*te_h1], [4*te_h1]}: the recurrent matrices act on
@@ -187,7 +187,7 @@ static int orc_feature_scratch(const orc_model *m) { return m->K + m->te_h0 + 11
 
 /*
  * Layers a scenario really has: jobs differ in their number of layers (Section 3.1 "Meta network
- * architecture": "different training tasks usually result in different number of layers"), the statistics
+ * architecture" notes that the layer count varies from one training task to the next), the statistics
  * tensor is padded to L.  layers_of == NULL: all L; values are clamped to [1, L].
  */
 static int orc_layers_of(const orc_model *m, const int32_t *layers_of, int64_t s)
@@ -420,8 +420,8 @@ int orc_trigger(const float *scores, int64_t S, int C, int64_t row_stride, const
  *   d_out_i = 2 (yhat_i - y_i) / B ; dW = d^T h_prev ; db = sum_i d_i ; d_prev = (d W) * [pre > 0].
  * Adam follows Kingma & Ba, Algorithm 1, with bias correction and epsilon outside the root.
  *
- * Transfer-learning form ("use transfer learning to update the offline trained model", Section 3.2; the
- * workflow of Section 3.3 adapts the trained network online): layers below first_trainable keep their
+ * Transfer-learning form (Section 3.2 "Offline training online adapting" updates the offline-trained model by
+ * transfer learning; the workflow of Section 3.3 adapts the trained network online): layers below first_trainable keep their
  * parameters and moments; back-propagation stops at the first trainable layer.  first_trainable = 0 is
  * the full update, first_trainable = n_hidden updates the output layer alone.  Frozen layers report
  * zero gradients.

@@ -323,8 +323,8 @@ def update(model: Model, state: TrainState, x_raw, target, lr=1e-3, beta1=0.9, b
 
 
 def replay_mix(x_new, t_new, x_old, t_old, pick):
-    """Minibatch assembled from freshly observed rows and the offline set ("update the offline trained model
-    and also update the dataset", Section 3.2): entry i of ``pick`` >= 0 takes new row pick[i], entry < 0 takes
+    """Minibatch assembled from freshly observed rows and the offline set (Section 3.2: online
+    adaptation refreshes the offline-trained model and extends its dataset with the new samples): entry i of ``pick`` >= 0 takes new row pick[i], entry < 0 takes
     old row -pick[i] - 1; an index outside its pool gives a NaN row.  Returns (x [B, F], target [B])."""
     x_new, t_new, x_old, t_old = _f64(x_new), _f64(t_new), _f64(x_old), _f64(t_old)
     pick = np.asarray(pick, dtype=np.int64)
