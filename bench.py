@@ -180,6 +180,29 @@ def main():
     else:
         roofline = None
 
+    # ---- the memory-bound stages against the HBM peak: the feature transform as it ran inside the pass, and the
+    # stand-alone argmax over the stored score matrix
+    hbm_stages = None
+    if cfg != 4:
+        hbm_stages = {"peak_GB/s": 8000.0}
+        if "encode_stats" in ksum:
+            r = ksum["encode_stats"]
+            rate = r["work"] / (r["total_ms"] * 1e-3)
+            hbm_stages["encode_stats"] = {"bytes_per_launch": r["work"] / r["launches"], "avg_us": round(r["avg_ms"] * 1e3, 2),
+                                          "GB/s": round(rate / 1e9, 1), "frac": round(rate / 8e12, 4)}
+        if want_scores and S * Cn >= (1 << 20):
+            idx2, best2 = torch.empty_like(idx), torch.empty_like(best)
+            for _ in range(3):
+                ab.ab_select_best(scores, idx2, best2)
+            with ab.KernelTimer() as kt2:
+                for _ in range(20):
+                    ab.ab_select_best(scores, idx2, best2)
+                r = kt2.summary()["select_best"]
+            rate = r["work"] / (r["total_ms"] * 1e-3)
+            hbm_stages["select_best"] = {"bytes_per_launch": r["work"] / r["launches"], "avg_us": round(r["avg_ms"] * 1e3, 2),
+                                         "GB/s": round(rate / 1e9, 1), "frac": round(rate / 8e12, 4),
+                                         "same_choice_as_fused": bool(torch.equal(idx2, idx))}
+
     # ---- transfer-learning form of the update and the minibatch assembly, timed next to the full step (cfg4 only)
     transfer = None
     if cfg == 4:
@@ -280,7 +303,7 @@ def main():
            "config": workload_desc,
            "algorithmic_flop_per_unit": flops_per_unit,
            "whole_step_TFLOP/s": round(units_per_step * flops_per_unit / (ms_per_step * 1e-3) / 1e12, 3),
-           "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "launch_floor": launch_floor, "encoder_roofline": encoder_roofline, "transfer_learning": transfer,
+           "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "launch_floor": launch_floor, "encoder_roofline": encoder_roofline, "hbm_stages": hbm_stages, "transfer_learning": transfer,
            "input_generation_s": round(t_gen, 2)}
     print(json.dumps(out))
 

@@ -51,6 +51,91 @@ __global__ __launch_bounds__(256) void encode_stats_kernel(const EncodeArgs a)
     else ((f32x2 *)a.xs)[o >> 1] = f32x2{v[0], v[1]};
 }
 
+// The same transform, four adjacent columns per thread (16-byte loads, 8- or 16-byte stores), for rows
+// whose statistics part is a multiple of four columns and 16-byte aligned.  A work-group takes `rpb`
+// rows; lane -> (row, quad) by a multiply-high with magic = floor(2^32 / q4) + 1 (exact while
+// index * q4 < 2^32), likewise column -> statistic index.  The transform constants sit in LDS so that a
+// lane can pick its own.  With bf16 as compute type the logarithm is the hardware's log2 (1 ulp, far
+// below what the rounding to bf16 keeps) times ln 2.
+template <typename T>
+__device__ __forceinline__ float phi_tab(float x, const f32x4 *tab, int i)
+{
+    float lg;
+    if constexpr (sizeof(T) == 2) lg = __builtin_amdgcn_logf(x) * 0.69314718056f;
+    else lg = logf(x);
+    const f32x4 t = tab[i];                        // (kind, shift, scale, -)
+    return ((t.x != 0.f ? lg : x) - t.y) * t.z;
+}
+
+template <typename T>
+__device__ __forceinline__ void store_quad(void *xs, int64_t o, const float (&v)[4])
+{
+    if constexpr (sizeof(T) == 2) {
+        typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+        *(u32x2 *)((uint16_t *)xs + o) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+    } else {
+        *(f32x4 *)((float *)xs + o) = f32x4{v[0], v[1], v[2], v[3]};
+    }
+}
+
+struct QuadSplit { int q4s, q4t; uint32_t magic_q4s, magic_q4t, magic_k; int rpb; };
+
+template <typename T>
+__global__ __launch_bounds__(256) void encode_stats_quad_kernel(const EncodeArgs a, const QuadSplit g)
+{
+    __shared__ f32x4 tab[AB_MAX_STATS + AB_MAX_SCALARS];     // statistics 0..7, scalars 8..23
+    if (threadIdx.x < AB_MAX_STATS + AB_MAX_SCALARS) {
+        const int i = threadIdx.x;
+        const ab_enc *e = i < AB_MAX_STATS ? &a.enc_stat[i] : &a.enc_scal[i - AB_MAX_STATS];
+        tab[i] = f32x4{e->kind == AB_ENC_LOG ? 1.f : 0.f, e->shift, e->scale, 0.f};
+    }
+    __syncthreads();
+    const int64_t row0 = (int64_t)blockIdx.x * g.rpb;
+    const int rows = (int)((a.S - row0 < g.rpb) ? a.S - row0 : g.rpb);
+
+    // the statistics columns: q4s quads a row, a thread's four loads issued before the first value is used
+    const uint32_t n_a = (uint32_t)rows * (uint32_t)g.q4s;
+    for (uint32_t base = 0; base < n_a; base += 1024) {
+        f32x4 x[4];
+        uint32_t r[4];
+        int col[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t i = base + u * 256 + threadIdx.x;
+            r[u] = __umulhi(i, g.magic_q4s);
+            col[u] = (int)(i - r[u] * (uint32_t)g.q4s) * 4;
+            if (i < n_a) x[u] = __builtin_nontemporal_load((const f32x4 *)(a.dyn + (row0 + r[u]) * a.n_stat + col[u]));
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (base + u * 256 + threadIdx.x >= n_a) break;
+            int k = a.n_stats_per_layer == 1
+                        ? 0 : col[u] - (int)__umulhi((uint32_t)col[u], g.magic_k) * a.n_stats_per_layer;
+            float v[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                v[e] = phi_tab<T>(x[u][e], tab, k);
+                k = (k + 1 == a.n_stats_per_layer) ? 0 : k + 1;
+            }
+            store_quad<T>(a.xs, (row0 + r[u]) * a.ld + a.col0 + col[u], v);
+        }
+    }
+
+    // the scalars and the zero padding behind them: q4t quads a row
+    const uint32_t n_b = (uint32_t)rows * (uint32_t)g.q4t;
+    for (uint32_t i = threadIdx.x; i < n_b; i += 256) {
+        const uint32_t r = __umulhi(i, g.magic_q4t);
+        const int q0 = (int)(i - r * (uint32_t)g.q4t) * 4;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int q = q0 + e;
+            v[e] = q < a.n_scal ? phi_tab<T>(a.scal[(row0 + r) * a.n_scal + q], tab, AB_MAX_STATS + q) : 0.f;
+        }
+        store_quad<T>(a.xs, (row0 + r) * a.ld + a.col0 + a.n_stat + q0, v);
+    }
+}
+
 // Raw update rows x_raw[B, F] (statistics, scalars, partition, credit) -> transformed x[B, ld]
 // (zero in the padding columns) and, optionally, its transpose x_t[ld, ld_t].
 struct EncodeRowsArgs {
@@ -216,6 +301,85 @@ __global__ __launch_bounds__(256) void finish_select_kernel(const FinishArgs a)
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int w = 1; w < 4; ++w) amax_take(bv, bi, sv[w], si[w]);
+        a.best_idx[s] = (bi == AB_NONE) ? -1 : bi;
+        if (a.best_score) a.best_score[s] = (bi == AB_NONE) ? __uint_as_float(0x7fc00000u) : bv;
+    }
+}
+
+// The same for short rows (C <= 1024): a wavefront per scenario, four scenarios per work-group, no LDS
+// and no barrier.  NT fixes the number of partial sums per candidate (one 4*NT-byte load each).
+template <int NT>
+__global__ __launch_bounds__(256) void finish_select_wave_kernel(const FinishArgs a, int64_t S)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t s = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (s >= S) return;
+    const float *p = a.partial + s * a.row_stride * NT;
+    const float b = a.b_out ? a.b_out[0] : 0.f;
+    float bv = -INFINITY;
+    int bi = AB_NONE;
+    {
+        typedef __attribute__((ext_vector_type(NT))) float vec_t;
+        for (int c = lane; c < a.C; c += 64) {
+            float v;
+            if constexpr (NT == 1) v = __builtin_nontemporal_load(p + c);
+            else {
+                const vec_t x = __builtin_nontemporal_load((const vec_t *)(p + (int64_t)c * NT));
+                v = x[0];
+#pragma unroll
+                for (int t = 1; t < NT; ++t) v += x[t];
+            }
+            v += b;
+            if (a.scores) a.scores[s * a.score_stride + c] = v;
+            amax_take(bv, bi, v, c);
+        }
+    }
+    if (!a.best_idx) return;
+    amax_wave(bv, bi);
+    if (lane == 0) {
+        a.best_idx[s] = (bi == AB_NONE) ? -1 : bi;
+        if (a.best_score) a.best_score[s] = (bi == AB_NONE) ? __uint_as_float(0x7fc00000u) : bv;
+    }
+}
+
+// Plain argmax over stored rows (C <= 1024, a multiple of 4, 16-byte aligned rows): sixteen lanes per
+// scenario, four scenarios per wavefront, all of a lane's 16-byte loads issued up front; the lanes of a
+// row of sixteen combine through four DPP exchanges (no LDS).
+template <int CTRL>
+__device__ __forceinline__ void amax_dpp(float &bv, int &bi)
+{
+    const float ov = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, bv), CTRL, 0xf, 0xf, false));
+    const int oi = __builtin_amdgcn_update_dpp(0, bi, CTRL, 0xf, 0xf, false);
+    amax_take(bv, bi, ov, oi);
+}
+
+template <int NLOAD>
+__global__ __launch_bounds__(256) void select_rows16_kernel(const FinishArgs a, int64_t S)
+{
+    const int l16 = threadIdx.x & 15;
+    const int64_t s = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const bool live = s < S;
+    const float *p = a.partial + (live ? s : 0) * a.row_stride;
+    f32x4 x[NLOAD];
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+        const int c = (i * 16 + l16) * 4;
+        x[i] = (live && c < a.C) ? __builtin_nontemporal_load((const f32x4 *)(p + c))
+                                 : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    }
+    float bv = -INFINITY;
+    int bi = AB_NONE;
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+        const int c = (i * 16 + l16) * 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) if (c < a.C) amax_take(bv, bi, x[i][e], c + e);
+    }
+    amax_dpp<0xB1>(bv, bi);      // lanes ^ 1   (quad_perm 1,0,3,2)
+    amax_dpp<0x4E>(bv, bi);      // lanes ^ 2   (quad_perm 2,3,0,1)
+    amax_dpp<0x141>(bv, bi);     // the other quad of the half row (row_half_mirror)
+    amax_dpp<0x140>(bv, bi);     // the other half of the row (row_mirror)
+    if (live && l16 == 0) {
         a.best_idx[s] = (bi == AB_NONE) ? -1 : bi;
         if (a.best_score) a.best_score[s] = (bi == AB_NONE) ? __uint_as_float(0x7fc00000u) : bv;
     }
@@ -606,7 +770,21 @@ hipError_t launch_encode_stats(int dtype, const ab_model_desc *d, const float *d
     a.n_stats_per_layer = d->n_stats; a.n_scal = d->n_scalars;
     for (int i = 0; i < AB_MAX_STATS; ++i) a.enc_stat[i] = d->enc_stat[i];
     for (int i = 0; i < AB_MAX_SCALARS; ++i) a.enc_scal[i] = d->enc_scalar[i];
-    const int64_t n = S * ((ld - col0) / 2);
+    const int width = ld - col0;
+    if (width % 4 == 0 && col0 % 4 == 0 && a.n_stat % 4 == 0 && a.n_stat != 4 && width - a.n_stat >= 8 && width / 4 < 65536 &&
+        ((uintptr_t)dyn & 15) == 0 && ((uintptr_t)xs & 15) == 0 && (ld * elem_size(dtype)) % 16 == 0) {
+        // magic = floor(2^32 / n) + 1 turns index / n into a multiply-high, exact while index * n < 2^32
+        auto magic = [](int n) { return n >= 2 ? (uint32_t)(0x100000000ull / (uint32_t)n) + 1u : 0u; };
+        QuadSplit g;
+        g.q4s = a.n_stat / 4; g.q4t = (width - a.n_stat) / 4;
+        g.rpb = width / 4 >= 2048 ? 1 : 2048 / (width / 4);      // about two thousand quads per work-group
+        g.magic_q4s = magic(g.q4s); g.magic_q4t = magic(g.q4t); g.magic_k = magic(d->n_stats);
+        const unsigned blocks = (unsigned)((S + g.rpb - 1) / g.rpb);
+        if (dtype == AB_BF16) encode_stats_quad_kernel<bf16_t><<<blocks, 256, 0, st>>>(a, g);
+        else encode_stats_quad_kernel<float><<<blocks, 256, 0, st>>>(a, g);
+        return hipGetLastError();
+    }
+    const int64_t n = S * (width / 2);
     if (dtype == AB_BF16) encode_stats_kernel<bf16_t><<<blocks_for(n), 256, 0, st>>>(a);
     else encode_stats_kernel<float><<<blocks_for(n), 256, 0, st>>>(a);
     return hipGetLastError();
@@ -652,7 +830,21 @@ hipError_t launch_finish_select(const float *partial, int nt, int64_t row_stride
     FinishArgs a;
     a.partial = partial; a.nt = nt; a.row_stride = row_stride; a.b_out = b_out; a.scores = scores;
     a.score_stride = score_stride; a.best_idx = best_idx; a.best_score = best_score; a.C = C;
-    finish_select_kernel<<<(unsigned)S, 256, 0, st>>>(a);
+    const unsigned wave_blocks = (unsigned)((S + 3) / 4);
+    if (C <= 1024 && nt == 1 && !b_out && !scores && best_idx && C % 4 == 0 && row_stride % 4 == 0 &&
+        ((uintptr_t)partial & 15) == 0) {
+        const unsigned blocks = (unsigned)((S + 15) / 16);
+        if (C <= 256) select_rows16_kernel<4><<<blocks, 256, 0, st>>>(a, S);
+        else if (C <= 512) select_rows16_kernel<8><<<blocks, 256, 0, st>>>(a, S);
+        else select_rows16_kernel<16><<<blocks, 256, 0, st>>>(a, S);
+    } else if (C <= 1024 && nt == 1)
+        finish_select_wave_kernel<1><<<wave_blocks, 256, 0, st>>>(a, S);
+    else if (C <= 1024 && nt == 2 && ((uintptr_t)partial & 7) == 0)
+        finish_select_wave_kernel<2><<<wave_blocks, 256, 0, st>>>(a, S);
+    else if (C <= 1024 && nt == 4 && ((uintptr_t)partial & 15) == 0)
+        finish_select_wave_kernel<4><<<wave_blocks, 256, 0, st>>>(a, S);
+    else
+        finish_select_kernel<<<(unsigned)S, 256, 0, st>>>(a);
     return hipGetLastError();
 }
 

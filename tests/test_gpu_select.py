@@ -26,7 +26,8 @@ def run_select(sc, C_=None, stride=None):
     return idx.cpu().numpy(), best.cpu().numpy()
 
 
-@pytest.mark.parametrize("S,Cn", [(1, 1), (3, 64), (17, 255), (5, 256), (9, 257), (4, 4096), (2, 5000), (1000, 33)])
+@pytest.mark.parametrize("S,Cn", [(1, 1), (3, 64), (17, 255), (5, 256), (9, 257), (4, 4096), (2, 5000), (1000, 33),
+                                  (1001, 1024), (13, 260), (6, 1028)])
 def test_random_rows_with_ties(S, Cn):
     rng = np.random.default_rng(S * 1000 + Cn)
     sc = rng.standard_normal((S, Cn)).astype(np.float32)
@@ -46,6 +47,16 @@ def test_nan_inf_and_stride():
     idx, best = run_select(sc, C_=5, stride=6)
     assert list(idx) == [1, -1, 1, 0]
     assert best[0] == 1.0 and np.isnan(best[1]) and best[2] == np.inf and best[3] == -np.inf
+
+
+@pytest.mark.parametrize("Cn,stride", [(8, 10), (8, 12), (260, 264), (259, 264)])
+def test_row_strides_of_both_alignments(Cn, stride):
+    rng = np.random.default_rng(Cn * 100 + stride)
+    sc = rng.standard_normal((37, stride)).astype(np.float32)
+    sc[:, Cn:] = 1e9                              # beyond the row's end: must never win
+    idx, best = run_select(sc, C_=Cn, stride=stride)
+    ridx, rbest, _ = orc.select(np.ascontiguousarray(sc[:, :Cn]))
+    assert (idx == ridx).all() and (best == rbest.astype(np.float32)).all()
 
 
 def test_large_matrix_matches_oracle():
