@@ -113,18 +113,18 @@ __device__ __forceinline__ void store_elem(void *base, int64_t idx, float v, int
     else ((uint16_t *)base)[idx] = (uint16_t)(pack_bf16x2(v, 0.f) & 0xffffu);
 }
 
+// One work-group's tile of the product: `id` is the work-group's number within the product's launch (or
+// within its share of a launch that holds several products), `smem` 2 * (BM + BN) * 128 bytes of LDS.
 template <typename T, int WMB, int WNB, int AMODE, int EPI>
-__global__ __launch_bounds__(256) void gemm_tn_kernel(const GemmArgs g)
+__device__ __forceinline__ void gemm_tn_tile(const GemmArgs &g, int64_t id, unsigned char *smem)
 {
     constexpr int BM = 64 * WMB, BN = 64 * WNB;
     constexpr int BK = TileTraits<T>::BK, EPC = TileTraits<T>::EPC;
     constexpr int A_CH = BM / 32, B_CH = BN / 32;        // 16-byte chunks per thread per slab
     constexpr int STAGE_BYTES = (BM + BN) * 128;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     // Work-group -> tile.  Consecutive work-group ids go to consecutive XCDs, so the n_tiles tiles
     // that share one panel of A are given ids that land on the same XCD (same L2) back to back.
-    int64_t id = blockIdx.x;
     int split = 0;
     if constexpr (EPI == EPI_SPLITK) { split = (int)(id % g.k_splits); id /= g.k_splits; }
     const int xcd = (int)(id & 7);
@@ -336,6 +336,13 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const GemmArgs g)
         if (t < BM && m0 + t < g.M)
             g.partial[(m0 + t) * g.n_tiles + tn] = red[t] + red[BM + t];
     }
+}
+
+template <typename T, int WMB, int WNB, int AMODE, int EPI>
+__global__ __launch_bounds__(256) void gemm_tn_kernel(const GemmArgs g)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    gemm_tn_tile<T, WMB, WNB, AMODE, EPI>(g, blockIdx.x, smem);
 }
 
 }  // namespace ab

@@ -17,6 +17,13 @@ struct TraceScope {
     ~TraceScope() { if (g_trace_fn) g_trace_fn(name, 1, work, bytes, (void *)st, g_trace_user); }
 };
 
+// Feature transform phi(x) = (g(x) - shift) * scale with g the identity or the natural logarithm.
+__device__ __forceinline__ float phi(float x, const ab_enc &e)
+{
+    const float gx = (e.kind == AB_ENC_LOG) ? logf(x) : x;
+    return (gx - e.shift) * e.scale;
+}
+
 enum { TILE_SMALL = 0, TILE_MID = 1, TILE_BIG = 2 };   // 64x64, 128x128, 256x256 work-group tiles
 
 static inline int tile_edge(int tile) { return 64 << tile; }
@@ -32,8 +39,6 @@ hipError_t launch_gemm_big(int amode, int epi, GemmArgs g, hipStream_t st);
 
 hipError_t launch_encode_stats(int dtype, const ab_model_desc *d, const float *dyn, const float *scal,
                                void *xs, int64_t S, int ld, int col0, int with_stats, hipStream_t st);
-hipError_t launch_encode_rows(int dtype, const ab_model_desc *d, const float *x_raw, void *x, void *x_t,
-                              int64_t B, int64_t ld_t, int F, int ld, hipStream_t st);
 hipError_t launch_prep_layer1(int dtype, const ab_model_desc *d, const void *W1, const float *b1, int F, int Fs,
                               int H1, int ld, void *w1s, const ab_grid *grid, float *b_term, float *cfg_vec,
                               const void *Wout, int H_last, float *w_out_f, hipStream_t st);

@@ -4,12 +4,6 @@
 
 namespace ab {
 
-__device__ __forceinline__ float phi(float x, const ab_enc &e)
-{
-    const float gx = (e.kind == AB_ENC_LOG) ? logf(x) : x;
-    return (gx - e.shift) * e.scale;
-}
-
 // ------------------------------------------------------------------------------------------------
 // Feature transform (Section 3.3 "Meta network optimizer": runtime statistics are turned into the
 // network's input vector).  One thread produces two adjacent columns of one scenario's row.
@@ -133,57 +127,6 @@ __global__ __launch_bounds__(256) void encode_stats_quad_kernel(const EncodeArgs
             v[e] = q < a.n_scal ? phi_tab<T>(a.scal[(row0 + r) * a.n_scal + q], tab, AB_MAX_STATS + q) : 0.f;
         }
         store_quad<T>(a.xs, (row0 + r) * a.ld + a.col0 + a.n_stat + q0, v);
-    }
-}
-
-// Raw update rows x_raw[B, F] (statistics, scalars, partition, credit) -> transformed x[B, ld]
-// (zero in the padding columns) and, optionally, its transpose x_t[ld, ld_t].
-struct EncodeRowsArgs {
-    const float *x_raw; void *x; void *x_t; int64_t B, ld_t; int32_t F, ld;
-    int32_t n_stat, n_stats_per_layer, n_scal;
-    ab_enc enc_stat[AB_MAX_STATS];
-    ab_enc enc_scal[AB_MAX_SCALARS];
-    ab_enc enc_part, enc_cred;
-};
-
-template <typename T>
-__global__ __launch_bounds__(256) void encode_rows_kernel(const EncodeRowsArgs a)
-{
-    const int pairs = a.ld >> 1;
-    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t r = gid / pairs;
-    if (r >= a.B) return;
-    const int j0 = (int)(gid - r * pairs) * 2;
-    float v[2];
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-        const int j = j0 + e;
-        float x = 0.f;
-        if (j < a.F) {
-            const float raw = a.x_raw[r * a.F + j];
-            if (j < a.n_stat) x = phi(raw, a.enc_stat[j % a.n_stats_per_layer]);
-            else if (j < a.n_stat + a.n_scal) x = phi(raw, a.enc_scal[j - a.n_stat]);
-            else if (j == a.F - 2) x = phi(raw, a.enc_part);
-            else x = phi(raw, a.enc_cred);
-        }
-        v[e] = x;
-    }
-    const int64_t o = r * a.ld + j0;
-    if constexpr (sizeof(T) == 2) {
-        ((uint32_t *)a.x)[o >> 1] = pack_bf16x2(v[0], v[1]);
-        if (a.x_t) {
-            uint16_t *xt = (uint16_t *)a.x_t;
-            const uint32_t p = pack_bf16x2(v[0], v[1]);
-            xt[(int64_t)j0 * a.ld_t + r] = (uint16_t)(p & 0xffffu);
-            xt[(int64_t)(j0 + 1) * a.ld_t + r] = (uint16_t)(p >> 16);
-        }
-    } else {
-        ((f32x2 *)a.x)[o >> 1] = f32x2{v[0], v[1]};
-        if (a.x_t) {
-            float *xt = (float *)a.x_t;
-            xt[(int64_t)j0 * a.ld_t + r] = v[0];
-            xt[(int64_t)(j0 + 1) * a.ld_t + r] = v[1];
-        }
     }
 }
 
@@ -787,21 +730,6 @@ hipError_t launch_encode_stats(int dtype, const ab_model_desc *d, const float *d
     const int64_t n = S * (width / 2);
     if (dtype == AB_BF16) encode_stats_kernel<bf16_t><<<blocks_for(n), 256, 0, st>>>(a);
     else encode_stats_kernel<float><<<blocks_for(n), 256, 0, st>>>(a);
-    return hipGetLastError();
-}
-
-hipError_t launch_encode_rows(int dtype, const ab_model_desc *d, const float *x_raw, void *x, void *x_t,
-                              int64_t B, int64_t ld_t, int F, int ld, hipStream_t st)
-{
-    EncodeRowsArgs a;
-    a.x_raw = x_raw; a.x = x; a.x_t = x_t; a.B = B; a.ld_t = ld_t; a.F = F; a.ld = ld;
-    a.n_stat = d->n_layers * d->n_stats; a.n_stats_per_layer = d->n_stats; a.n_scal = d->n_scalars;
-    for (int i = 0; i < AB_MAX_STATS; ++i) a.enc_stat[i] = d->enc_stat[i];
-    for (int i = 0; i < AB_MAX_SCALARS; ++i) a.enc_scal[i] = d->enc_scalar[i];
-    a.enc_part = d->enc_partition; a.enc_cred = d->enc_credit;
-    const int64_t n = B * (ld / 2);
-    if (dtype == AB_BF16) encode_rows_kernel<bf16_t><<<blocks_for(n), 256, 0, st>>>(a);
-    else encode_rows_kernel<float><<<blocks_for(n), 256, 0, st>>>(a);
     return hipGetLastError();
 }
 

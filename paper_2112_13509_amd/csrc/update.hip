@@ -108,9 +108,9 @@ struct UpdPrepArgs {
 enum { JOB_PAD_COPY = 0, JOB_TRANSPOSE = 1, JOB_ZERO_COLS = 2 };
 
 template <typename T>
-__global__ __launch_bounds__(256) void update_prep_kernel(const UpdPrepArgs a)
+__device__ __forceinline__ void update_prep_block(const UpdPrepArgs &a, unsigned id)
 {
-    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t gid = (int64_t)id * 256 + threadIdx.x;
     if (gid == 0) {                            // step counter and Adam bias corrections 1 - beta^t
         const int64_t t = *a.step + 1;
         *a.step = t;
@@ -174,7 +174,7 @@ struct OutGradArgs {
     const void *ht; const void *w_out; const float *dout; const float *yhat; const float *target;
     void *dt; float *gw_out; float *gb_out; float *loss_out; int64_t B, Bp; int32_t H;
 };
-__device__ __forceinline__ float block_sum_256(float v, float *sh)
+__device__ __forceinline__ float block_sum_256(float v, float *sh)      // sh: four floats of LDS
 {
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
@@ -185,10 +185,9 @@ __device__ __forceinline__ float block_sum_256(float v, float *sh)
     return r;
 }
 template <typename T>
-__global__ __launch_bounds__(256) void output_grad_kernel(const OutGradArgs a)
+__device__ __forceinline__ void output_grad_block(const OutGradArgs &a, unsigned id, float *sh)
 {
-    __shared__ float sh[4];
-    const int c = blockIdx.x;
+    const int c = (int)id;
     if (c < a.H) {
         const float w = ld_f32<T>(a.w_out, c);
         float acc = 0.f;
@@ -222,16 +221,125 @@ struct BiasGradArgs {
     int64_t B, Bp;
 };
 template <typename T>
-__global__ __launch_bounds__(256) void bias_grad_kernel(const BiasGradArgs a)
+__device__ __forceinline__ void bias_grad_block(const BiasGradArgs &a, unsigned id, float *sh)
 {
-    __shared__ float sh[4];
     int k = 0;
-    while (k + 1 < a.n && (int)blockIdx.x >= a.l[k + 1].start) ++k;
-    const int c = blockIdx.x - a.l[k].start;
+    while (k + 1 < a.n && (int)id >= a.l[k + 1].start) ++k;
+    const int c = (int)id - a.l[k].start;
     float acc = 0.f;
     for (int64_t r = threadIdx.x; r < a.B; r += 256) acc += ld_f32<T>(a.l[k].dt, (int64_t)c * a.Bp + r);
     const float s = block_sum_256(acc, sh);
     if (threadIdx.x == 0) a.l[k].gb[c] = s;
+}
+
+// Raw update rows x_raw[B, F] (statistics, scalars, partition, credit) -> transformed x[B, ld] (zero in the
+// padding columns) and its transpose x_t[ld, ld_t].  A work-group takes a tile of 64 rows x 64 columns: a
+// thread transforms one pair of columns for eight rows (so it looks its two transforms up once), writes the
+// row-major pairs, and parks the values in LDS, from which the transposed tile leaves as 32- or 64-byte
+// pieces of a row of x_t.  Rows at and beyond B of the tile are written as zeros into x_t (ld_t is the batch
+// rounded up to 64).
+struct EncodeRowsArgs {
+    const float *x_raw; void *x; void *x_t; int64_t B, ld_t; int32_t F, ld, col_tiles;
+    int32_t n_stat, n_stats_per_layer, n_scal;
+    ab_enc enc_stat[AB_MAX_STATS];
+    ab_enc enc_scal[AB_MAX_SCALARS];
+    ab_enc enc_part, enc_cred;
+};
+
+template <typename T>
+__device__ __forceinline__ void encode_rows_block(const EncodeRowsArgs &a, unsigned id, unsigned char *smem)
+{
+    constexpr int LD_TILE = sizeof(T) == 2 ? 66 : 65;          // elements per tile row (one column of x, 64 rows)
+    T *tile = (T *)smem;
+    const int c0 = (int)(id % (unsigned)a.col_tiles) * 64;
+    const int64_t r0 = (int64_t)(id / (unsigned)a.col_tiles) * 64;
+    const int t = threadIdx.x, cp = t & 31, rr = t >> 5;
+    const int j0 = c0 + 2 * cp;
+    ab_enc e[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int j = j0 + q;
+        const ab_enc *src = j < a.n_stat ? &a.enc_stat[j % a.n_stats_per_layer]
+                          : j < a.n_stat + a.n_scal ? &a.enc_scal[j - a.n_stat]
+                          : j == a.F - 2 ? &a.enc_part : &a.enc_cred;
+        e[q] = *src;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int rl = rr + 8 * i;
+        const int64_t row = r0 + rl;
+        float v0 = 0.f, v1 = 0.f;
+        if (row < a.B) {
+            if (j0 < a.F) v0 = phi(a.x_raw[row * a.F + j0], e[0]);
+            if (j0 + 1 < a.F) v1 = phi(a.x_raw[row * a.F + j0 + 1], e[1]);
+            const int64_t o = row * a.ld + j0;
+            if constexpr (sizeof(T) == 2) ((uint32_t *)a.x)[o >> 1] = pack_bf16x2(v0, v1);
+            else ((f32x2 *)a.x)[o >> 1] = f32x2{v0, v1};
+        }
+        if constexpr (sizeof(T) == 2) {
+            const uint32_t pk = pack_bf16x2(v0, v1);
+            ((uint16_t *)tile)[(2 * cp) * LD_TILE + rl] = (uint16_t)(pk & 0xffffu);
+            ((uint16_t *)tile)[(2 * cp + 1) * LD_TILE + rl] = (uint16_t)(pk >> 16);
+        } else {
+            ((float *)tile)[(2 * cp) * LD_TILE + rl] = v0;
+            ((float *)tile)[(2 * cp + 1) * LD_TILE + rl] = v1;
+        }
+    }
+    __syncthreads();
+    if (!a.x_t) return;
+    const int col = t >> 2, rc = (t & 3) * 16;
+    const int64_t o = (int64_t)(c0 + col) * a.ld_t + r0 + rc;
+    if constexpr (sizeof(T) == 2) {
+        const uint32_t *src = (const uint32_t *)((const uint16_t *)tile + col * LD_TILE + rc);
+        i32x4 lo = {(int)src[0], (int)src[1], (int)src[2], (int)src[3]};
+        i32x4 hi = {(int)src[4], (int)src[5], (int)src[6], (int)src[7]};
+        i32x4 *dst = (i32x4 *)((uint16_t *)a.x_t + o);
+        dst[0] = lo; dst[1] = hi;
+    } else {
+        const float *src = (const float *)tile + col * LD_TILE + rc;
+        f32x4 *dst = (f32x4 *)((float *)a.x_t + o);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) dst[q] = f32x4{src[4 * q], src[4 * q + 1], src[4 * q + 2], src[4 * q + 3]};
+    }
+}
+
+// First launch of a step: the row transform and, next to it, the weight copies and the step counter.
+template <typename T>
+__global__ __launch_bounds__(256) void update_first_kernel(const EncodeRowsArgs e, const UpdPrepArgs p, unsigned enc_blocks)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char smem[64 * 66 * 4];
+    if (blockIdx.x < enc_blocks) encode_rows_block<T>(e, blockIdx.x, smem);
+    else update_prep_block<T>(p, blockIdx.x - enc_blocks);
+}
+
+// Several independent pieces of the backward pass in one launch (each launch of this chain costs about as
+// much as the piece itself): up to two matrix products on 64 x 64 tiles (delta of the layer below, split-K
+// weight gradient) and either the output unit's gradients or the hidden layers' bias gradients.
+enum { UJ_NONE = 0, UJ_GEMM_DRELU = 1, UJ_GEMM_SPLITK = 2, UJ_OUT_GRAD = 3, UJ_BIAS_GRAD = 4 };
+struct GroupArgs {
+    unsigned start[4];            // slot s owns work-groups [start[s], start[s + 1])
+    int kind[3];                  // slots 0 and 1: matrix products; slot 2: output-unit or bias gradients
+    GemmArgs gemm[2];
+    OutGradArgs og;
+    BiasGradArgs bg;
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void update_group_kernel(const GroupArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const unsigned b = blockIdx.x;
+    if (b < a.start[2]) {
+        const int s = b < a.start[1] ? 0 : 1;
+        if (a.kind[s] == UJ_GEMM_DRELU)
+            gemm_tn_tile<T, 1, 1, AMODE_LOAD, EPI_DRELU>(a.gemm[s], b - a.start[s], smem);
+        else
+            gemm_tn_tile<T, 1, 1, AMODE_LOAD, EPI_SPLITK>(a.gemm[s], b - a.start[s], smem);
+    } else if (a.kind[2] == UJ_OUT_GRAD) {
+        output_grad_block<T>(a.og, b - a.start[2], (float *)smem);
+    } else {
+        bias_grad_block<T>(a.bg, b - a.start[2], (float *)smem);
+    }
 }
 
 // Adam (Kingma & Ba, Algorithm 1; bias-corrected, epsilon outside the root) over every parameter
@@ -282,11 +390,16 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
     float *gw_out = (float *)(ws + p.off_gwout), *gb_out = (float *)(ws + p.off_gbout);
 
     const double esz = (double)elem_size(dt);
-    {
-        TraceScope ts("upd_encode_rows", (double)B * (p.F * 4.0 + 2.0 * p.Kp * esz), 1, st);
-        AB_HIP(launch_encode_rows(dt, d, x_raw, x, xt, B, Bp, p.F, p.Kp, st));
-    }
-    {
+    {   // launch 1: rows -> x, x^T; padded copy of W_1, transposed hidden weights, zero padding; step counter
+        EncodeRowsArgs e;
+        memset(&e, 0, sizeof(e));
+        e.x_raw = x_raw; e.x = x; e.x_t = xt; e.B = B; e.ld_t = Bp; e.F = p.F; e.ld = p.Kp; e.col_tiles = p.Kp / 64;
+        e.n_stat = d->n_layers * d->n_stats; e.n_stats_per_layer = d->n_stats; e.n_scal = d->n_scalars;
+        for (int i = 0; i < AB_MAX_STATS; ++i) e.enc_stat[i] = d->enc_stat[i];
+        for (int i = 0; i < AB_MAX_SCALARS; ++i) e.enc_scal[i] = d->enc_scalar[i];
+        e.enc_part = d->enc_partition; e.enc_cred = d->enc_credit;
+        const unsigned enc_blocks = (unsigned)(Bp / 64) * (unsigned)e.col_tiles;
+
         UpdPrepArgs a;
         memset(&a, 0, sizeof(a));
         int64_t start = 0;
@@ -300,8 +413,7 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
         for (int k = (k0 > 0 ? k0 + 1 : 1); k < D; ++k)      // W_k^T is the operand of the delta of layer k - 1
             add(JOB_TRANSPOSE, prm->W[k], ws + p.off_wt[k], p.H[k], p.H[k - 1], p.H[k - 1], p.H[k],
                 (int64_t)p.H[k] * p.H[k - 1]);
-        if (Bp > B) {
-            add(JOB_ZERO_COLS, nullptr, xt, p.Kp, (int)B, 0, (int)Bp, (int64_t)p.Kp * (Bp - B));
+        if (Bp > B) {                                        // (x^T gets its zero columns from the row transform)
             for (int k = 0; k < D; ++k) {
                 add(JOB_ZERO_COLS, nullptr, ws + p.off_ht[k], p.H[k], (int)B, 0, (int)Bp, (int64_t)p.H[k] * (Bp - B));
                 add(JOB_ZERO_COLS, nullptr, ws + p.off_dt[k], p.H[k], (int)B, 0, (int)Bp, (int64_t)p.H[k] * (Bp - B));
@@ -309,8 +421,9 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
         }
         a.total = start;
         a.step = prm->step; a.scal = scal; a.beta1 = beta1; a.beta2 = beta2;
-        TraceScope ts("upd_prep_weights", 2.0 * (double)start * esz, 1, st);
-        update_prep_kernel<T><<<(unsigned)((start + 255) / 256 > 0 ? (start + 255) / 256 : 1), 256, 0, st>>>(a);
+        const unsigned prep_blocks = (unsigned)((start + 255) / 256 > 0 ? (start + 255) / 256 : 1);
+        TraceScope ts("upd_encode_prep", (double)B * (p.F * 4.0 + 2.0 * p.Kp * esz) + 2.0 * (double)start * esz, 1, st);
+        update_first_kernel<T><<<enc_blocks + prep_blocks, 256, 0, st>>>(e, a, enc_blocks);
         AB_HIP(hipGetLastError());
     }
     // forward
@@ -330,55 +443,104 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
     }
     {
         OutFwdArgs a{ws + p.off_h[D - 1], prm->W[D], prm->b[D], target, yhat, dout, ws + p.off_d[D - 1], B, p.H[D - 1]};
-        {
-            TraceScope ts("upd_output_forward", (double)B * p.H[D - 1] * 3.0 * esz, 1, st);
-            output_forward_kernel<T><<<(unsigned)((B + 3) / 4), 256, 0, st>>>(a);
-            AB_HIP(hipGetLastError());
-        }
-        OutGradArgs b{ws + p.off_ht[D - 1], prm->W[D], dout, yhat, target, ws + p.off_dt[D - 1], gw_out, gb_out,
-                      loss_out, B, Bp, p.H[D - 1]};
-        TraceScope ts("upd_output_grad", (double)B * p.H[D - 1] * 2.0 * esz, 1, st);
-        output_grad_kernel<T><<<(unsigned)(p.H[D - 1] + 1), 256, 0, st>>>(b);
+        TraceScope ts("upd_output_forward", (double)B * p.H[D - 1] * 3.0 * esz, 1, st);
+        output_forward_kernel<T><<<(unsigned)((B + 3) / 4), 256, 0, st>>>(a);
         AB_HIP(hipGetLastError());
     }
-    // backward
-    for (int k = D - 1; k >= k0; --k) {
-        {   // dW_k = d_k^T h_{k-1}, split over the batch
-            GemmArgs g;
-            memset(&g, 0, sizeof(g));
-            g.A = ws + p.off_dt[k]; g.lda = Bp;
-            g.B = (k == 0) ? xt : (void *)(ws + p.off_ht[k - 1]); g.ldb = Bp;
-            g.M = p.H[k]; g.N = p.in_w[k]; g.K = (int32_t)Bp;
-            g.out = ws + p.off_gw[k]; g.ldo = p.in_w[k];
-            g.k_splits = p.splits[k]; g.split_stride = (int64_t)p.H[k] * p.in_w[k];
-            TraceScope ts("upd_gemm_dw", 2.0 * Bp * p.H[k] * p.in_w[k], 0, st);
-            AB_HIP(launch_gemm(dt, TILE_SMALL, AMODE_LOAD, EPI_SPLITK, g, st));
+
+    // backward: the chain delta_{D-1} -> delta_{D-2} -> ... sets the number of launches; everything else rides
+    // along.  Launch i holds the delta product of layer D-1-i (while that layer is above k0), the weight gradient
+    // of layer D-i (its delta^T was written one launch earlier) and, in launch 0, the output unit's gradients;
+    // the last launch holds the weight gradients still open and the bias gradients.
+    auto dw_args = [&](int k) {
+        GemmArgs g;
+        memset(&g, 0, sizeof(g));
+        g.A = ws + p.off_dt[k]; g.lda = Bp;
+        g.B = (k == 0) ? xt : (void *)(ws + p.off_ht[k - 1]); g.ldb = Bp;
+        g.M = p.H[k]; g.N = p.in_w[k]; g.K = (int32_t)Bp;
+        g.out = ws + p.off_gw[k]; g.ldo = p.in_w[k];
+        g.k_splits = p.splits[k]; g.split_stride = (int64_t)p.H[k] * p.in_w[k];
+        return g;
+    };
+    auto dx_args = [&](int k) {                 // d_{k-1} = (d_k W_k) * [h_{k-1} > 0]
+        GemmArgs g;
+        memset(&g, 0, sizeof(g));
+        g.A = ws + p.off_d[k]; g.lda = p.H[k];
+        g.B = ws + p.off_wt[k]; g.ldb = p.H[k];
+        g.M = B; g.N = p.H[k - 1]; g.K = p.H[k];
+        g.mask = ws + p.off_h[k - 1]; g.ldmask = p.H[k - 1];
+        g.out = ws + p.off_d[k - 1]; g.ldo = p.H[k - 1];
+        g.out_t = ws + p.off_dt[k - 1]; g.ldo_t = Bp;
+        return g;
+    };
+    struct Group {
+        GroupArgs a; int n_gemm; double flops, bytes;
+        Group() { memset(&a, 0, sizeof(a)); n_gemm = 0; flops = bytes = 0.0; }
+    };
+    // a product on 64 x 64 tiles joins the group; one that wants larger tiles (large batches) is launched alone
+    auto add_gemm = [&](Group &gr, int kind, GemmArgs g, int tile, const char *name) -> hipError_t {
+        const double fl = 2.0 * (double)g.M * g.N * g.K;
+        if (tile != TILE_SMALL) {
+            TraceScope ts(name, fl, 0, st);
+            return launch_gemm(dt, tile, AMODE_LOAD, kind == UJ_GEMM_DRELU ? EPI_DRELU : EPI_SPLITK, g, st);
         }
-        if (k > k0) {   // d_{k-1} = (d_k W_k) * [h_{k-1} > 0]
-            GemmArgs g;
-            memset(&g, 0, sizeof(g));
-            g.A = ws + p.off_d[k]; g.lda = p.H[k];
-            g.B = ws + p.off_wt[k]; g.ldb = p.H[k];
-            g.M = B; g.N = p.H[k - 1]; g.K = p.H[k];
-            g.mask = ws + p.off_h[k - 1]; g.ldmask = p.H[k - 1];
-            g.out = ws + p.off_d[k - 1]; g.ldo = p.H[k - 1];
-            g.out_t = ws + p.off_dt[k - 1]; g.ldo_t = Bp;
-            TraceScope ts("upd_gemm_dx", 2.0 * B * p.H[k - 1] * p.H[k], 0, st);
-            AB_HIP(launch_gemm(dt, update_tile(B, p.H[k - 1]), AMODE_LOAD, EPI_DRELU, g, st));
-        }
+        g.m_tiles = (g.M + 63) / 64;
+        g.n_tiles = g.N / 64;
+        int64_t blocks = (g.m_tiles + 7) / 8 * 8 * g.n_tiles;
+        if (kind == UJ_GEMM_SPLITK) blocks *= g.k_splits;
+        if (blocks > 0x3fffffffLL) return hipErrorInvalidValue;
+        const int s = gr.n_gemm++;
+        gr.a.kind[s] = kind; gr.a.gemm[s] = g;
+        gr.a.start[s + 1] = gr.a.start[s] + (unsigned)blocks;
+        gr.flops += fl;
+        return hipSuccess;
+    };
+    auto launch_group = [&](Group &gr, const char *name) -> hipError_t {
+        for (int s = gr.n_gemm; s < 2; ++s) gr.a.start[s + 1] = gr.a.start[s];
+        unsigned extra = 0;
+        if (gr.a.kind[2] == UJ_OUT_GRAD) extra = (unsigned)gr.a.og.H + 1;
+        else if (gr.a.kind[2] == UJ_BIAS_GRAD) extra = (unsigned)gr.a.bg.l[gr.a.bg.n - 1].start + (unsigned)gr.a.bg.l[gr.a.bg.n - 1].H;
+        gr.a.start[3] = gr.a.start[2] + extra;
+        if (gr.a.start[3] == 0) return hipSuccess;
+        TraceScope ts(name, gr.n_gemm ? gr.flops : gr.bytes, gr.n_gemm ? 0 : 1, st);
+        update_group_kernel<T><<<gr.a.start[3], 256, 2 * 128 * 128, st>>>(gr.a);
+        return hipGetLastError();
+    };
+
+    const int n_dx = D - 1 - k0 > 0 ? D - 1 - k0 : 0;       // delta products: layers D-1 ... k0+1
+    int next_dw = D - 1;                                    // weight gradients are taken in the order D-1, D-2, ...
+    {
+        Group gr;
+        if (n_dx > 0) AB_HIP(add_gemm(gr, UJ_GEMM_DRELU, dx_args(D - 1), update_tile(B, p.H[D - 2]), "upd_gemm_dx"));
+        gr.a.kind[2] = UJ_OUT_GRAD;
+        gr.a.og = OutGradArgs{ws + p.off_ht[D - 1], prm->W[D], dout, yhat, target, ws + p.off_dt[D - 1], gw_out, gb_out,
+                              loss_out, B, Bp, p.H[D - 1]};
+        gr.bytes = (double)B * p.H[D - 1] * 2.0 * esz;
+        AB_HIP(launch_group(gr, n_dx > 0 ? "upd_gemm_dx_outgrad" : "upd_output_grad"));
     }
-    if (k0 < D) {
-        BiasGradArgs a;
-        memset(&a, 0, sizeof(a));
-        a.n = D - k0; a.B = B; a.Bp = Bp;
-        int start = 0;
-        for (int k = k0; k < D; ++k) {
-            a.l[k - k0].dt = ws + p.off_dt[k]; a.l[k - k0].gb = (float *)(ws + p.off_gb[k]); a.l[k - k0].H = p.H[k];
-            a.l[k - k0].start = start; start += p.H[k];
+    for (int i = 1; i < n_dx; ++i) {
+        Group gr;
+        AB_HIP(add_gemm(gr, UJ_GEMM_DRELU, dx_args(D - 1 - i), update_tile(B, p.H[D - 2 - i]), "upd_gemm_dx"));
+        AB_HIP(add_gemm(gr, UJ_GEMM_SPLITK, dw_args(next_dw), TILE_SMALL, "upd_gemm_dw"));
+        --next_dw;
+        AB_HIP(launch_group(gr, "upd_gemm_dx_dw"));
+    }
+    while (next_dw >= k0) {                                 // at most two products are still open here
+        Group gr;
+        AB_HIP(add_gemm(gr, UJ_GEMM_SPLITK, dw_args(next_dw), TILE_SMALL, "upd_gemm_dw"));
+        --next_dw;
+        if (next_dw >= k0) { AB_HIP(add_gemm(gr, UJ_GEMM_SPLITK, dw_args(next_dw), TILE_SMALL, "upd_gemm_dw")); --next_dw; }
+        if (next_dw < k0) {
+            BiasGradArgs &a = gr.a.bg;
+            a.n = D - k0; a.B = B; a.Bp = Bp;
+            int start = 0;
+            for (int k = k0; k < D; ++k) {
+                a.l[k - k0].dt = ws + p.off_dt[k]; a.l[k - k0].gb = (float *)(ws + p.off_gb[k]); a.l[k - k0].H = p.H[k];
+                a.l[k - k0].start = start; start += p.H[k];
+            }
+            gr.a.kind[2] = UJ_BIAS_GRAD;
         }
-        TraceScope ts("upd_bias_grad", (double)start * Bp * esz, 1, st);
-        bias_grad_kernel<T><<<(unsigned)start, 256, 0, st>>>(a);
-        AB_HIP(hipGetLastError());
+        AB_HIP(launch_group(gr, "upd_gemm_dw_bias"));
     }
     {
         AdamArgs a;

@@ -110,6 +110,17 @@ def test_single_step_small(dtype, L, hidden, B):
     print("single-step worst gradient error: %.3g, %.3g (tol %g)" % (w1, w2, TOL[dtype]))
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_single_step_large_batch(dtype):
+    """A batch large enough that the delta products take 128 x 128 tiles and leave the grouped launches."""
+    B = 16384 + 37
+    u = wl.make_update("upd-large", N=B, batch=B, L=4, hidden=(256, 256), dtype=dtype, seed=77, P=8, Q=8)
+    tr = GpuTrainer(u, B)
+    st = orc.TrainState.fresh(u.W, u.b)
+    w = check_single_step(u, tr, st, np.arange(B), TOL[dtype])
+    print("large batch worst gradient error: %.3g (tol %g)" % (w, TOL[dtype]))
+
+
 def test_weight_update_exact_against_oracle_fp32():
     """fp32 path: away from tiny gradients the updated weights match to fp32 rounding."""
     u = wl.make_update("upd-w", N=128, batch=128, L=4, hidden=(64, 64), dtype="f32", seed=3, P=4, Q=4)
