@@ -111,8 +111,16 @@ static void orc_dense(const double *W, const double *b, int n_out, int n_in,
  *                      [input ; previous hidden state], gate blocks in the order input, forget,
  *                      candidate, output
  *  n_hidden, hidden[]: widths of the scorer's hidden layers (ReLU after each)
- *  W[n_hidden+1], b[]: scorer weights, W[k] is [out,in] row-major; the last one has out = 1 and
+ *  W[n_hidden+1], b[]: scorer weights, W[k] is [out,in] row-major; the last one has out = n_out and
  *                      is linear (V is a regression target)
+ *  n_out             : width of V (Table 1 gives V one entry per worker); 0 or 1 -> a single value.
+ *                      The speed a configuration is ranked by is the mean of the n_out predictions
+ *                      (Eq. 1 ranks configurations by V without saying how a vector is ordered: in
+ *                      synchronous data-parallel training the job advances at one rate, of which the
+ *                      per-worker entries are n_out measurements -- this build's reading)
+ *  loss_kind         : 0 -> mean over the minibatch of the squared error summed over the n_out entries;
+ *                      1 -> mean over the minibatch of the Euclidean norm of the error vector (Eq. 2 as
+ *                           printed: an unsquared L2 norm)
  *
  * Input vector order: [statistics block | scalars | phi(partition) | phi(credit)].
  */
@@ -128,7 +136,10 @@ typedef struct {
     int round_stored_bf16;   /* diagnostic, default 0: round to bf16 the values a bf16 pipeline keeps in
                                 memory (statistics block + scalars, tensor-encoder hidden layer, every
                                 hidden activation except the last) */
+    int n_out, loss_kind;
 } orc_model;
+
+static int orc_n_out(const orc_model *m) { return m->n_out > 1 ? m->n_out : 1; }
 
 static int orc_stats_width(const orc_model *m)
 {
@@ -258,9 +269,12 @@ static double orc_mlp_forward(const orc_model *m, const double *x, int F, double
         cur = out;
         n_in = m->hidden[k];
     }
-    double score;
-    orc_dense(m->W[m->n_hidden], m->b[m->n_hidden], 1, n_in, cur, &score, 0);
-    return score;
+    /* V has n_out entries; the configuration's score is their mean */
+    double v[64], score = 0.0;
+    const int no = orc_n_out(m);
+    orc_dense(m->W[m->n_hidden], m->b[m->n_hidden], no, n_in, cur, v, 0);
+    for (int w = 0; w < no; ++w) score += v[w];
+    return score / (double)no;
 }
 
 /*
@@ -270,10 +284,13 @@ static double orc_mlp_forward(const orc_model *m, const double *x, int F, double
  *   part [P], cred [Q]   raw partition sizes and credit multiples; candidate c = p*Q + q
  *   scores [S, P*Q]  predicted V
  */
-int orc_score_layers(const orc_model *m, const double *dyn, const double *scal, int64_t S,
-                     const int32_t *layers_of, const double *part, int P, const double *cred, int Q, double *scores)
+/* grid_per_scenario != 0: part is [S, P] and cred is [S, Q], every scenario brings its own candidate values
+ * (Table 1 lists S_p and S_c as inputs of the one job being tuned; a batch of jobs need not share a grid). */
+int orc_score_grids(const orc_model *m, const double *dyn, const double *scal, int64_t S,
+                    const int32_t *layers_of, const double *part, int P, const double *cred, int Q,
+                    int grid_per_scenario, double *scores)
 {
-    if (!m || !scores || S < 0 || P <= 0 || Q <= 0) return ORC_ERR_ARG;
+    if (!m || !scores || S < 0 || P <= 0 || Q <= 0 || orc_n_out(m) > 64) return ORC_ERR_ARG;
     if (layers_of && !m->tensor_encoder) return ORC_ERR_ARG;      /* the flat layout has one width */
     const int Fs = orc_stats_width(m), F = Fs + 2;
     int maxw = 1;
@@ -292,10 +309,12 @@ int orc_score_layers(const orc_model *m, const double *dyn, const double *scal, 
             for (int64_t s = 0; s < S; ++s) {
                 orc_scenario_features(m, dyn + (size_t)s * m->L * m->K, scal + (size_t)s * m->Ns,
                                       orc_layers_of(m, layers_of, s), x, tmp);
+                const double *part_s = grid_per_scenario ? part + (size_t)s * P : part;
+                const double *cred_s = grid_per_scenario ? cred + (size_t)s * Q : cred;
                 for (int p = 0; p < P; ++p)
                     for (int q = 0; q < Q; ++q) {
-                        x[Fs]     = orc_phi(part[p], m->cfg_kind[0], m->cfg_shift[0], m->cfg_scale[0]);
-                        x[Fs + 1] = orc_phi(cred[q], m->cfg_kind[1], m->cfg_shift[1], m->cfg_scale[1]);
+                        x[Fs]     = orc_phi(part_s[p], m->cfg_kind[0], m->cfg_shift[0], m->cfg_scale[0]);
+                        x[Fs + 1] = orc_phi(cred_s[q], m->cfg_kind[1], m->cfg_shift[1], m->cfg_scale[1]);
                         scores[(size_t)s * P * Q + (size_t)p * Q + q] = orc_mlp_forward(m, x, F, buf, maxw);
                     }
             }
@@ -303,6 +322,12 @@ int orc_score_layers(const orc_model *m, const double *dyn, const double *scal, 
         }
     }
     return err ? ORC_ERR_MEM : ORC_OK;
+}
+
+int orc_score_layers(const orc_model *m, const double *dyn, const double *scal, int64_t S,
+                     const int32_t *layers_of, const double *part, int P, const double *cred, int Q, double *scores)
+{
+    return orc_score_grids(m, dyn, scal, S, layers_of, part, P, cred, Q, 0, scores);
 }
 
 int orc_score(const orc_model *m, const double *dyn, const double *scal, int64_t S,
@@ -408,7 +433,7 @@ int orc_trigger(const float *scores, int64_t S, int C, int64_t row_stride, const
  * adapting"; loss per Eq. 2 read as the mean squared error over the minibatch).
  *
  *   x_raw [B, F]   raw rows: L*K statistics, Ns scalars, partition size, credit multiple
- *   target [B]     observed speed
+ *   target [B, n_out]  observed speed (one value per row, or one per worker)
  *   Wf[k]          weights used by forward/backward (pass the master weights, or a rounded copy
  *                  of them to reproduce a reduced-precision forward); bf[k] biases
  *   Wm,bm          master parameters updated in place by Adam; mW,vW,mb,vb its moments
@@ -416,8 +441,10 @@ int orc_trigger(const float *scores, int64_t S, int C, int64_t row_stride, const
  *   gW,gb          optional outputs: the gradients (may be NULL)
  *   do_adam        0 -> only loss and gradients
  *
- * Backward is exact back-propagation of loss = (1/B) sum_i (yhat_i - y_i)^2:
- *   d_out_i = 2 (yhat_i - y_i) / B ; dW = d^T h_prev ; db = sum_i d_i ; d_prev = (d W) * [pre > 0].
+ * Backward is exact back-propagation of the loss.  With e_i = yhat_i - y_i (a vector of n_out entries):
+ *   loss_kind 0:  loss = (1/B) sum_i |e_i|^2 ,  d_out_i = 2 e_i / B
+ *   loss_kind 1:  loss = (1/B) sum_i |e_i|   ,  d_out_i = e_i / (|e_i| B)   (zero where e_i = 0)
+ * then dW = d^T h_prev ; db = sum_i d_i ; d_prev = (d W) * [pre > 0].
  * Adam follows Kingma & Ba, Algorithm 1, with bias correction and epsilon outside the root.
  *
  * Transfer-learning form (Section 3.2 "Offline training online adapting" updates the offline-trained model by
@@ -442,7 +469,7 @@ int orc_update_tail(const orc_model *m, const double *x_raw, const double *targe
     if (nl > 15) return ORC_ERR_ARG;
     width[0] = F;
     for (int k = 0; k < m->n_hidden; ++k) width[k + 1] = m->hidden[k];
-    width[nl] = 1;
+    width[nl] = orc_n_out(m);
 
     /* activations h[k]: [B, width[k]] (h[0] = encoded input), deltas d[k]: [B, width[k]] */
     double **h = (double **)calloc((size_t)nl + 1, sizeof(double *));
@@ -485,11 +512,21 @@ int orc_update_tail(const orc_model *m, const double *x_raw, const double *targe
     /* loss and output delta */
     {
         double loss = 0.0;
+        const int no = width[nl];
         for (int64_t i = 0; i < B; ++i) {
-            double e = h[nl][i] - target[i];
-            loss += e * e;
-            d[nl][i] = 2.0 * e / (double)B;
-            if (yhat_out) yhat_out[i] = h[nl][i];
+            double sq = 0.0;
+            for (int w = 0; w < no; ++w) {
+                double e = h[nl][(size_t)i * no + w] - target[(size_t)i * no + w];
+                sq += e * e;
+                if (yhat_out) yhat_out[(size_t)i * no + w] = h[nl][(size_t)i * no + w];
+            }
+            const double nrm = sqrt(sq);
+            loss += m->loss_kind == 1 ? nrm : sq;
+            for (int w = 0; w < no; ++w) {
+                double e = h[nl][(size_t)i * no + w] - target[(size_t)i * no + w];
+                if (m->loss_kind == 1) d[nl][(size_t)i * no + w] = nrm > 0.0 ? e / (nrm * (double)B) : 0.0;
+                else d[nl][(size_t)i * no + w] = 2.0 * e / (double)B;
+            }
         }
         if (loss_out) *loss_out = loss / (double)B;
     }

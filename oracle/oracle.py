@@ -60,7 +60,8 @@ class _CModel(C.Structure):
                 ("tensor_encoder", C.c_int), ("te_h0", C.c_int), ("te_h1", C.c_int),
                 ("te_W", _dpp), ("te_b", _dpp),
                 ("n_hidden", C.c_int), ("hidden", _ip),
-                ("W", _dpp), ("b", _dpp), ("round_stored_bf16", C.c_int)]
+                ("W", _dpp), ("b", _dpp), ("round_stored_bf16", C.c_int),
+                ("n_out", C.c_int), ("loss_kind", C.c_int)]
 
 
 def _f64(a) -> np.ndarray:
@@ -91,6 +92,7 @@ class Model:
     te_kind: str = "mlp"                     # "mlp": shared per-layer MLP + mean; "lstm": embedding + 2-layer LSTM,
                                              #   te_W = [[E,K], [4H,E+H], [4H,2H]], te_b = [[E], [4H], [4H]]
     round_stored_bf16: bool = False          # diagnostic: mimic a bf16 pipeline's stored activations
+    loss_kind: str = "mse"                   # "mse": mean of the summed squared error; "l2norm": mean Euclidean norm (Eq. 2)
     _keep: list = field(default_factory=list, repr=False)
 
     @property
@@ -106,6 +108,11 @@ class Model:
     @property
     def F(self) -> int:
         return self.stats_width + 2
+
+    @property
+    def n_out(self) -> int:
+        """Entries of V (one per worker, Table 1); candidates are ranked by their mean."""
+        return int(np.asarray(self.W[-1]).shape[0])
 
     def _c(self) -> _CModel:
         keep = []
@@ -145,7 +152,7 @@ class Model:
         Ws = [_f64(w) for w in self.W]
         bs = [_f64(x) for x in self.b]
         assert len(Ws) == len(self.hidden) + 1 == len(bs)
-        widths = [self.F] + list(self.hidden) + [1]
+        widths = [self.F] + list(self.hidden) + [self.n_out]
         for k, w in enumerate(Ws):
             assert w.shape == (widths[k + 1], widths[k]), (k, w.shape, widths)
             assert bs[k].shape == (widths[k + 1],)
@@ -153,6 +160,8 @@ class Model:
         keep.extend([hid, pW, pb] + Ws + bs)
         m.W, m.b = C.cast(pW, _dpp), C.cast(pb, _dpp)
         m.round_stored_bf16 = 1 if self.round_stored_bf16 else 0
+        m.n_out = self.n_out
+        m.loss_kind = {"mse": 0, "l2norm": 1}[self.loss_kind]
         self._keep = keep
         return m
 
@@ -172,20 +181,25 @@ def _check(rc: int, what: str):
 
 def score(model: Model, dyn, scal, part, cred, layers_of=None) -> np.ndarray:
     """Predicted V for every scenario and candidate: returns float64 [S, P*Q], c = p*Q + q.
-    ``layers_of`` [S] (encoder models only): how many of the L padded layers each scenario really has."""
+    ``layers_of`` [S] (encoder models only): how many of the L padded layers each scenario really has.
+    ``part`` [P] and ``cred`` [Q] are shared by all scenarios; given as [S, P] and [S, Q] every scenario
+    has its own grid."""
     lib = _load()
     dyn, scal, part, cred = _f64(dyn), _f64(scal), _f64(part), _f64(cred)
     S = dyn.shape[0]
     assert dyn.shape == (S, model.L, model.K) and scal.shape == (S, model.Ns)
-    P, Q = part.shape[0], cred.shape[0]
+    per_scenario = part.ndim == 2
+    assert cred.ndim == part.ndim and (not per_scenario or (part.shape[0] == S and cred.shape[0] == S))
+    P, Q = part.shape[-1], cred.shape[-1]
     out = np.empty((S, P * Q), dtype=np.float64)
     cm = model._c()
     lo = None if layers_of is None else np.ascontiguousarray(layers_of, dtype=np.int32)
     assert lo is None or lo.shape == (S,)
-    _check(lib.orc_score_layers(C.byref(cm), dyn.ctypes.data_as(_dp), scal.ctypes.data_as(_dp),
-                                C.c_int64(S), None if lo is None else lo.ctypes.data_as(_ip),
-                                part.ctypes.data_as(_dp), C.c_int(P),
-                                cred.ctypes.data_as(_dp), C.c_int(Q), out.ctypes.data_as(_dp)), "score")
+    _check(lib.orc_score_grids(C.byref(cm), dyn.ctypes.data_as(_dp), scal.ctypes.data_as(_dp),
+                               C.c_int64(S), None if lo is None else lo.ctypes.data_as(_ip),
+                               part.ctypes.data_as(_dp), C.c_int(P),
+                               cred.ctypes.data_as(_dp), C.c_int(Q), C.c_int(1 if per_scenario else 0),
+                               out.ctypes.data_as(_dp)), "score")
     return out
 
 
@@ -284,7 +298,8 @@ class TrainState:
 
 def update(model: Model, state: TrainState, x_raw, target, lr=1e-3, beta1=0.9, beta2=0.999,
            eps=1e-8, do_adam=True, forward_weights=None, want_grads=True, first_trainable=0):
-    """One online-adaptation step (forward, MSE loss, back-propagation, Adam) on ``state``.
+    """One online-adaptation step (forward, loss of ``model.loss_kind``, back-propagation, Adam) on ``state``.
+    ``target`` is [B], or [B, n_out] when the output layer predicts one speed per worker.
 
     ``model`` supplies the feature layout and widths; its own W/b are ignored in favour of
     ``state``.  ``forward_weights`` optionally replaces the weights used by forward/backward
@@ -294,15 +309,17 @@ def update(model: Model, state: TrainState, x_raw, target, lr=1e-3, beta1=0.9, b
     lib = _load()
     x_raw, target = _f64(x_raw), _f64(target)
     B = x_raw.shape[0]
-    assert model.te_W is None and x_raw.shape == (B, model.F) and target.shape == (B,)
+    n_out = int(state.W[-1].shape[0])
+    assert model.te_W is None and x_raw.shape == (B, model.F)
+    assert target.shape == (B, n_out) or (n_out == 1 and target.shape == (B,))
     tmp = Model(model.L, model.K, model.stat_enc, model.scal_enc, model.part_enc, model.cred_enc,
-                model.hidden, state.W, state.b)
+                model.hidden, state.W, state.b, loss_kind=model.loss_kind)
     cm = tmp._c()
     Wf = [_f64(w) for w in (forward_weights if forward_weights is not None else state.W)]
     n = len(state.W)
     gW = [np.zeros_like(w) for w in state.W] if want_grads else [None] * n
     gb = [np.zeros_like(x) for x in state.b] if want_grads else [None] * n
-    yhat = np.empty(B, dtype=np.float64)
+    yhat = np.empty((B, n_out) if target.ndim == 2 else B, dtype=np.float64)
     loss = C.c_double(0.0)
     for lst in (state.W, state.b, state.mW, state.vW, state.mb, state.vb):
         for a in lst:

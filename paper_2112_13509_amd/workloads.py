@@ -288,10 +288,11 @@ class UpdateWorkload:
     W: List[np.ndarray]        # initial master weights, float32
     b: List[np.ndarray]
     x_raw: np.ndarray          # [N, F] float32: statistics, scalars, partition bytes, credit multiple
-    target: np.ndarray         # [N] float32 observed speed-up
+    target: np.ndarray         # [N] float32 observed speed-up, or [N, n_workers] (one observation per worker)
     batch: int
     seed: int
     noise_var: float
+    loss_kind: str = "mse"     # "mse", or "l2norm": Euclidean norm of the per-worker error vector (Eq. 2)
 
     @property
     def F(self) -> int:
@@ -308,14 +309,16 @@ class UpdateWorkload:
 
 def make_update(name="cfg4-online-update", N=65536, batch=4096, L=128, hidden=(512, 512, 512),
                 dtype="bf16", seed: Optional[int] = None, P=64, Q=64,
-                noise_var=0.01) -> UpdateWorkload:
+                noise_var=0.01, n_workers: int = 0, loss_kind: str = "mse") -> UpdateWorkload:
     """Pool of ``N`` (statistics + one configuration) rows with a synthetic observed speed-up
     ``1 + 0.3*tanh(u.z) + noise``: ``z`` are the standardised latents the raw values were drawn
-    from, ``u`` ~ N(0, 1/F) is a fixed probe, noise ~ N(0, noise_var)."""
+    from, ``u`` ~ N(0, 1/F) is a fixed probe, noise ~ N(0, noise_var).  With ``n_workers`` > 0 the
+    output layer has one unit per worker and the target one column per worker: the job's speed-up
+    plus an independent N(0, noise_var) term per worker (Table 1: V has one entry per worker)."""
     seed = BASE_SEED + 4 if seed is None else seed
     rng = np.random.default_rng(seed)
     F = L * 3 + 4 + 2
-    Ws, bs = _draw_mlp(rng, [F] + list(hidden) + [1], "f32")
+    Ws, bs = _draw_mlp(rng, [F] + list(hidden) + [max(1, n_workers)], "f32")
     bytes_lo, bytes_hi = 4.0 * KIB, 400.0 * MIB
     part_lo, part_hi, cred_lo, cred_hi = 16.0 * KIB, 64.0 * MIB, 1.0, 64.0
     dyn, lat_dyn = _draw_layer_stats(rng, N, L, bytes_lo, bytes_hi)
@@ -330,6 +333,8 @@ def make_update(name="cfg4-online-update", N=65536, batch=4096, L=128, hidden=(5
     x_raw = np.concatenate([dyn.reshape(N, L * 3), scal, part[pi][:, None], cred[qi][:, None]],
                            axis=1).astype(np.float32)
     stat_enc = [_time_enc(), _time_enc(), _log_uniform_enc(bytes_lo, bytes_hi)]
+    if n_workers > 0:
+        y = y[:, None] + math.sqrt(noise_var) * rng.standard_normal((N, n_workers))
     return UpdateWorkload(name, dtype, L, 3, stat_enc, _scalar_encs(1),
                           _log_uniform_enc(part_lo, part_hi), _log_uniform_enc(cred_lo, cred_hi),
-                          list(hidden), Ws, bs, x_raw, y.astype(np.float32), batch, seed, noise_var)
+                          list(hidden), Ws, bs, x_raw, y.astype(np.float32), batch, seed, noise_var, loss_kind)

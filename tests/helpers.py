@@ -9,7 +9,8 @@ def oracle_model(wl, W=None, b=None) -> orc.Model:
                      part_enc=wl.part_enc, cred_enc=wl.cred_enc, hidden=list(wl.hidden),
                      W=[np.asarray(w, dtype=np.float64) for w in (W if W is not None else wl.W)],
                      b=[np.asarray(x, dtype=np.float64) for x in (b if b is not None else wl.b)],
-                     te_W=getattr(wl, "te_W", None), te_b=getattr(wl, "te_b", None), te_kind=getattr(wl, "te_kind", "mlp"))
+                     te_W=getattr(wl, "te_W", None), te_b=getattr(wl, "te_b", None), te_kind=getattr(wl, "te_kind", "mlp"),
+                     loss_kind=getattr(wl, "loss_kind", "mse"))
 
 
 # ---- parity measures -----------------------------------------------------------------------
