@@ -55,6 +55,7 @@ extern "C" {
 #define AB_MAX_STATS   8    /* statistics per layer (K)                    */
 #define AB_MAX_SCALARS 16   /* scalar features per scenario                */
 #define AB_MAX_HIDDEN  8    /* hidden layers of the scorer                 */
+#define AB_MAX_OUTPUTS 16   /* entries of the predicted speed V            */
 #define AB_MAX_LAYERS  12   /* encoder (up to 3) + hidden (8) + output (1)                */
 
 typedef int32_t ab_status;
@@ -71,6 +72,7 @@ enum {
 
 enum { AB_F32 = 0, AB_BF16 = 1 };          /* arithmetic type of weights and activations; accumulation is fp32 */
 enum { AB_ENC_LINEAR = 0, AB_ENC_LOG = 1 };
+enum { AB_LOSS_MSE = 0, AB_LOSS_L2NORM = 1 };
 
 /* phi(x) = (g(x) - shift) * scale, g(x) = x (AB_ENC_LINEAR) or ln x (AB_ENC_LOG). */
 typedef struct { int32_t kind; float shift; float scale; } ab_enc;
@@ -94,6 +96,15 @@ typedef struct { int32_t kind; float shift; float scale; } ab_enc;
  *                          Both encoders need compute_dtype = AB_BF16
  *   compute_dtype          AB_F32: fp32 weights, activations and fp32 MFMA; AB_BF16: bf16 weights and
  *                          activations with fp32 accumulation
+ *   n_outputs              entries of the predicted speed V (Table 1 gives V one entry per worker); 0 or 1:
+ *                          a single value; at most AB_MAX_OUTPUTS.  A candidate's score is the mean of the
+ *                          n_outputs predictions (Eq. 1 ranks candidates by V; for a vector the mean is this
+ *                          library's reading: a synchronous job advances at one rate, which the per-worker
+ *                          entries measure n_outputs times)
+ *   loss_kind              loss of ab_online_update: AB_LOSS_MSE: mean over the minibatch of the squared
+ *                          error summed over the n_outputs entries; AB_LOSS_L2NORM: mean over the minibatch
+ *                          of the Euclidean norm of the error vector (Eq. 2 as printed; a row predicted
+ *                          exactly contributes no gradient)
  * The scorer's input width is F = (L*K or enc_hidden[1]) + n_scalars + 2.
  */
 typedef struct {
@@ -106,6 +117,8 @@ typedef struct {
     int32_t tensor_encoder;
     int32_t enc_hidden[2];
     int32_t compute_dtype;
+    int32_t n_outputs;
+    int32_t loss_kind;
 } ab_model_desc;
 
 /*
@@ -114,7 +127,7 @@ typedef struct {
  * embedding [E, K], then per LSTM layer one matrix [4H, n_in + H] = [W_ih | W_hh] acting on
  * [input ; previous hidden state] with gate blocks in the order input, forget, candidate, output and one
  * bias [4H], n_in = E for the first and H for the second layer), then the scorer's hidden layers, then
- * the output layer (1 x last hidden width).
+ * the output layer (n_outputs x last hidden width).
  *   W[k]         [out, in] row-major in compute_dtype (bf16 = upper 16 bits of an fp32), 16-byte aligned
  *   b[k]         [out] fp32
  * Only ab_online_update uses the rest (flat model, so index k counts scorer layers from 0):
@@ -199,11 +212,11 @@ ab_status ab_trigger(const float *scores, int64_t S, int32_t C, int64_t row_stri
 
 /*
  * One online-adaptation step of the flat model (tensor_encoder = 0) on a minibatch of B observed rows:
- * forward, loss = mean_i (V_hat_i - V_i)^2 (Eq. 2 as mean squared error), exact back-propagation, Adam
- * with bias correction (epsilon outside the square root).
+ * forward, the loss of desc->loss_kind (mean_i |V_hat_i - V_i|^2, or Eq. 2's unsquared norm mean_i |V_hat_i - V_i|),
+ * exact back-propagation, Adam with bias correction (epsilon outside the square root).
  *   x_raw     DEVICE [B, F] fp32 raw rows: L*K statistics, n_scalars scalars, partition bytes, credit
  *             multiple (transformed on the device with the description's constants)
- *   target    DEVICE [B] fp32 observed speed V
+ *   target    DEVICE [B, n_outputs] fp32 observed speed V (one value per row, or one per worker)
  *   loss_out  DEVICE one fp32 (loss before the step), or NULL
  * Mutates W_master, b, the Adam moments, *step (incremented by one) and refreshes W[k] (the
  * compute_dtype copy used by scoring).  With AB_BF16 the GEMMs run on bf16 copies of the masters.

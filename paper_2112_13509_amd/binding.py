@@ -30,7 +30,7 @@ class ab_model_desc(C.Structure):
                 ("enc_partition", ab_enc), ("enc_credit", ab_enc),
                 ("n_hidden", C.c_int32), ("hidden", C.c_int32 * AB_MAX_HIDDEN),
                 ("tensor_encoder", C.c_int32), ("enc_hidden", C.c_int32 * 2),
-                ("compute_dtype", C.c_int32)]
+                ("compute_dtype", C.c_int32), ("n_outputs", C.c_int32), ("loss_kind", C.c_int32)]
 
 
 _vp = C.c_void_p
@@ -170,7 +170,7 @@ def ab_status_string(status: int) -> str:
 def make_desc(L: int, K: int, stat_enc: Sequence[Tuple[int, float, float]],
               scal_enc: Sequence[Tuple[int, float, float]], part_enc, cred_enc,
               hidden: Sequence[int], dtype: str, te_hidden: Optional[Sequence[int]] = None,
-              te_kind: str = "mlp") -> ab_model_desc:
+              te_kind: str = "mlp", n_outputs: int = 1, loss_kind: str = "mse") -> ab_model_desc:
     d = ab_model_desc()
     d.n_layers, d.n_stats, d.n_scalars = int(L), int(K), len(scal_enc)
     if K > AB_MAX_STATS or len(scal_enc) > AB_MAX_SCALARS or len(hidden) > AB_MAX_HIDDEN:
@@ -188,12 +188,15 @@ def make_desc(L: int, K: int, stat_enc: Sequence[Tuple[int, float, float]],
     if te_hidden:
         d.enc_hidden[0], d.enc_hidden[1] = int(te_hidden[0]), int(te_hidden[1])
     d.compute_dtype = {"f32": AB_F32, "bf16": AB_BF16}[dtype]
+    d.n_outputs = int(n_outputs)
+    d.loss_kind = {"mse": 0, "l2norm": 1}[loss_kind]
     return d
 
 
 def desc_from_workload(wl) -> ab_model_desc:
     return make_desc(wl.L, wl.K, wl.stat_enc, wl.scal_enc, wl.part_enc, wl.cred_enc, wl.hidden,
-                     wl.dtype, getattr(wl, "te_hidden", None), getattr(wl, "te_kind", "mlp"))
+                     wl.dtype, getattr(wl, "te_hidden", None), getattr(wl, "te_kind", "mlp"),
+                     n_outputs=int(wl.W[-1].shape[0]), loss_kind=getattr(wl, "loss_kind", "mse"))
 
 
 def _ptr(t: Optional[torch.Tensor], dtype, what: str) -> Optional[int]:
@@ -352,8 +355,8 @@ def ab_online_update(desc: ab_model_desc, params: Params, x_raw: torch.Tensor, t
     lib = load()
     B = int(x_raw.shape[0])
     F = desc.n_layers * desc.n_stats + desc.n_scalars + 2
-    if x_raw.numel() != B * F or target.numel() != B:
-        raise ValueError("x_raw must be [B, %d] and target [B]" % F)
+    if x_raw.numel() != B * F or target.numel() != B * max(1, int(desc.n_outputs)):
+        raise ValueError("x_raw must be [B, %d] and target [B, n_outputs]" % F)
     if params.step is None:
         raise ValueError("params were not created with trainable=True")
     rc = lib.ab_online_update(C.byref(desc), C.byref(params.c), _ptr(x_raw, torch.float32, "x_raw"),
@@ -374,8 +377,8 @@ def ab_online_update_tail(desc: ab_model_desc, params: Params, x_raw: torch.Tens
     lib = load()
     B = int(x_raw.shape[0])
     F = desc.n_layers * desc.n_stats + desc.n_scalars + 2
-    if x_raw.numel() != B * F or target.numel() != B:
-        raise ValueError("x_raw must be [B, %d] and target [B]" % F)
+    if x_raw.numel() != B * F or target.numel() != B * max(1, int(desc.n_outputs)):
+        raise ValueError("x_raw must be [B, %d] and target [B, n_outputs]" % F)
     if params.step is None:
         raise ValueError("params were not created with trainable=True")
     rc = lib.ab_online_update_tail(C.byref(desc), C.byref(params.c), _ptr(x_raw, torch.float32, "x_raw"),

@@ -36,6 +36,8 @@ static ab_status check_desc(const ab_model_desc *d)
         if (d->enc_stat[k].kind != AB_ENC_LINEAR && d->enc_stat[k].kind != AB_ENC_LOG) return AB_ERR_SHAPE;
     for (int k = 0; k < d->n_scalars; ++k)
         if (d->enc_scalar[k].kind != AB_ENC_LINEAR && d->enc_scalar[k].kind != AB_ENC_LOG) return AB_ERR_SHAPE;
+    if (d->n_outputs < 0 || d->n_outputs > AB_MAX_OUTPUTS) return AB_ERR_SHAPE;
+    if (d->loss_kind != AB_LOSS_MSE && d->loss_kind != AB_LOSS_L2NORM) return AB_ERR_SHAPE;
     if (d->tensor_encoder < 0 || d->tensor_encoder > 2) return AB_ERR_SHAPE;
     if (d->tensor_encoder) {
         if (d->enc_hidden[0] <= 0 || d->enc_hidden[1] <= 0) return AB_ERR_SHAPE;
@@ -99,7 +101,7 @@ static ab_status plan_scoring(const ab_model_desc *d, int64_t S, int32_t C, Scor
     p->off_aterm = take((size_t)(S > 0 ? S : 1) * p->H[0] * 4);
     p->off_bterm = take((size_t)C * p->H[0] * 4);
     p->off_cfgv = take(((size_t)2 * p->H[0] + 2 * (size_t)C) * 4);
-    p->off_wout = take((size_t)p->H[p->D - 1] * 4);
+    p->off_wout = take((size_t)(p->H[p->D - 1] + 1) * 4);     // folded output weights, then the folded bias
     p->off_partial = take((size_t)p->chunk_rows * p->nt_last * 4);
     p->off_act0 = p->off_act1 = 0;
     if (p->D >= 3) p->off_act0 = take((size_t)p->chunk_rows * hmax * es);
@@ -127,7 +129,7 @@ using namespace ab;
 
 extern "C" {
 
-int32_t ab_version(void) { return 102; }
+int32_t ab_version(void) { return 103; }
 
 void ab_set_trace(ab_trace_fn fn, void *user) { g_trace_fn = fn; g_trace_user = user; }
 
@@ -244,7 +246,8 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
     {
         TraceScope ts("prep_layer1", (double)p.H[0] * (p.F * es + p.Kp * es) + (double)C * p.H[0] * 4.0, 1, st);
         AB_HIP(launch_prep_layer1(dt, desc, params->W[p.base], params->b[p.base], p.F, p.Fs, p.H[0], p.Kp, w1s,
-                                  grid, b_term, cfg_vec, params->W[p.base + p.D], p.H[p.D - 1], w_out_f, st));
+                                  grid, b_term, cfg_vec, params->W[p.base + p.D], params->b[p.base + p.D],
+                                  p.H[p.D - 1], w_out_f, st));
     }
     // 3. scenario term A[s] = x_s W1_s^T + b1 (fp32 out)
     {
@@ -294,7 +297,7 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
             }
         }
         TraceScope ts("finish_select", (double)rows * (nt * 4.0 + (scores ? 4.0 : 0.0)) + ns * 8.0, 1, st);
-        AB_HIP(launch_finish_select(partial, nt, C, params->b[p.base + p.D],
+        AB_HIP(launch_finish_select(partial, nt, C, w_out_f + p.H[p.D - 1],
                                     scores ? scores + s0 * C : nullptr, C,
                                     best_idx ? best_idx + s0 : nullptr,
                                     best_score ? best_score + s0 : nullptr, ns, C, st));

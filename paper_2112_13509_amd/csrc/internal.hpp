@@ -41,7 +41,7 @@ hipError_t launch_encode_stats(int dtype, const ab_model_desc *d, const float *d
                                void *xs, int64_t S, int ld, int col0, int with_stats, hipStream_t st);
 hipError_t launch_prep_layer1(int dtype, const ab_model_desc *d, const void *W1, const float *b1, int F, int Fs,
                               int H1, int ld, void *w1s, const ab_grid *grid, float *b_term, float *cfg_vec,
-                              const void *Wout, int H_last, float *w_out_f, hipStream_t st);
+                              const void *Wout, const float *b_out, int H_last, float *w_out_f, hipStream_t st);
 hipError_t launch_finish_select(const float *partial, int nt, int64_t row_stride, const float *b_out,
                                 float *scores, int64_t score_stride, int32_t *best_idx, float *best_score,
                                 int64_t S, int C, hipStream_t st);

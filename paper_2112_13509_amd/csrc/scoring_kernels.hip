@@ -147,7 +147,7 @@ struct PrepArgs {
     ab_enc enc_part, enc_cred;
     float *b_term;                               // [P*Q, H1]
     float *wp_f, *wc_f, *xp_f, *xc_f;            // [H1], [H1], [P*Q], [P*Q]
-    const void *Wout; int32_t H_last; float *w_out_f;
+    const void *Wout; const float *b_out; int32_t H_last, n_out; float *w_out_f;   // w_out_f[H_last + 1]
 };
 
 template <typename T>
@@ -180,7 +180,15 @@ __global__ __launch_bounds__(256) void prep_layer1_kernel(const PrepArgs a)
         a.b_term[e] = wp * xp + wc * xc;
     } else if (gid < n_pack + n_bt + a.H_last) {
         const int h = (int)(gid - n_pack - n_bt);
-        a.w_out_f[h] = load_as_f32<T>(a.Wout, h);
+        // the output layer folded to one unit: the mean over its n_out rows (a candidate's score is the mean
+        // of the per-worker predictions); the folded bias follows the weights
+        float acc = 0.f, bacc = 0.f;
+        for (int w = 0; w < a.n_out; ++w) acc += load_as_f32<T>(a.Wout, (int64_t)w * a.H_last + h);
+        a.w_out_f[h] = acc / (float)a.n_out;
+        if (h == 0) {
+            for (int w = 0; w < a.n_out; ++w) bacc += a.b_out[w];
+            a.w_out_f[a.H_last] = bacc / (float)a.n_out;
+        }
     } else if (gid < n_pack + n_bt + a.H_last + a.H1) {
         const int h = (int)(gid - n_pack - n_bt - a.H_last);
         a.wp_f[h] = load_as_f32<T>(a.W1, (int64_t)h * a.F + a.Fs);
@@ -735,7 +743,7 @@ hipError_t launch_encode_stats(int dtype, const ab_model_desc *d, const float *d
 
 hipError_t launch_prep_layer1(int dtype, const ab_model_desc *d, const void *W1, const float *b1, int F, int Fs,
                               int H1, int ld, void *w1s, const ab_grid *grid, float *b_term, float *cfg_vec,
-                              const void *Wout, int H_last, float *w_out_f, hipStream_t st)
+                              const void *Wout, const float *b_out, int H_last, float *w_out_f, hipStream_t st)
 {
     PrepArgs a;
     a.W1 = W1; a.F = F; a.Fs = Fs; a.H1 = H1; a.ld = ld; a.w1s = w1s; a.b1 = b1;
@@ -743,7 +751,7 @@ hipError_t launch_prep_layer1(int dtype, const ab_model_desc *d, const void *W1,
     a.enc_part = d->enc_partition; a.enc_cred = d->enc_credit; a.b_term = b_term;
     const int Cn = grid->P * grid->Q;
     a.wp_f = cfg_vec; a.wc_f = cfg_vec + H1; a.xp_f = cfg_vec + 2 * H1; a.xc_f = cfg_vec + 2 * H1 + Cn;
-    a.Wout = Wout; a.H_last = H_last; a.w_out_f = w_out_f;
+    a.Wout = Wout; a.b_out = b_out; a.H_last = H_last; a.n_out = d->n_outputs > 1 ? d->n_outputs : 1; a.w_out_f = w_out_f;
     const int64_t n = (int64_t)H1 * ld + (int64_t)Cn * H1 + H_last + H1 + Cn;
     if (dtype == AB_BF16) prep_layer1_kernel<bf16_t><<<blocks_for(n), 256, 0, st>>>(a);
     else prep_layer1_kernel<float><<<blocks_for(n), 256, 0, st>>>(a);
@@ -778,7 +786,7 @@ hipError_t launch_finish_select(const float *partial, int nt, int64_t row_stride
 
 bool score_tiny_supported(const ab_model_desc *d, int64_t S, int32_t C)
 {
-    if (d->tensor_encoder || d->n_hidden < 1) return false;
+    if (d->tensor_encoder || d->n_hidden < 1 || d->n_outputs > 1) return false;
     for (int k = 0; k < d->n_hidden; ++k) if (d->hidden[k] > 128) return false;     // (multiples of 64 already)
     const int64_t Fs = (int64_t)d->n_layers * d->n_stats + d->n_scalars;
     return Fs <= 2048 && C <= 256 && S >= 1 && S * C <= 16384;

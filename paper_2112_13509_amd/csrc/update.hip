@@ -18,7 +18,7 @@ static inline int round_up(int x, int a) { return (x + a - 1) / a * a; }
 #define AB_HIP(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return AB_ERR_DEVICE; } while (0)
 
 struct UpdatePlan {
-    int dtype, F, Kp, D;
+    int dtype, F, Kp, D, n_out;
     int H[AB_MAX_HIDDEN];
     int64_t B, Bp;
     int in_w[AB_MAX_HIDDEN + 1];        // padded input width of layer k (Kp for k = 0)
@@ -42,6 +42,7 @@ static void plan_update(const ab_model_desc *d, int64_t B, UpdatePlan *p)
     p->F = d->n_layers * d->n_stats + d->n_scalars + 2;
     p->Kp = round_up(p->F, 64);
     p->D = d->n_hidden;
+    p->n_out = d->n_outputs > 1 ? d->n_outputs : 1;
     p->B = B;
     p->Bp = (B + 63) / 64 * 64;
     const size_t es = elem_size(p->dtype);
@@ -50,8 +51,8 @@ static void plan_update(const ab_model_desc *d, int64_t B, UpdatePlan *p)
     p->off_scal = take(64);
     p->off_x = take((size_t)B * p->Kp * es);
     p->off_xt = take((size_t)p->Kp * p->Bp * es);
-    p->off_yhat = take((size_t)B * 4);
-    p->off_dout = take((size_t)p->Bp * 4);
+    p->off_yhat = take((size_t)B * p->n_out * 4);
+    p->off_dout = take((size_t)p->Bp * p->n_out * 4);
     for (int k = 0; k < p->D; ++k) {
         p->H[k] = d->hidden[k];
         p->in_w[k] = (k == 0) ? p->Kp : d->hidden[k - 1];
@@ -70,8 +71,8 @@ static void plan_update(const ab_model_desc *d, int64_t B, UpdatePlan *p)
         p->off_gw[k] = take((size_t)s * p->H[k] * p->in_w[k] * 4);
         p->off_gb[k] = take((size_t)p->H[k] * 4);
     }
-    p->off_gwout = take((size_t)p->H[p->D - 1] * 4);
-    p->off_gbout = take(64);
+    p->off_gwout = take((size_t)p->n_out * p->H[p->D - 1] * 4);
+    p->off_gbout = take((size_t)AB_MAX_OUTPUTS * 4);
     p->total = off;
 }
 
@@ -142,11 +143,12 @@ __device__ __forceinline__ void update_prep_block(const UpdPrepArgs &a, unsigned
     }
 }
 
-// Output unit forward and its delta: one wavefront per sample.
-//   yhat = w_out . h + b_out ; dout = 2 (yhat - y) / B ; d[r, :] = dout * w_out * [h > 0]
+// Output layer forward and its delta: one wavefront per sample.  With e = yhat - y (n_out entries):
+//   squared loss:  dout = 2 e / B ;   norm loss (Eq. 2):  dout = e / (|e| B), zero where e = 0
+//   d[r, :] = (sum_w dout[w] W_out[w, :]) * [h > 0]
 struct OutFwdArgs {
     const void *h; const void *w_out; const float *b_out; const float *target;
-    float *yhat; float *dout; void *d; int64_t B; int32_t H;
+    float *yhat; float *dout; void *d; int64_t B; int32_t H, n_out, loss_kind;
 };
 template <typename T>
 __global__ __launch_bounds__(256) void output_forward_kernel(const OutFwdArgs a)
@@ -154,25 +156,46 @@ __global__ __launch_bounds__(256) void output_forward_kernel(const OutFwdArgs a)
     const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= a.B) return;
     const int lane = threadIdx.x & 63;
-    float acc = 0.f;
-    for (int c = lane; c < a.H; c += 64) acc += ld_f32<T>(a.h, r * a.H + c) * ld_f32<T>(a.w_out, c);
+    float dv[AB_MAX_OUTPUTS];
+    float sq = 0.f;
 #pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
-    const float yh = acc + a.b_out[0];
-    const float dout = 2.f * (yh - a.target[r]) / (float)a.B;
-    if (lane == 0) { a.yhat[r] = yh; a.dout[r] = dout; }
+    for (int w = 0; w < AB_MAX_OUTPUTS; ++w) {
+        dv[w] = 0.f;
+        if (w < a.n_out) {
+            float acc = 0.f;
+            for (int c = lane; c < a.H; c += 64)
+                acc += ld_f32<T>(a.h, r * a.H + c) * ld_f32<T>(a.w_out, (int64_t)w * a.H + c);
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+            const float yh = acc + a.b_out[w];
+            if (lane == 0) a.yhat[r * a.n_out + w] = yh;
+            dv[w] = yh - a.target[r * a.n_out + w];
+            sq += dv[w] * dv[w];
+        }
+    }
+    const float nrm = sqrtf(sq);
+    const float f = a.loss_kind == AB_LOSS_L2NORM ? (nrm > 0.f ? 1.f / (nrm * (float)a.B) : 0.f) : 2.f / (float)a.B;
+#pragma unroll
+    for (int w = 0; w < AB_MAX_OUTPUTS; ++w) {
+        dv[w] *= f;
+        if (w < a.n_out && lane == 0) a.dout[r * a.n_out + w] = dv[w];
+    }
     for (int c = lane; c < a.H; c += 64) {
         const float hv = ld_f32<T>(a.h, r * a.H + c);
-        st_T<T>(a.d, r * a.H + c, hv > 0.f ? dout * ld_f32<T>(a.w_out, c) : 0.f);
+        float acc = 0.f;
+#pragma unroll
+        for (int w = 0; w < AB_MAX_OUTPUTS; ++w)
+            if (w < a.n_out) acc += dv[w] * ld_f32<T>(a.w_out, (int64_t)w * a.H + c);
+        st_T<T>(a.d, r * a.H + c, hv > 0.f ? acc : 0.f);
     }
 }
 
-// Output unit gradients: block c < H handles column c of the last hidden layer:
-//   gw_out[c] = sum_r dout[r] h[r, c]  and  d^T[c, r] = dout[r] w_out[c] [h^T[c, r] > 0];
-// block H reduces the bias gradient sum_r dout[r] and the loss mean_r (yhat - y)^2.
+// Output layer gradients: block c < H handles column c of the last hidden layer:
+//   gw_out[w, c] = sum_r dout[r, w] h[r, c]  and  d^T[c, r] = (sum_w dout[r, w] W_out[w, c]) [h^T[c, r] > 0];
+// block H reduces the bias gradients sum_r dout[r, w] and the loss.
 struct OutGradArgs {
     const void *ht; const void *w_out; const float *dout; const float *yhat; const float *target;
-    void *dt; float *gw_out; float *gb_out; float *loss_out; int64_t B, Bp; int32_t H;
+    void *dt; float *gw_out; float *gb_out; float *loss_out; int64_t B, Bp; int32_t H, n_out, loss_kind;
 };
 __device__ __forceinline__ float block_sum_256(float v, float *sh)      // sh: four floats of LDS
 {
@@ -189,28 +212,49 @@ __device__ __forceinline__ void output_grad_block(const OutGradArgs &a, unsigned
 {
     const int c = (int)id;
     if (c < a.H) {
-        const float w = ld_f32<T>(a.w_out, c);
-        float acc = 0.f;
+        float wv[AB_MAX_OUTPUTS], acc[AB_MAX_OUTPUTS];
+#pragma unroll
+        for (int w = 0; w < AB_MAX_OUTPUTS; ++w) {
+            wv[w] = w < a.n_out ? ld_f32<T>(a.w_out, (int64_t)w * a.H + c) : 0.f;
+            acc[w] = 0.f;
+        }
         for (int64_t r = threadIdx.x; r < a.B; r += 256) {
             const float hv = ld_f32<T>(a.ht, (int64_t)c * a.Bp + r);
-            const float dv = a.dout[r];
-            acc += dv * hv;
-            st_T<T>(a.dt, (int64_t)c * a.Bp + r, hv > 0.f ? dv * w : 0.f);
+            float dsum = 0.f;
+#pragma unroll
+            for (int w = 0; w < AB_MAX_OUTPUTS; ++w) {
+                if (w < a.n_out) {
+                    const float dv = a.dout[r * a.n_out + w];
+                    acc[w] += dv * hv;
+                    dsum += dv * wv[w];
+                }
+            }
+            st_T<T>(a.dt, (int64_t)c * a.Bp + r, hv > 0.f ? dsum : 0.f);
         }
-        const float s = block_sum_256(acc, sh);
-        if (threadIdx.x == 0) a.gw_out[c] = s;
+#pragma unroll
+        for (int w = 0; w < AB_MAX_OUTPUTS; ++w) {
+            if (w < a.n_out) {
+                const float s = block_sum_256(acc[w], sh);
+                if (threadIdx.x == 0) a.gw_out[(int64_t)w * a.H + c] = s;
+            }
+        }
     } else {
-        float sd = 0.f, sl = 0.f;
+        float sl = 0.f;
         for (int64_t r = threadIdx.x; r < a.B; r += 256) {
-            sd += a.dout[r];
-            const float e = a.yhat[r] - a.target[r];
-            sl += e * e;
+            float sq = 0.f;
+            for (int w = 0; w < a.n_out; ++w) {
+                const float e = a.yhat[r * a.n_out + w] - a.target[r * a.n_out + w];
+                sq += e * e;
+            }
+            sl += a.loss_kind == AB_LOSS_L2NORM ? sqrtf(sq) : sq;
         }
-        const float s1 = block_sum_256(sd, sh);
         const float s2 = block_sum_256(sl, sh);
-        if (threadIdx.x == 0) {
-            a.gb_out[0] = s1;
-            if (a.loss_out) a.loss_out[0] = s2 / (float)a.B;
+        if (threadIdx.x == 0 && a.loss_out) a.loss_out[0] = s2 / (float)a.B;
+        for (int w = 0; w < a.n_out; ++w) {
+            float sd = 0.f;
+            for (int64_t r = threadIdx.x; r < a.B; r += 256) sd += a.dout[r * a.n_out + w];
+            const float s1 = block_sum_256(sd, sh);
+            if (threadIdx.x == 0) a.gb_out[w] = s1;
         }
     }
 }
@@ -442,7 +486,8 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
         AB_HIP(launch_gemm(dt, update_tile(B, p.H[k]), AMODE_LOAD, EPI_STORE, g, st));
     }
     {
-        OutFwdArgs a{ws + p.off_h[D - 1], prm->W[D], prm->b[D], target, yhat, dout, ws + p.off_d[D - 1], B, p.H[D - 1]};
+        OutFwdArgs a{ws + p.off_h[D - 1], prm->W[D], prm->b[D], target, yhat, dout, ws + p.off_d[D - 1], B, p.H[D - 1],
+                     p.n_out, d->loss_kind};
         TraceScope ts("upd_output_forward", (double)B * p.H[D - 1] * 3.0 * esz, 1, st);
         output_forward_kernel<T><<<(unsigned)((B + 3) / 4), 256, 0, st>>>(a);
         AB_HIP(hipGetLastError());
@@ -514,7 +559,7 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
         if (n_dx > 0) AB_HIP(add_gemm(gr, UJ_GEMM_DRELU, dx_args(D - 1), update_tile(B, p.H[D - 2]), "upd_gemm_dx"));
         gr.a.kind[2] = UJ_OUT_GRAD;
         gr.a.og = OutGradArgs{ws + p.off_ht[D - 1], prm->W[D], dout, yhat, target, ws + p.off_dt[D - 1], gw_out, gb_out,
-                              loss_out, B, Bp, p.H[D - 1]};
+                              loss_out, B, Bp, p.H[D - 1], p.n_out, d->loss_kind};
         gr.bytes = (double)B * p.H[D - 1] * 2.0 * esz;
         AB_HIP(launch_group(gr, n_dx > 0 ? "upd_gemm_dx_outgrad" : "upd_output_grad"));
     }
@@ -558,8 +603,8 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
                 p.H[k], cols, p.in_w[k], p.splits[k], (int64_t)p.H[k] * p.in_w[k]);
             add(prm->b[k], prm->adam_mb[k], prm->adam_vb[k], nullptr, (float *)(ws + p.off_gb[k]), 1, p.H[k], p.H[k], 1, 0);
         }
-        add(prm->W_master[D], prm->adam_mW[D], prm->adam_vW[D], (void *)prm->W[D], gw_out, 1, p.H[D - 1], p.H[D - 1], 1, 0);
-        add(prm->b[D], prm->adam_mb[D], prm->adam_vb[D], nullptr, gb_out, 1, 1, 1, 1, 0);
+        add(prm->W_master[D], prm->adam_mW[D], prm->adam_vW[D], (void *)prm->W[D], gw_out, p.n_out, p.H[D - 1], p.H[D - 1], 1, 0);
+        add(prm->b[D], prm->adam_mb[D], prm->adam_vb[D], nullptr, gb_out, 1, p.n_out, p.n_out, 1, 0);
         a.total = start; a.scal = scal; a.lr = lr; a.beta1 = beta1; a.beta2 = beta2; a.eps = eps;
         TraceScope ts("upd_adam", (double)start * (28.0 + esz), 1, st);
         adam_kernel<T><<<(unsigned)((start + 255) / 256), 256, 0, st>>>(a);

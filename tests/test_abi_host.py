@@ -34,9 +34,9 @@ def test_exports_every_declared_symbol(lib):
 
 
 def test_struct_layout_matches_header_sizes():
-    # ab_enc = 12 bytes; desc = 3 ints + 26 encs + int + 8 ints + int + 2 ints + int
+    # ab_enc = 12 bytes; desc = 3 ints + 26 encs + int + 8 ints + int + 2 ints + int + 2 ints
     assert C.sizeof(ab.ab_enc) == 12
-    assert C.sizeof(ab.ab_model_desc) == 4 * 3 + 12 * (8 + 16 + 2) + 4 + 4 * 8 + 4 + 8 + 4
+    assert C.sizeof(ab.ab_model_desc) == 4 * 3 + 12 * (8 + 16 + 2) + 4 + 4 * 8 + 4 + 8 + 4 + 8
     assert C.sizeof(ab.ab_params) == 8 * (12 * 7 + 1)
     assert C.sizeof(ab.ab_stats) == 32 and C.sizeof(ab.ab_grid) == 32
 
@@ -124,6 +124,11 @@ def test_score_argument_errors(lib):
     d5 = _desc(2)
     d5.n_stats = 99
     assert _call_score(lib, d5, p) == -2
+    d6 = _desc(2)
+    d6.n_outputs = 17                                                          # more entries of V than the ABI holds
+    assert _call_score(lib, d6, p) == -2 and ab.ab_workspace_bytes(d6, 16, 4) == 0
+    d6.n_outputs, d6.loss_kind = 8, 2                                          # unknown loss
+    assert _call_score(lib, d6, p) == -2
     # S = 0 is a valid no-op that never touches the device
     assert _call_score(lib, d, p, stats=ab.ab_stats(None, None, 0)) == 0
     assert _call_score(lib, d, p, stats=ab.ab_stats(None, None, 0), scores=None, idx=None, ws=None) == 0

@@ -1,0 +1,97 @@
+"""Per-worker prediction V (one output unit per worker, Table 1) and the unsquared L2 loss of Eq. 2 on the
+GPU against the oracle: scoring ranks candidates by the mean of the per-worker predictions, the update
+back-propagates the chosen loss through the n-wide output layer."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2112_13509_amd import binding as ab
+from paper_2112_13509_amd import workloads as wl
+from helpers import oracle_model, scaled_error, check_selection
+from gpu_helpers import Scorer
+from test_gpu_update import GpuTrainer, check_single_step, TOL
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    ab.load()
+
+
+def with_worker_outputs(w, n_workers, seed):
+    """The scoring workload with its output layer redrawn as n_workers units (weights N(0, 1/fan_in))."""
+    rng = np.random.default_rng(seed)
+    H = w.hidden[-1]
+    Wo = (rng.standard_normal((n_workers, H)) / np.sqrt(H)).astype(np.float32)
+    if w.dtype == "bf16":
+        Wo = wl.bf16_round(Wo)
+    w.W = list(w.W[:-1]) + [Wo]
+    w.b = list(w.b[:-1]) + [(0.1 * rng.standard_normal(n_workers)).astype(np.float32)]
+    return w
+
+
+@pytest.mark.parametrize("dtype,hidden,S,P,Q,n_workers", [
+    ("f32", [64, 64], 9, 8, 8, 4),            # generic tiles
+    ("bf16", [128], 33, 5, 7, 3),             # single hidden layer
+    ("bf16", [256, 256, 256], 70, 16, 16, 8),  # 256 x 256 streaming kernels (70 tiles per launch)
+    ("f32", [64, 64], 1, 8, 8, 16),           # a size the single-launch path would take with one output
+])
+def test_scores_are_the_mean_of_the_per_worker_predictions(dtype, hidden, S, P, Q, n_workers):
+    w = wl.make_scoring("workers", S, 6, hidden, P, Q, 16e3, 64e6, 1.0, 16.0, False, dtype, seed=S * 7 + n_workers)
+    w = with_worker_outputs(w, n_workers, seed=n_workers)
+    sc = Scorer(w)
+    assert sc.desc.n_outputs == n_workers
+    scores, idx, best = sc.run()
+    ref = orc.score(oracle_model(w), w.dyn, w.scal, w.part, w.cred)
+    err = scaled_error(scores, ref)
+    tol = TOL[dtype]
+    assert err <= tol, err
+    frac = check_selection(idx, ref, tol)
+    print("n_workers=%d %s: scaled err %.3g, exact-argmax fraction %.2f" % (n_workers, dtype, err, frac))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n_workers,loss_kind", [(1, "l2norm"), (3, "l2norm"), (8, "l2norm"), (16, "l2norm"), (4, "mse")])
+def test_single_update_step(dtype, n_workers, loss_kind):
+    B = 300
+    u = wl.make_update("upd-workers", N=512, batch=B, L=5, hidden=(128, 64), dtype=dtype, seed=n_workers * 10 + 1,
+                       P=8, Q=8, n_workers=n_workers, loss_kind=loss_kind)
+    tr = GpuTrainer(u, B)
+    assert tr.desc.n_outputs == n_workers and tr.desc.loss_kind == (1 if loss_kind == "l2norm" else 0)
+    st = orc.TrainState.fresh(u.W, u.b)
+    tol_inf = TOL[dtype] if dtype == "f32" else 0.15          # small bf16 problems: see test_gpu_update.py
+    w1 = check_single_step(u, tr, st, np.arange(B), TOL[dtype], tol_inf=tol_inf)
+    w2 = check_single_step(u, tr, st, np.arange(B)[::-1].copy() + 100, TOL[dtype], tol_inf=tol_inf)
+    print("%s n_workers=%d %s: worst gradient error %.3g, %.3g" % (dtype, n_workers, loss_kind, w1, w2))
+
+
+def test_norm_loss_at_the_real_shape_bf16():
+    """Configuration 4's network and batch with eight workers and the norm loss."""
+    u = wl.make_update("cfg4-workers", N=4096, batch=4096, n_workers=8, loss_kind="l2norm")
+    tr = GpuTrainer(u, 4096)
+    st = orc.TrainState.fresh(u.W, u.b)
+    w = check_single_step(u, tr, st, np.arange(4096), TOL["bf16"])
+    print("cfg4 shape, 8 workers, norm loss: worst gradient error %.3g" % w)
+
+
+def test_a_row_predicted_exactly_gives_no_gradient_and_no_nan():
+    u = wl.make_update("upd-exact", N=64, batch=64, L=2, hidden=(64,), dtype="f32", seed=5, P=4, Q=4,
+                       n_workers=2, loss_kind="l2norm")
+    tr = GpuTrainer(u, 64)
+    # zero output layer and zero targets: every error vector is exactly zero
+    u.W[-1][:] = 0.0
+    u.b[-1][:] = 0.0
+    u.target[:] = 0.0
+    tr = GpuTrainer(u, 64)
+    st = orc.TrainState.fresh(u.W, u.b)
+    tr.load_state(st)
+    tr.step(np.arange(64))
+    assert tr.loss_value() == 0.0
+    for k in range(len(st.W)):
+        assert torch.equal(tr.params.mW[k], torch.zeros_like(tr.params.mW[k]))
+        assert torch.isfinite(tr.params.W_master[k]).all()
