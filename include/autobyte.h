@@ -156,10 +156,14 @@ typedef struct {
                                  stops after them); must be NULL for the flat layout                       */
 } ab_stats;
 
-/* Candidate grid shared by all scenarios (struct HOST, pointers DEVICE). Candidate c = p*Q + q. */
+/* Candidate grid (struct HOST, pointers DEVICE). Candidate c = p*Q + q.
+ * per_scenario = 0: one grid shared by all scenarios.  per_scenario = 1: every scenario brings its own P
+ * partition sizes and Q credit multiples (Table 1 lists S_p and S_c as inputs of the one job being tuned; jobs
+ * of different models need not be offered the same values): partition_bytes is [S, P], credit_mult [S, Q]. */
 typedef struct {
-    const float *partition_bytes;  int32_t P;   /* [P] partition sizes S_p                    */
-    const float *credit_mult;      int32_t Q;   /* [Q] credit sizes as multiples of S_p       */
+    const float *partition_bytes;  int32_t P;   /* [P] or [S, P] partition sizes S_p                    */
+    const float *credit_mult;      int32_t Q;   /* [Q] or [S, Q] credit sizes as multiples of S_p       */
+    int32_t      per_scenario;
 } ab_grid;
 
 /*

@@ -49,7 +49,8 @@ class ab_stats(C.Structure):
 
 
 class ab_grid(C.Structure):
-    _fields_ = [("partition_bytes", _vp), ("P", C.c_int32), ("credit_mult", _vp), ("Q", C.c_int32)]
+    _fields_ = [("partition_bytes", _vp), ("P", C.c_int32), ("credit_mult", _vp), ("Q", C.c_int32),
+                ("per_scenario", C.c_int32)]
 
 
 class AutoByteError(RuntimeError):
@@ -276,16 +277,21 @@ def ab_score_candidates(desc: ab_model_desc, params: Params, dyn: torch.Tensor, 
                         best_score: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
                         stream=None, check: bool = True, layers_of: Optional[torch.Tensor] = None) -> int:
     """Enqueue scoring of every (scenario, candidate); outputs are written into the given tensors.
-    ``layers_of`` (int32 [S], encoder models only): how many of the L padded layers each scenario really has."""
+    ``layers_of`` (int32 [S], encoder models only): how many of the L padded layers each scenario really has.
+    ``partition_bytes`` [P] and ``credit_mult`` [Q] are shared by all scenarios; given as [S, P] and [S, Q]
+    every scenario brings its own grid."""
     lib = load()
     S = int(dyn.shape[0])
     if layers_of is not None and layers_of.numel() != S:
         raise ValueError("layers_of must have one entry per scenario")
     st = ab_stats(_ptr(dyn, torch.float32, "dyn"), _ptr(scalars, torch.float32, "scalars"), S,
                   _ptr(layers_of, torch.int32, "layers_of"))
-    P, Q = int(partition_bytes.numel()), int(credit_mult.numel())
+    per_scenario = partition_bytes.dim() == 2
+    if per_scenario and (credit_mult.dim() != 2 or partition_bytes.shape[0] != S or credit_mult.shape[0] != S):
+        raise ValueError("per-scenario grids must be [S, P] and [S, Q]")
+    P, Q = int(partition_bytes.shape[-1]), int(credit_mult.shape[-1])
     gr = ab_grid(_ptr(partition_bytes, torch.float32, "partition_bytes"), P,
-                 _ptr(credit_mult, torch.float32, "credit_mult"), Q)
+                 _ptr(credit_mult, torch.float32, "credit_mult"), Q, 1 if per_scenario else 0)
     if dyn.numel() != S * desc.n_layers * desc.n_stats or scalars.numel() != S * desc.n_scalars:
         raise ValueError("dyn / scalars do not match the description")
     for t, n, what in ((scores, S * P * Q, "scores"), (best_idx, S, "best_idx"), (best_score, S, "best_score")):

@@ -58,7 +58,7 @@ struct ScorePlan {
     int tile_a;                   // tile of the scenario-term GEMM
     int nt_last;
     int64_t chunk_scen, chunk_rows;
-    size_t off_xs, off_w1s, off_aterm, off_bterm, off_cfgv, off_wout, off_partial, off_act0, off_act1, total;
+    size_t off_xs, off_w1s, off_aterm, off_bterm, off_cfgv, off_wout, off_xrow, off_partial, off_act0, off_act1, total;
 };
 
 static const int64_t kTargetChunkRows = 1 << 20;
@@ -102,6 +102,7 @@ static ab_status plan_scoring(const ab_model_desc *d, int64_t S, int32_t C, Scor
     p->off_bterm = take((size_t)C * p->H[0] * 4);
     p->off_cfgv = take(((size_t)2 * p->H[0] + 2 * (size_t)C) * 4);
     p->off_wout = take((size_t)(p->H[p->D - 1] + 1) * 4);     // folded output weights, then the folded bias
+    p->off_xrow = take((size_t)p->chunk_rows * 2 * 4);          // per-scenario grids: (phi(S_p), phi(S_c)) of a chunk's rows
     p->off_partial = take((size_t)p->chunk_rows * p->nt_last * 4);
     p->off_act0 = p->off_act1 = 0;
     if (p->D >= 3) p->off_act0 = take((size_t)p->chunk_rows * hmax * es);
@@ -179,6 +180,8 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
     if (stats->S < 0 || grid->P <= 0 || grid->Q <= 0) return AB_ERR_SHAPE;
     if ((int64_t)grid->P * grid->Q > (1 << 24)) return AB_ERR_SHAPE;
     if (!grid->partition_bytes || !grid->credit_mult) return AB_ERR_NULL;
+    if (grid->per_scenario != 0 && grid->per_scenario != 1) return AB_ERR_SHAPE;
+    if (misaligned(grid->partition_bytes, 4) || misaligned(grid->credit_mult, 4)) return AB_ERR_ALIGN;
     const int64_t S = stats->S;
     const int32_t C = grid->P * grid->Q;
     if (S > 0 && (!stats->dyn || (desc->n_scalars > 0 && !stats->scalars))) return AB_ERR_NULL;
@@ -205,7 +208,8 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
         for (int k = 0; k < p.D; ++k) fl += 2.0 * S * C * p.H[k] * (k ? p.H[k - 1] : 3);
         TraceScope ts("score_tiny", fl, 0, st);
         AB_HIP(launch_score_tiny(p.dtype, desc, params, stats->dyn, stats->scalars, grid->partition_bytes,
-                                 grid->credit_mult, grid->P, grid->Q, S, scores, best_idx, best_score, st));
+                                 grid->credit_mult, grid->P, grid->Q, grid->per_scenario, S, scores, best_idx,
+                                 best_score, st));
         return AB_OK;
     }
     unsigned char *ws = (unsigned char *)workspace;
@@ -213,6 +217,8 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
     float *a_term = (float *)(ws + p.off_aterm), *b_term = (float *)(ws + p.off_bterm);
     float *w_out_f = (float *)(ws + p.off_wout), *partial = (float *)(ws + p.off_partial);
     float *cfg_vec = (float *)(ws + p.off_cfgv);
+    float *xp_row = (float *)(ws + p.off_xrow), *xc_row = xp_row + p.chunk_rows;
+    const int per_scenario = grid->per_scenario;
     void *act[2] = {ws + p.off_act0, ws + p.off_act1};
     const int dt = p.dtype;
 
@@ -266,9 +272,16 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
         const int64_t rows = ns * C;
         const float *a_chunk = a_term + s0 * p.H[0];
         int nt = 1;
+        if (per_scenario) {
+            TraceScope ts("grid_rows", (double)rows * 8.0, 1, st);
+            AB_HIP(launch_grid_rows(desc, grid->partition_bytes + s0 * grid->P, grid->credit_mult + s0 * grid->Q,
+                                    grid->P, grid->Q, xp_row, xc_row, rows, st));
+        }
         if (p.D == 1) {
             TraceScope ts("score_single_hidden", 3.0 * rows * p.H[0], 0, st);
-            AB_HIP(launch_score_single_hidden(a_chunk, b_term, w_out_f, partial, rows, C, p.H[0], st));
+            AB_HIP(launch_score_single_hidden(a_chunk, b_term, w_out_f, partial, rows, C, p.H[0], cfg_vec,
+                                              cfg_vec + p.H[0], per_scenario ? xp_row : nullptr,
+                                              per_scenario ? xc_row : nullptr, st));
         } else {
             for (int k = 1; k < p.D; ++k) {
                 GemmArgs g;
@@ -276,6 +289,7 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
                 if (k == 1) {
                     g.a_term = a_chunk; g.b_term = b_term; g.ldt = p.H[0]; g.C = C;
                     g.wp = cfg_vec; g.wc = cfg_vec + p.H[0]; g.xp = cfg_vec + 2 * p.H[0]; g.xc = cfg_vec + 2 * p.H[0] + C;
+                    if (per_scenario) { g.xp = xp_row; g.xc = xc_row; g.x_per_row = 1; }
                 }
                 else { g.A = act[k & 1]; g.lda = p.H[k - 1]; }
                 g.B = params->W[p.base + k]; g.ldb = p.H[k - 1];
@@ -292,8 +306,8 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
                     AB_HIP(launch_gemm_big(amode, epi, g, st));
                 else if (p.big[k])
                     return AB_ERR_UNSUPPORTED;     // cannot happen: the plan checked the same conditions
-                else
-                    AB_HIP(launch_gemm(dt, p.tile[k], amode, epi, g, st));
+                else    // the generic tiles take a per-scenario grid's operand in its factored form
+                    AB_HIP(launch_gemm(dt, p.tile[k], amode == AMODE_GEN && per_scenario ? AMODE_GENV : amode, epi, g, st));
             }
         }
         TraceScope ts("finish_select", (double)rows * (nt * 4.0 + (scores ? 4.0 : 0.0)) + ns * 8.0, 1, st);

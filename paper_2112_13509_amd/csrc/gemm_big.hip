@@ -103,8 +103,8 @@ __global__ __launch_bounds__(512) void gemm_big_kernel(const GemmArgs g)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int r = (t >> 3) + 64 * i;
-            gen_xp[i] = g.xp[c0 + r];
-            gen_xc[i] = g.xc[c0 + r];
+            gen_xp[i] = g.xp[(g.x_per_row ? m0 : (int64_t)c0) + r];
+            gen_xc[i] = g.xc[(g.x_per_row ? m0 : (int64_t)c0) + r];
             gen_st[i] = r * 128 + ((cc ^ ((r >> 1) & 7)) << 4);
         }
     }
@@ -763,7 +763,7 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
             if (i > KT - 1) i = KT - 1;
             dma4(g.a_term + (int64_t)s * g.ldt + i * 64 + ln, smem + V_AT + b * 4096 + i * 256);
         }
-        dma4((wave < 4 ? g.xp : g.xc) + c0 + (wave & 3) * 64 + ln,
+        dma4((wave < 4 ? g.xp : g.xc) + (g.x_per_row ? m0u : c0) + (wave & 3) * 64 + ln,
              smem + V_XP + b * 2048 + (wave >> 2) * 1024 + (wave & 3) * 256);
     };
     auto fetch_wp_wc = [&]() {                              // 4 requests per wavefront, once

@@ -41,7 +41,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 }
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 
-enum { AMODE_LOAD = 0, AMODE_GEN = 1 };
+enum { AMODE_LOAD = 0, AMODE_GEN = 1, AMODE_GENV = 2 };
 enum { EPI_STORE = 0, EPI_SCORE = 1, EPI_DRELU = 2, EPI_SPLITK = 3 };
 
 struct GemmArgs {
@@ -50,8 +50,10 @@ struct GemmArgs {
     // A operand, AMODE_GEN: row r stands for (scenario s = r / C, candidate c = r % C) and
     // A[r, k] = relu(a_term[s*ldt + k] + b_term[c*ldt + k]) rounded to the compute type
     const float *a_term; const float *b_term; int32_t ldt; int32_t C;
-    // the same b_term in factored form, b_term[c*ldt + k] = wp[k]*xp[c] + wc[k]*xc[c] (256x256 kernel)
-    const float *wp, *wc, *xp, *xc;
+    // the same b_term in factored form, b_term[c*ldt + k] = wp[k]*xp[c] + wc[k]*xc[c] (256x256 kernel);
+    // with x_per_row the two candidate vectors are indexed by the row r instead (xp[r], xc[r]: every scenario
+    // has its own candidate values).  AMODE_GENV: the generic tiles' form of the factored operand
+    const float *wp, *wc, *xp, *xc; int32_t x_per_row;
     // B operand: B[N, K], leading dimension ldb
     const void *B; int64_t ldb;
     int64_t M; int32_t N; int32_t K;          // K is a multiple of the K-slab; N a multiple of the tile width
@@ -106,6 +108,31 @@ __device__ __forceinline__ i32x4 gen_chunk(const float *pa, const float *pb)
     }
 }
 
+// relu(a + wp * xp + wc * xc) for one 16-byte chunk of the generated operand in its factored form.
+template <typename T>
+__device__ __forceinline__ i32x4 gen_chunk_v(const float *pa, const float *pp, const float *pc, float xp, float xc)
+{
+    if constexpr (sizeof(T) == 2) {
+        float h[8];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const f32x4 a = *(const f32x4 *)(pa + 4 * q), wp = *(const f32x4 *)(pp + 4 * q), wc = *(const f32x4 *)(pc + 4 * q);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) h[4 * q + e] = relu_keep_nan(fmaf(wc[e], xc, fmaf(wp[e], xp, a[e])));
+        }
+        i32x4 r;
+        r.x = (int)pack_bf16x2(h[0], h[1]); r.y = (int)pack_bf16x2(h[2], h[3]);
+        r.z = (int)pack_bf16x2(h[4], h[5]); r.w = (int)pack_bf16x2(h[6], h[7]);
+        return r;
+    } else {
+        const f32x4 a = *(const f32x4 *)pa, wp = *(const f32x4 *)pp, wc = *(const f32x4 *)pc;
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = relu_keep_nan(fmaf(wc[e], xc, fmaf(wp[e], xp, a[e])));
+        return __builtin_bit_cast(i32x4, v);
+    }
+}
+
 template <typename T>
 __device__ __forceinline__ void store_elem(void *base, int64_t idx, float v, int as_f32)
 {
@@ -148,6 +175,7 @@ __device__ __forceinline__ void gemm_tn_tile(const GemmArgs &g, int64_t id, unsi
 
     // per-thread source offsets (elements) of its chunks within the A panel / B panel
     int32_t a_off[A_CH], a2_off[A_CH], b_off[B_CH];
+    float gx_p[A_CH], gx_c[A_CH];             // AMODE_GENV: this thread's rows' candidate values
     const T *Ab = nullptr;
     if constexpr (AMODE == AMODE_LOAD) {
         Ab = (const T *)g.A + m0 * g.lda;
@@ -165,6 +193,10 @@ __device__ __forceinline__ void gemm_tn_tile(const GemmArgs &g, int64_t id, unsi
             int32_t c = (int32_t)(r - s * g.C);
             a_off[i] = (int32_t)s * g.ldt + ld_cc * EPC;
             a2_off[i] = c * g.ldt + ld_cc * EPC;
+            if constexpr (AMODE == AMODE_GENV) {
+                gx_p[i] = g.xp[g.x_per_row ? r : (int64_t)c];
+                gx_c[i] = g.xc[g.x_per_row ? r : (int64_t)c];
+            }
         }
     }
     const T *Bb = (const T *)g.B + (int64_t)n0 * g.ldb;
@@ -200,10 +232,15 @@ __device__ __forceinline__ void gemm_tn_tile(const GemmArgs &g, int64_t id, unsi
         if constexpr (AMODE == AMODE_LOAD) {
 #pragma unroll
             for (int i = 0; i < A_CH; ++i) ra[i] = *(const i32x4 *)(Ab + a_off[i] + k0);
-        } else {
+        } else if constexpr (AMODE == AMODE_GEN) {
 #pragma unroll
             for (int i = 0; i < A_CH; ++i)
                 ra[i] = gen_chunk<T>(g.a_term + a_off[i] + k0, g.b_term + a2_off[i] + k0);
+        } else {
+#pragma unroll
+            for (int i = 0; i < A_CH; ++i)
+                ra[i] = gen_chunk_v<T>(g.a_term + a_off[i] + k0, g.wp + ld_cc * EPC + k0, g.wc + ld_cc * EPC + k0,
+                                       gx_p[i], gx_c[i]);
         }
 #pragma unroll
         for (int i = 0; i < B_CH; ++i) rb[i] = *(const i32x4 *)(Bb + b_off[i] + k0);

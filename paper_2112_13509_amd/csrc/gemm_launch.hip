@@ -32,10 +32,15 @@ static hipError_t launch_tile(int amode, int epi, const GemmArgs &g, hipStream_t
         case EPI_DRELU:  if constexpr (WB <= 2) return launch_one<T, WB, AMODE_LOAD, EPI_DRELU>(g, st); break;
         case EPI_SPLITK: if constexpr (WB <= 2) return launch_one<T, WB, AMODE_LOAD, EPI_SPLITK>(g, st); break;
         }
-    } else {
+    } else if (amode == AMODE_GEN) {
         switch (epi) {
         case EPI_STORE:  return launch_one<T, WB, AMODE_GEN, EPI_STORE>(g, st);
         case EPI_SCORE:  return launch_one<T, WB, AMODE_GEN, EPI_SCORE>(g, st);
+        }
+    } else {
+        switch (epi) {
+        case EPI_STORE:  return launch_one<T, WB, AMODE_GENV, EPI_STORE>(g, st);
+        case EPI_SCORE:  return launch_one<T, WB, AMODE_GENV, EPI_SCORE>(g, st);
         }
     }
     return hipErrorInvalidValue;

@@ -49,11 +49,15 @@ hipError_t launch_trigger(const float *scores, int64_t S, int C, int64_t row_str
                           const float *observed, float gain_threshold, float error_threshold, int32_t *best_idx,
                           float *gain, uint8_t *reconf, uint8_t *adapt, hipStream_t st);
 hipError_t launch_score_single_hidden(const float *a_term, const float *b_term, const float *w_out_f,
-                                      float *partial, int64_t rows, int C, int H, hipStream_t st);
+                                      float *partial, int64_t rows, int C, int H, const float *wp, const float *wc,
+                                      const float *xp_row, const float *xc_row, hipStream_t st);
+hipError_t launch_grid_rows(const ab_model_desc *d, const float *part, const float *cred, int P, int Q,
+                            float *xp_row, float *xc_row, int64_t rows, hipStream_t st);
 bool score_tiny_supported(const ab_model_desc *d, int64_t S, int32_t C);
 hipError_t launch_score_tiny(int dtype, const ab_model_desc *d, const ab_params *prm, const float *dyn,
                              const float *scal, const float *part, const float *cred, int32_t P, int32_t Q,
-                             int64_t S, float *scores, int32_t *best_idx, float *best_score, hipStream_t st);
+                             int per_scenario, int64_t S, float *scores, int32_t *best_idx, float *best_score,
+                             hipStream_t st);
 hipError_t launch_lstm_encoder(const ab_model_desc *d, const float *dyn, const void *We, const float *be,
                                const void *W1, const float *b1, const void *W2, const float *b2, void *xs,
                                int ld, int64_t S, const int32_t *layers_of, hipStream_t st);

@@ -200,6 +200,29 @@ __global__ __launch_bounds__(256) void prep_layer1_kernel(const PrepArgs a)
     }
 }
 
+// Per-scenario candidate grids: the transformed pair (phi(S_p), phi(S_c)) of every (scenario, candidate) row
+// of a chunk, row = s * P * Q + p * Q + q, from part[S, P] and cred[S, Q].
+struct GridRowsArgs { const float *part, *cred; int32_t P, Q; ab_enc enc_part, enc_cred; float *xp_row, *xc_row; int64_t rows; };
+__global__ __launch_bounds__(256) void grid_rows_kernel(const GridRowsArgs a)
+{
+    const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (row >= a.rows) return;
+    const int Cn = a.P * a.Q;
+    const int64_t s = row / Cn;
+    const int c = (int)(row - s * Cn);
+    a.xp_row[row] = phi(a.part[s * a.P + c / a.Q], a.enc_part);
+    a.xc_row[row] = phi(a.cred[s * a.Q + c % a.Q], a.enc_cred);
+}
+
+hipError_t launch_grid_rows(const ab_model_desc *d, const float *part, const float *cred, int P, int Q,
+                            float *xp_row, float *xc_row, int64_t rows, hipStream_t st)
+{
+    if (rows == 0) return hipSuccess;
+    GridRowsArgs a{part, cred, P, Q, d->enc_partition, d->enc_credit, xp_row, xc_row, rows};
+    grid_rows_kernel<<<(unsigned)((rows + 255) / 256), 256, 0, st>>>(a);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------------------
 // Argmax helpers: (value, index) pairs, larger value wins, lower index wins ties, NaN never wins.
 // "Nothing yet" is (-inf, INT_MAX).
@@ -351,6 +374,7 @@ __global__ __launch_bounds__(256) void select_rows16_kernel(const FinishArgs a, 
 // ------------------------------------------------------------------------------------------------
 struct TinyArgs {
     const float *dyn, *scal, *part, *cred;
+    int32_t part_stride, cred_stride;            // elements between two scenarios' grids (0: one shared grid)
     int32_t L, K, Ns, Q, C, F, Fs, D;
     int32_t H[AB_MAX_HIDDEN];
     const void *W[AB_MAX_HIDDEN + 1];
@@ -434,7 +458,8 @@ __global__ __launch_bounds__(256) void score_tiny_kernel(const TinyArgs a)
     for (int c0 = 0; c0 < a.C; c0 += G) {
         const int c = c0 + lane;
         const int cc = c < a.C ? c : a.C - 1;
-        const float xp = phi(a.part[cc / a.Q], a.enc_part), xc = phi(a.cred[cc % a.Q], a.enc_cred);
+        const float xp = phi(a.part[(int64_t)blockIdx.x * a.part_stride + cc / a.Q], a.enc_part);
+        const float xc = phi(a.cred[(int64_t)blockIdx.x * a.cred_stride + cc % a.Q], a.enc_cred);
         float *mine = &hb[0][lane * STR];
         {
             const int hq = H1 >> 2;
@@ -554,7 +579,10 @@ __global__ __launch_bounds__(256) void trigger_kernel(const TriggerArgs a)
 
 // Scorer with a single hidden layer: score = w_out . relu(A[s] + B[c]) + b_out, one wavefront per
 // (scenario, candidate) row, written into the same partial buffer layout (nt = 1, no bias yet).
-struct ScoreD1Args { const float *a_term, *b_term, *w_out_f; float *partial; int64_t rows; int32_t C, H; };
+struct ScoreD1Args {
+    const float *a_term, *b_term, *w_out_f; float *partial; int64_t rows; int32_t C, H;
+    const float *wp, *wc, *xp_row, *xc_row;      // xp_row != NULL: B = wp * xp_row[row] + wc * xc_row[row] instead of b_term[c]
+};
 __global__ __launch_bounds__(256) void score_single_hidden_kernel(const ScoreD1Args a)
 {
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -563,8 +591,14 @@ __global__ __launch_bounds__(256) void score_single_hidden_kernel(const ScoreD1A
     const int64_t s = row / a.C;
     const int c = (int)(row - s * a.C);
     float acc = 0.f;
-    for (int h = lane; h < a.H; h += 64)
-        acc += relu_keep_nan(a.a_term[s * a.H + h] + a.b_term[(int64_t)c * a.H + h]) * a.w_out_f[h];
+    if (a.xp_row) {
+        const float xp = a.xp_row[row], xc = a.xc_row[row];
+        for (int h = lane; h < a.H; h += 64)
+            acc += relu_keep_nan(fmaf(a.wc[h], xc, fmaf(a.wp[h], xp, a.a_term[s * a.H + h]))) * a.w_out_f[h];
+    } else {
+        for (int h = lane; h < a.H; h += 64)
+            acc += relu_keep_nan(a.a_term[s * a.H + h] + a.b_term[(int64_t)c * a.H + h]) * a.w_out_f[h];
+    }
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
     if (lane == 0) a.partial[row] = acc;
@@ -794,10 +828,12 @@ bool score_tiny_supported(const ab_model_desc *d, int64_t S, int32_t C)
 
 hipError_t launch_score_tiny(int dtype, const ab_model_desc *d, const ab_params *prm, const float *dyn,
                              const float *scal, const float *part, const float *cred, int32_t P, int32_t Q,
-                             int64_t S, float *scores, int32_t *best_idx, float *best_score, hipStream_t st)
+                             int per_scenario, int64_t S, float *scores, int32_t *best_idx, float *best_score,
+                             hipStream_t st)
 {
     TinyArgs a = {};
     a.dyn = dyn; a.scal = scal; a.part = part; a.cred = cred;
+    a.part_stride = per_scenario ? P : 0; a.cred_stride = per_scenario ? Q : 0;
     a.L = d->n_layers; a.K = d->n_stats; a.Ns = d->n_scalars; a.Q = Q; a.C = P * Q;
     a.Fs = d->n_layers * d->n_stats + d->n_scalars; a.F = a.Fs + 2; a.D = d->n_hidden;
     for (int k = 0; k < d->n_hidden; ++k) a.H[k] = d->hidden[k];
@@ -831,10 +867,11 @@ hipError_t launch_trigger(const float *scores, int64_t S, int C, int64_t row_str
 }
 
 hipError_t launch_score_single_hidden(const float *a_term, const float *b_term, const float *w_out_f,
-                                      float *partial, int64_t rows, int C, int H, hipStream_t st)
+                                      float *partial, int64_t rows, int C, int H, const float *wp, const float *wc,
+                                      const float *xp_row, const float *xc_row, hipStream_t st)
 {
     if (rows == 0) return hipSuccess;
-    ScoreD1Args a{a_term, b_term, w_out_f, partial, rows, C, H};
+    ScoreD1Args a{a_term, b_term, w_out_f, partial, rows, C, H, wp, wc, xp_row, xc_row};
     score_single_hidden_kernel<<<(unsigned)((rows + 3) / 4), 256, 0, st>>>(a);
     return hipGetLastError();
 }
