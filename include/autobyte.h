@@ -53,7 +53,7 @@ extern "C" {
 #endif
 
 #define AB_MAX_STATS   8    /* statistics per layer (K)                    */
-#define AB_MAX_SCALARS 16   /* scalar features per scenario                */
+#define AB_MAX_SCALARS 40   /* scalar features per scenario (Table 1: n, l, type vectors, B_d and B_u per worker) */
 #define AB_MAX_HIDDEN  8    /* hidden layers of the scorer                 */
 #define AB_MAX_OUTPUTS 16   /* entries of the predicted speed V            */
 #define AB_MAX_LAYERS  12   /* encoder (up to 3) + hidden (8) + output (1)                */

@@ -14,7 +14,7 @@ import torch
 
 AB_F32, AB_BF16 = 0, 1
 AB_ENC_LINEAR, AB_ENC_LOG = 0, 1
-AB_MAX_STATS, AB_MAX_SCALARS, AB_MAX_HIDDEN, AB_MAX_LAYERS = 8, 16, 8, 12
+AB_MAX_STATS, AB_MAX_SCALARS, AB_MAX_HIDDEN, AB_MAX_LAYERS = 8, 40, 8, 12
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libautobyte.so")
 _lib = None

@@ -77,7 +77,7 @@ struct QuadSplit { int q4s, q4t; uint32_t magic_q4s, magic_q4t, magic_k; int rpb
 template <typename T>
 __global__ __launch_bounds__(256) void encode_stats_quad_kernel(const EncodeArgs a, const QuadSplit g)
 {
-    __shared__ f32x4 tab[AB_MAX_STATS + AB_MAX_SCALARS];     // statistics 0..7, scalars 8..23
+    __shared__ f32x4 tab[AB_MAX_STATS + AB_MAX_SCALARS];     // statistics first, then the scalars
     if (threadIdx.x < AB_MAX_STATS + AB_MAX_SCALARS) {
         const int i = threadIdx.x;
         const ab_enc *e = i < AB_MAX_STATS ? &a.enc_stat[i] : &a.enc_scal[i - AB_MAX_STATS];

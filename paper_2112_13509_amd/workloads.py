@@ -211,6 +211,33 @@ def make_scoring(name: str, S: int, L: int, hidden: List[int], P: int, Q: int,
                     list(hidden), Ws, bs, None, None, None, dyn, scal, part, cred, seed)
 
 
+def make_per_worker(name: str, S: int, L: int, n_workers: int, hidden: List[int], P: int, Q: int,
+                    dtype: str, seed: int) -> Workload:
+    """Scoring problem with the input record of Table 1: per layer the backward time on each of the
+    ``n_workers`` workers (T is l x n: a layer's base time ~ lognormal(ln 2 ms, 0.5), times a per-worker speed
+    factor ~ lognormal(0, 0.1), times a per-sample jitter ~ lognormal(0, 0.05)); scalars n, l, a 2-way model-type
+    and a 2-way architecture-type vector, then the download and the upload speed of every worker (B_d, B_u:
+    U(1, 100) Gbps each); the output layer predicts one speed per worker."""
+    rng = np.random.default_rng(seed)
+    Ns = 2 + 4 + 2 * n_workers
+    Ws, bs = _draw_mlp(rng, [L * n_workers + Ns + 2] + list(hidden) + [n_workers], dtype)
+    base = np.exp(TIME_MU + TIME_SIGMA * rng.standard_normal((S, L, 1)))
+    dyn = (base * np.exp(0.1 * rng.standard_normal((S, 1, n_workers)))
+           * np.exp(0.05 * rng.standard_normal((S, L, n_workers)))).astype(np.float32)
+    t1, t2 = rng.integers(0, 2, size=S), rng.integers(0, 2, size=S)
+    cols = [np.full(S, float(n_workers)), np.full(S, float(L)), t1 == 0, t1 == 1, t2 == 0, t2 == 1]
+    bw = BW_LO + (BW_HI - BW_LO) * rng.random((S, 2 * n_workers))
+    scal = np.concatenate([np.stack(cols, axis=1).astype(np.float64), bw], axis=1).astype(np.float32)
+    bw_enc = (ENC_LINEAR, 0.5 * (BW_LO + BW_HI), math.sqrt(12.0) / (BW_HI - BW_LO))
+    scal_enc = [(ENC_LOG, math.log(8.0), 1.0), (ENC_LINEAR, 64.0, 1.0 / 64.0)] + [(ENC_LINEAR, 0.0, 1.0)] * 4 \
+        + [bw_enc] * (2 * n_workers)
+    part_lo, part_hi, cred_lo, cred_hi = 16.0 * KIB, 64.0 * MIB, 1.0, 64.0
+    return Workload(name, dtype, L, n_workers, [_time_enc()] * n_workers, scal_enc,
+                    _log_uniform_enc(part_lo, part_hi), _log_uniform_enc(cred_lo, cred_hi),
+                    list(hidden), Ws, bs, None, None, None, dyn, scal,
+                    log_spaced(part_lo, part_hi, P), log_spaced(cred_lo, cred_hi, Q), seed)
+
+
 def make_tensor_encoder(name: str, S: int, hidden: List[int], te_hidden: List[int], P: int, Q: int,
                         dtype: str, seed: int, n_blocks=24, per_block=16, extra=16) -> Workload:
     """Per-tensor-encoder scoring problem (transformer-like tensor list, 4 statistics per tensor,

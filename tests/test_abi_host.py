@@ -36,7 +36,7 @@ def test_exports_every_declared_symbol(lib):
 def test_struct_layout_matches_header_sizes():
     # ab_enc = 12 bytes; desc = 3 ints + 26 encs + int + 8 ints + int + 2 ints + int + 2 ints
     assert C.sizeof(ab.ab_enc) == 12
-    assert C.sizeof(ab.ab_model_desc) == 4 * 3 + 12 * (8 + 16 + 2) + 4 + 4 * 8 + 4 + 8 + 4 + 8
+    assert C.sizeof(ab.ab_model_desc) == 4 * 3 + 12 * (8 + 40 + 2) + 4 + 4 * 8 + 4 + 8 + 4 + 8
     assert C.sizeof(ab.ab_params) == 8 * (12 * 7 + 1)
     assert C.sizeof(ab.ab_stats) == 32 and C.sizeof(ab.ab_grid) == 32
 

@@ -92,3 +92,15 @@ def test_a_row_predicted_exactly_gives_no_gradient_and_no_nan():
     for k in range(len(st.W)):
         assert torch.equal(tr.params.mW[k], torch.zeros_like(tr.params.mW[k]))
         assert torch.isfinite(tr.params.W_master[k]).all()
+
+
+@pytest.mark.parametrize("dtype,S,L,hidden", [("f32", 40, 12, [128, 64]), ("bf16", 300, 48, [256, 256, 256])])
+def test_table1_record_with_per_worker_inputs_and_outputs(dtype, S, L, hidden):
+    """Eight workers: T is L x 8, B_d and B_u have eight entries each (22 scalars), V has eight entries."""
+    w = wl.make_per_worker("table1", S, L, 8, hidden, 16, 16, dtype, seed=S + L)
+    sc = Scorer(w)
+    assert sc.desc.n_stats == 8 and sc.desc.n_scalars == 22 and sc.desc.n_outputs == 8
+    scores, idx, best = sc.run()
+    ref = orc.score(oracle_model(w), w.dyn, w.scal, w.part, w.cred)
+    err, frac = check_scores(dtype, scores, idx, ref)
+    print("Table 1 record %s: err %.3g, exact-argmax fraction %.2f" % (dtype, err, frac))
