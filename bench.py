@@ -203,6 +203,25 @@ def main():
                                          "GB/s": round(rate / 1e9, 1), "frac": round(rate / 8e12, 4),
                                          "same_choice_as_fused": bool(torch.equal(idx2, idx))}
 
+    # ---- the same pass with a grid of its own for every scenario (a repeated copy of the shared one)
+    grid_variant = None
+    if cfg in (2, 3, 5):
+        part_s = part.repeat(S, 1).contiguous()
+        cred_s = cred.repeat(S, 1).contiguous()
+        idx_s = torch.empty_like(idx)
+        for _ in range(2):
+            ab.ab_score_candidates(d, prm, dyn, scal, part_s, cred_s, scores, idx_s, best, ws)
+        torch.cuda.synchronize()
+        f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        f0.record()
+        for _ in range(3):
+            ab.ab_score_candidates(d, prm, dyn, scal, part_s, cred_s, scores, idx_s, best, ws)
+        f1.record()
+        torch.cuda.synchronize()
+        grid_variant = {"ms_per_step": round(f0.elapsed_time(f1) / 3, 4),
+                        "same_choice_as_shared_grid": float((idx_s == idx).float().mean().item())}
+        step()                       # leave the shared-grid results in place for what follows
+
     # ---- transfer-learning form of the update and the minibatch assembly, timed next to the full step (cfg4 only)
     transfer = None
     if cfg == 4:
@@ -233,6 +252,23 @@ def main():
         us = f0.elapsed_time(f1) * 1e3 / 200
         transfer["replay_mix_us"] = round(us, 2)
         transfer["replay_mix_GB/s"] = round(u.batch * (u.F + 1) * 8.0 / (us * 1e-6) / 1e9, 1)
+        # the same network with one output per worker (eight workers) and the unsquared L2 loss of Eq. 2
+        uw = wl.make_update(N=4096 * 4, n_workers=8, loss_kind="l2norm")
+        dw = ab.desc_from_workload(uw)
+        pw = ab.Params(uw.W, uw.b, uw.dtype, dev, trainable=True)
+        wsw = ab.alloc_workspace(dw, B=uw.batch, device=dev)
+        xw, yw = torch.from_numpy(uw.x_raw).to(dev), torch.from_numpy(uw.target).to(dev)
+        bw = [(xw[i * 4096:(i + 1) * 4096].contiguous(), yw[i * 4096:(i + 1) * 4096].contiguous()) for i in range(4)]
+        for i in range(20):
+            ab.ab_online_update(dw, pw, bw[i % 4][0], bw[i % 4][1], loss_out=loss, workspace=wsw)
+        torch.cuda.synchronize()
+        f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        f0.record()
+        for i in range(200):
+            ab.ab_online_update(dw, pw, bw[i % 4][0], bw[i % 4][1], loss_out=loss, workspace=wsw)
+        f1.record()
+        torch.cuda.synchronize()
+        transfer["eight_workers_norm_loss_us_per_step"] = round(f0.elapsed_time(f1) * 1e3 / 200, 2)
         transfer["note"] = ("first_trainable = D-1 trains the last hidden layer and the output unit, D the output "
                             "unit alone; replay_mix gathers one 4096-row minibatch from a 4096-row and a 65536-row pool")
 
@@ -303,7 +339,7 @@ def main():
            "config": workload_desc,
            "algorithmic_flop_per_unit": flops_per_unit,
            "whole_step_TFLOP/s": round(units_per_step * flops_per_unit / (ms_per_step * 1e-3) / 1e12, 3),
-           "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "launch_floor": launch_floor, "encoder_roofline": encoder_roofline, "hbm_stages": hbm_stages, "transfer_learning": transfer,
+           "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "launch_floor": launch_floor, "encoder_roofline": encoder_roofline, "hbm_stages": hbm_stages, "per_scenario_grids": grid_variant, "transfer_learning": transfer,
            "input_generation_s": round(t_gen, 2)}
     print(json.dumps(out))
 

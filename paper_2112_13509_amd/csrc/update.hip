@@ -23,7 +23,7 @@ struct UpdatePlan {
     int64_t B, Bp;
     int in_w[AB_MAX_HIDDEN + 1];        // padded input width of layer k (Kp for k = 0)
     int splits[AB_MAX_HIDDEN];
-    size_t off_scal, off_x, off_xt, off_w1p, off_yhat, off_dout, off_gwout, off_gbout;
+    size_t off_scal, off_x, off_xt, off_w1p, off_yhat, off_dout, off_lossrow, off_gwout, off_gbout;
     size_t off_wt[AB_MAX_HIDDEN], off_h[AB_MAX_HIDDEN], off_ht[AB_MAX_HIDDEN];
     size_t off_d[AB_MAX_HIDDEN], off_dt[AB_MAX_HIDDEN], off_gw[AB_MAX_HIDDEN], off_gb[AB_MAX_HIDDEN];
     size_t total;
@@ -53,6 +53,7 @@ static void plan_update(const ab_model_desc *d, int64_t B, UpdatePlan *p)
     p->off_xt = take((size_t)p->Kp * p->Bp * es);
     p->off_yhat = take((size_t)B * p->n_out * 4);
     p->off_dout = take((size_t)p->Bp * p->n_out * 4);
+    p->off_lossrow = take((size_t)p->Bp * 4);
     for (int k = 0; k < p->D; ++k) {
         p->H[k] = d->hidden[k];
         p->in_w[k] = (k == 0) ? p->Kp : d->hidden[k - 1];
@@ -148,8 +149,41 @@ __device__ __forceinline__ void update_prep_block(const UpdPrepArgs &a, unsigned
 //   d[r, :] = (sum_w dout[w] W_out[w, :]) * [h > 0]
 struct OutFwdArgs {
     const void *h; const void *w_out; const float *b_out; const float *target;
-    float *yhat; float *dout; void *d; int64_t B; int32_t H, n_out, loss_kind;
+    float *yhat; float *dout; float *lossrow; void *d; int64_t B; int32_t H, n_out, loss_kind;
 };
+// Eight consecutive elements of the compute type as fp32 (i a multiple of 8 on a 16-byte aligned base).
+template <typename T>
+__device__ __forceinline__ void load8(const void *p, int64_t i, float (&v)[8])
+{
+    if constexpr (sizeof(T) == 2) {
+        const i32x4 x = *(const i32x4 *)((const uint16_t *)p + i);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            v[2 * q] = __uint_as_float((uint32_t)x[q] << 16);
+            v[2 * q + 1] = __uint_as_float((uint32_t)x[q] & 0xffff0000u);
+        }
+    } else {
+        const f32x4 x = *(const f32x4 *)((const float *)p + i), y = *(const f32x4 *)((const float *)p + i + 4);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { v[q] = x[q]; v[4 + q] = y[q]; }
+    }
+}
+template <typename T>
+__device__ __forceinline__ void store8(void *p, int64_t i, const float (&v)[8])
+{
+    if constexpr (sizeof(T) == 2) {
+        i32x4 x;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) x[q] = (int)pack_bf16x2(v[2 * q], v[2 * q + 1]);
+        *(i32x4 *)((uint16_t *)p + i) = x;
+    } else {
+        *(f32x4 *)((float *)p + i) = f32x4{v[0], v[1], v[2], v[3]};
+        *(f32x4 *)((float *)p + i + 4) = f32x4{v[4], v[5], v[6], v[7]};
+    }
+}
+
+// A lane takes eight adjacent columns per 512 (the widths are multiples of 64, so a group of eight is inside
+// the row or outside it as a whole); the hidden row is read once for all outputs.
 template <typename T>
 __global__ __launch_bounds__(256) void output_forward_kernel(const OutFwdArgs a)
 {
@@ -157,14 +191,26 @@ __global__ __launch_bounds__(256) void output_forward_kernel(const OutFwdArgs a)
     if (r >= a.B) return;
     const int lane = threadIdx.x & 63;
     float dv[AB_MAX_OUTPUTS];
+#pragma unroll
+    for (int w = 0; w < AB_MAX_OUTPUTS; ++w) dv[w] = 0.f;
+    for (int c0 = lane * 8; c0 < a.H; c0 += 512) {
+        float hv[8];
+        load8<T>(a.h, r * a.H + c0, hv);
+#pragma unroll
+        for (int w = 0; w < AB_MAX_OUTPUTS; ++w) {
+            if (w < a.n_out) {
+                float wv[8];
+                load8<T>(a.w_out, (int64_t)w * a.H + c0, wv);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dv[w] = fmaf(hv[e], wv[e], dv[w]);
+            }
+        }
+    }
     float sq = 0.f;
 #pragma unroll
     for (int w = 0; w < AB_MAX_OUTPUTS; ++w) {
-        dv[w] = 0.f;
         if (w < a.n_out) {
-            float acc = 0.f;
-            for (int c = lane; c < a.H; c += 64)
-                acc += ld_f32<T>(a.h, r * a.H + c) * ld_f32<T>(a.w_out, (int64_t)w * a.H + c);
+            float acc = dv[w];
 #pragma unroll
             for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
             const float yh = acc + a.b_out[w];
@@ -175,26 +221,37 @@ __global__ __launch_bounds__(256) void output_forward_kernel(const OutFwdArgs a)
     }
     const float nrm = sqrtf(sq);
     const float f = a.loss_kind == AB_LOSS_L2NORM ? (nrm > 0.f ? 1.f / (nrm * (float)a.B) : 0.f) : 2.f / (float)a.B;
+    if (lane == 0) a.lossrow[r] = a.loss_kind == AB_LOSS_L2NORM ? nrm : sq;       // this row's term of the loss
 #pragma unroll
     for (int w = 0; w < AB_MAX_OUTPUTS; ++w) {
         dv[w] *= f;
         if (w < a.n_out && lane == 0) a.dout[r * a.n_out + w] = dv[w];
     }
-    for (int c = lane; c < a.H; c += 64) {
-        const float hv = ld_f32<T>(a.h, r * a.H + c);
-        float acc = 0.f;
+    for (int c0 = lane * 8; c0 < a.H; c0 += 512) {
+        float hv[8], acc[8];
+        load8<T>(a.h, r * a.H + c0, hv);
 #pragma unroll
-        for (int w = 0; w < AB_MAX_OUTPUTS; ++w)
-            if (w < a.n_out) acc += dv[w] * ld_f32<T>(a.w_out, (int64_t)w * a.H + c);
-        st_T<T>(a.d, r * a.H + c, hv > 0.f ? acc : 0.f);
+        for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+#pragma unroll
+        for (int w = 0; w < AB_MAX_OUTPUTS; ++w) {
+            if (w < a.n_out) {
+                float wv[8];
+                load8<T>(a.w_out, (int64_t)w * a.H + c0, wv);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e] = fmaf(dv[w], wv[e], acc[e]);
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = hv[e] > 0.f ? acc[e] : 0.f;
+        store8<T>(a.d, r * a.H + c0, acc);
     }
 }
 
 // Output layer gradients: block c < H handles column c of the last hidden layer:
 //   gw_out[w, c] = sum_r dout[r, w] h[r, c]  and  d^T[c, r] = (sum_w dout[r, w] W_out[w, c]) [h^T[c, r] > 0];
-// block H reduces the bias gradients sum_r dout[r, w] and the loss.
+// block H + w (w < n_out) reduces the bias gradient sum_r dout[r, w], block H + n_out the loss.
 struct OutGradArgs {
-    const void *ht; const void *w_out; const float *dout; const float *yhat; const float *target;
+    const void *ht; const void *w_out; const float *dout; const float *lossrow;
     void *dt; float *gw_out; float *gb_out; float *loss_out; int64_t B, Bp; int32_t H, n_out, loss_kind;
 };
 __device__ __forceinline__ float block_sum_256(float v, float *sh)      // sh: four floats of LDS
@@ -212,24 +269,43 @@ __device__ __forceinline__ void output_grad_block(const OutGradArgs &a, unsigned
 {
     const int c = (int)id;
     if (c < a.H) {
+        // a thread takes eight adjacent rows per 2048 of column c of h^T (the batch is padded to a multiple of
+        // 64 with zero columns, whose deltas are taken as zero)
         float wv[AB_MAX_OUTPUTS], acc[AB_MAX_OUTPUTS];
 #pragma unroll
         for (int w = 0; w < AB_MAX_OUTPUTS; ++w) {
             wv[w] = w < a.n_out ? ld_f32<T>(a.w_out, (int64_t)w * a.H + c) : 0.f;
             acc[w] = 0.f;
         }
-        for (int64_t r = threadIdx.x; r < a.B; r += 256) {
-            const float hv = ld_f32<T>(a.ht, (int64_t)c * a.Bp + r);
-            float dsum = 0.f;
+        for (int64_t r0 = (int64_t)threadIdx.x * 8; r0 < a.Bp; r0 += 2048) {
+            float hv[8], ds[8];
+            load8<T>(a.ht, (int64_t)c * a.Bp + r0, hv);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ds[e] = 0.f;
+            // (dout is allocated for the padded batch; what lies beyond B is read and discarded)
 #pragma unroll
             for (int w = 0; w < AB_MAX_OUTPUTS; ++w) {
                 if (w < a.n_out) {
-                    const float dv = a.dout[r * a.n_out + w];
-                    acc[w] += dv * hv;
-                    dsum += dv * wv[w];
+                    float dv[8];
+                    if (a.n_out == 1) {
+                        const f32x4 x = *(const f32x4 *)(a.dout + r0), y = *(const f32x4 *)(a.dout + r0 + 4);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) { dv[q] = x[q]; dv[4 + q] = y[q]; }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) dv[e] = a.dout[(r0 + e) * a.n_out + w];
+                    }
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float v = r0 + e < a.B ? dv[e] : 0.f;
+                        acc[w] = fmaf(v, hv[e], acc[w]);
+                        ds[e] = fmaf(v, wv[w], ds[e]);
+                    }
                 }
             }
-            st_T<T>(a.dt, (int64_t)c * a.Bp + r, hv > 0.f ? dsum : 0.f);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ds[e] = hv[e] > 0.f ? ds[e] : 0.f;
+            store8<T>(a.dt, (int64_t)c * a.Bp + r0, ds);
         }
 #pragma unroll
         for (int w = 0; w < AB_MAX_OUTPUTS; ++w) {
@@ -238,24 +314,19 @@ __device__ __forceinline__ void output_grad_block(const OutGradArgs &a, unsigned
                 if (threadIdx.x == 0) a.gw_out[(int64_t)w * a.H + c] = s;
             }
         }
+    } else if (c < a.H + a.n_out) {
+        const int w = c - a.H;
+        float sd = 0.f;
+#pragma unroll 4
+        for (int64_t r = threadIdx.x; r < a.B; r += 256) sd += a.dout[r * a.n_out + w];
+        const float s1 = block_sum_256(sd, sh);
+        if (threadIdx.x == 0) a.gb_out[w] = s1;
     } else {
         float sl = 0.f;
-        for (int64_t r = threadIdx.x; r < a.B; r += 256) {
-            float sq = 0.f;
-            for (int w = 0; w < a.n_out; ++w) {
-                const float e = a.yhat[r * a.n_out + w] - a.target[r * a.n_out + w];
-                sq += e * e;
-            }
-            sl += a.loss_kind == AB_LOSS_L2NORM ? sqrtf(sq) : sq;
-        }
+#pragma unroll 4
+        for (int64_t r = threadIdx.x; r < a.B; r += 256) sl += a.lossrow[r];
         const float s2 = block_sum_256(sl, sh);
         if (threadIdx.x == 0 && a.loss_out) a.loss_out[0] = s2 / (float)a.B;
-        for (int w = 0; w < a.n_out; ++w) {
-            float sd = 0.f;
-            for (int64_t r = threadIdx.x; r < a.B; r += 256) sd += a.dout[r * a.n_out + w];
-            const float s1 = block_sum_256(sd, sh);
-            if (threadIdx.x == 0) a.gb_out[w] = s1;
-        }
     }
 }
 
@@ -486,8 +557,8 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
         AB_HIP(launch_gemm(dt, update_tile(B, p.H[k]), AMODE_LOAD, EPI_STORE, g, st));
     }
     {
-        OutFwdArgs a{ws + p.off_h[D - 1], prm->W[D], prm->b[D], target, yhat, dout, ws + p.off_d[D - 1], B, p.H[D - 1],
-                     p.n_out, d->loss_kind};
+        OutFwdArgs a{ws + p.off_h[D - 1], prm->W[D], prm->b[D], target, yhat, dout, (float *)(ws + p.off_lossrow),
+                     ws + p.off_d[D - 1], B, p.H[D - 1], p.n_out, d->loss_kind};
         TraceScope ts("upd_output_forward", (double)B * p.H[D - 1] * 3.0 * esz, 1, st);
         output_forward_kernel<T><<<(unsigned)((B + 3) / 4), 256, 0, st>>>(a);
         AB_HIP(hipGetLastError());
@@ -543,7 +614,7 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
     auto launch_group = [&](Group &gr, const char *name) -> hipError_t {
         for (int s = gr.n_gemm; s < 2; ++s) gr.a.start[s + 1] = gr.a.start[s];
         unsigned extra = 0;
-        if (gr.a.kind[2] == UJ_OUT_GRAD) extra = (unsigned)gr.a.og.H + 1;
+        if (gr.a.kind[2] == UJ_OUT_GRAD) extra = (unsigned)gr.a.og.H + (unsigned)gr.a.og.n_out + 1;
         else if (gr.a.kind[2] == UJ_BIAS_GRAD) extra = (unsigned)gr.a.bg.l[gr.a.bg.n - 1].start + (unsigned)gr.a.bg.l[gr.a.bg.n - 1].H;
         gr.a.start[3] = gr.a.start[2] + extra;
         if (gr.a.start[3] == 0) return hipSuccess;
@@ -558,7 +629,7 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
         Group gr;
         if (n_dx > 0) AB_HIP(add_gemm(gr, UJ_GEMM_DRELU, dx_args(D - 1), update_tile(B, p.H[D - 2]), "upd_gemm_dx"));
         gr.a.kind[2] = UJ_OUT_GRAD;
-        gr.a.og = OutGradArgs{ws + p.off_ht[D - 1], prm->W[D], dout, yhat, target, ws + p.off_dt[D - 1], gw_out, gb_out,
+        gr.a.og = OutGradArgs{ws + p.off_ht[D - 1], prm->W[D], dout, (const float *)(ws + p.off_lossrow), ws + p.off_dt[D - 1], gw_out, gb_out,
                               loss_out, B, Bp, p.H[D - 1], p.n_out, d->loss_kind};
         gr.bytes = (double)B * p.H[D - 1] * 2.0 * esz;
         AB_HIP(launch_group(gr, n_dx > 0 ? "upd_gemm_dx_outgrad" : "upd_output_grad"));
