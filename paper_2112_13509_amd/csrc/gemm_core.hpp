@@ -133,6 +133,13 @@ __device__ __forceinline__ i32x4 gen_chunk_v(const float *pa, const float *pp, c
     }
 }
 
+// The value another lane holds, by a DPP control word; lanes of rows not in ROW_MASK receive 0.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, false));
+}
+
 template <typename T>
 __device__ __forceinline__ void store_elem(void *base, int64_t idx, float v, int as_f32)
 {
@@ -225,13 +232,29 @@ __device__ __forceinline__ void gemm_tn_tile(const GemmArgs &g, int64_t id, unsi
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    // With fp32 the generated operand is kept raw in registers (its two addends, or the scenario term and
+    // the slab's wp / wc chunks) and combined when the slab is written to LDS, after the matrix work of the
+    // slab before: all of a slab's loads are then in flight together instead of being waited for one by one.
+    constexpr bool RAW_GEN = AMODE != AMODE_LOAD && sizeof(T) == 4;
     i32x4 ra[A_CH], rb[B_CH];
+    i32x4 ra2[RAW_GEN && AMODE == AMODE_GEN ? A_CH : 1];
+    f32x4 rwp = {0.f, 0.f, 0.f, 0.f}, rwc = {0.f, 0.f, 0.f, 0.f};
 
     auto load_slab = [&](int kt) {
         const int k0 = kt * BK;
         if constexpr (AMODE == AMODE_LOAD) {
 #pragma unroll
             for (int i = 0; i < A_CH; ++i) ra[i] = *(const i32x4 *)(Ab + a_off[i] + k0);
+        } else if constexpr (RAW_GEN) {
+#pragma unroll
+            for (int i = 0; i < A_CH; ++i) ra[i] = *(const i32x4 *)(g.a_term + a_off[i] + k0);
+            if constexpr (AMODE == AMODE_GEN) {
+#pragma unroll
+                for (int i = 0; i < A_CH; ++i) ra2[i] = *(const i32x4 *)(g.b_term + a2_off[i] + k0);
+            } else {
+                rwp = *(const f32x4 *)(g.wp + ld_cc * EPC + k0);
+                rwc = *(const f32x4 *)(g.wc + ld_cc * EPC + k0);
+            }
         } else if constexpr (AMODE == AMODE_GEN) {
 #pragma unroll
             for (int i = 0; i < A_CH; ++i)
@@ -248,24 +271,63 @@ __device__ __forceinline__ void gemm_tn_tile(const GemmArgs &g, int64_t id, unsi
     auto store_slab = [&](int stage) {
         unsigned char *sa = smem + stage * STAGE_BYTES, *sb = sa + BM * 128;
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i) *(i32x4 *)(sa + st_off[i]) = ra[i];
+        for (int i = 0; i < A_CH; ++i) {
+            i32x4 v = ra[i];
+            if constexpr (RAW_GEN) {
+                const f32x4 a = __builtin_bit_cast(f32x4, ra[i]);
+                f32x4 h;
+                if constexpr (AMODE == AMODE_GEN) {
+                    const f32x4 b = __builtin_bit_cast(f32x4, ra2[i]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) h[e] = relu_keep_nan(a[e] + b[e]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) h[e] = relu_keep_nan(fmaf(rwc[e], gx_c[i], fmaf(rwp[e], gx_p[i], a[e])));
+                }
+                v = __builtin_bit_cast(i32x4, h);
+            }
+            *(i32x4 *)(sa + st_off[i]) = v;
+        }
 #pragma unroll
         for (int i = 0; i < B_CH; ++i) *(i32x4 *)(sb + st_off[i]) = rb[i];
     };
     auto compute_slab = [&](int stage) {
         const unsigned char *sa = smem + stage * STAGE_BYTES + a_rd_base;
         const unsigned char *sb = smem + stage * STAGE_BYTES + b_rd_base;
+        if constexpr (sizeof(T) == 4 && WMB * WNB == 16) {
+            // one wavefront per SIMD here, so nothing else hides the LDS latency: the operands of quarter q + 1
+            // are requested before the matrix instructions of quarter q (two register sets)
+            i32x4 fa[2][WMB], fb[2][WNB];
+            auto fetch = [&](int q, int set) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            i32x4 fa[WMB], fb[WNB];
+                for (int i = 0; i < WMB; ++i) fa[set][i] = *(const i32x4 *)(sa + i * 4096 + rd_off[q]);
 #pragma unroll
-            for (int i = 0; i < WMB; ++i) fa[i] = *(const i32x4 *)(sa + i * 4096 + rd_off[q]);
+                for (int j = 0; j < WNB; ++j) fb[set][j] = *(const i32x4 *)(sb + j * 4096 + rd_off[q]);
+            };
+            fetch(0, 0);
 #pragma unroll
-            for (int j = 0; j < WNB; ++j) fb[j] = *(const i32x4 *)(sb + j * 4096 + rd_off[q]);
+            for (int q = 0; q < 4; ++q) {
+                if (q < 3) fetch(q + 1, (q + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < WMB; ++i)
+                for (int i = 0; i < WMB; ++i)
 #pragma unroll
-                for (int j = 0; j < WNB; ++j) mma_chunk<T>(fa[i], fb[j], acc[i][j]);
+                    for (int j = 0; j < WNB; ++j) mma_chunk<T>(fa[q & 1][i], fb[q & 1][j], acc[i][j]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                i32x4 fa[WMB], fb[WNB];
+#pragma unroll
+                for (int i = 0; i < WMB; ++i) fa[i] = *(const i32x4 *)(sa + i * 4096 + rd_off[q]);
+#pragma unroll
+                for (int j = 0; j < WNB; ++j) fb[j] = *(const i32x4 *)(sb + j * 4096 + rd_off[q]);
+#pragma unroll
+                for (int i = 0; i < WMB; ++i)
+#pragma unroll
+                    for (int j = 0; j < WNB; ++j) mma_chunk<T>(fa[i], fb[j], acc[i][j]);
+            }
         }
     };
 
@@ -361,13 +423,16 @@ __device__ __forceinline__ void gemm_tn_tile(const GemmArgs &g, int64_t id, unsi
         for (int i = 0; i < WMB; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
+                // sum over the 32 lanes of a half (one row's columns) by DPP exchanges, no LDS round trips:
+                // within a row of sixteen lanes every lane ends up with the row's sum, then lanes 16..31 of a
+                // half take in the sum of lanes 0..15
                 float v = rs[i][r];
-                v += __shfl_xor(v, 1, 64);
-                v += __shfl_xor(v, 2, 64);
-                v += __shfl_xor(v, 4, 64);
-                v += __shfl_xor(v, 8, 64);
-                v += __shfl_xor(v, 16, 64);
-                if ((lane & 31) == 0) red[wave_n * BM + row_l0 + i * 32 + (r >> 2) * 8 + (r & 3)] = v;
+                v += dpp_move<0xB1>(v);          // quad_perm 1,0,3,2
+                v += dpp_move<0x4E>(v);          // quad_perm 2,3,0,1
+                v += dpp_move<0x141>(v);         // row_half_mirror
+                v += dpp_move<0x140>(v);         // row_mirror
+                v += dpp_move<0x142, 0xA>(v);    // row_bcast:15 into the odd rows of sixteen
+                if ((lane & 31) == 31) red[wave_n * BM + row_l0 + i * 32 + (r >> 2) * 8 + (r & 3)] = v;
             }
         __syncthreads();
         if (t < BM && m0 + t < g.M)
