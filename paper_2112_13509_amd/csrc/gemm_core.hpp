@@ -140,6 +140,19 @@ __device__ __forceinline__ float dpp_move(float v)
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, false));
 }
 
+// Sum over the 64 lanes of a wavefront, returned to every lane: four exchanges inside the rows of sixteen, two
+// row broadcasts, one read of lane 63 (no LDS round trips).
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v += dpp_move<0xB1>(v);
+    v += dpp_move<0x4E>(v);
+    v += dpp_move<0x141>(v);
+    v += dpp_move<0x140>(v);
+    v += dpp_move<0x142, 0xA>(v);    // row_bcast:15
+    v += dpp_move<0x143, 0xC>(v);    // row_bcast:31
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+
 template <typename T>
 __device__ __forceinline__ void store_elem(void *base, int64_t idx, float v, int as_f32)
 {

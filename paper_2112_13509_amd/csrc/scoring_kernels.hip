@@ -439,10 +439,7 @@ __global__ __launch_bounds__(256) void score_tiny_kernel(const TinyArgs a)
             for (int u = 0; u < 4; ++u) acc[u] = fmaf(load_as_f32<T>(a.W[0], (int64_t)(j0 + u) * a.F + i), x, acc[u]);
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-#pragma unroll
-            for (int m = 32; m >= 1; m >>= 1) acc[u] += __shfl_xor(acc[u], m, 64);
-        }
+        for (int u = 0; u < 4; ++u) acc[u] = wave_sum(acc[u]);
         if (lane < 4) {
             const int j = j0 + lane;
             const float av = lane == 0 ? acc[0] : lane == 1 ? acc[1] : lane == 2 ? acc[2] : acc[3];
@@ -599,8 +596,7 @@ __global__ __launch_bounds__(256) void score_single_hidden_kernel(const ScoreD1A
         for (int h = lane; h < a.H; h += 64)
             acc += relu_keep_nan(a.a_term[s * a.H + h] + a.b_term[(int64_t)c * a.H + h]) * a.w_out_f[h];
     }
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+    acc = wave_sum(acc);
     if (lane == 0) a.partial[row] = acc;
 }
 

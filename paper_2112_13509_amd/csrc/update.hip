@@ -210,9 +210,7 @@ __global__ __launch_bounds__(256) void output_forward_kernel(const OutFwdArgs a)
 #pragma unroll
     for (int w = 0; w < AB_MAX_OUTPUTS; ++w) {
         if (w < a.n_out) {
-            float acc = dv[w];
-#pragma unroll
-            for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+            const float acc = wave_sum(dv[w]);
             const float yh = acc + a.b_out[w];
             if (lane == 0) a.yhat[r * a.n_out + w] = yh;
             dv[w] = yh - a.target[r * a.n_out + w];
@@ -256,8 +254,7 @@ struct OutGradArgs {
 };
 __device__ __forceinline__ float block_sum_256(float v, float *sh)      // sh: four floats of LDS
 {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    v = wave_sum(v);
     if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
     __syncthreads();
     const float r = (sh[0] + sh[1]) + (sh[2] + sh[3]);
