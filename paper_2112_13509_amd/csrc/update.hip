@@ -338,8 +338,12 @@ __device__ __forceinline__ void bias_grad_block(const BiasGradArgs &a, unsigned 
     int k = 0;
     while (k + 1 < a.n && (int)id >= a.l[k + 1].start) ++k;
     const int c = (int)id - a.l[k].start;
-    float acc = 0.f;
-    for (int64_t r = threadIdx.x; r < a.B; r += 256) acc += ld_f32<T>(a.l[k].dt, (int64_t)c * a.Bp + r);
+    float acc = 0.f;                 // (the padding columns of d^T beyond B are zero)
+    for (int64_t r0 = (int64_t)threadIdx.x * 8; r0 < a.Bp; r0 += 2048) {
+        float v[8];
+        load8<T>(a.l[k].dt, (int64_t)c * a.Bp + r0, v);
+        acc += ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+    }
     const float s = block_sum_256(acc, sh);
     if (threadIdx.x == 0) a.l[k].gb[c] = s;
 }
@@ -460,32 +464,54 @@ struct AdamArgs {
     int n;
     struct Tn {
         float *w, *m, *v; void *w_compute;        // master, moments, compute-type copy (NULL for biases)
-        const float *g; int rows, cols, ldg, splits; int64_t split_stride;
-        int64_t start;
+        const float *g; int rows, cols, ldg, splits, vw; int64_t split_stride;
+        int64_t start;                            // in threads: a thread takes vw adjacent elements
     } tn[2 * (AB_MAX_HIDDEN + 1)];
     int64_t total;
     const float *scal;                            // {1 - beta1^t, 1 - beta2^t}
     float lr, beta1, beta2, eps;
 };
+// VW adjacent elements of one tensor (VW divides the row length, so they share a row of the gradient buffer).
+template <typename T, int VW>
+__device__ __forceinline__ void adam_elems(const AdamArgs &a, const AdamArgs::Tn &tn, int64_t e)
+{
+    typedef __attribute__((ext_vector_type(VW))) float vec;
+    const uint32_t r = (uint32_t)e / (uint32_t)tn.cols, c = (uint32_t)e - r * (uint32_t)tn.cols;
+    vec g = *(const vec *)(tn.g + (int64_t)r * tn.ldg + c);
+    for (int s = 1; s < tn.splits; ++s) g += *(const vec *)(tn.g + s * tn.split_stride + (int64_t)r * tn.ldg + c);
+    vec m = *(const vec *)(tn.m + e), v = *(const vec *)(tn.v + e), w = *(const vec *)(tn.w + e);
+    const float c1 = a.scal[0], c2 = a.scal[1];
+#pragma unroll
+    for (int q = 0; q < VW; ++q) {
+        m[q] = a.beta1 * m[q] + (1.f - a.beta1) * g[q];
+        v[q] = a.beta2 * v[q] + (1.f - a.beta2) * g[q] * g[q];
+        w[q] = w[q] - a.lr * (m[q] / c1) / (sqrtf(v[q] / c2) + a.eps);
+    }
+    *(vec *)(tn.m + e) = m;
+    *(vec *)(tn.v + e) = v;
+    *(vec *)(tn.w + e) = w;
+    if (tn.w_compute) {
+        if constexpr (sizeof(T) == 2 && VW >= 2) {
+#pragma unroll
+            for (int q = 0; q < VW; q += 2) ((uint32_t *)tn.w_compute)[(e + q) >> 1] = pack_bf16x2(w[q], w[q + 1]);
+        } else {
+#pragma unroll
+            for (int q = 0; q < VW; ++q) st_T<T>(tn.w_compute, e + q, w[q]);
+        }
+    }
+}
 template <typename T>
 __global__ __launch_bounds__(256) void adam_kernel(const AdamArgs a)
 {
-    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;       // one thread per group of tn.vw elements
     if (gid >= a.total) return;
     int j = 0;
     while (j + 1 < a.n && gid >= a.tn[j + 1].start) ++j;
     const AdamArgs::Tn &tn = a.tn[j];
-    const int64_t e = gid - tn.start;
-    const int r = (int)(e / tn.cols), c = (int)(e % tn.cols);
-    float g = 0.f;
-    for (int s = 0; s < tn.splits; ++s) g += tn.g[s * tn.split_stride + (int64_t)r * tn.ldg + c];
-    const float m = a.beta1 * tn.m[e] + (1.f - a.beta1) * g;
-    const float v = a.beta2 * tn.v[e] + (1.f - a.beta2) * g * g;
-    tn.m[e] = m;
-    tn.v[e] = v;
-    const float w = tn.w[e] - a.lr * (m / a.scal[0]) / (sqrtf(v / a.scal[1]) + a.eps);
-    tn.w[e] = w;
-    if (tn.w_compute) st_T<T>(tn.w_compute, e, w);
+    const int64_t e = (gid - tn.start) * tn.vw;
+    if (tn.vw == 4) adam_elems<T, 4>(a, tn, e);
+    else if (tn.vw == 2) adam_elems<T, 2>(a, tn, e);
+    else adam_elems<T, 1>(a, tn, e);
 }
 
 template <typename T>
@@ -663,7 +689,12 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
                        int splits, int64_t stride) {
             AdamArgs::Tn &t = a.tn[a.n++];
             t.w = w; t.m = m; t.v = v; t.w_compute = wc; t.g = g; t.rows = rows; t.cols = cols; t.ldg = ldg;
-            t.splits = splits; t.split_stride = stride; t.start = start; start += (int64_t)rows * cols;
+            t.splits = splits; t.split_stride = stride;
+            // widest vector that divides the row length and the gradient rows' pitch and that every pointer is aligned to
+            const uintptr_t ptrs = (uintptr_t)w | (uintptr_t)m | (uintptr_t)v | (uintptr_t)g | (uintptr_t)wc;
+            t.vw = (cols % 4 == 0 && ldg % 4 == 0 && stride % 4 == 0 && ptrs % 16 == 0) ? 4
+                 : (cols % 2 == 0 && ldg % 2 == 0 && stride % 2 == 0 && ptrs % 8 == 0) ? 2 : 1;
+            t.start = start; start += (int64_t)rows * cols / t.vw;
         };
         for (int k = k0; k < D; ++k) {
             const int cols = (k == 0) ? p.F : p.H[k - 1];
@@ -674,7 +705,9 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
         add(prm->W_master[D], prm->adam_mW[D], prm->adam_vW[D], (void *)prm->W[D], gw_out, p.n_out, p.H[D - 1], p.H[D - 1], 1, 0);
         add(prm->b[D], prm->adam_mb[D], prm->adam_vb[D], nullptr, gb_out, 1, p.n_out, p.n_out, 1, 0);
         a.total = start; a.scal = scal; a.lr = lr; a.beta1 = beta1; a.beta2 = beta2; a.eps = eps;
-        TraceScope ts("upd_adam", (double)start * (28.0 + esz), 1, st);
+        double n_param = 0.0;
+        for (int i = 0; i < a.n; ++i) n_param += (double)a.tn[i].rows * a.tn[i].cols;
+        TraceScope ts("upd_adam", n_param * (28.0 + esz), 1, st);
         adam_kernel<T><<<(unsigned)((start + 255) / 256), 256, 0, st>>>(a);
         AB_HIP(hipGetLastError());
     }
