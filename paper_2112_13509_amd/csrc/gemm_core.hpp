@@ -344,6 +344,22 @@ __device__ __forceinline__ void gemm_tn_tile(const GemmArgs &g, int64_t id, unsi
         }
     };
 
+    const int row_l0 = wave_m * (WMB * 32) + half * 4;        // + i*32 + (r>>2)*8 + (r&3)
+    const int col_l0 = wave_n * (WNB * 32) + (lane & 31);     // + j*32
+    // What the epilogue of the 64 x 64 tile needs from memory is requested before the K loop (these launches are
+    // short chains of memory round trips): the bias, or the sixteen mask values of this lane.
+    constexpr bool PRE = WMB * WNB == 1 && (EPI == EPI_STORE || EPI == EPI_DRELU);
+    float pre_bias = 0.f, pre_mask[PRE && EPI == EPI_DRELU ? 16 : 1];
+    if constexpr (PRE && EPI == EPI_STORE) pre_bias = g.bias ? g.bias[n0 + col_l0] : 0.f;
+    if constexpr (PRE && EPI == EPI_DRELU) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int64_t row = min(m0 + row_l0 + (q >> 2) * 8 + (q & 3), g.M - 1);
+            if constexpr (sizeof(T) == 2) pre_mask[q] = bf16_bits_to_f32(((const uint16_t *)g.mask)[row * g.ldmask + n0 + col_l0]);
+            else pre_mask[q] = ((const float *)g.mask)[row * g.ldmask + n0 + col_l0];
+        }
+    }
+
     if (kt_begin < kt_end) {
         load_slab(kt_begin);
         store_slab(0);
@@ -358,8 +374,6 @@ __device__ __forceinline__ void gemm_tn_tile(const GemmArgs &g, int64_t id, unsi
     }
 
     // ---------------------------------------------------------------- epilogues
-    const int row_l0 = wave_m * (WMB * 32) + half * 4;        // + i*32 + (r>>2)*8 + (r&3)
-    const int col_l0 = wave_n * (WNB * 32) + (lane & 31);     // + j*32
     if constexpr (EPI == EPI_STORE || EPI == EPI_DRELU || EPI == EPI_SPLITK) {
         float *out_split = nullptr;
         if constexpr (EPI == EPI_SPLITK) out_split = (float *)g.out + (int64_t)split * g.split_stride;
@@ -367,7 +381,7 @@ __device__ __forceinline__ void gemm_tn_tile(const GemmArgs &g, int64_t id, unsi
         for (int j = 0; j < WNB; ++j) {
             const int col = n0 + col_l0 + j * 32;
             float bv = 0.f;
-            if constexpr (EPI == EPI_STORE) bv = g.bias ? g.bias[col] : 0.f;
+            if constexpr (EPI == EPI_STORE) { if constexpr (PRE) bv = pre_bias; else bv = g.bias ? g.bias[col] : 0.f; }
 #pragma unroll
             for (int i = 0; i < WMB; ++i)
 #pragma unroll
@@ -383,7 +397,9 @@ __device__ __forceinline__ void gemm_tn_tile(const GemmArgs &g, int64_t id, unsi
                             v[e] += bv;
                             if (g.relu) v[e] = relu_keep_nan(v[e]);
                         } else if constexpr (EPI == EPI_DRELU) {
-                            if (row < g.M) {
+                            if constexpr (PRE) {
+                                v[e] = pre_mask[rg * 4 + e] > 0.f ? v[e] : 0.f;
+                            } else if (row < g.M) {
                                 float mk;
                                 if constexpr (sizeof(T) == 2)
                                     mk = bf16_bits_to_f32(((const uint16_t *)g.mask)[row * g.ldmask + col]);
