@@ -39,6 +39,10 @@ def run_and_compare(w, label):
     (260, 16, 16, [64, 256, 256], "K = 64: the first hidden GEMM falls back to the one-tile-per-work-group kernel"),
     (70, 32, 32, [1024, 1024], "1024 candidates: four row tiles per scenario"),
     (300, 16, 16, [256, 256, 64, 256], "K = 64 in a stored-operand layer: one slab per tile"),
+    (40, 16, 16, [256, 1280, 256], "five column tiles in a stored layer: bias through the scalar cache, K = 1280 after it"),
+    (40, 16, 16, [256, 256, 1280], "five column tiles in the layer that feeds the output unit"),
+    (40, 16, 16, [1280, 1280], "five column tiles, generated operand with K = 1280 (one tile per work-group) feeding the output unit"),
+    (150, 16, 16, [512, 1024, 512], "four and two column tiles: bias and output weights in registers, tiles change column block"),
 ])
 def test_streaming_gemm_corner_shapes(S, P, Q, hidden, label):
     w = wl.make_scoring("stream-shapes", S, 16, hidden, P, Q, 16 * wl.KIB, 64 * wl.MIB, 1.0, 64.0, False, "bf16",
