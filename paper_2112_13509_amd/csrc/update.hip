@@ -280,23 +280,42 @@ __device__ __forceinline__ void output_grad_block(const OutGradArgs &a, unsigned
 #pragma unroll
             for (int e = 0; e < 8; ++e) ds[e] = 0.f;
             // (dout is allocated for the padded batch; what lies beyond B is read and discarded)
+            if ((a.n_out & 3) == 0) {          // four outputs of a row per 16-byte load
 #pragma unroll
-            for (int w = 0; w < AB_MAX_OUTPUTS; ++w) {
-                if (w < a.n_out) {
-                    float dv[8];
-                    if (a.n_out == 1) {
-                        const f32x4 x = *(const f32x4 *)(a.dout + r0), y = *(const f32x4 *)(a.dout + r0 + 4);
+                for (int e = 0; e < 8; ++e) {
+                    const float live = r0 + e < a.B ? 1.f : 0.f;
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) { dv[q] = x[q]; dv[4 + q] = y[q]; }
-                    } else {
+                    for (int w4 = 0; w4 < AB_MAX_OUTPUTS / 4; ++w4) {
+                        if (w4 * 4 < a.n_out) {
+                            const f32x4 dv = *(const f32x4 *)(a.dout + (r0 + e) * a.n_out + w4 * 4);
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) dv[e] = a.dout[(r0 + e) * a.n_out + w];
+                            for (int q = 0; q < 4; ++q) {
+                                const float v = live != 0.f ? dv[q] : 0.f;
+                                acc[w4 * 4 + q] = fmaf(v, hv[e], acc[w4 * 4 + q]);
+                                ds[e] = fmaf(v, wv[w4 * 4 + q], ds[e]);
+                            }
+                        }
                     }
+                }
+            } else {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float v = r0 + e < a.B ? dv[e] : 0.f;
-                        acc[w] = fmaf(v, hv[e], acc[w]);
-                        ds[e] = fmaf(v, wv[w], ds[e]);
+                for (int w = 0; w < AB_MAX_OUTPUTS; ++w) {
+                    if (w < a.n_out) {
+                        float dv[8];
+                        if (a.n_out == 1) {
+                            const f32x4 x = *(const f32x4 *)(a.dout + r0), y = *(const f32x4 *)(a.dout + r0 + 4);
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) { dv[q] = x[q]; dv[4 + q] = y[q]; }
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) dv[e] = a.dout[(r0 + e) * a.n_out + w];
+                        }
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const float v = r0 + e < a.B ? dv[e] : 0.f;
+                            acc[w] = fmaf(v, hv[e], acc[w]);
+                            ds[e] = fmaf(v, wv[w], ds[e]);
+                        }
                     }
                 }
             }
