@@ -310,28 +310,37 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import oracle as orc
         if cfg == 4:
-            n_rows = 1024
+            n_steps = 32                                  # whole minibatches: about ten seconds of CPU work
             st = orc.TrainState.fresh(u.W, u.b)
-            rows = u.batch_indices(0)[:n_rows]
+            om = oracle_model(orc, np, u)
             t0 = time.perf_counter()
-            orc.update(oracle_model(orc, np, u), st, u.x_raw[rows], u.target[rows], want_grads=False)
+            for k in range(n_steps):
+                rows = u.batch_indices(k)
+                orc.update(om, st, u.x_raw[rows], u.target[rows], want_grads=False)
             dt = time.perf_counter() - t0
-            cpu = {"value": n_rows / dt, "unit": unit, "cores": orc.num_threads(), "kind": "oracle",
-                   "sample": "one fp64 step on the first %d rows of minibatch 0 (%.1f s)" % (n_rows, dt)}
+            cpu = {"value": n_steps * u.batch / dt, "unit": unit, "cores": orc.num_threads(), "kind": "oracle",
+                   "sample": "%d fp64 steps on the first %d minibatches of %d rows (%.1f s)" % (n_steps, n_steps, u.batch, dt)}
         else:
-            n_s = {1: 1, 2: 8, 3: 96, 5: 24, 6: 24}[cfg]
+            n_s = {1: 1, 2: 768, 3: 512, 5: 1200, 6: 1200}[cfg]       # sized for 10-20 s of CPU work on 16 cores
             n_s = min(n_s, w.S)
             sub = w.subset(np.arange(n_s))
+            reps = 2000 if cfg == 1 else 1                # the tiny workload is repeated to get a measurable time
+            om = oracle_model(orc, np, sub)
             t0 = time.perf_counter()
-            ref = orc.score(oracle_model(orc, np, sub), sub.dyn, sub.scal, sub.part, sub.cred)
-            ridx, _, _ = orc.select(ref)
+            for _ in range(reps):
+                ref = orc.score(om, sub.dyn, sub.scal, sub.part, sub.cred)
+                ridx, _, _ = orc.select(ref)
             dt = time.perf_counter() - t0
-            cpu = {"value": n_s * w.C / dt, "unit": unit, "cores": orc.num_threads(), "kind": "oracle",
-                   "sample": "first %d scenarios x all %d candidates, fp64, unfactorised (%.1f s)" % (n_s, w.C, dt)}
+            cpu = {"value": reps * n_s * w.C / dt, "unit": unit, "cores": orc.num_threads(), "kind": "oracle",
+                   "sample": "first %d scenarios x all %d candidates%s, fp64, unfactorised (%.1f s)"
+                             % (n_s, w.C, ", %d times" % reps if reps > 1 else "", dt)}
             if want_scores:
+                # the parity tests' two measures on this sample: per-tensor (the bar: 1e-4 fp32, 2e-2 bf16) and the
+                # strict per-scenario one (bf16 is held to 5e-2 there)
                 got = scores[:n_s].cpu().numpy().astype(np.float64)
                 scale = np.maximum(np.abs(ref).max(axis=1, keepdims=True), np.sqrt(np.mean(ref ** 2)))
-                cpu["gpu_vs_oracle_max_scaled_err"] = float((np.abs(got - ref) / scale).max())
+                cpu["gpu_vs_oracle_err_per_tensor"] = float(np.abs(got - ref).max() / np.abs(ref).max())
+                cpu["gpu_vs_oracle_err_strict_per_scenario"] = float((np.abs(got - ref) / scale).max())
 
     out = {"metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": steps, "warmup": warmup,
            "ms_per_step": ms_per_step, "ms_per_step_wall": ms_wall, "higher_is_better": True, "scaling": "weak",
