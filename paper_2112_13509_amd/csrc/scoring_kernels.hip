@@ -603,11 +603,12 @@ __global__ __launch_bounds__(256) void score_single_hidden_kernel(const ScoreD1A
 // ------------------------------------------------------------------------------------------------
 // Shared per-tensor encoder (Section 3.1 "Meta network architecture": the layer-wise statistics are
 // embedded into a fixed-dimension feature space so that models with different layer counts can be
-// handled).  One work-group per scenario:
+// handled).  A work-group takes scenarios blockIdx.x, blockIdx.x + gridDim.x, ... (two work-groups per CU):
 //   e[l] = relu(W_b relu(W_a phi(stat[l]) + b_a) + b_b)   (K -> 128 on the vector ALUs, 128 -> 128 on
 //   the matrix cores), pooled[s] = mean_l e[l], written as the first 128 columns of the scenario row.
 // W_b (bf16, 32 KB) is staged once per work-group in LDS.  After that the four wavefronts work on
-// their own 32-tensor blocks without meeting: a wavefront transforms its block's statistics, runs
+// their own 32-tensor blocks without meeting, each block's raw statistics fetched while the block before
+// is computed: a wavefront transforms its block's statistics, runs
 // the first layer (a lane owns two of the 128 units, weights in registers), parks the bf16 result in
 // its private 8 KB of LDS, multiplies it with W_b (32 matrix instructions) and adds relu(. + b_b) of the
 // valid tensors to per-lane column sums.  One reduction over the wavefronts at the end.
@@ -620,6 +621,7 @@ struct TensorEncArgs {
     const void *Wb; const float *bb;     // [128, 128]
     void *xs; int32_t ld;                // scenario rows; columns [0,128) written here
     const int32_t *layers_of;            // [S] or NULL: layers the scenario really has (clamped to [1, L])
+    int64_t S;
     ab_enc enc_stat[AB_MAX_STATS];
 };
 
@@ -633,11 +635,12 @@ __global__ __launch_bounds__(256) void tensor_encoder_kernel(const TensorEncArgs
     __shared__ __attribute__((aligned(16))) float wa_s[H * AB_MAX_STATS];       // [unit][AB_MAX_STATS], zero padded
     __shared__ float ba_s[H];
     __shared__ float red[4][H];
-    const int64_t s = blockIdx.x;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, half = lane >> 5, l31 = lane & 31;
-    const float *dyn = a.dyn + s * (int64_t)a.L * a.K;
-    int Ls = a.L;                                           // this scenario's own layer count
-    if (a.layers_of) { Ls = a.layers_of[s]; Ls = Ls < 1 ? 1 : (Ls > a.L ? a.L : Ls); }
+    auto layers = [&](int64_t sc) {                        // a scenario's own layer count
+        int n = a.L;
+        if (a.layers_of) { n = a.layers_of[sc]; n = n < 1 ? 1 : (n > a.L ? a.L : n); }
+        return n;
+    };
 
     for (int i = t; i < H * AB_MAX_STATS; i += 256) {
         const int o = i / AB_MAX_STATS, k = i % AB_MAX_STATS;
@@ -671,11 +674,42 @@ __global__ __launch_bounds__(256) void tensor_encoder_kernel(const TensorEncArgs
     }
     const float ba0 = ba_s[2 * lane], ba1 = ba_s[2 * lane + 1];
 
-    for (int l0 = wave * 32; l0 < Ls; l0 += 128) {
+    // this lane's slots of a block's statistics: element i = lane + 64 j of [32 tensors][AB_MAX_STATS], i.e.
+    // tensor (lane >> 3) + 8 j, statistic lane & 7 (the same statistic for all four: one transform)
+    const int my_k = lane & (AB_MAX_STATS - 1);
+    const ab_enc my_enc = a.enc_stat[my_k];
+    auto fetch_raw = [&](int64_t sc, int n_layers, int l0, float (&raw)[4]) {
+        const float *dyn = a.dyn + sc * (int64_t)a.L * a.K;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int l = l0 + (lane >> 3) + 8 * j;
+            raw[j] = (sc < a.S && l < n_layers && my_k < a.K) ? dyn[(int64_t)l * a.K + my_k] : 1.f;
+        }
+    };
+
+    int64_t sc = blockIdx.x;
+    int Ls = sc < a.S ? layers(sc) : 0;
+    int l0 = wave * 32;
+    float raw[4];
+    fetch_raw(sc, Ls, l0, raw);
+    for (; sc < a.S; ) {
+      const bool has_block = l0 < Ls;                        // (its last block fetches the next scenario's first)
+      for (; l0 < Ls; ) {
+        // the block after this one (of this scenario, or the first of this wavefront in the next scenario)
+        int64_t sc_n = sc;
+        int Ls_n = Ls, l0_n = l0 + 128;
+        if (l0_n >= Ls) { sc_n = sc + gridDim.x; Ls_n = sc_n < a.S ? layers(sc_n) : 0; l0_n = wave * 32; }
+        float raw_n[4];
+        fetch_raw(sc_n, Ls_n, l0_n, raw_n);
         // transformed statistics of the block's 32 tensors (zero rows past the end)
-        for (int i = lane; i < 32 * AB_MAX_STATS; i += 64) {
-            const int r = i / AB_MAX_STATS, k = i % AB_MAX_STATS, l = l0 + r;
-            xw[i] = (l < Ls && k < a.K) ? phi(dyn[(int64_t)l * a.K + k], a.enc_stat[k]) : 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int l = l0 + (lane >> 3) + 8 * j;
+            float lg;
+            if constexpr (sizeof(T) == 2) lg = __builtin_amdgcn_logf(raw[j]) * 0.69314718056f;
+            else lg = logf(raw[j]);
+            const float y = ((my_enc.kind == AB_ENC_LOG ? lg : raw[j]) - my_enc.shift) * my_enc.scale;
+            xw[lane + 64 * j] = (l < Ls && my_k < a.K) ? y : 0.f;
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // same wavefront: LDS ops are in order
         // first layer: this lane owns units 2*lane and 2*lane+1 (weights in registers) for all 32 tensors;
@@ -721,18 +755,29 @@ __global__ __launch_bounds__(256) void tensor_encoder_kernel(const TensorEncArgs
             }
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // fragment reads done before the block buffer is reused
-    }
 #pragma unroll
-    for (int jn = 0; jn < 4; ++jn) {
-        const float v = colsum[jn] + __shfl_xor(colsum[jn], 32, 64);
-        if (half == 0) red[wave][jn * 32 + l31] = v;
-    }
-    __syncthreads();
-    if (t < H) {
-        const float pooled = ((red[0][t] + red[1][t]) + (red[2][t] + red[3][t])) / (float)Ls;
-        const int64_t o = s * a.ld + t;
-        if constexpr (sizeof(T) == 2) ((uint16_t *)a.xs)[o] = (uint16_t)(pack_bf16x2(pooled, 0.f) & 0xffffu);
-        else ((float *)a.xs)[o] = pooled;
+        for (int j = 0; j < 4; ++j) raw[j] = raw_n[j];
+        l0 += 128;
+      }
+      // the scenario is complete for this wavefront: combine the four wavefronts' column sums
+#pragma unroll
+      for (int jn = 0; jn < 4; ++jn) {
+          const float v = colsum[jn] + __shfl_xor(colsum[jn], 32, 64);
+          if (half == 0) red[wave][jn * 32 + l31] = v;
+          colsum[jn] = 0.f;
+      }
+      __syncthreads();
+      if (t < H) {
+          const float pooled = ((red[0][t] + red[1][t]) + (red[2][t] + red[3][t])) / (float)Ls;
+          const int64_t o = sc * a.ld + t;
+          if constexpr (sizeof(T) == 2) ((uint16_t *)a.xs)[o] = (uint16_t)(pack_bf16x2(pooled, 0.f) & 0xffffu);
+          else ((float *)a.xs)[o] = pooled;
+      }
+      __syncthreads();                                       // `red` may be written again
+      sc += gridDim.x;
+      Ls = sc < a.S ? layers(sc) : 0;
+      l0 = wave * 32;
+      if (!has_block) fetch_raw(sc, Ls, l0, raw);
     }
 }
 
@@ -1124,10 +1169,15 @@ hipError_t launch_tensor_encoder(int dtype, const ab_model_desc *d, const float 
     TensorEncArgs a;
     a.layers_of = layers_of;
     a.dyn = dyn; a.L = d->n_layers; a.K = d->n_stats; a.Wa = Wa; a.ba = ba; a.Wb = Wb; a.bb = bb;
-    a.xs = xs; a.ld = ld;
+    a.xs = xs; a.ld = ld; a.S = S;
     for (int i = 0; i < AB_MAX_STATS; ++i) a.enc_stat[i] = d->enc_stat[i];
-    if (dtype == AB_BF16) tensor_encoder_kernel<bf16_t><<<(unsigned)S, 256, 0, st>>>(a);
-    else tensor_encoder_kernel<float><<<(unsigned)S, 256, 0, st>>>(a);
+    int dev = 0, cus = 0;
+    hipError_t e;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+    const int64_t grid = S < 2 * (int64_t)cus ? S : 2 * (int64_t)cus;      // two work-groups fit a CU's LDS
+    if (dtype == AB_BF16) tensor_encoder_kernel<bf16_t><<<(unsigned)grid, 256, 0, st>>>(a);
+    else tensor_encoder_kernel<float><<<(unsigned)grid, 256, 0, st>>>(a);
     return hipGetLastError();
 }
 
