@@ -293,19 +293,30 @@ __global__ __launch_bounds__(256) void finish_select_wave_kernel(const FinishArg
     float bv = -INFINITY;
     int bi = AB_NONE;
     {
+        // four candidates of this lane at a time, their loads issued together
         typedef __attribute__((ext_vector_type(NT))) float vec_t;
-        for (int c = lane; c < a.C; c += 64) {
-            float v;
-            if constexpr (NT == 1) v = __builtin_nontemporal_load(p + c);
-            else {
-                const vec_t x = __builtin_nontemporal_load((const vec_t *)(p + (int64_t)c * NT));
-                v = x[0];
+        for (int c0 = lane; c0 < a.C; c0 += 256) {
+            vec_t x[4];
 #pragma unroll
-                for (int t = 1; t < NT; ++t) v += x[t];
+            for (int u = 0; u < 4; ++u) {
+                const int c = c0 + 64 * u;
+                if (c < a.C) {
+                    if constexpr (NT == 1) x[u] = vec_t(__builtin_nontemporal_load(p + c));
+                    else x[u] = __builtin_nontemporal_load((const vec_t *)(p + (int64_t)c * NT));
+                }
             }
-            v += b;
-            if (a.scores) a.scores[s * a.score_stride + c] = v;
-            amax_take(bv, bi, v, c);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int c = c0 + 64 * u;
+                if (c < a.C) {
+                    float v = x[u][0];
+#pragma unroll
+                    for (int t = 1; t < NT; ++t) v += x[u][t];
+                    v += b;
+                    if (a.scores) a.scores[s * a.score_stride + c] = v;
+                    amax_take(bv, bi, v, c);
+                }
+            }
         }
     }
     if (!a.best_idx) return;
