@@ -259,12 +259,29 @@ __global__ __launch_bounds__(256) void finish_select_kernel(const FinishArgs a)
     const float b = a.b_out ? a.b_out[0] : 0.f;
     float bv = -INFINITY;
     int bi = AB_NONE;
-    for (int c = threadIdx.x; c < a.C; c += 256) {
-        float v = p[(int64_t)c * a.nt];
-        for (int t = 1; t < a.nt; ++t) v += p[(int64_t)c * a.nt + t];
-        v += b;
-        if (a.scores) a.scores[s * a.score_stride + c] = v;
-        amax_take(bv, bi, v, c);
+    for (int c0 = threadIdx.x; c0 < a.C; c0 += 1024) {      // four candidates per thread at a time, loads together
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + 256 * u;
+            v[u] = c < a.C ? p[(int64_t)c * a.nt] : 0.f;
+        }
+        for (int t = 1; t < a.nt; ++t) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int c = c0 + 256 * u;
+                if (c < a.C) v[u] += p[(int64_t)c * a.nt + t];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + 256 * u;
+            if (c < a.C) {
+                const float x = v[u] + b;
+                if (a.scores) a.scores[s * a.score_stride + c] = x;
+                amax_take(bv, bi, x, c);
+            }
+        }
     }
     if (!a.best_idx) return;
     amax_wave(bv, bi);

@@ -399,14 +399,21 @@ __device__ __forceinline__ void encode_rows_block(const EncodeRowsArgs &a, unsig
                           : j == a.F - 2 ? &a.enc_part : &a.enc_cred;
         e[q] = *src;
     }
+    float raw0[8], raw1[8];                       // all of the thread's loads first: eight rows x two columns
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int64_t row = r0 + rr + 8 * i;
+        raw0[i] = (row < a.B && j0 < a.F) ? a.x_raw[row * a.F + j0] : 1.f;
+        raw1[i] = (row < a.B && j0 + 1 < a.F) ? a.x_raw[row * a.F + j0 + 1] : 1.f;
+    }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int rl = rr + 8 * i;
         const int64_t row = r0 + rl;
         float v0 = 0.f, v1 = 0.f;
         if (row < a.B) {
-            if (j0 < a.F) v0 = phi(a.x_raw[row * a.F + j0], e[0]);
-            if (j0 + 1 < a.F) v1 = phi(a.x_raw[row * a.F + j0 + 1], e[1]);
+            if (j0 < a.F) v0 = phi(raw0[i], e[0]);
+            if (j0 + 1 < a.F) v1 = phi(raw1[i], e[1]);
             const int64_t o = row * a.ld + j0;
             if constexpr (sizeof(T) == 2) ((uint32_t *)a.x)[o >> 1] = pack_bf16x2(v0, v1);
             else ((f32x2 *)a.x)[o >> 1] = f32x2{v0, v1};
