@@ -503,8 +503,21 @@ __device__ __forceinline__ void adam_elems(const AdamArgs &a, const AdamArgs::Tn
 {
     typedef __attribute__((ext_vector_type(VW))) float vec;
     const uint32_t r = (uint32_t)e / (uint32_t)tn.cols, c = (uint32_t)e - r * (uint32_t)tn.cols;
-    vec g = *(const vec *)(tn.g + (int64_t)r * tn.ldg + c);
-    for (int s = 1; s < tn.splits; ++s) g += *(const vec *)(tn.g + s * tn.split_stride + (int64_t)r * tn.ldg + c);
+    // the split-K partial sums (at most eight): eight loads without a branch between them (splits past the last
+    // one read the last one again and are not added), then the sum in split order
+    vec gs[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        const int se = s < tn.splits ? s : tn.splits - 1;
+        gs[s] = *(const vec *)(tn.g + se * tn.split_stride + (int64_t)r * tn.ldg + c);
+    }
+    vec g = gs[0];
+#pragma unroll
+    for (int s = 1; s < 8; ++s) {
+        const vec sum = g + gs[s];
+#pragma unroll
+        for (int q = 0; q < VW; ++q) g[q] = s < tn.splits ? sum[q] : g[q];
+    }
     vec m = *(const vec *)(tn.m + e), v = *(const vec *)(tn.v + e), w = *(const vec *)(tn.w + e);
     const float c1 = a.scal[0], c2 = a.scal[1];
 #pragma unroll
