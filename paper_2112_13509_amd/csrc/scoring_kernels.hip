@@ -438,12 +438,12 @@ __device__ __forceinline__ float as_stored(float v)        // what a value becom
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void score_tiny_kernel(const TinyArgs a)
+__global__ __launch_bounds__(1024) void score_tiny_kernel(const TinyArgs a)
 {
-    constexpr int HM = 128, G = 64, STR = HM + 4, FS_MAX = 2048;
+    constexpr int HM = 128, G = 64, STR = HM + 4, FS_MAX = 2048, NW = 16;   // sixteen wavefronts
     __shared__ float xs[FS_MAX];
     __shared__ float A1[HM], wp[HM], wc[HM];
-    __shared__ float red[4][G];
+    __shared__ float red[NW][G];
     extern __shared__ __attribute__((aligned(16))) float tiny_dyn[];      // two activation buffers, one weight matrix
     float (*hb)[G * STR] = (float (*)[G * STR])tiny_dyn;
     float *w_lds = tiny_dyn + 2 * G * STR;
@@ -453,13 +453,13 @@ __global__ __launch_bounds__(256) void score_tiny_kernel(const TinyArgs a)
 
     // transformed statistics and scalars of the scenario
     const int n_stat = a.L * a.K;
-    for (int i = t; i < a.Fs; i += 256)
+    for (int i = t; i < a.Fs; i += 64 * NW)
         xs[i] = as_stored<T>(i < n_stat ? phi(a.dyn[s * n_stat + i], a.enc_stat[i % a.K])
                                         : phi(a.scal[s * a.Ns + (i - n_stat)], a.enc_scalar[i - n_stat]));
     __syncthreads();
     // scenario term of layer 1 and its two configuration columns
     const int H1 = a.H[0];
-    for (int j0 = wave * 4; j0 < H1; j0 += 16) {           // four outputs at a time: four loads in flight
+    for (int j0 = wave * 4; j0 < H1; j0 += 4 * NW) {           // four outputs at a time: four loads in flight
         float acc[4] = {0.f, 0.f, 0.f, 0.f};
         for (int i = lane; i < a.Fs; i += 64) {
             const float x = xs[i];
@@ -487,7 +487,7 @@ __global__ __launch_bounds__(256) void score_tiny_kernel(const TinyArgs a)
         const float xc = phi(a.cred[(int64_t)blockIdx.x * a.cred_stride + cc % a.Q], a.enc_cred);
         float *mine = &hb[0][lane * STR];
         {
-            const int hq = H1 >> 2;
+            const int hq = H1 / NW;
             for (int jj = 0; jj < hq; ++jj) {
                 const int j = wave * hq + jj;
                 const float h = relu_keep_nan(fmaf(wc[j], xc, fmaf(wp[j], xp, A1[j])));
@@ -497,9 +497,9 @@ __global__ __launch_bounds__(256) void score_tiny_kernel(const TinyArgs a)
         __syncthreads();
         int cur = 0;
         for (int k = 1; k < a.D; ++k) {
-            const int hin = a.H[k - 1], hq = a.H[k] >> 2;
+            const int hin = a.H[k - 1], hq = a.H[k] / NW;
             // the layer's weights -> LDS as fp32 (the previous layer's readers are past the barrier above)
-            for (int e = t * 4; e < a.H[k] * hin; e += 1024) {
+            for (int e = t * 4; e < a.H[k] * hin; e += 256 * NW) {
                 f32x4 w;
                 if constexpr (sizeof(T) == 2) {
                     const uint2 r = *(const uint2 *)((const uint16_t *)a.W[k] + e);
@@ -531,7 +531,7 @@ __global__ __launch_bounds__(256) void score_tiny_kernel(const TinyArgs a)
             cur ^= 1;
         }
         {   // output unit: a quarter of the dot product per wavefront
-            const int hl = a.H[a.D - 1], hq = hl >> 2;
+            const int hl = a.H[a.D - 1], hq = hl / NW;
             const float *src = &hb[cur][lane * STR + wave * hq];
             float acc = 0.f;
             for (int i = 0; i < hq; i += 4) {
@@ -545,7 +545,9 @@ __global__ __launch_bounds__(256) void score_tiny_kernel(const TinyArgs a)
         }
         __syncthreads();
         if (wave == 0 && c < a.C) {
-            const float v = ((red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane])) + a.b[a.D][0];
+            float v = a.b[a.D][0];
+#pragma unroll
+            for (int w = 0; w < NW; ++w) v += red[w][lane];
             if (a.scores) a.scores[s * a.C + c] = v;
             amax_take(bv, bi, v, c);
         }
@@ -916,11 +918,11 @@ hipError_t launch_score_tiny(int dtype, const ab_model_desc *d, const ab_params 
     if (dtype == AB_BF16) {
         e = hipFuncSetAttribute((const void *)score_tiny_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
-        score_tiny_kernel<bf16_t><<<(unsigned)S, 256, smem, st>>>(a);
+        score_tiny_kernel<bf16_t><<<(unsigned)S, 1024, smem, st>>>(a);
     } else {
         e = hipFuncSetAttribute((const void *)score_tiny_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
-        score_tiny_kernel<float><<<(unsigned)S, 256, smem, st>>>(a);
+        score_tiny_kernel<float><<<(unsigned)S, 1024, smem, st>>>(a);
     }
     return hipGetLastError();
 }
