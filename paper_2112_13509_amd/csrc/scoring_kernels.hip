@@ -392,7 +392,7 @@ __global__ __launch_bounds__(256) void select_rows16_kernel(const FinishArgs a, 
 // scorer; Section 3.3 "Meta network optimizer"): at that size the chain of launches of the batched path
 // costs more than the arithmetic.  One work-group per scenario:
 //   transformed features -> LDS; scenario term A[j] = W1[j, :Fs] x + b1[j] (a wavefront per output,
-//   lanes over the inputs); then 64 candidates at a time, a candidate per lane and a quarter of a layer's
+//   lanes over the inputs); then 64 candidates at a time, a candidate per lane and a sixteenth of a layer's
 //   outputs per wavefront: h1 = relu(A + wp phi(S_p) + wc phi(S_c)), the further layers as dot products
 //   whose weights are staged in LDS (wave-uniform broadcast reads) against the candidate's activations
 //   (read once per layer into registers from LDS rows of stride H + 4 floats: no bank conflicts), the output unit, and
