@@ -530,7 +530,7 @@ __global__ __launch_bounds__(1024) void score_tiny_kernel(const TinyArgs a)
             __syncthreads();
             cur ^= 1;
         }
-        {   // output unit: a quarter of the dot product per wavefront
+        {   // output unit: each wavefront its share of the dot product
             const int hl = a.H[a.D - 1], hq = hl / NW;
             const float *src = &hb[cur][lane * STR + wave * hq];
             float acc = 0.f;
