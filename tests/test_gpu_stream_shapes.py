@@ -43,6 +43,7 @@ def run_and_compare(w, label):
     (40, 16, 16, [256, 256, 1280], "five column tiles in the layer that feeds the output unit"),
     (40, 16, 16, [1280, 1280], "five column tiles, generated operand with K = 1280 (one tile per work-group) feeding the output unit"),
     (150, 16, 16, [512, 1024, 512], "four and two column tiles: bias and output weights in registers, tiles change column block"),
+    (32, 16, 16, [4096, 4096], "the widest layers the library takes: sixteen column tiles, K = 4096 (64 slabs per tile)"),
 ])
 def test_streaming_gemm_corner_shapes(S, P, Q, hidden, label):
     w = wl.make_scoring("stream-shapes", S, 16, hidden, P, Q, 16 * wl.KIB, 64 * wl.MIB, 1.0, 64.0, False, "bf16",
