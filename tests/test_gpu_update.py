@@ -121,6 +121,28 @@ def test_single_step_large_batch(dtype):
     print("large batch worst gradient error: %.3g (tol %g)" % (w, TOL[dtype]))
 
 
+@pytest.mark.parametrize("first_trainable", [0, 5])
+def test_eight_hidden_layers(first_trainable):
+    """The deepest scorer the ABI takes: eight hidden layers (ten launches backward and forward each)."""
+    B = 200
+    u = wl.make_update("upd-deep", N=256, batch=B, L=3, hidden=(64,) * 8, dtype="f32", seed=88, P=4, Q=4)
+    tr = GpuTrainer(u, B)
+    st = orc.TrainState.fresh(u.W, u.b)
+    tr.load_state(st)
+    rows = np.arange(B)
+    idx = torch.from_numpy(rows).to(DEV)
+    ab.ab_online_update_tail(tr.desc, tr.params, tr.x[idx].contiguous(), tr.y[idx].contiguous(), first_trainable,
+                             loss_out=tr.loss, workspace=tr.ws)
+    gl = tr.loss_value()
+    ref = orc.update(oracle_model(u), st, u.x_raw[rows], u.target[rows], first_trainable=first_trainable)
+    assert abs(gl - ref["loss"]) <= 1e-4 * abs(ref["loss"])
+    for k in range(9):
+        got = tr.params.W_master[k].cpu().numpy()
+        assert tensor_error(got, st.W[k]) <= 1e-4, k
+        assert tensor_error(tr.params.b[k].cpu().numpy(), st.b[k]) <= 1e-4, k
+    assert int(tr.params.step.item()) == 1
+
+
 def test_weight_update_exact_against_oracle_fp32():
     """fp32 path: away from tiny gradients the updated weights match to fp32 rounding."""
     u = wl.make_update("upd-w", N=128, batch=128, L=4, hidden=(64, 64), dtype="f32", seed=3, P=4, Q=4)
