@@ -49,7 +49,7 @@ def main():
                     help="also run one plain 1 GiB device-to-device copy (a reference dispatch for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (scenarios are independent, so more GPUs would "
+        print("bench.py: this program runs on one GPU only (scenarios are independent, so more GPUs would "
               "each take a slice with no exchange); run it with --gpus 1", file=sys.stderr)
         sys.exit(2)
 

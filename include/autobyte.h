@@ -66,7 +66,7 @@ enum {
     AB_ERR_DTYPE = -3,        /* compute_dtype is not AB_F32 / AB_BF16                         */
     AB_ERR_ALIGN = -4,        /* a pointer misses its required alignment                       */
     AB_ERR_WORKSPACE = -5,    /* workspace is NULL or smaller than ab_workspace_bytes(...)     */
-    AB_ERR_UNSUPPORTED = -6,  /* valid description that this build has no kernel for           */
+    AB_ERR_UNSUPPORTED = -6,  /* valid description that this library has no kernel for         */
     AB_ERR_DEVICE = -7        /* HIP reported a launch / runtime error                         */
 };
 

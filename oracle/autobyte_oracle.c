@@ -40,7 +40,7 @@
 
 /* ---- feature transform: phi(x) = (g(x) - shift) * scale, g = identity (kind 0) or ln (kind 1).
  * The paper only says the metrics are turned into vector inputs (Section 3.3, "Meta network
- * optimizer"); the per-feature affine / log-affine normalisation is this build's reading. */
+ * optimizer"); the per-feature affine / log-affine normalisation is this implementation's reading. */
 static double orc_phi(double x, int kind, double shift, double scale)
 {
     double g = (kind == 1) ? log(x) : x;
@@ -119,7 +119,7 @@ static void orc_dense(const double *W, const double *b, int n_out, int n_in,
  *                      The speed a configuration is ranked by is the mean of the n_out predictions
  *                      (Eq. 1 ranks configurations by V without saying how a vector is ordered: in
  *                      synchronous data-parallel training the job advances at one rate, of which the
- *                      per-worker entries are n_out measurements -- this build's reading)
+ *                      per-worker entries are n_out measurements -- this implementation's reading)
  *  loss_kind         : 0 -> mean over the minibatch of the squared error summed over the n_out entries;
  *                      1 -> mean over the minibatch of the Euclidean norm of the error vector (Eq. 2 as
  *                           printed: an unsquared L2 norm)

@@ -143,7 +143,7 @@ const char *ab_status_string(ab_status s)
     case AB_ERR_DTYPE: return "unknown compute dtype";
     case AB_ERR_ALIGN: return "a pointer misses its required alignment";
     case AB_ERR_WORKSPACE: return "workspace missing or too small";
-    case AB_ERR_UNSUPPORTED: return "description not supported by this build";
+    case AB_ERR_UNSUPPORTED: return "description not supported by this library";
     case AB_ERR_DEVICE: return "HIP reported an error";
     default: return "unknown status";
     }
