@@ -66,6 +66,9 @@ double orc_encode_value(double x, int kind, double shift, double scale)
     return orc_phi(x, kind, shift, scale);
 }
 
+/* The diagnostic rounding alone, so that a test can hold it against a library conversion. */
+double orc_round_bf16_value(double v) { return orc_round_bf16(v); }
+
 int orc_num_threads(void)
 {
 #ifdef _OPENMP

@@ -43,6 +43,8 @@ def _load():
         _lib = C.CDLL(build())
         _lib.orc_encode_value.restype = C.c_double
         _lib.orc_encode_value.argtypes = [C.c_double, C.c_int, C.c_double, C.c_double]
+        _lib.orc_round_bf16_value.restype = C.c_double
+        _lib.orc_round_bf16_value.argtypes = [C.c_double]
         _lib.orc_num_threads.restype = C.c_int
     return _lib
 
@@ -168,6 +170,11 @@ class Model:
 
 def encode_value(x: float, enc: Tuple[int, float, float]) -> float:
     return float(_load().orc_encode_value(float(x), int(enc[0]), float(enc[1]), float(enc[2])))
+
+
+def round_bf16_value(x: float) -> float:
+    """The rounding used by ``round_stored_bf16`` (diagnostic mode), for one value."""
+    return float(_load().orc_round_bf16_value(float(x)))
 
 
 def num_threads() -> int:

@@ -251,3 +251,50 @@ def test_tensor_pooling_is_permutation_invariant_and_a_mean():
     h = np.maximum(t @ m.te_W[0].T.astype(np.float64) + m.te_b[0], 0)
     h = np.maximum(h @ m.te_W[1].T.astype(np.float64) + m.te_b[1], 0)
     np.testing.assert_allclose(X[:, 0, :5], h.mean(axis=1), rtol=1e-12, atol=1e-14)
+
+
+# ---- the diagnostic rounding mode (used by the GPU tests to tell kernel bugs from rounding noise) ----------
+def test_diagnostic_rounding_is_the_bfloat16_format_rounding():
+    import torch
+    # the format: 8 significand bits, ties to even -- spot values from the definition
+    assert orc.round_bf16_value(1.0) == 1.0
+    assert orc.round_bf16_value(1.0 + 2.0 ** -8) == 1.0                      # tie -> even (1.0)
+    assert orc.round_bf16_value(1.0 + 2.0 ** -7 + 2.0 ** -8) == 1.0 + 2.0 ** -6   # tie -> even (upwards)
+    assert orc.round_bf16_value(1.0 + 2.0 ** -8 + 2.0 ** -20) == 1.0 + 2.0 ** -7
+    assert orc.round_bf16_value(-3.0e38) == -float(torch.tensor(-3.0e38).bfloat16().float().abs())
+    assert math.isnan(orc.round_bf16_value(float("nan"))) and orc.round_bf16_value(0.0) == 0.0
+    # a library conversion on random values over many binades
+    rng = np.random.default_rng(5)
+    v = (rng.standard_normal(4000) * np.exp(rng.uniform(-60, 60, 4000))).astype(np.float32)
+    want = torch.from_numpy(v).bfloat16().float().numpy()
+    got = np.array([orc.round_bf16_value(float(x)) for x in v], dtype=np.float32)
+    assert (got == want).all()
+
+
+def test_diagnostic_rounding_is_a_no_op_on_exactly_representable_activations():
+    """Small-integer inputs, weights and biases: every stored value is an integer below 256, which bfloat16
+    holds exactly, so the rounding mode must reproduce the plain oracle bit for bit; with generic weights it
+    must differ, but by no more than a few roundings of 2^-9 relative size."""
+    rng = np.random.default_rng(9)
+    S, L, K, P, Q = 4, 3, 2, 3, 2
+    lin = (0, 0.0, 1.0)
+    hidden = [5, 4, 3]
+    dims = [L * K + 1 + 2] + hidden + [1]
+    W = [rng.integers(-1, 2, (dims[i + 1], dims[i])).astype(np.float32) for i in range(len(dims) - 1)]
+    b = [rng.integers(-2, 3, dims[i + 1]).astype(np.float32) for i in range(len(dims) - 1)]
+    dyn = rng.integers(0, 3, (S, L, K)).astype(np.float32)
+    scal = rng.integers(0, 3, (S, 1)).astype(np.float32)
+    part, cred = np.array([1, 2, 3], np.float32), np.array([0, 1], np.float32)
+    m = orc.Model(L, K, [lin] * K, [lin], lin, lin, hidden, W, b)
+    plain = orc.score(m, dyn, scal, part, cred)
+    assert np.abs(plain).max() > 0
+    m.round_stored_bf16 = True
+    assert (orc.score(m, dyn, scal, part, cred) == plain).all()
+    # generic weights: rounding shows, and stays small
+    w = wl.make_scoring("rnd", 6, 4, [32, 32], 3, 3, 16 * wl.KIB, 64 * wl.MIB, 1.0, 8.0, False, "bf16", 31)
+    mg = oracle_model(w)
+    exact = orc.score(mg, w.dyn, w.scal, w.part, w.cred)
+    mg.round_stored_bf16 = True
+    rounded = orc.score(mg, w.dyn, w.scal, w.part, w.cred)
+    d = np.abs(rounded - exact).max() / np.abs(exact).max()
+    assert 0 < d < 2e-2
