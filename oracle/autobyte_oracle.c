@@ -139,8 +139,9 @@ typedef struct {
     int n_hidden; const int *hidden;
     const double *const *W; const double *const *b;
     int round_stored_bf16;   /* diagnostic, default 0: round to bf16 the values a bf16 pipeline keeps in
-                                memory (statistics block + scalars, tensor-encoder hidden layer, every
-                                hidden activation except the last) */
+                                memory (scoring: statistics block + scalars, tensor-encoder hidden layer, every
+                                hidden activation except the last; update: the transformed row, every hidden
+                                activation and every hidden layer's delta) */
     int n_out, loss_kind;
 } orc_model;
 
@@ -507,13 +508,17 @@ int orc_update_tail(const orc_model *m, const double *x_raw, const double *targe
             e[nstat + j] = orc_phi(r[nstat + j], m->scal_kind[j], m->scal_shift[j], m->scal_scale[j]);
         e[F - 2] = orc_phi(r[F - 2], m->cfg_kind[0], m->cfg_shift[0], m->cfg_scale[0]);
         e[F - 1] = orc_phi(r[F - 1], m->cfg_kind[1], m->cfg_shift[1], m->cfg_scale[1]);
+        if (m->round_stored_bf16) for (int j = 0; j < F; ++j) e[j] = orc_round_bf16(e[j]);
     }
     /* forward: h[k+1] = relu(W_k h[k] + b_k), last layer linear */
 #pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < B; ++i)
-        for (int k = 0; k < nl; ++k)
-            orc_dense(Wf[k], bf[k], width[k + 1], width[k], h[k] + (size_t)i * width[k],
-                      h[k + 1] + (size_t)i * width[k + 1], k < nl - 1);
+        for (int k = 0; k < nl; ++k) {
+            double *out = h[k + 1] + (size_t)i * width[k + 1];
+            orc_dense(Wf[k], bf[k], width[k + 1], width[k], h[k] + (size_t)i * width[k], out, k < nl - 1);
+            if (m->round_stored_bf16 && k < nl - 1)
+                for (int j = 0; j < width[k + 1]; ++j) out[j] = orc_round_bf16(out[j]);
+        }
     /* loss and output delta */
     {
         double loss = 0.0;
@@ -561,6 +566,7 @@ int orc_update_tail(const orc_model *m, const double *x_raw, const double *targe
                     double acc = 0.0;
                     for (int o = 0; o < no; ++o) acc += dn[o] * Wf[k][(size_t)o * ni + i];
                     dp[i] = (hp[i] > 0.0) ? acc : 0.0; /* h = relu(pre): h > 0 <=> pre > 0 */
+                    if (m->round_stored_bf16) dp[i] = orc_round_bf16(dp[i]);
                 }
             }
         }

@@ -321,6 +321,7 @@ def update(model: Model, state: TrainState, x_raw, target, lr=1e-3, beta1=0.9, b
     assert target.shape == (B, n_out) or (n_out == 1 and target.shape == (B,))
     tmp = Model(model.L, model.K, model.stat_enc, model.scal_enc, model.part_enc, model.cred_enc,
                 model.hidden, state.W, state.b, loss_kind=model.loss_kind)
+    tmp.round_stored_bf16 = model.round_stored_bf16
     cm = tmp._c()
     Wf = [_f64(w) for w in (forward_weights if forward_weights is not None else state.W)]
     n = len(state.W)

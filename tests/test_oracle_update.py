@@ -169,3 +169,35 @@ def test_minibatch_order_is_seeded_and_covers_the_pool():
     assert sorted(seen.tolist()) == list(range(512))
     assert (u.batch_indices(3) == u.batch_indices(3)).all()
     assert not (u.batch_indices(3) == u.batch_indices(11)).all()
+
+
+def test_diagnostic_rounding_in_the_update_is_a_no_op_on_exactly_representable_values():
+    """Small-integer rows, weights and targets with a batch of four: every stored activation and delta is a
+    multiple of 1/2 below 128, which bfloat16 holds exactly, so the rounding-matched mode must give the plain
+    oracle's loss and gradients bit for bit; with generic values it must differ, slightly."""
+    rng = np.random.default_rng(17)
+    L, K, B = 2, 2, 4
+    lin = (0, 0.0, 1.0)
+    hidden = [4, 3]
+    dims = [L * K + 1 + 2] + hidden + [1]
+    W = [rng.integers(-1, 2, (dims[i + 1], dims[i])).astype(np.float64) for i in range(3)]
+    b = [rng.integers(0, 3, dims[i + 1]).astype(np.float64) for i in range(3)]      # (keeps units alive)
+    x = rng.integers(0, 3, (B, dims[0])).astype(np.float64)
+    y = rng.integers(-2, 3, B).astype(np.float64)
+    m = orc.Model(L, K, [lin] * K, [lin], lin, lin, hidden, W, b)
+    plain = orc.update(m, orc.TrainState.fresh(W, b), x, y, do_adam=False)
+    assert max(np.abs(g).max() for g in plain["gW"]) > 0
+    m.round_stored_bf16 = True
+    rounded = orc.update(m, orc.TrainState.fresh(W, b), x, y, do_adam=False)
+    assert rounded["loss"] == plain["loss"]
+    for k in range(3):
+        assert (rounded["gW"][k] == plain["gW"][k]).all() and (rounded["gb"][k] == plain["gb"][k]).all()
+    # generic values
+    Wg = [rng.standard_normal(w.shape) / np.sqrt(w.shape[1]) for w in W]
+    xg, yg = rng.standard_normal((64, dims[0])), rng.standard_normal(64)
+    m.round_stored_bf16 = False
+    a = orc.update(m, orc.TrainState.fresh(Wg, b), xg, yg, do_adam=False)
+    m.round_stored_bf16 = True
+    c = orc.update(m, orc.TrainState.fresh(Wg, b), xg, yg, do_adam=False)
+    d = max(np.abs(a["gW"][k] - c["gW"][k]).max() / np.abs(a["gW"][k]).max() for k in range(3))
+    assert 0 < d < 0.1
