@@ -9,7 +9,7 @@ from oracle import oracle as orc
 from paper_2112_13509_amd import binding as ab
 from paper_2112_13509_amd import workloads as wl
 from helpers import oracle_model
-from gpu_helpers import to_dev, DEV, check_scores
+from gpu_helpers import to_dev, DEV, check_scores, matched_scores
 
 pytestmark = pytest.mark.gpu
 TOL = {"f32": 1e-4, "bf16": 2e-2}
@@ -53,7 +53,8 @@ def test_scores_and_choices(dtype, hidden, S, P, Q, what):
                            scores, idx, best, ws)
     torch.cuda.synchronize()
     ref = orc.score(oracle_model(w), w.dyn, w.scal, part, cred)
-    err, frac = check_scores(dtype, scores.cpu().numpy(), idx.cpu().numpy(), ref)
+    err, frac = check_scores(dtype, scores.cpu().numpy(), idx.cpu().numpy(), ref,
+                             matched_scores(w, part, cred) if dtype == "bf16" else None)
     # a repeated shared grid must give what the shared-grid call gives, bit for bit
     rep_p, rep_c = np.repeat(part[:1], S, axis=0), np.repeat(cred[:1], S, axis=0)
     s_rep = torch.empty_like(scores)
