@@ -211,6 +211,35 @@ def make_scoring(name: str, S: int, L: int, hidden: List[int], P: int, Q: int,
                     list(hidden), Ws, bs, None, None, None, dyn, scal, part, cred, seed)
 
 
+def make_integer_scoring(name: str, S: int, L: int, hidden: List[int], P: int, Q: int, dtype: str, seed: int,
+                         nonzeros: int = 8) -> Workload:
+    """Flat-feature scoring problem in small integers, for tests that want arithmetic without rounding: raw
+    statistics, scalars and grid values are integers in 0..2 under the identity transform, every weight row
+    holds ``nonzeros`` entries of +-1 (half of each sign, at seeded positions; the rest zero), biases are in
+    {-1, 0, 1}.  With few non-zeros per row the activations stay small integers, which bf16 and fp32 both
+    hold exactly (the caller checks that on its reference), so every summation order gives the same result."""
+    rng = np.random.default_rng(seed)
+    widths = [L * 3 + 4 + 2] + list(hidden) + [1]
+    Ws, bs = [], []
+    for k in range(len(widths) - 1):
+        n_out, n_in = widths[k + 1], widths[k]
+        nz = min(nonzeros, n_in // 2 * 2)
+        W = np.zeros((n_out, n_in), dtype=np.float32)
+        for o in range(n_out):
+            cols = rng.choice(n_in, size=nz, replace=False)
+            W[o, cols[:nz // 2]] = 1.0
+            W[o, cols[nz // 2:]] = -1.0
+        Ws.append(W)
+        bs.append(rng.integers(-1, 2, n_out).astype(np.float32))
+    dyn = rng.integers(0, 3, (S, L, 3)).astype(np.float32)
+    scal = rng.integers(0, 3, (S, 4)).astype(np.float32)
+    part = rng.integers(0, 3, P).astype(np.float32)
+    cred = rng.integers(0, 3, Q).astype(np.float32)
+    lin = (ENC_LINEAR, 0.0, 1.0)
+    return Workload(name, dtype, L, 3, [lin] * 3, [lin] * 4, lin, lin, list(hidden), Ws, bs, None, None, None,
+                    dyn, scal, part, cred, seed)
+
+
 def make_per_worker(name: str, S: int, L: int, n_workers: int, hidden: List[int], P: int, Q: int,
                     dtype: str, seed: int) -> Workload:
     """Scoring problem with the input record of Table 1: per layer the backward time on each of the

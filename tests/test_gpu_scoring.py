@@ -215,3 +215,37 @@ def test_more_than_2_pow_32_candidates():
     active = check_selection(idx[torch.from_numpy(rows).to(DEV)].cpu().numpy(), ref, TOL["bf16"], per_scenario=False)
     print("S x C = %.3g: sampled rel err %.3g, exact-index check active on %.0f%%" % (S * w.C, err, 100 * active))
     assert err <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("dtype,hidden,S,L,P,Q", [
+    ("bf16", [1024] * 4, 130, 128, 16, 16),    # 256 x 256 streaming kernels: generated, stored and fused-output forms
+    ("bf16", [512, 512], 70, 44, 32, 32),      # generated operand feeding the output unit directly
+    ("bf16", [256, 256, 256], 33, 20, 16, 16),
+    ("bf16", [2048, 2048], 3, 8, 16, 16),      # K above the streaming kernel's range: one tile per work-group
+    ("bf16", [128, 64], 40, 5, 5, 7),          # generic tiles
+    ("bf16", [64], 9, 3, 4, 4),                # one hidden layer
+    ("f32", [256, 256], 9, 128, 64, 64),       # fp32 256 x 256 tiles
+    ("f32", [64, 64], 1, 16, 8, 8),            # single-launch path
+])
+def test_integer_network_is_reproduced_exactly(dtype, hidden, S, L, P, Q):
+    """A network in small integers (inputs 0..2 under the identity transform, sixteen +-1 weights per row, biases
+    in {-1, 0, 1}): every stored activation is an integer that bf16 holds exactly (checked on the oracle: its
+    rounding-matched mode changes nothing), so no rounding happens anywhere and scores, choices and best scores
+    must equal the oracle's exactly -- with integer scores most candidates tie, so the lowest-index rule decides
+    nearly every scenario."""
+    from gpu_helpers import Scorer
+    w = wl.make_integer_scoring("int", S, L, hidden, P, Q, dtype, 1000 + S + L, nonzeros=16)
+    m = oracle_model(w)
+    ref = orc.score(m, w.dyn, w.scal, w.part, w.cred)
+    if dtype == "bf16":
+        few = w.subset(np.arange(min(S, 8)))
+        m.round_stored_bf16 = True
+        assert (orc.score(m, few.dyn, few.scal, few.part, few.cred) == ref[:min(S, 8)]).all()
+    assert (ref == np.round(ref)).all() and np.abs(ref).max() < 2 ** 24
+    scores, idx, best = Scorer(w).run()
+    ridx, rbest, _ = orc.select(ref)
+    ties = float(np.mean([(r == r.max()).sum() > 1 for r in ref]))
+    print("integer network %s %s: score range [%d, %d], scenarios with a tied maximum %.0f%%"
+          % (dtype, hidden, ref.min(), ref.max(), 100 * ties))
+    assert (scores == ref.astype(np.float32)).all()
+    assert (idx == ridx).all() and (best == rbest.astype(np.float32)).all()
