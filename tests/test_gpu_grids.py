@@ -65,3 +65,35 @@ def test_scores_and_choices(dtype, hidden, S, P, Q, what):
     same = float((s_rep - s_shared).abs().max())
     print("%s: scaled err %.3g, exact-argmax fraction %.2f, repeated-vs-shared grid max diff %.3g" % (what, err, frac, same))
     assert same <= TOL[dtype] * float(s_shared.abs().max())
+
+
+@pytest.mark.parametrize("dtype,hidden,S,P,Q", [
+    ("bf16", [256, 256, 256], 70, 16, 16),     # 256 x 256 streaming kernels with row-indexed candidate vectors
+    ("bf16", [256, 256], 130, 16, 32),         # generated operand feeding the output unit
+    ("bf16", [192, 128, 64], 50, 8, 8),        # generic tiles
+    ("f32", [128], 37, 5, 7),                  # one hidden layer
+    ("f32", [64, 64], 3, 8, 8),                # single launch
+])
+def test_integer_network_with_a_grid_per_scenario_is_reproduced_exactly(dtype, hidden, S, P, Q):
+    """The exact case of the scoring tests (integer inputs, +-1 weights: nothing rounds) with every scenario
+    bringing its own integer grid: scores and choices must equal the oracle's bit for bit."""
+    w = wl.make_integer_scoring("int-grids", S, 6, hidden, P, Q, dtype, 500 + S, nonzeros=16)
+    rng = np.random.default_rng(S + P)
+    part = rng.integers(0, 4, (S, P)).astype(np.float32)
+    cred = rng.integers(0, 4, (S, Q)).astype(np.float32)
+    m = oracle_model(w)
+    ref = orc.score(m, w.dyn, w.scal, part, cred)
+    if dtype == "bf16":
+        m.round_stored_bf16 = True
+        assert (orc.score(m, w.dyn[:8], w.scal[:8], part[:8], cred[:8]) == ref[:8]).all()    # nothing to round
+    desc = ab.desc_from_workload(w)
+    params = ab.Params.from_workload(w, DEV)
+    scores = torch.full((S, P * Q), float("nan"), dtype=torch.float32, device=DEV)
+    idx = torch.full((S,), -7, dtype=torch.int32, device=DEV)
+    best = torch.full((S,), float("nan"), dtype=torch.float32, device=DEV)
+    ws = ab.alloc_workspace(desc, S, P * Q, device=DEV)
+    ab.ab_score_candidates(desc, params, to_dev(w.dyn), to_dev(w.scal), to_dev(part), to_dev(cred), scores, idx, best, ws)
+    torch.cuda.synchronize()
+    ridx, rbest, _ = orc.select(ref)
+    assert (scores.cpu().numpy() == ref.astype(np.float32)).all()
+    assert (idx.cpu().numpy() == ridx).all() and (best.cpu().numpy() == rbest.astype(np.float32)).all()
