@@ -394,3 +394,27 @@ def make_update(name="cfg4-online-update", N=65536, batch=4096, L=128, hidden=(5
     return UpdateWorkload(name, dtype, L, 3, stat_enc, _scalar_encs(1),
                           _log_uniform_enc(part_lo, part_hi), _log_uniform_enc(cred_lo, cred_hi),
                           list(hidden), Ws, bs, x_raw, y.astype(np.float32), batch, seed, noise_var, loss_kind)
+
+
+def make_integer_update(name: str, N: int, L: int, hidden, dtype: str, seed: int, nonzeros: int = 16,
+                        n_workers: int = 0) -> UpdateWorkload:
+    """Update rows and initial parameters in small integers (see ``make_integer_scoring``): raw values 0..2 under
+    the identity transform, ``nonzeros`` entries of +-1 per weight row, biases in {-1, 0, 1}.  The target is left
+    at zero for the caller to set (a test puts it a few integers away from its reference's prediction, so that
+    every delta is a small multiple of 2/B)."""
+    rng = np.random.default_rng(seed)
+    n_out = max(1, n_workers)
+    w = make_integer_scoring(name, 1, L, list(hidden), 1, 1, dtype, seed, nonzeros)
+    Ws, bs = w.W, w.b
+    if n_out > 1:
+        Wl = np.zeros((n_out, hidden[-1]), dtype=np.float32)
+        for o in range(n_out):
+            cols = rng.choice(hidden[-1], size=min(nonzeros, hidden[-1] // 2 * 2), replace=False)
+            Wl[o, cols[:len(cols) // 2]] = 1.0
+            Wl[o, cols[len(cols) // 2:]] = -1.0
+        Ws, bs = Ws[:-1] + [Wl], bs[:-1] + [rng.integers(-1, 2, n_out).astype(np.float32)]
+    F = L * 3 + 4 + 2
+    x_raw = rng.integers(0, 3, (N, F)).astype(np.float32)
+    y = np.zeros((N, n_out) if n_workers > 0 else N, dtype=np.float32)
+    return UpdateWorkload(name, dtype, L, 3, w.stat_enc, w.scal_enc, w.part_enc, w.cred_enc, list(hidden),
+                          Ws, bs, x_raw, y, N, seed, 0.0, "mse")

@@ -259,3 +259,45 @@ def test_resume_is_bitwise_identical():
         for x, y in zip(getattr(a.params, name), getattr(c.params, name)):
             assert torch.equal(x, y), name
     assert a.loss_value() == c.loss_value()
+
+
+@pytest.mark.parametrize("dtype,L,hidden,B,n_workers,first_trainable", [
+    ("bf16", 128, (512, 512, 512), 4096, 0, 0),      # the real shape
+    ("bf16", 128, (512, 512, 512), 4096, 0, 2),      # ... with the lower layers frozen
+    ("bf16", 4, (256, 256), 16384, 0, 0),            # a batch large enough for the 128 x 128 tiles
+    ("bf16", 8, (64, 64), 256, 4, 0),                # four outputs
+    ("f32", 5, (128, 64, 64), 128, 0, 0),
+])
+def test_integer_network_step_is_reproduced_exactly(dtype, L, hidden, B, n_workers, first_trainable):
+    """An update step in which nothing rounds: integer rows, +-1 weights, a batch that is a power of two and targets
+    a few integers away from the reference's predictions, so that activations are small integers and deltas small
+    multiples of 2/B (bf16 holds them: the oracle's rounding-matched mode changes nothing), and every sum is exact
+    in fp32 whatever its order.  With beta1 = 1/2 the first moment after one step from a zero state is half the
+    gradient exactly: loss, every weight-gradient entry and every bias-gradient entry must equal the oracle's."""
+    u = wl.make_integer_update("int-upd", B, L, hidden, dtype, 7 + B, n_workers=n_workers)
+    m = oracle_model(u)
+    st0 = orc.TrainState.fresh(u.W, u.b)
+    pred = orc.update(m, st0.copy(), u.x_raw, u.target, do_adam=False)["yhat"]
+    u.target = (pred - np.random.default_rng(B).integers(-3, 4, pred.shape)).astype(np.float32)
+    ref = orc.update(m, st0.copy(), u.x_raw, u.target, do_adam=False, first_trainable=first_trainable)
+    m.round_stored_bf16 = True
+    refq = orc.update(m, st0.copy(), u.x_raw, u.target, do_adam=False, first_trainable=first_trainable)
+    for a, b in zip(ref["gW"] + ref["gb"], refq["gW"] + refq["gb"]):
+        assert (a == b).all()                                          # nothing to round
+        assert (a.astype(np.float32).astype(np.float64) == a).all()   # and fp32 holds every gradient entry
+    tr = GpuTrainer(u, B)
+    tr.load_state(st0)
+    idx = torch.arange(B, device=DEV)
+    call = ab.ab_online_update if first_trainable == 0 else \
+        (lambda *a, **k: ab.ab_online_update_tail(*a, first_trainable=first_trainable, **k))
+    call(tr.desc, tr.params, tr.x[idx].contiguous(), tr.y[idx].contiguous(), loss_out=tr.loss, workspace=tr.ws,
+         beta1=0.5, beta2=0.75)
+    assert tr.loss_value() == float(np.float32(ref["loss"]))
+    p = tr.params
+    for k in range(len(u.W)):
+        gw, gb = 2.0 * p.mW[k].cpu().numpy().astype(np.float64), 2.0 * p.mb[k].cpu().numpy().astype(np.float64)
+        assert (gw == ref["gW"][k]).all() and (gb == ref["gb"][k]).all(), k
+        if k >= first_trainable:
+            assert np.abs(ref["gW"][k]).max() > 0
+    print("integer step %s %s B=%d: loss %.6g and all %d gradient tensors equal the oracle's exactly"
+          % (dtype, hidden, B, ref["loss"], 2 * len(u.W)))
