@@ -285,6 +285,43 @@ def make_tensor_encoder(name: str, S: int, hidden: List[int], te_hidden: List[in
                     log_spaced(part_lo, part_hi, P), log_spaced(cred_lo, cred_hi, Q), seed)
 
 
+def make_integer_tensor_encoder(name: str, S: int, L: int, hidden: List[int], P: int, Q: int, dtype: str,
+                                seed: int, kinds: int = 2) -> Workload:
+    """The per-tensor-encoder problem in small integers (see ``make_integer_scoring``): 4 integer statistics per
+    tensor under the identity transform, encoder 4 -> 128 -> 128 and scorer with a few +-1 weights per row.  A
+    scenario's L tensors (L a multiple of ``kinds``) are ``kinds`` distinct ones, each L / kinds times, in a seeded
+    order, so that the mean over the tensors is a multiple of 1 / kinds: with kinds = 2 and L a power of two the
+    pooled block keeps one fractional bit and stays exactly representable."""
+    assert L % kinds == 0
+    rng = np.random.default_rng(seed)
+
+    def sparse(n_out, n_in, nz):
+        W = np.zeros((n_out, n_in), dtype=np.float32)
+        nz = min(nz, n_in // 2 * 2)
+        for o in range(n_out):
+            cols = rng.choice(n_in, size=nz, replace=False)
+            W[o, cols[:nz // 2]] = 1.0
+            W[o, cols[nz // 2:]] = -1.0
+        return W, rng.integers(-1, 2, n_out).astype(np.float32)
+
+    Wa, ba = sparse(128, 4, 2)
+    Wb, bb = sparse(128, 128, 4)
+    widths = [128 + 6 + 2] + list(hidden) + [1]
+    Ws, bs = [], []
+    for k in range(len(widths) - 1):
+        W, b = sparse(widths[k + 1], widths[k], 8)
+        Ws.append(W)
+        bs.append(b)
+    proto = rng.integers(0, 3, (S, kinds, 4)).astype(np.float32)
+    order = np.stack([rng.permutation(np.repeat(np.arange(kinds), L // kinds)) for _ in range(S)])
+    dyn = np.take_along_axis(proto, order[:, :, None].repeat(4, axis=2), axis=1)
+    scal = rng.integers(0, 3, (S, 6)).astype(np.float32)
+    lin = (ENC_LINEAR, 0.0, 1.0)
+    return Workload(name, dtype, L, 4, [lin] * 4, [lin] * 6, lin, lin, list(hidden), Ws, bs, [128, 128],
+                    [Wa, Wb], [ba, bb], np.ascontiguousarray(dyn), scal,
+                    rng.integers(0, 3, P).astype(np.float32), rng.integers(0, 3, Q).astype(np.float32), seed)
+
+
 def make_lstm_encoder(name: str, S: int, hidden: List[int], P: int, Q: int, dtype: str, seed: int,
                       n_blocks=24, per_block=16, extra=16, E: int = 32, H: int = 64) -> Workload:
     """The tensor-encoder problem with the temporal encoder in front: per-tensor statistics embedded into E

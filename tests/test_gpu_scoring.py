@@ -249,3 +249,27 @@ def test_integer_network_is_reproduced_exactly(dtype, hidden, S, L, P, Q):
           % (dtype, hidden, ref.min(), ref.max(), 100 * ties))
     assert (scores == ref.astype(np.float32)).all()
     assert (idx == ridx).all() and (best == rbest.astype(np.float32)).all()
+
+
+@pytest.mark.parametrize("dtype,L,hidden,S,P,Q", [
+    ("bf16", 16, [512, 512], 70, 32, 32),       # configuration 5's scorer shape
+    ("bf16", 400, [512, 512], 40, 16, 16),      # its tensor count (the mean divides by 400)
+    ("bf16", 64, [256, 256, 256], 33, 16, 16),
+    ("bf16", 8, [128, 64], 20, 5, 7),           # generic tiles behind the encoder (encoders are bf16 only)
+])
+def test_integer_tensor_encoder_is_reproduced_exactly(dtype, L, hidden, S, P, Q):
+    """The exact case with the per-tensor encoder in front: integer statistics, +-1 weights, two kinds of tensor
+    per scenario in equal numbers, so the pooled block is a multiple of 1/2 and nothing rounds (checked on the
+    oracle); scores and choices must equal the oracle's bit for bit."""
+    from gpu_helpers import Scorer
+    w = wl.make_integer_tensor_encoder("int-te", S, L, hidden, P, Q, dtype, 2000 + S + L)
+    m = oracle_model(w)
+    ref = orc.score(m, w.dyn, w.scal, w.part, w.cred)
+    if dtype == "bf16":
+        m.round_stored_bf16 = True
+        assert (orc.score(m, w.dyn, w.scal, w.part, w.cred) == ref).all()
+    scores, idx, best = Scorer(w).run()
+    ridx, rbest, _ = orc.select(ref)
+    assert (scores == ref.astype(np.float32)).all()
+    assert (idx == ridx).all() and (best == rbest.astype(np.float32)).all()
+    assert len(np.unique(ref)) > 8
