@@ -298,3 +298,37 @@ def test_diagnostic_rounding_is_a_no_op_on_exactly_representable_activations():
     rounded = orc.score(mg, w.dyn, w.scal, w.part, w.cred)
     d = np.abs(rounded - exact).max() / np.abs(exact).max()
     assert 0 < d < 2e-2
+
+
+def test_integer_network_equals_integer_arithmetic():
+    """On an integer-valued network the oracle's fp64 result must equal the same network evaluated in int64
+    (a different arithmetic altogether), for every scenario and candidate; with the tensor encoder the pooled
+    block is a multiple of 1/2, so twice the score is compared."""
+    w = wl.make_integer_scoring("int", 5, 7, [48, 32, 16], 4, 5, "f32", 77, nonzeros=16)
+    ref = orc.score(oracle_model(w), w.dyn, w.scal, w.part, w.cred)
+    Wi = [x.astype(np.int64) for x in w.W]
+    bi = [x.astype(np.int64) for x in w.b]
+    for s in range(5):
+        for p in range(4):
+            for q in range(5):
+                x = np.concatenate([w.dyn[s].reshape(-1), w.scal[s], [w.part[p]], [w.cred[q]]]).astype(np.int64)
+                for k in range(3):
+                    x = np.maximum(Wi[k] @ x + bi[k], 0)
+                assert ref[s, p * 5 + q] == float((Wi[3] @ x + bi[3])[0])
+    t = wl.make_integer_tensor_encoder("int-te", 4, 6, [64, 64], 3, 3, "bf16", 78)
+    ref = orc.score(oracle_model(t), t.dyn, t.scal, t.part, t.cred)
+    Wi = [x.astype(np.int64) for x in t.W]
+    bi = [x.astype(np.int64) for x in t.b]
+    A, a, Bm, bb = (t.te_W[0].astype(np.int64), t.te_b[0].astype(np.int64), t.te_W[1].astype(np.int64),
+                    t.te_b[1].astype(np.int64))
+    for s in range(4):
+        e = sum(np.maximum(Bm @ np.maximum(A @ t.dyn[s, l].astype(np.int64) + a, 0) + bb, 0) for l in range(6))
+        assert (e % 3 == 0).all()                    # six tensors of two kinds: the sum is a multiple of three
+        pool2 = e // 3                               # = 2 * mean
+        for p in range(3):
+            for q in range(3):
+                # everything doubled: x2 = 2x, biases doubled, relu commutes with the positive factor
+                x2 = np.concatenate([pool2, 2 * t.scal[s].astype(np.int64), [2 * int(t.part[p])], [2 * int(t.cred[q])]])
+                for k in range(2):
+                    x2 = np.maximum(Wi[k] @ x2 + 2 * bi[k], 0)
+                assert 2.0 * ref[s, p * 3 + q] == float((Wi[2] @ x2 + 2 * bi[2])[0])

@@ -201,3 +201,26 @@ def test_diagnostic_rounding_in_the_update_is_a_no_op_on_exactly_representable_v
     c = orc.update(m, orc.TrainState.fresh(Wg, b), xg, yg, do_adam=False)
     d = max(np.abs(a["gW"][k] - c["gW"][k]).max() / np.abs(a["gW"][k]).max() for k in range(3))
     assert 0 < d < 0.1
+
+
+def test_integer_network_gradients_equal_integer_arithmetic():
+    """Integer rows, weights and targets, a batch of 64: with every delta scaled by B/2 the whole backward pass
+    is integer arithmetic; the oracle's loss and gradients must equal the int64 evaluation exactly."""
+    B = 64
+    u = wl.make_integer_update("int-upd", B, 3, (24, 16), "f32", 91, n_workers=3)
+    u.target = np.random.default_rng(4).integers(-5, 6, u.target.shape).astype(np.float32)
+    ref = orc.update(oracle_model(u), orc.TrainState.fresh(u.W, u.b), u.x_raw, u.target, do_adam=False)
+    Wi = [x.astype(np.int64) for x in u.W]
+    bi = [x.astype(np.int64) for x in u.b]
+    h = [u.x_raw.astype(np.int64)]
+    for k in range(2):
+        h.append(np.maximum(h[-1] @ Wi[k].T + bi[k], 0))
+    E = h[-1] @ Wi[2].T + bi[2] - u.target.astype(np.int64)            # [B, 3]; delta_out = 2 E / B
+    assert ref["loss"] == float((E * E).sum()) / B
+    d = E
+    for k in (2, 1, 0):
+        assert (ref["gW"][k] == (d.T @ h[k]).astype(np.float64) * (2.0 / B)).all()
+        assert (ref["gb"][k] == d.sum(axis=0).astype(np.float64) * (2.0 / B)).all()
+        if k > 0:
+            d = (d @ Wi[k]) * (h[k] > 0)
+    assert np.abs(ref["gW"][0]).max() > 0
