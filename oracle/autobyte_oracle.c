@@ -22,7 +22,8 @@
  * Pins: see tests/test_oracle_*.py (brute force on tiny grids, library matmul chain,
  * one-layer closed form, permutation invariance, finite differences, autograd, reference Adam;
  * for the per-worker output, the norm loss and per-scenario grids: library chain and linearity of
- * the mean, finite differences, autograd, the absolute-error closed form, scenario-by-scenario calls).
+ * the mean, finite differences, autograd, the absolute-error closed form, scenario-by-scenario calls;
+ * integer-valued networks against int64 arithmetic; the diagnostic rounding against the bfloat16 format).
  * Nothing here is pinned against numbers printed in the paper, because the paper prints no
  * numeric example of the meta-network.
  */
