@@ -273,3 +273,32 @@ def test_integer_tensor_encoder_is_reproduced_exactly(dtype, L, hidden, S, P, Q)
     assert (scores == ref.astype(np.float32)).all()
     assert (idx == ridx).all() and (best == rbest.astype(np.float32)).all()
     assert len(np.unique(ref)) > 8
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 5])
+def test_integer_network_at_full_size(cfg):
+    """The exact case at the benchmark's sizes and launch configurations: a sample of scenarios (both ends and
+    seeded ones in between) is compared with the oracle bit for bit, and over the whole result every score is a
+    (half-)integer and every choice the first maximum of its row."""
+    from gpu_helpers import Scorer
+    if cfg == 2:
+        w = wl.make_integer_scoring("int-cfg2", 1024, 128, [256, 256], 64, 64, "f32", 3002)
+    elif cfg == 3:
+        w = wl.make_integer_scoring("int-cfg3", 65536, 128, [1024] * 4, 16, 16, "bf16", 3003)
+    else:
+        w = wl.make_integer_tensor_encoder("int-cfg5", 8192, 400, [512, 512], 32, 32, "bf16", 3005)
+    S = w.S
+    scores, idx, best = Scorer(w).run()
+    rows = np.unique(np.concatenate([[0, 1, S - 2, S - 1], np.random.default_rng(cfg).integers(0, S, 12)]))
+    sub = w.subset(rows)
+    m = oracle_model(sub)
+    ref = orc.score(m, sub.dyn, sub.scal, sub.part, sub.cred)
+    if w.dtype == "bf16":
+        m.round_stored_bf16 = True
+        assert (orc.score(m, sub.dyn, sub.scal, sub.part, sub.cred) == ref).all()
+    ridx, rbest, _ = orc.select(ref)
+    assert (scores[rows] == ref.astype(np.float32)).all()
+    assert (idx[rows] == ridx).all() and (best[rows] == rbest.astype(np.float32)).all()
+    assert (2 * scores == np.round(2 * scores)).all()
+    assert (idx == np.argmax(scores, axis=1)).all()          # numpy's argmax returns the first maximum
+    assert (best == scores.max(axis=1)).all()
