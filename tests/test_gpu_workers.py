@@ -104,3 +104,28 @@ def test_table1_record_with_per_worker_inputs_and_outputs(dtype, S, L, hidden):
     ref = orc.score(oracle_model(w), w.dyn, w.scal, w.part, w.cred)
     err, frac = check_scores(dtype, scores, idx, ref, matched_scores(w) if dtype == "bf16" else None)
     print("Table 1 record %s: err %.3g, exact-argmax fraction %.2f" % (dtype, err, frac))
+
+
+@pytest.mark.parametrize("dtype,hidden,S,P,Q,n_workers", [
+    ("bf16", [256, 256, 256], 70, 16, 16, 8),
+    ("bf16", [128, 64], 40, 5, 7, 16),
+    ("f32", [64, 64], 9, 8, 8, 4),
+])
+def test_integer_network_with_per_worker_outputs_is_reproduced_exactly(dtype, hidden, S, P, Q, n_workers):
+    """The exact case (integer inputs, +-1 weights) with a power-of-two number of output units: the mean of the
+    per-worker predictions is a multiple of 1 / n_workers, nothing rounds, and scores and choices must equal the
+    oracle's bit for bit although the library folds the output layer into one unit and the oracle does not."""
+    w = wl.make_integer_scoring("int-workers", S, 6, hidden, P, Q, dtype, 700 + S, nonzeros=16)
+    rng = np.random.default_rng(n_workers)
+    w.W = list(w.W[:-1]) + [rng.integers(-1, 2, (n_workers, hidden[-1])).astype(np.float32)]
+    w.b = list(w.b[:-1]) + [rng.integers(-2, 3, n_workers).astype(np.float32)]
+    m = oracle_model(w)
+    ref = orc.score(m, w.dyn, w.scal, w.part, w.cred)
+    if dtype == "bf16":
+        m.round_stored_bf16 = True
+        assert (orc.score(m, w.dyn, w.scal, w.part, w.cred) == ref).all()
+    assert (ref * n_workers == np.round(ref * n_workers)).all() and len(np.unique(ref)) > 8
+    scores, idx, best = Scorer(w).run()
+    ridx, rbest, _ = orc.select(ref)
+    assert (scores == ref.astype(np.float32)).all()
+    assert (idx == ridx).all() and (best == rbest.astype(np.float32)).all()
