@@ -286,12 +286,13 @@ def make_tensor_encoder(name: str, S: int, hidden: List[int], te_hidden: List[in
 
 
 def make_integer_tensor_encoder(name: str, S: int, L: int, hidden: List[int], P: int, Q: int, dtype: str,
-                                seed: int, kinds: int = 2) -> Workload:
+                                seed: int, kinds: int = 2, alternate: bool = False) -> Workload:
     """The per-tensor-encoder problem in small integers (see ``make_integer_scoring``): 4 integer statistics per
     tensor under the identity transform, encoder 4 -> 128 -> 128 and scorer with a few +-1 weights per row.  A
     scenario's L tensors (L a multiple of ``kinds``) are ``kinds`` distinct ones, each L / kinds times, in a seeded
     order, so that the mean over the tensors is a multiple of 1 / kinds: with kinds = 2 and L a power of two the
-    pooled block keeps one fractional bit and stays exactly representable."""
+    pooled block keeps one fractional bit and stays exactly representable.  With ``alternate`` the kinds take turns
+    (0, 1, 0, 1, ...), so that every prefix of a length that is a multiple of ``kinds`` is balanced as well."""
     assert L % kinds == 0
     rng = np.random.default_rng(seed)
 
@@ -314,6 +315,8 @@ def make_integer_tensor_encoder(name: str, S: int, L: int, hidden: List[int], P:
         bs.append(b)
     proto = rng.integers(0, 3, (S, kinds, 4)).astype(np.float32)
     order = np.stack([rng.permutation(np.repeat(np.arange(kinds), L // kinds)) for _ in range(S)])
+    if alternate:
+        order = np.tile(np.arange(L) % kinds, (S, 1))
     dyn = np.take_along_axis(proto, order[:, :, None].repeat(4, axis=2), axis=1)
     scal = rng.integers(0, 3, (S, 6)).astype(np.float32)
     lin = (ENC_LINEAR, 0.0, 1.0)

@@ -107,3 +107,25 @@ def test_scenarios_with_fewer_layers_than_the_padded_tensor(kind):
     lens2[lens == 1] = -3
     s2, _, _ = Scorer(w).run(layers_of=lens2)
     assert np.array_equal(s2, scores)
+
+
+def test_integer_tensor_encoder_with_own_layer_counts_is_reproduced_exactly():
+    """The exact case behind the mean-pooled encoder with every scenario having its own (even) number of layers:
+    two kinds of tensor take turns, so the mean over any even prefix is a multiple of 1/2 and nothing rounds;
+    scores and choices must equal the oracle's bit for bit (the padding holds NaN)."""
+    from gpu_helpers import Scorer
+    S, L = 90, 48
+    w = wl.make_integer_tensor_encoder("int-te-len", S, L, [256, 256], 8, 8, "bf16", 4100, alternate=True)
+    lens = (2 * np.random.default_rng(3).integers(1, L // 2 + 1, S)).astype(np.int32)
+    lens[:3] = [2, L, 34]
+    for s in range(S):
+        w.dyn[s, lens[s]:] = np.nan
+    m = oracle_model(w)
+    ref = orc.score(m, w.dyn, w.scal, w.part, w.cred, layers_of=lens)
+    m.round_stored_bf16 = True
+    assert (orc.score(m, w.dyn, w.scal, w.part, w.cred, layers_of=lens) == ref).all()
+    scores, idx, best = Scorer(w).run(layers_of=lens)
+    ridx, rbest, _ = orc.select(ref)
+    assert np.isfinite(ref).all() and len(np.unique(ref)) > 8
+    assert (scores == ref.astype(np.float32)).all()
+    assert (idx == ridx).all() and (best == rbest.astype(np.float32)).all()
