@@ -112,3 +112,37 @@ def test_update_graph_replays_equal_eager():
         for a, b in zip(getattr(eager, name), getattr(graphed, name)):
             assert torch.equal(a, b), name
     assert int(graphed.step.item()) == 12
+
+
+def test_calls_on_two_streams_do_not_disturb_each_other():
+    """The library keeps no state between or across calls: a scoring pass and update steps issued on two streams
+    at the same time (each with its own buffers and workspace) give what they give one after the other."""
+    w = wl.make_config(3, S=2048)             # about 2.5 ms of streaming-kernel work to overlap with
+    bufs, _ = _scoring_setup(w)
+    d = ab.desc_from_workload(w)
+    prm = ab.Params.from_workload(w, DEV)
+    u = wl.make_update("upd-two-streams", N=1024, batch=256, L=6, hidden=(128, 64), dtype="bf16", seed=35, P=4, Q=4)
+    du = ab.desc_from_workload(u)
+    x, y = torch.from_numpy(u.x_raw[:256]).to(DEV), torch.from_numpy(u.target[:256]).to(DEV)
+
+    def run(s_score, s_upd):
+        pu = ab.Params(u.W, u.b, u.dtype, DEV, trainable=True)
+        ws_u = ab.alloc_workspace(du, B=256, device=DEV)
+        loss = torch.zeros(8, dtype=torch.float32, device=DEV)
+        bufs["scores"].zero_()
+        torch.cuda.synchronize()
+        ab.ab_score_candidates(d, prm, bufs["dyn"], bufs["scal"], bufs["part"], bufs["cred"], bufs["scores"],
+                               bufs["idx"], bufs["best"], bufs["ws"], stream=s_score)
+        for i in range(8):
+            ab.ab_online_update(du, pu, x, y, loss_out=loss[i:i + 1], workspace=ws_u, stream=s_upd)
+        torch.cuda.synchronize()
+        return bufs["scores"].clone(), bufs["idx"].clone(), loss.clone(), [t.clone() for t in pu.W_master]
+
+    one = torch.cuda.current_stream()
+    serial = run(one, one)
+    a, b = torch.cuda.Stream(), torch.cuda.Stream()
+    both = run(a, b)
+    assert torch.equal(serial[0], both[0]) and torch.equal(serial[1], both[1]) and torch.equal(serial[2], both[2])
+    for p, q in zip(serial[3], both[3]):
+        assert torch.equal(p, q)
+    assert float(serial[2][-1]) < float(serial[2][0])
