@@ -40,7 +40,7 @@
  *   width before anything else reads them).  Every raw value x is transformed as phi(x) = (g(x) - shift) * scale with
  *   g = identity or natural logarithm; S_c is expressed as a multiple of S_p (Section 2.4).
  *
- * Network: hidden dense layers with ReLU, then one linear output unit (V is a regression target).
+ * Network: hidden dense layers with ReLU, then a linear output layer of n_outputs units (V is a regression target).
  */
 #ifndef AUTOBYTE_H
 #define AUTOBYTE_H
