@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 PEAK = {"bf16": 2.5e15, "f32": 157.3e12}     # dense MFMA peaks of MI355X, flop/s
 # HBM bytes per hidden-GEMM launch from the FETCH_SIZE / WRITE_SIZE counter runs recorded under profiles/,
 # keyed by (workload, library version the counters were taken with); any other version reports null.
-TRAFFIC = {("cfg3", 104): {"read_bytes": 1.607e9, "written_bytes": 1.437e9, "source": "profiles/gemm_stream_cfg3.md"}}
+TRAFFIC = {("cfg3", 105): {"read_bytes": 1.556e9, "written_bytes": 1.437e9, "source": "profiles/gemm_stream_cfg3.md"}}
 HBM_PEAK = 8.0e12
 
 

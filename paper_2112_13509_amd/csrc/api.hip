@@ -130,7 +130,7 @@ using namespace ab;
 
 extern "C" {
 
-int32_t ab_version(void) { return 104; }
+int32_t ab_version(void) { return 105; }
 
 void ab_set_trace(ab_trace_fn fn, void *user) { g_trace_fn = fn; g_trace_user = user; }
 
