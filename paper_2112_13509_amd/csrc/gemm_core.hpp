@@ -351,6 +351,15 @@ __device__ __forceinline__ void gemm_tn_tile(const GemmArgs &g, int64_t id, unsi
     constexpr bool PRE = WMB * WNB == 1 && (EPI == EPI_STORE || EPI == EPI_DRELU);
     float pre_bias = 0.f, pre_mask[PRE && EPI == EPI_DRELU ? 16 : 1];
     if constexpr (PRE && EPI == EPI_STORE) pre_bias = g.bias ? g.bias[n0 + col_l0] : 0.f;
+    // the output unit's epilogue: bias and output weight of this lane's columns, likewise asked for up front
+    float pre_b[EPI == EPI_SCORE ? WNB : 1], pre_w[EPI == EPI_SCORE ? WNB : 1];
+    if constexpr (EPI == EPI_SCORE) {
+#pragma unroll
+        for (int j = 0; j < WNB; ++j) {
+            pre_b[j] = g.bias[n0 + col_l0 + j * 32];
+            pre_w[j] = g.w_out[n0 + col_l0 + j * 32];
+        }
+    }
     if constexpr (PRE && EPI == EPI_DRELU) {
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
@@ -440,8 +449,7 @@ __device__ __forceinline__ void gemm_tn_tile(const GemmArgs &g, int64_t id, unsi
             for (int r = 0; r < 16; ++r) rs[i][r] = 0.f;
 #pragma unroll
         for (int j = 0; j < WNB; ++j) {
-            const int col = n0 + col_l0 + j * 32;
-            const float bv = g.bias[col], wv = g.w_out[col];
+            const float bv = pre_b[j], wv = pre_w[j];
 #pragma unroll
             for (int i = 0; i < WMB; ++i)
 #pragma unroll
