@@ -19,7 +19,9 @@
  *
  * General rules
  *   - Every pointer marked DEVICE is HIP device memory on the current device, owned by the caller.  The
- *     library never allocates, frees or retains device memory and keeps no state between calls.
+ *     library never allocates, frees or retains device memory.  It keeps no state between calls apart from
+ *     the tracing hook (ab_set_trace), per-device launch attributes it looks up once, and the fixed scratch
+ *     array of ab_score_candidates_static.
  *   - Every pointer marked HOST is ordinary host memory, read during the call only.
  *   - Work is enqueued on the HIP stream passed as `stream` (a hipStream_t cast to void*, NULL = the
  *     default stream).  Calls return as soon as the work is enqueued; nothing synchronises.
@@ -186,6 +188,24 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
                               const ab_stats *stats, const ab_grid *grid,
                               float *scores, int32_t *best_idx, float *best_score,
                               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * ab_score_candidates for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The workspace is a fixed array of
+ * AB_STATIC_SCRATCH_BYTES inside the library's code object (every device the library runs on holds its own
+ * copy until the process ends); the call allocates nothing, on the device or through any library.
+ * Arguments, outputs and results as ab_score_candidates (the same kernels run).  A problem whose
+ * ab_workspace_bytes(desc, S, C, 0) exceeds AB_STATIC_SCRATCH_BYTES is refused with AB_ERR_WORKSPACE before
+ * anything is enqueued.  All calls on one device share the one array: calls that may overlap in time on a
+ * device (different streams, different host threads) race and must be ordered by the caller; the array's
+ * contents are undefined between calls and nothing in it has to be cleared (every kernel writes what it later
+ * reads).  ab_static_scratch_bytes returns AB_STATIC_SCRATCH_BYTES.
+ */
+#define AB_STATIC_SCRATCH_BYTES (32u << 20)
+size_t ab_static_scratch_bytes(void);
+ab_status ab_score_candidates_static(const ab_model_desc *desc, const ab_params *params,
+                                     const ab_stats *stats, const ab_grid *grid,
+                                     float *scores, int32_t *best_idx, float *best_score, void *stream);
 
 /*
  * Per-scenario argmax over a stored score matrix (same rules as above).

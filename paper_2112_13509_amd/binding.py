@@ -80,6 +80,12 @@ def load():
         lib.ab_score_candidates.argtypes = [C.POINTER(ab_model_desc), C.POINTER(ab_params),
                                             C.POINTER(ab_stats), C.POINTER(ab_grid),
                                             _vp, _vp, _vp, _vp, C.c_size_t, _vp]
+        lib.ab_static_scratch_bytes.restype = C.c_size_t
+        lib.ab_static_scratch_bytes.argtypes = []
+        lib.ab_score_candidates_static.restype = C.c_int32
+        lib.ab_score_candidates_static.argtypes = [C.POINTER(ab_model_desc), C.POINTER(ab_params),
+                                                   C.POINTER(ab_stats), C.POINTER(ab_grid),
+                                                   _vp, _vp, _vp, _vp]
         lib.ab_select_best.restype = C.c_int32
         lib.ab_select_best.argtypes = [_vp, C.c_int64, C.c_int32, C.c_int64, _vp, _vp, _vp]
         lib.ab_trigger.restype = C.c_int32
@@ -275,7 +281,8 @@ def ab_score_candidates(desc: ab_model_desc, params: Params, dyn: torch.Tensor, 
                         partition_bytes: torch.Tensor, credit_mult: torch.Tensor,
                         scores: Optional[torch.Tensor] = None, best_idx: Optional[torch.Tensor] = None,
                         best_score: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                        stream=None, check: bool = True, layers_of: Optional[torch.Tensor] = None) -> int:
+                        stream=None, check: bool = True, layers_of: Optional[torch.Tensor] = None,
+                        static_scratch: bool = False) -> int:
     """Enqueue scoring of every (scenario, candidate); outputs are written into the given tensors.
     ``layers_of`` (int32 [S], encoder models only): how many of the L padded layers each scenario really has.
     ``partition_bytes`` [P] and ``credit_mult`` [Q] are shared by all scenarios; given as [S, P] and [S, Q]
@@ -297,6 +304,16 @@ def ab_score_candidates(desc: ab_model_desc, params: Params, dyn: torch.Tensor, 
     for t, n, what in ((scores, S * P * Q, "scores"), (best_idx, S, "best_idx"), (best_score, S, "best_score")):
         if t is not None and t.numel() != n:
             raise ValueError("%s has %d elements, expected %d" % (what, t.numel(), n))
+    if static_scratch:
+        if workspace is not None:
+            raise ValueError("the static-scratch form takes no workspace")
+        rc = lib.ab_score_candidates_static(C.byref(desc), C.byref(params.c), C.byref(st), C.byref(gr),
+                                            _ptr(scores, torch.float32, "scores"),
+                                            _ptr(best_idx, torch.int32, "best_idx"),
+                                            _ptr(best_score, torch.float32, "best_score"), _stream_handle(stream))
+        if check and rc != 0:
+            raise AutoByteError(rc, "ab_score_candidates_static")
+        return rc
     ws_ptr = _ptr(workspace, torch.uint8, "workspace")
     rc = lib.ab_score_candidates(C.byref(desc), C.byref(params.c), C.byref(st), C.byref(gr),
                                  _ptr(scores, torch.float32, "scores"), _ptr(best_idx, torch.int32, "best_idx"),
@@ -305,6 +322,20 @@ def ab_score_candidates(desc: ab_model_desc, params: Params, dyn: torch.Tensor, 
     if check and rc != 0:
         raise AutoByteError(rc, "ab_score_candidates")
     return rc
+
+
+def ab_score_candidates_static(desc: ab_model_desc, params: Params, dyn: torch.Tensor, scalars: torch.Tensor,
+                               partition_bytes: torch.Tensor, credit_mult: torch.Tensor,
+                               scores: Optional[torch.Tensor] = None, best_idx: Optional[torch.Tensor] = None,
+                               best_score: Optional[torch.Tensor] = None, stream=None, check: bool = True,
+                               layers_of: Optional[torch.Tensor] = None) -> int:
+    """``ab_score_candidates`` on the library's fixed scratch array: no workspace, nothing allocated."""
+    return ab_score_candidates(desc, params, dyn, scalars, partition_bytes, credit_mult, scores, best_idx,
+                               best_score, None, stream, check, layers_of, static_scratch=True)
+
+
+def ab_static_scratch_bytes() -> int:
+    return int(load().ab_static_scratch_bytes())
 
 
 def ab_select_best(scores: torch.Tensor, best_idx: torch.Tensor, best_score: Optional[torch.Tensor] = None,

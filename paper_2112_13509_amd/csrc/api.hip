@@ -1,6 +1,7 @@
 // C-ABI entry points: host-side argument checks, workspace layout, launch sequences.
 #include "internal.hpp"
 #include <string.h>
+#include <mutex>
 
 namespace ab {
 
@@ -166,10 +167,13 @@ size_t ab_workspace_bytes(const ab_model_desc *desc, int64_t S, int32_t C, int64
     return need;
 }
 
-ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params,
-                              const ab_stats *stats, const ab_grid *grid,
-                              float *scores, int32_t *best_idx, float *best_score,
-                              void *workspace, size_t workspace_bytes, void *stream)
+}  // extern "C"
+
+// Scoring with the workspace given by address: the body of both scoring entry points.
+static ab_status score_candidates_in(const ab_model_desc *desc, const ab_params *params,
+                                     const ab_stats *stats, const ab_grid *grid,
+                                     float *scores, int32_t *best_idx, float *best_score,
+                                     void *workspace, size_t workspace_bytes, void *stream)
 {
     ab_status rc = check_desc(desc);
     if (rc != AB_OK) return rc;
@@ -317,6 +321,63 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
                                     best_score ? best_score + s0 : nullptr, ns, C, st));
     }
     return AB_OK;
+}
+
+// Workspace of ab_score_candidates_static: lives in the code object, one copy per device.  The name is a
+// host-side stand-in only; the device address is looked up once per device and kept in g_scratch_ptr.
+static __device__ __align__(256) unsigned char scratch[AB_STATIC_SCRATCH_BYTES];
+static const int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+static ab_status static_scratch(void **out)
+{
+    int dev = -1;
+    AB_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return AB_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        AB_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return AB_ERR_DEVICE;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return AB_OK;
+}
+
+extern "C" {
+
+ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params,
+                              const ab_stats *stats, const ab_grid *grid,
+                              float *scores, int32_t *best_idx, float *best_score,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    return score_candidates_in(desc, params, stats, grid, scores, best_idx, best_score,
+                               workspace, workspace_bytes, stream);
+}
+
+size_t ab_static_scratch_bytes(void) { return AB_STATIC_SCRATCH_BYTES; }
+
+ab_status ab_score_candidates_static(const ab_model_desc *desc, const ab_params *params,
+                                     const ab_stats *stats, const ab_grid *grid,
+                                     float *scores, int32_t *best_idx, float *best_score, void *stream)
+{
+    ab_status rc = check_desc(desc);
+    if (rc != AB_OK) return rc;
+    if (!params || !stats || !grid) return AB_ERR_NULL;
+    if (stats->S > 0 && grid->P > 0 && grid->Q > 0 && (int64_t)grid->P * grid->Q <= (1 << 24)) {
+        // refuse what does not fit before anything else is looked at
+        ScorePlan p;
+        rc = plan_scoring(desc, stats->S, grid->P * grid->Q, &p);
+        if (rc != AB_OK) return rc;
+        if (p.total > AB_STATIC_SCRATCH_BYTES) return AB_ERR_WORKSPACE;
+    }
+    void *ptr = nullptr;
+    rc = static_scratch(&ptr);
+    if (rc != AB_OK) return rc;
+    return score_candidates_in(desc, params, stats, grid, scores, best_idx, best_score,
+                               ptr, AB_STATIC_SCRATCH_BYTES, stream);
 }
 
 ab_status ab_select_best(const float *scores, int64_t S, int32_t C, int64_t row_stride,

@@ -26,7 +26,7 @@ def test_exports_every_declared_symbol(lib):
     names = set(re.findall(r"\b(ab_[a-z_]+)\s*\(", header))
     assert {"ab_score_candidates", "ab_select_best", "ab_online_update", "ab_workspace_bytes",
             "ab_status_string", "ab_version", "ab_trigger", "ab_set_trace", "ab_online_update_tail",
-            "ab_replay_mix"} <= names
+            "ab_replay_mix", "ab_score_candidates_static", "ab_static_scratch_bytes"} <= names
     for n in names:
         assert hasattr(lib, n), n
     assert ab.ab_version() >= 100
@@ -201,3 +201,23 @@ def test_binding_refuses_cpu_tensors(lib):
     d = ab.desc_from_workload(w)
     with pytest.raises(TypeError):
         ab.ab_select_best(torch.zeros(2, 4), torch.zeros(2, dtype=torch.int32))
+
+
+def test_static_scratch_form_checks_its_arguments_on_the_host(lib):
+    """The allocation-free scoring entry point refuses bad arguments and oversized problems before any
+    device call is made (so these run without a GPU)."""
+    assert ab.ab_static_scratch_bytes() == 32 << 20
+    d = ab.make_desc(128, 3, [(1, 0.7, 2.0)] * 3, [(0, 0.0, 1.0)] * 4, (1, 12.0, 0.5), (1, 2.0, 0.5),
+                     (1024, 1024, 1024, 1024), "bf16")
+    call = lambda desc, prm, st, gr: lib.ab_score_candidates_static(
+        None if desc is None else C.byref(desc), None if prm is None else C.byref(prm),
+        None if st is None else C.byref(st), None if gr is None else C.byref(gr), 0x7000, 0x8000, None, None)
+    p = ab.ab_params()
+    assert call(None, p, ab.ab_stats(0x3000, 0x4000, 4), ab.ab_grid(0x5000, 16, 0x6000, 16)) == -1
+    assert call(d, None, ab.ab_stats(0x3000, 0x4000, 4), ab.ab_grid(0x5000, 16, 0x6000, 16)) == -1
+    big = ab.ab_stats(0x3000, 0x4000, 4096)
+    assert ab.ab_workspace_bytes(d, 4096, 256) > ab.ab_static_scratch_bytes()
+    assert call(d, p, big, ab.ab_grid(0x5000, 16, 0x6000, 16)) == -5
+    bad = ab.make_desc(128, 3, [(1, 0.7, 2.0)] * 3, [(0, 0.0, 1.0)] * 4, (1, 12.0, 0.5), (1, 2.0, 0.5),
+                       (1000,), "bf16")
+    assert call(bad, p, ab.ab_stats(0x3000, 0x4000, 4), ab.ab_grid(0x5000, 16, 0x6000, 16)) == -6
