@@ -41,24 +41,31 @@ class Scorer:
 
 def check_scores(dtype, got_scores, got_idx, ref, matched=None):
     """The scoring tests' yardsticks (see test_gpu_scoring.py): fp32 is held to 1e-4 in the strict per-scenario
-    measure; bf16 to 2e-2 in the per-tensor norm and 5e-2 in the strict one.  ``matched`` = (scores of the
-    oracle in its rounding-matched diagnostic mode, number of hidden layers): bf16 must agree with those to
-    5e-3 (strict measure) up to two hidden layers (a pre-activation that lands on the other side of a bf16
-    rounding boundary in fp32 than in fp64 moves one activation by one unit in the last place) and to 2e-2
-    beyond (such flips cascade through deeper networks).  Returns (error, fraction of scenarios on which the exact-index check applied)."""
-    from helpers import scaled_error, tensor_scaled_error, check_selection
+    measure; bf16 to 2e-2 in the per-tensor norm and, in the strict one, to the larger of 2e-2 and 1.5 times what
+    bf16 storage alone does on the same scenarios.  ``matched`` = (scores of the oracle in its rounding-matched
+    mode, number of hidden layers): 95 % of the scenarios must agree with those to 2e-3 (strict measure) up to two
+    hidden layers (a pre-activation that lands on the other side of a bf16 rounding boundary in fp32 than in fp64
+    moves one activation by one unit in the last place) and to 1e-2 beyond (such flips cascade through deeper
+    networks), every scenario to twice that, and choose the same candidate wherever that oracle's top-2 margin exceeds the same figure.  The chosen index
+    must equal the exact oracle's wherever its top-2 margin exceeds the tolerance on the scenario's own scale.
+    Returns (error, fraction of scenarios on which the exact-index check applied)."""
+    from helpers import scaled_error, tensor_scaled_error, check_selection, check_against_matched
     strict = scaled_error(got_scores, ref)
     if dtype == "f32":
         assert strict <= 1e-4, strict
         return strict, check_selection(got_idx, ref, 1e-4)
     err = tensor_scaled_error(got_scores, ref)
-    assert err <= 2e-2 and strict <= 5e-2, (err, strict)
+    assert err <= 2e-2, (err, strict)
     if matched is not None:
         refq, n_hidden = matched
-        errq = scaled_error(got_scores, refq)
-        print("   vs rounding-matched oracle: strict err %.3g" % errq)
-        assert errq <= (5e-3 if n_hidden <= 2 else 2e-2), errq
-    return err, check_selection(got_idx, ref, 2e-2, per_scenario=False)
+        tolq = 2e-3 if n_hidden <= 2 else 1e-2
+        errq, above = check_against_matched(got_scores, refq, tolq)
+        print("   vs rounding-matched oracle: strict err %.3g (tol %g, %.1f%% of scenarios above it)" % (errq, tolq, 100 * above))
+        check_selection(got_idx, refq, tolq)
+        assert strict <= max(2e-2, 1.5 * scaled_error(refq, ref)), strict
+    else:
+        assert strict <= 5e-2, strict
+    return err, check_selection(got_idx, ref, 2e-2)
 
 
 def matched_scores(w, part=None, cred=None):

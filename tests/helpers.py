@@ -77,3 +77,41 @@ def tensor_error(got, ref):
     got, ref = np.asarray(got, dtype=np.float64), np.asarray(ref, dtype=np.float64)
     den = np.abs(ref).max()
     return float(np.abs(got - ref).max() / (den if den > 0 else 1.0))
+
+
+def frob_error(got, ref):
+    """||got - ref||_F / ||ref||_F."""
+    got, ref = np.asarray(got, dtype=np.float64), np.asarray(ref, dtype=np.float64)
+    den = np.linalg.norm(ref)
+    return float(np.linalg.norm(got - ref) / (den if den > 0 else 1.0))
+
+
+def full_size_sample(S, n_first, n_last, n_mid, edge, seed):
+    """Scenario indices for an oracle sample of a full-size run: the first ``n_first``, the last ``n_last``
+    and ``n_mid`` in between, of which as many as fit sit on both sides of a multiple of ``edge`` (the number
+    of scenarios one chunk of the launch sequence holds, so the last tile of one chunk and the first of the
+    next are both looked at); the rest are seeded random draws."""
+    rng = np.random.default_rng(seed)
+    borders = np.arange(edge, S, edge, dtype=np.int64)
+    mid = np.concatenate([borders - 1, borders])
+    if mid.size > n_mid:
+        mid = rng.choice(mid, n_mid, replace=False)
+    lo, hi = min(n_first, S), max(min(n_first, S) + 1, S - n_last)
+    extra = rng.integers(lo, hi, max(0, n_mid - mid.size)) if hi > lo else np.zeros(0, dtype=np.int64)
+    rows = np.concatenate([np.arange(min(n_first, S)), np.arange(max(0, S - n_last), S), mid, extra])
+    return np.unique(rows[(rows >= 0) & (rows < S)].astype(np.int64))
+
+
+def check_against_matched(got, refq, tolq):
+    """The GPU's scores against the oracle in its rounding-matched mode, strict per-scenario measure.
+    What is left between the two is accumulation order, which now and then lands a pre-activation on the
+    other side of a bf16 rounding boundary; in wide, deep scorers such a flip perturbs every unit of the
+    next layer a little and so causes further flips there.  Single scenarios are hit, and the worst of a
+    sample grows with its size; so: at least 95 % of the scenarios within ``tolq`` and every one within twice
+    that.  Returns (worst scenario's error, fraction of scenarios above tolq)."""
+    got, refq = np.asarray(got, dtype=np.float64), np.asarray(refq, dtype=np.float64)
+    per_scenario = (np.abs(got - refq) / score_scale(refq)[:, None]).max(axis=1)
+    worst, above = float(per_scenario.max()), float((per_scenario > tolq).mean())
+    assert worst <= 2 * tolq, (worst, tolq)
+    assert above <= 0.05, (above, tolq)
+    return worst, above

@@ -5,10 +5,12 @@ import pytest
 
 from oracle import oracle as orc
 from paper_2112_13509_amd import workloads as wl
-from helpers import oracle_model, scaled_error, tensor_scaled_error, check_selection
+from helpers import oracle_model, scaled_error, tensor_scaled_error, check_selection, check_against_matched
 
 pytestmark = pytest.mark.gpu
 
+TOL_MATCHED = 1e-2  # against the oracle rounding its stored values to bf16 where the kernels do (strict measure;
+                    # 95 % of the scenarios within it, all within twice that: see helpers.check_against_matched)
 TOL = 2e-2          # bf16 bar, per-tensor norm (the recurrent state is rounded to bf16 once per step and layer)
 
 
@@ -16,9 +18,9 @@ def compare(w, scores, idx, best, label=""):
     m = oracle_model(w)
     ref = orc.score(m, w.dyn, w.scal, w.part, w.cred)
     err, strict = tensor_scaled_error(scores, ref), scaled_error(scores, ref)
-    active = check_selection(idx, ref, TOL, per_scenario=False)
+    active = check_selection(idx, ref, TOL)
     m.round_stored_bf16 = True
-    errq = scaled_error(scores, orc.score(m, w.dyn, w.scal, w.part, w.cred))
+    errq, _ = check_against_matched(scores, orc.score(m, w.dyn, w.scal, w.part, w.cred), TOL_MATCHED)
     msg = "%s L=%d S=%d: rel err %.3g (tol %g), strict %.3g, vs rounding-matched oracle %.3g, exact-index check on %.0f%%" % (
         label, w.L, w.S, err, TOL, strict, errq, 100 * active)
     print(msg)
@@ -100,7 +102,7 @@ def test_scenarios_with_fewer_layers_than_the_padded_tensor(kind):
     err, strict = tensor_scaled_error(scores, ref), scaled_error(scores, ref)
     print("%s with own layer counts: rel err %.3g strict %.3g" % (kind, err, strict))
     assert err <= TOL and strict <= 5e-2
-    check_selection(idx, ref, TOL, per_scenario=False)
+    check_selection(idx, ref, TOL)
     # out-of-range counts are clamped to [1, L]
     lens2 = lens.copy()
     lens2[lens == w.L] = w.L + 50

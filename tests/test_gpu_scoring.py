@@ -4,14 +4,20 @@ Tolerances: max relative error 1e-4 for the fp32 path and 2e-2 for the bf16 path
 index equal to the oracle's wherever the oracle's top-2 margin exceeds that tolerance.
 
 Scores are zero-mean, so "relative" needs a yardstick.  fp32 is held to the strict one: each
-scenario's own score magnitude floored by the batch RMS.  For bf16 that yardstick is not attainable
-by any bf16 pipeline (the oracle's own rounding emulation differs from the exact oracle by 1.7e-2 to
-2.4e-2 on the deep 1024-wide configuration), so bf16 is held to 2e-2 in the per-tensor norm
-||g - o||_inf / ||o||_inf (the norm used for gradients and weights) and to 5e-2 in the strict one.
-A diagnostic comparison lets the oracle round stored activations to bf16 where the pipeline does:
-for scorers with at most two hidden layers it must agree to 2e-3 (one rounding stage, no cascade of
-rounding flips), which separates kernel bugs from rounding noise and makes the exact-index check
-bite on most scenarios.
+scenario's own score magnitude floored by the batch RMS.  bf16 is held to 2e-2 in the per-tensor norm
+||g - o||_inf / ||o||_inf (the norm used for gradients and weights); its strict figure is printed and
+held to the larger of 2e-2 and 1.5 times what bf16 storage alone does to the same scenarios (the
+distance between the oracle's two modes, computed on the spot; tests/test_oracle_bf16_rounding_band.py
+shows on the CPU that this alone reaches 1.7e-2 on 48 scenarios of the deep 1024-wide scorer).
+The chosen index must equal the oracle's wherever the oracle's top-2 margin exceeds the tolerance
+relative to the scenario's own scale, and be near-optimal elsewhere; the fraction of scenarios on which
+the exact rule applied is printed.
+Against the oracle in its rounding-matched mode (stored activations rounded to bf16 where the pipeline
+stores them) at least 95 % of the scenarios must agree to 2e-3 (strict measure) up to two hidden layers
+and to 1e-2 beyond, and every scenario to twice that (a pre-activation that lands on the other side of
+a rounding boundary moves one activation by one unit in the last place, deeper and wider networks
+cascade such flips, and the worst scenario of a sample grows with the sample); the exact-index rule is
+applied against that oracle too, at that tolerance, where it bites on far more scenarios.
 """
 import numpy as np
 import pytest
@@ -20,12 +26,13 @@ import torch
 from oracle import oracle as orc
 from paper_2112_13509_amd import binding as ab
 from paper_2112_13509_amd import workloads as wl
-from helpers import oracle_model, scaled_error, tensor_scaled_error, check_selection
+from helpers import oracle_model, scaled_error, tensor_scaled_error, check_selection, check_against_matched
 
 pytestmark = pytest.mark.gpu
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
-TOL_MATCHED = 2e-3
+TOL_MATCHED = 2e-3         # against the rounding-matched oracle, scorers with at most two hidden layers
+TOL_MATCHED_DEEP = 1e-2    # ... deeper ones (observed 6.6e-3 to 7.9e-3 on the four-layer 1024-wide scorer)
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -43,26 +50,26 @@ def compare(w, scores, idx, best, rows=None, label=""):
     ref = orc.score(m, sub.dyn, sub.scal, sub.part, sub.cred)
     tol = TOL[w.dtype]
     strict = scaled_error(scores[sel], ref)
-    if w.dtype == "f32":
-        err = strict
-        active = check_selection(idx[sel], ref, tol)
-    else:
-        err = tensor_scaled_error(scores[sel], ref)
-        active = check_selection(idx[sel], ref, tol, per_scenario=False)
+    err = strict if w.dtype == "f32" else tensor_scaled_error(scores[sel], ref)
+    # exact index wherever the oracle's top-2 margin exceeds the tolerance on the scenario's own scale
+    active = check_selection(idx[sel], ref, tol)
     agree = float((idx[sel] == orc.select(ref)[0]).mean())
     msg = ("%s %s: max rel err %.3g (tol %g; strict per-scenario measure %.3g), exact-index check active on "
-           "%.0f%% of %d scenarios, argmax equal on %.0f%%" % (label, w.name, err, tol, strict, 100 * active,
+           "%.1f%% of %d scenarios, argmax equal on %.0f%%" % (label, w.name, err, tol, strict, 100 * active,
                                                                ref.shape[0], 100 * agree))
     if w.dtype == "bf16":
         m.round_stored_bf16 = True
         refq = orc.score(m, sub.dyn, sub.scal, sub.part, sub.cred)
-        errq = scaled_error(scores[sel], refq)
-        msg += "; vs rounding-matched oracle: strict err %.3g" % errq
-        if len(w.hidden) <= 2:
-            activeq = check_selection(idx[sel], refq, TOL_MATCHED)
-            msg += ", exact-index active on %.0f%%" % (100 * activeq)
-            assert errq <= TOL_MATCHED, msg
-        assert strict <= 5e-2, msg
+        rounding_alone = scaled_error(refq, ref)       # what bf16 storage alone does to these scenarios
+        tolq = TOL_MATCHED if len(w.hidden) <= 2 else TOL_MATCHED_DEEP
+        print("%s %s: rounding alone moves the oracle by %.3g (strict)" % (label, w.name, rounding_alone))
+        errq, above = check_against_matched(scores[sel], refq, tolq)
+        msg += ("; rounding alone moves the oracle by %.3g (strict); vs rounding-matched oracle: strict err %.3g "
+                "(tol %g, %.1f%% of scenarios above it)" % (rounding_alone, errq, tolq, 100 * above))
+        activeq = check_selection(idx[sel], refq, tolq)
+        agreeq = float((idx[sel] == orc.select(refq)[0]).mean())
+        msg += ", its exact-index check active on %.0f%%, argmax equal on %.0f%%" % (100 * activeq, 100 * agreeq)
+        assert strict <= max(2e-2, 1.5 * rounding_alone), msg
     print(msg)
     assert err <= tol, msg
     # best_score is the score at best_idx, and idx is the argmax of the GPU's own scores
@@ -161,16 +168,19 @@ def test_non_finite_statistics_give_minus_one():
     check_selection(idx[ok], ref[ok], 1e-4)
 
 
-@pytest.mark.parametrize("cfg,S,n_sample", [(2, 1024, 6), (3, 65536, 24), (5, 8192, 6)])
-def test_full_size_sampled(cfg, S, n_sample):
-    """The benchmark's launch configuration at full size; the oracle checks a sample of scenarios
-    (first, last and seeded random ones) and size-independent properties hold everywhere."""
+@pytest.mark.parametrize("cfg,S,n_first,n_last,n_mid", [(2, 1024, 4, 4, 8), (3, 65536, 64, 64, 128),
+                                                        (5, 8192, 8, 8, 16)])
+def test_full_size_sampled(cfg, S, n_first, n_last, n_mid):
+    """The benchmark's launch configuration at full size; the oracle checks a sample of scenarios (the first
+    and last ones, and in between scenarios on both sides of every border between two chunks of 2^20 candidate
+    rows plus seeded random ones: 16, 256 and 32 scenarios) and size-independent properties hold everywhere."""
     from gpu_helpers import Scorer
+    from helpers import full_size_sample
     w = wl.make_config(cfg, S=S)
     scores, idx, best = Scorer(w).run()
-    rng = np.random.default_rng(cfg)
-    rows = np.unique(np.concatenate([[0, 1, S - 2, S - 1], rng.integers(0, S, n_sample - 4)]))
-    compare(w, scores, idx, best, rows, label="full size, rows %s" % rows.tolist())
+    rows = full_size_sample(S, n_first, n_last, n_mid, (1 << 20) // w.C, seed=cfg)
+    assert len(rows) >= n_first + n_last + n_mid // 2
+    compare(w, scores, idx, best, rows, label="full size, %d sampled scenarios" % len(rows))
     assert np.isfinite(scores).all()
     assert (idx == np.argmax(scores, axis=1)).all()
     assert (best == scores.max(axis=1)).all()
@@ -212,7 +222,7 @@ def test_more_than_2_pow_32_candidates():
     ref = orc.score(oracle_model(sub), sub.dyn, sub.scal, sub.part, sub.cred)
     got = scores[torch.from_numpy(rows).to(DEV)].cpu().numpy()
     err = tensor_scaled_error(got, ref)
-    active = check_selection(idx[torch.from_numpy(rows).to(DEV)].cpu().numpy(), ref, TOL["bf16"], per_scenario=False)
+    active = check_selection(idx[torch.from_numpy(rows).to(DEV)].cpu().numpy(), ref, TOL["bf16"])
     print("S x C = %.3g: sampled rel err %.3g, exact-index check active on %.0f%%" % (S * w.C, err, 100 * active))
     assert err <= TOL["bf16"]
 

@@ -25,7 +25,7 @@ def run_and_compare(w, label):
     print("%s: S=%d C=%d hidden=%s launches=%s rel err %.3g strict %.3g" % (
         label, w.S, w.C, w.hidden, sorted(set(n for n in names if n.startswith("gemm_hidden"))), err, strict))
     assert err <= 2e-2 and strict <= 5e-2
-    check_selection(idx, ref, 2e-2, per_scenario=False)
+    check_selection(idx, ref, 2e-2)
     assert np.array_equal(idx, np.argmax(scores, axis=1)) and np.array_equal(best, scores[np.arange(w.S), idx])
 
 

@@ -7,8 +7,8 @@ import torch
 from oracle import oracle as orc
 from paper_2112_13509_amd import binding as ab
 from paper_2112_13509_amd import workloads as wl
-from helpers import oracle_model, tensor_error
-from test_gpu_update import GpuTrainer, TOL
+from helpers import oracle_model, tensor_error, frob_error
+from test_gpu_update import GpuTrainer, TOL, TOL_MATCHED, gradient_bounds
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -31,17 +31,21 @@ def test_tail_step_freezes_below_and_matches_the_oracle_above(dtype):
     u = wl.make_update("upd-tail", N=B, batch=B, L=6, hidden=(128, 64, 64), dtype=dtype, seed=21, P=8, Q=8)
     rows = np.arange(B)
     fw = [wl.bf16_round(w.astype(np.float32)).astype(np.float64) for w in u.W] if dtype == "bf16" else None
-    tol_g = TOL[dtype] if dtype == "f32" else 0.15          # (small bf16 problems: ReLU mask flips, as in the full step)
     for k0 in (0, 1, 2, 3):
         tr = GpuTrainer(u, B)
         st = orc.TrainState.fresh(u.W, u.b)
         tr.load_state(st)
         before = snapshot(tr.params)
+        st0 = st.copy()
         ab.ab_online_update_tail(tr.desc, tr.params, tr.x[:B].contiguous(), tr.y[:B].contiguous(), k0,
                                  loss_out=tr.loss, workspace=tr.ws)
         gl = tr.loss_value()
         ref = orc.update(oracle_model(u), st, u.x_raw[rows], u.target[rows], forward_weights=fw, first_trainable=k0)
         assert abs(gl - ref["loss"]) <= TOL[dtype] * abs(ref["loss"])
+        # bounds against the exact oracle (bf16: relative to what rounding alone does) and the rounding-matched reference
+        bounds, refq = gradient_bounds(u, st0, rows, ref, 1e-3, fw, first_trainable=k0)
+        if refq is not None:
+            assert abs(gl - refq["loss"]) <= TOL_MATCHED * abs(refq["loss"])
         after = snapshot(tr.params)
         for k in range(4):
             if k < k0:
@@ -50,7 +54,11 @@ def test_tail_step_freezes_below_and_matches_the_oracle_above(dtype):
             else:
                 gW = after[3][k].cpu().numpy().astype(np.float64) / 0.1        # first moment from zero: m = 0.1 g
                 gb = after[5][k].cpu().numpy().astype(np.float64) / 0.1
-                assert tensor_error(gW, ref["gW"][k]) <= tol_g and tensor_error(gb, ref["gb"][k]) <= tol_g, (k0, k)
+                assert tensor_error(gW, ref["gW"][k]) <= bounds[k][0] and tensor_error(gb, ref["gb"][k]) <= bounds[k][1], (k0, k)
+                assert frob_error(gW, ref["gW"][k]) <= bounds[k][2] and frob_error(gb, ref["gb"][k]) <= bounds[k][3], (k0, k)
+                if refq is not None:
+                    for g, r in ((gW, refq["gW"][k]), (gb, refq["gb"][k])):
+                        assert tensor_error(g, r) <= TOL_MATCHED and frob_error(g, r) <= TOL_MATCHED, (k0, k)
                 assert np.abs(after[1][k].cpu().numpy() - st.W[k]).max() <= 2e-3 + 1e-6
                 cdt = torch.bfloat16 if dtype == "bf16" else torch.float32
                 assert torch.equal(after[0][k], after[1][k].to(cdt))

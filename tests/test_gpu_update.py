@@ -13,12 +13,12 @@ import torch
 from oracle import oracle as orc
 from paper_2112_13509_amd import binding as ab
 from paper_2112_13509_amd import workloads as wl
-from helpers import oracle_model, tensor_error
+from helpers import oracle_model, tensor_error, frob_error
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 TOL = {"f32": 1e-4, "bf16": 2e-2}
-TOL_MATCHED = 1e-2      # bf16 against the oracle in its rounding-matched diagnostic mode
+TOL_MATCHED = 1e-2      # bf16 against the oracle in its rounding-matched diagnostic mode (both norms)
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -61,12 +61,42 @@ class GpuTrainer:
         return float(self.loss.item())
 
 
-def check_single_step(u, tr, st, rows, tol, lr=1e-3, tol_inf=None):
+def gradient_bounds(u, before, rows, ref, lr, fw, first_trainable=0):
+    """Per gradient tensor the bound the GPU is held to against the exact oracle, in the norms ||.||_inf / ||.||_inf
+    and Frobenius: the tolerance itself for fp32; for bf16 the larger of the tolerance and 1.25 times what bf16
+    storage alone does to that tensor in this very step (the distance between the oracle's two modes).  A unit whose
+    pre-activation lies within the rounding noise of zero flips its ReLU mask, its delta entry is then wrong by
+    100 %, and a fraction f of flipped entries costs about sqrt(f) in the Frobenius norm: rounding alone moves the
+    first layer's weight gradient by 3e-2 at configuration 4's real shape (tests/test_oracle_bf16_rounding_band.py),
+    by 4e-2 in both norms once the loss has fallen and the gradients are small (step 10 of its trajectory), and by
+    up to 9e-2 on batches of a few hundred rows.  Returns (bounds, rounding-matched reference or None)."""
+    tol = TOL[u.dtype]
+    n = len(ref["gW"])
+    if u.dtype != "bf16":
+        return [(tol, tol, tol, tol)] * n, None
+    mq = oracle_model(u)
+    mq.round_stored_bf16 = True
+    refq = orc.update(mq, before.copy(), u.x_raw[rows], u.target[rows], lr=lr, forward_weights=fw, do_adam=False,
+                      first_trainable=first_trainable)
+    out = []
+    for k in range(n):
+        out.append((max(tol, 1.25 * tensor_error(refq["gW"][k], ref["gW"][k])),
+                    max(tol, 1.25 * tensor_error(refq["gb"][k], ref["gb"][k])),
+                    max(tol, 1.25 * frob_error(refq["gW"][k], ref["gW"][k])),
+                    max(tol, 1.25 * frob_error(refq["gb"][k], ref["gb"][k]))))
+    return out, refq
+
+
+def check_single_step(u, tr, st, rows, tol, lr=1e-3):
     """One step on GPU and in the oracle from the same state ``st`` (oracle state is advanced).
-    Loss must agree to ``tol``; gradients to ``tol_inf`` (default ``tol``) in ||.||_inf / ||.||_inf.
+    Loss must agree to ``tol``; every gradient tensor to ``gradient_bounds`` in two norms, and for bf16 to
+    TOL_MATCHED in both norms against the oracle in its rounding-matched mode (what is left there is accumulation
+    order and the rare rounding flip, so an implementation slip that rounding noise would cover shows).  Late in
+    a trajectory, where the loss sits at the noise floor and every gradient entry is what is left of a
+    cancellation, rounding alone moves the gradients by 3e-2 to 7e-2 and one flip shows in single entries: there
+    the inf-norm bound against the rounding-matched oracle is half of what rounding alone does to the tensor.
     For bf16 the oracle's forward/backward use the stored (bf16-rounded) weights, so that weight
     quantisation is part of the problem rather than an error; Adam still updates the fp64 masters."""
-    tol_inf = tol if tol_inf is None else tol_inf
     fw = [wl.bf16_round(w.astype(np.float32)).astype(np.float64) for w in st.W] if u.dtype == "bf16" else None
     tr.load_state(st)
     before = st.copy()
@@ -74,37 +104,36 @@ def check_single_step(u, tr, st, rows, tol, lr=1e-3, tol_inf=None):
     gl = tr.loss_value()
     ref = orc.update(oracle_model(u), st, u.x_raw[rows], u.target[rows], lr=lr, forward_weights=fw)
     assert abs(gl - ref["loss"]) <= tol * abs(ref["loss"]), (gl, ref["loss"])
+    bounds, refq = gradient_bounds(u, before, rows, ref, lr, fw)
     p = tr.params
-    worst = 0.0
+    worst = worst_frob = worst_q = frob_q = 0.0
     for k in range(len(st.W)):
         # gradients via the first moment: m' = 0.9 m + 0.1 g
         gW = (p.mW[k].cpu().numpy().astype(np.float64) - 0.9 * before.mW[k]) / 0.1
         gb = (p.mb[k].cpu().numpy().astype(np.float64) - 0.9 * before.mb[k]) / 0.1
         eW, eb = tensor_error(gW, ref["gW"][k]), tensor_error(gb, ref["gb"][k])
-        worst = max(worst, eW, eb)
-        assert eW <= tol_inf and eb <= tol_inf, (k, eW, eb)
-        assert tensor_error(p.vW[k].cpu().numpy(), st.vW[k]) <= 2.5 * tol
+        fW, fb = frob_error(gW, ref["gW"][k]), frob_error(gb, ref["gb"][k])
+        worst, worst_frob = max(worst, eW, eb), max(worst_frob, fW, fb)
+        assert eW <= bounds[k][0] and eb <= bounds[k][1], (k, eW, eb, bounds[k])
+        assert fW <= bounds[k][2] and fb <= bounds[k][3], (k, fW, fb, bounds[k])
+        if refq is not None:
+            for g, r, alone in ((gW, refq["gW"][k], bounds[k][0]), (gb, refq["gb"][k], bounds[k][1])):
+                worst_q, frob_q = max(worst_q, tensor_error(g, r)), max(frob_q, frob_error(g, r))
+                # (the bounds hold 1.25 x rounding alone, so 0.4 of one is half of what rounding alone does)
+                assert tensor_error(g, r) <= max(TOL_MATCHED, 0.4 * alone), (k, tensor_error(g, r), alone)
+        assert tensor_error(p.vW[k].cpu().numpy(), st.vW[k]) <= 2.5 * max(tol, bounds[k][0])
         # updated parameters: each moved by at most ~lr, so two paths differ by at most 2 lr
         assert np.abs(p.W_master[k].cpu().numpy() - st.W[k]).max() <= 2 * lr + 1e-6
         assert np.abs(p.b[k].cpu().numpy() - st.b[k]).max() <= 2 * lr + 1e-6
         cdt = torch.bfloat16 if u.dtype == "bf16" else torch.float32
         assert torch.equal(p.W[k], p.W_master[k].to(cdt))        # compute copy refreshed
     assert int(p.step.item()) == st.t
-    if u.dtype == "bf16":
-        # diagnostic: the oracle rounding its stored rows, activations and deltas to bf16 where the kernels do;
-        # what is left is accumulation order and the rare rounding flip, so implementation slips that the
-        # rounding noise above would cover show here
-        mq = oracle_model(u)
-        mq.round_stored_bf16 = True
-        refq = orc.update(mq, before.copy(), u.x_raw[rows], u.target[rows], lr=lr, forward_weights=fw, do_adam=False)
-        worst_q = 0.0
-        for k in range(len(st.W)):
-            gW = (p.mW[k].cpu().numpy().astype(np.float64) - 0.9 * before.mW[k]) / 0.1
-            gb = (p.mb[k].cpu().numpy().astype(np.float64) - 0.9 * before.mb[k]) / 0.1
-            worst_q = max(worst_q, tensor_error(gW, refq["gW"][k]), tensor_error(gb, refq["gb"][k]))
-        print("   vs rounding-matched oracle: loss %.3g, worst gradient error %.3g"
-              % (abs(gl - refq["loss"]) / abs(refq["loss"]), worst_q))
-        assert worst_q <= TOL_MATCHED and abs(gl - refq["loss"]) <= TOL_MATCHED * abs(refq["loss"])
+    if refq is not None:
+        print("   gradients vs exact oracle: worst %.3g (inf norm), %.3g (Frobenius); vs rounding-matched oracle: "
+              "loss %.3g, gradients %.3g (inf norm), %.3g (Frobenius)"
+              % (worst, worst_frob, abs(gl - refq["loss"]) / abs(refq["loss"]), worst_q, frob_q))
+        assert frob_q <= TOL_MATCHED
+        assert abs(gl - refq["loss"]) <= TOL_MATCHED * abs(refq["loss"])
     return worst
 
 
@@ -117,14 +146,8 @@ def test_single_step_small(dtype, L, hidden, B):
     tr = GpuTrainer(u, B)
     st = orc.TrainState.fresh(u.W, u.b)
     rows = np.arange(B)
-    # bf16 rounding of activations perturbs pre-activations by ~1e-3, which flips the ReLU mask of the
-    # few units that sit that close to zero; a flipped unit's delta is wrong by 100 %, and with a small
-    # batch few rows average it out.  Entry-wise gradient agreement of small bf16 problems is therefore
-    # held to a looser bound (the same kernels in fp32 agree to 1e-6 here, and the real shape is held
-    # to 2e-2 in the configuration-4 test below).
-    tol_inf = TOL[dtype] if dtype == "f32" else 0.15
-    w1 = check_single_step(u, tr, st, rows, TOL[dtype], tol_inf=tol_inf)
-    w2 = check_single_step(u, tr, st, rows[::-1].copy(), TOL[dtype], tol_inf=tol_inf)   # non-zero moments
+    w1 = check_single_step(u, tr, st, rows, TOL[dtype])
+    w2 = check_single_step(u, tr, st, rows[::-1].copy(), TOL[dtype])   # non-zero moments
     print("single-step worst gradient error: %.3g, %.3g (tol %g)" % (w1, w2, TOL[dtype]))
 
 
@@ -178,19 +201,20 @@ def test_weight_update_exact_against_oracle_fp32():
 
 def test_config4_single_steps_along_oracle_trajectory():
     """Configuration 4 at its real shape (B = 4096, 390 -> 512 -> 512 -> 512 -> 1, bf16 GEMMs).
-    The oracle advances a trajectory; at steps 1, 2 and 6 the GPU takes the same step from the
-    oracle's state."""
+    The oracle advances a trajectory of 100 steps; at steps 1, 2, 6, 10 and 100 the GPU takes the same step
+    from the oracle's state (non-trivial Adam moments and, late in the run, small gradients)."""
     u = wl.make_update()
     tr = GpuTrainer(u, u.batch)
     st = orc.TrainState.fresh(u.W, u.b)
     m = oracle_model(u)
-    for step in range(6):
+    for step in range(100):
         rows = u.batch_indices(step)
-        if step in (0, 1, 5):
+        if step + 1 in (1, 2, 6, 10, 100):
             w = check_single_step(u, tr, st, rows, TOL["bf16"])
-            print("cfg4 step %d: worst gradient error %.3g" % (step + 1, w))
+            print("cfg4 step %d: worst gradient error %.3g" % (step + 1, w), flush=True)
         else:
-            orc.update(m, st, u.x_raw[rows], u.target[rows], want_grads=False)
+            fw = [wl.bf16_round(x.astype(np.float32)).astype(np.float64) for x in st.W]
+            orc.update(m, st, u.x_raw[rows], u.target[rows], want_grads=False, forward_weights=fw)
 
 
 def test_loss_curve_tracks_oracle_and_reaches_noise_floor():
