@@ -3,10 +3,15 @@
 
 One *step* = one pass of the whole hot path over one batch of synthetic input, inputs already
 resident in HBM:
-  scoring workloads (cfg2, cfg3, cfg5): ab_score_candidates on all scenarios x all candidates,
-      writing the score matrix (cfg3) and the per-scenario choice  -> candidates scored / s
-  update workload (cfg4): ab_online_update on one 4096-row minibatch             -> samples / s
-The default workload is cfg3 (65536 scenarios x 256 candidates, 390 -> 1024^4 -> 1, bf16).
+  scoring workloads (cfg1, cfg2, cfg3, cfg5): ab_score_candidates on all scenarios x all candidates,
+      writing the score matrix (cfg1, cfg3) and the per-scenario choice  -> candidates scored / s
+  update workload (cfg4): ab_online_update on one 4096-row minibatch     -> samples / s
+The primary workload (``--workload``, default cfg3: 65536 scenarios x 256 candidates,
+390 -> 1024^4 -> 1, bf16) is timed over exactly ``--steps`` steps and fills the top-level fields.
+After it, short legs of the other configurations run in the same process and are reported under
+``other_workloads`` (value, ms per step, roofline position, launch floor of the update step), so that
+both halves of the metric -- candidates scored per second and online-update samples per second --
+come from one run.
 
 Prints ONE JSON line with the throughput, the roofline position of the dominant kernel (device
 time per launch from events recorded around each launch on the launching stream) and the CPU
@@ -23,10 +28,14 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK = {"bf16": 2.5e15, "f32": 157.3e12}     # dense MFMA peaks of MI355X, flop/s
-# HBM bytes per hidden-GEMM launch from the FETCH_SIZE / WRITE_SIZE counter runs recorded under profiles/,
-# keyed by (workload, library version the counters were taken with); any other version reports null.
-TRAFFIC = {("cfg3", 105): {"read_bytes": 1.556e9, "written_bytes": 1.437e9, "source": "profiles/gemm_stream_cfg3.md"}}
 HBM_PEAK = 8.0e12
+# HBM bytes per hidden-GEMM launch from the FETCH_SIZE / WRITE_SIZE counter runs recorded under profiles/.
+# They describe the kernels of ONE library version; any other version reports null and says why.
+TRAFFIC = {"cfg3": {"library_version": 105, "read_bytes": 1.556e9, "written_bytes": 1.437e9,
+                    "source": "profiles/gemm_stream_cfg3.md"}}
+ALL_WORKLOADS = ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "lstm"]
+ROLE_OF = {"gemm_hidden_first": "first", "gemm_hidden_mid": "middle", "gemm_hidden_last": "last",
+           "gemm_hidden_first_last": "first+last"}
 
 
 def oracle_model(orc, np, w):
@@ -37,14 +46,354 @@ def oracle_model(orc, np, w):
                      te_W=getattr(w, "te_W", None), te_b=getattr(w, "te_b", None), te_kind=getattr(w, "te_kind", "mlp"))
 
 
+def traffic_entry(workload, version):
+    """The counter figures recorded for ``workload``, or null with the reason when they were taken with another
+    library version (a changed kernel invalidates them)."""
+    t = TRAFFIC.get(workload)
+    if t is None:
+        return None, "no HBM counter run recorded for this workload"
+    if t["library_version"] != version:
+        return None, ("counters in %s were taken with library version %d, this is version %d: not reported"
+                      % (t["source"], t["library_version"], version))
+    return {k: t[k] for k in ("read_bytes", "written_bytes", "source")}, None
+
+
+def timed_steps(torch, step, steps, warmup):
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return max(e0.elapsed_time(e1), 0.0) / steps, wall * 1e3 / steps
+
+
+def kernel_table(ab, step, trace_steps):
+    """Device time of every launch of ``trace_steps`` steps, from events around each launch on the launching stream."""
+    with ab.KernelTimer() as kt:
+        for _ in range(trace_steps):
+            step()
+        ksum = kt.summary()
+    kernels = {}
+    for name, r in sorted(ksum.items(), key=lambda kv: -kv[1]["total_ms"]):
+        rate = r["work"] / (r["total_ms"] * 1e-3) if r["total_ms"] > 0 else 0.0
+        kernels[name] = {"launches_per_step": r["launches"] / trace_steps, "avg_ms": round(r["avg_ms"], 5),
+                         "ms_per_step": round(r["total_ms"] / trace_steps, 5),
+                         ("GB/s" if r["is_bytes"] else "TFLOP/s"): round(rate / (1e9 if r["is_bytes"] else 1e12), 3)}
+    return ksum, kernels
+
+
+def gemm_roofline(ab, workload, ksum, dtype, trace_steps, ms_per_step):
+    """Roofline position of the hidden-layer matrix products: all their launches together, and each role."""
+    names = [n for n in ksum if n.startswith("gemm_hidden") or n.startswith("upd_gemm")]
+    if not names:
+        return None
+    tot_ms = sum(ksum[n]["total_ms"] for n in names)
+    tot_work = sum(ksum[n]["work"] for n in names)
+    launches = sum(ksum[n]["launches"] for n in names)
+    achieved = tot_work / (tot_ms * 1e-3)
+    traffic, why = traffic_entry(workload, ab.ab_version())
+    per_role = {}
+    for n in names:
+        r = ksum[n]
+        rate = r["work"] / (r["total_ms"] * 1e-3)
+        per_role[ROLE_OF.get(n, n)] = {"avg_launch_ms": round(r["avg_ms"], 5), "TFLOP/s": round(rate / 1e12, 1),
+                                       "frac": round(rate / PEAK[dtype], 4)}
+    out = {"bound": "mfma", "kernel": "hidden-layer GEMM launches (" + ", ".join(sorted(names)) + ")",
+           "achieved": round(achieved / 1e12, 3), "peak": PEAK[dtype] / 1e12, "unit": "TFLOP/s",
+           "frac": round(achieved / PEAK[dtype], 4), "traffic": traffic,
+           "flop_per_launch": tot_work / launches, "avg_launch_ms": round(tot_ms / launches, 5),
+           "share_of_step_time": round(tot_ms / trace_steps / ms_per_step, 3), "per_role": per_role}
+    if why:
+        out["traffic_note"] = why
+    return out
+
+
+def launch_floor_of(torch, dev, n_launch):
+    """The same number of back-to-back trivial dependent launches as one update step makes."""
+    tiny = torch.zeros(64, dtype=torch.float32, device=dev)
+    for _ in range(50):
+        tiny.add_(1.0)
+    torch.cuda.synchronize()
+    f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    f0.record()
+    for _ in range(100 * n_launch):
+        tiny.add_(1.0)
+    f1.record()
+    torch.cuda.synchronize()
+    return {"launches_per_step": n_launch,
+            "us_per_step_of_trivial_launches": round(f0.elapsed_time(f1) * 10.0, 2),
+            "note": "the step is a chain of short dependent launches (16.2 GFLOP in all); replaying it "
+                    "from a captured HIP graph gave the same time, so the gaps are on the device side"}
+
+
+def run_update(mods, args, primary):
+    np, torch, ab, wl = mods
+    dev = "cuda:0"
+    t_gen = time.time()
+    u = wl.make_update()
+    d = ab.desc_from_workload(u)
+    prm = ab.Params(u.W, u.b, u.dtype, dev, trainable=True)
+    ws = ab.alloc_workspace(d, B=u.batch, device=dev)
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    xall, yall = torch.from_numpy(u.x_raw).to(dev), torch.from_numpy(u.target).to(dev)
+    batches = []
+    for s in range(16):
+        idx = torch.from_numpy(u.batch_indices(s)).to(dev)
+        batches.append((xall[idx].contiguous(), yall[idx].contiguous()))
+    counter = [0]
+    t_gen = time.time() - t_gen
+
+    def step():
+        x, y = batches[counter[0] % 16]
+        counter[0] += 1
+        ab.ab_online_update(d, prm, x, y, loss_out=loss, workspace=ws)
+
+    steps = args.steps if (primary and args.steps is not None) else (1000 if primary else 400)
+    warmup = args.warmup if (primary and args.warmup is not None) else 20
+    ms_per_step, ms_wall = timed_steps(torch, step, steps, warmup)
+    widths = [u.F] + list(u.hidden) + [1]
+    flops_per_unit = sum(6.0 * widths[i] * widths[i + 1] for i in range(len(widths) - 1)) - 2.0 * widths[0] * widths[1]
+    ksum, kernels = kernel_table(ab, step, 20)
+    n_launch = int(round(sum(r["launches"] for r in ksum.values()) / 20))
+    out = {"metric": "online-update samples/sec", "value": u.batch / (ms_per_step * 1e-3), "unit": "samples/s",
+           "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "ms_per_step_wall": ms_wall,
+           "us_per_step": round(ms_per_step * 1e3, 2), "dtype": u.dtype,
+           "config": {"workload": "cfg4: online adaptation, minibatch 4096, 390->512->512->512->1, "
+                                  "bf16 GEMMs, fp32 masters, Adam lr 1e-3", "batch": u.batch},
+           "algorithmic_flop_per_unit": flops_per_unit,
+           "whole_step_TFLOP/s": round(u.batch * flops_per_unit / (ms_per_step * 1e-3) / 1e12, 3),
+           "whole_step_frac_of_mfma_peak": round(u.batch * flops_per_unit / (ms_per_step * 1e-3) / PEAK[u.dtype], 4),
+           "roofline": gemm_roofline(ab, "cfg4", ksum, u.dtype, 20, ms_per_step),
+           "launch_floor": launch_floor_of(torch, dev, n_launch), "input_generation_s": round(t_gen, 2)}
+    out["us_per_launch"] = round(ms_per_step * 1e3 / n_launch, 2)
+    out["us_per_trivial_launch"] = round(out["launch_floor"]["us_per_step_of_trivial_launches"] / n_launch, 2)
+    if not primary:
+        return out
+    out["kernels"] = kernels
+
+    # ---- transfer-learning form of the update and the minibatch assembly, timed next to the full step
+    transfer = {}
+    D = len(u.hidden)
+
+    def time_calls(fn, n_warm, n):
+        for i in range(n_warm):
+            fn(i)
+        torch.cuda.synchronize()
+        f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        f0.record()
+        for i in range(n):
+            fn(i)
+        f1.record()
+        torch.cuda.synchronize()
+        return f0.elapsed_time(f1) * 1e3 / n
+
+    for k0 in (D - 1, D):
+        us = time_calls(lambda i: ab.ab_online_update_tail(d, prm, batches[i % 16][0], batches[i % 16][1], k0,
+                                                           loss_out=loss, workspace=ws), 20, 200)
+        transfer["first_trainable_%d_us_per_step" % k0] = round(us, 2)
+    pick = torch.randint(-u.x_raw.shape[0], 4096, (u.batch,), dtype=torch.int32, device=dev)
+    xo, to = torch.empty_like(batches[0][0]), torch.empty_like(batches[0][1])
+    us = time_calls(lambda i: ab.ab_replay_mix(batches[1][0], batches[1][1], xall, yall, pick, xo, to), 10, 200)
+    transfer["replay_mix_us"] = round(us, 2)
+    transfer["replay_mix_GB/s"] = round(u.batch * (u.F + 1) * 8.0 / (us * 1e-6) / 1e9, 1)
+    # the same network with one output per worker (eight workers) and the unsquared L2 loss of Eq. 2
+    uw = wl.make_update(N=4096 * 4, n_workers=8, loss_kind="l2norm")
+    dw = ab.desc_from_workload(uw)
+    pw = ab.Params(uw.W, uw.b, uw.dtype, dev, trainable=True)
+    wsw = ab.alloc_workspace(dw, B=uw.batch, device=dev)
+    xw, yw = torch.from_numpy(uw.x_raw).to(dev), torch.from_numpy(uw.target).to(dev)
+    bw = [(xw[i * 4096:(i + 1) * 4096].contiguous(), yw[i * 4096:(i + 1) * 4096].contiguous()) for i in range(4)]
+    us = time_calls(lambda i: ab.ab_online_update(dw, pw, bw[i % 4][0], bw[i % 4][1], loss_out=loss, workspace=wsw), 20, 200)
+    transfer["eight_workers_norm_loss_us_per_step"] = round(us, 2)
+    transfer["note"] = ("first_trainable = D-1 trains the last hidden layer and the output unit, D the output "
+                        "unit alone; replay_mix gathers one 4096-row minibatch from a 4096-row and a 65536-row pool")
+    out["transfer_learning"] = transfer
+
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        n_steps = 32                                  # whole minibatches: about ten seconds of CPU work
+        st = orc.TrainState.fresh(u.W, u.b)
+        om = oracle_model(orc, np, u)
+        t0 = time.perf_counter()
+        for k in range(n_steps):
+            rows = u.batch_indices(k)
+            orc.update(om, st, u.x_raw[rows], u.target[rows], want_grads=False)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": n_steps * u.batch / dt, "unit": "samples/s", "cores": orc.num_threads(),
+                               "kind": "oracle", "sample": "%d fp64 steps on the first %d minibatches of %d rows (%.1f s)"
+                                                           % (n_steps, n_steps, u.batch, dt)}
+    return out
+
+
+def run_scoring(mods, args, name, primary):
+    np, torch, ab, wl = mods
+    dev = "cuda:0"
+    cfg = 6 if name == "lstm" else int(name[3:])      # "lstm": cfg5's shape behind the LSTM encoder
+    t_gen = time.time()
+    w = wl.make_config(cfg, S=args.scenarios if primary else None)
+    d = ab.desc_from_workload(w)
+    prm = ab.Params.from_workload(w, dev)
+    S, Cn = w.S, w.C
+    ws = ab.alloc_workspace(d, S, Cn, device=dev)
+    dyn, scal = torch.from_numpy(w.dyn).to(dev), torch.from_numpy(w.scal).to(dev)
+    part, cred = torch.from_numpy(w.part).to(dev), torch.from_numpy(w.cred).to(dev)
+    want_scores = cfg in (1, 3)
+    scores = torch.empty(S, Cn, dtype=torch.float32, device=dev) if want_scores else None
+    idx = torch.empty(S, dtype=torch.int32, device=dev)
+    best = torch.empty(S, dtype=torch.float32, device=dev)
+    t_gen = time.time() - t_gen
+
+    def step():
+        ab.ab_score_candidates(d, prm, dyn, scal, part, cred, scores, idx, best, ws)
+
+    default_steps = {1: 500, 3: 10}.get(cfg, 20)
+    steps = args.steps if (primary and args.steps is not None) else default_steps
+    warmup = args.warmup if (primary and args.warmup is not None) else 2
+    ms_per_step, ms_wall = timed_steps(torch, step, steps, warmup)
+    dtype = w.dtype
+    H = list(w.hidden)
+    flops_per_unit = H[0] + sum(2.0 * H[i] * H[i + 1] for i in range(len(H) - 1)) + 2.0 * H[-1]
+    trace_steps = 2 if cfg != 1 else 50
+    ksum, kernels = kernel_table(ab, step, trace_steps)
+    out = {"metric": "candidate configs scored/sec (meta-net fwd+argmax)", "value": S * Cn / (ms_per_step * 1e-3),
+           "unit": "candidates/s", "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
+           "ms_per_step_wall": ms_wall, "dtype": dtype,
+           "config": {"workload": "%s: %d scenarios x %d candidates, scorer %d->%s->1%s, %s"
+                                  % (name, S, Cn, w.F, "->".join(map(str, H)),
+                                     (", embedding 4->32 + two-layer LSTM (64 units) over %d tensors" % w.L
+                                      if w.te_kind == "lstm" else
+                                      ", tensor encoder 4->128->128 mean-pooled over %d tensors" % w.L)
+                                     if w.te_hidden else "", dtype),
+                      "scenarios": S, "candidates_per_scenario": Cn,
+                      "outputs": "scores+argmax" if want_scores else "argmax"},
+           "algorithmic_flop_per_unit": flops_per_unit,
+           "whole_step_TFLOP/s": round(S * Cn * flops_per_unit / (ms_per_step * 1e-3) / 1e12, 3),
+           "roofline": gemm_roofline(ab, name, ksum, dtype, trace_steps, ms_per_step),
+           "input_generation_s": round(t_gen, 2)}
+    if cfg == 1:
+        out["us_per_call"] = round(ms_per_step * 1e3, 2)
+        out["launches_per_call"] = int(round(sum(r["launches"] for r in ksum.values()) / trace_steps))
+
+    # ---- the memory-bound stages against the HBM peak: the feature transform as it ran inside the pass (time
+    # between events around the launch, which includes the launch itself; profiles/ has the kernel time), and the
+    # stand-alone argmax over the stored score matrix
+    hbm_stages = {"peak_GB/s": 8000.0}
+    for kname in ("encode_stats", "encode_and_prep"):
+        if kname in ksum:
+            r = ksum[kname]
+            rate = r["work"] / (r["total_ms"] * 1e-3)
+            hbm_stages[kname] = {"bytes_per_launch": r["work"] / r["launches"], "avg_us": round(r["avg_ms"] * 1e3, 2),
+                                 "GB/s": round(rate / 1e9, 1), "frac": round(rate / HBM_PEAK, 4),
+                                 "timed": "events around the launch"}
+    if want_scores and S * Cn >= (1 << 20):
+        idx2, best2 = torch.empty_like(idx), torch.empty_like(best)
+        for _ in range(3):
+            ab.ab_select_best(scores, idx2, best2)
+        with ab.KernelTimer() as kt2:
+            for _ in range(20):
+                ab.ab_select_best(scores, idx2, best2)
+            r = kt2.summary()["select_best"]
+        rate = r["work"] / (r["total_ms"] * 1e-3)
+        hbm_stages["select_best"] = {"bytes_per_launch": r["work"] / r["launches"], "avg_us": round(r["avg_ms"] * 1e3, 2),
+                                     "GB/s": round(rate / 1e9, 1), "frac": round(rate / HBM_PEAK, 4),
+                                     "timed": "events around the launch",
+                                     "same_choice_as_fused": bool(torch.equal(idx2, idx))}
+    out["hbm_stages"] = hbm_stages
+
+    # ---- the temporal encoder is bound by the vector ALUs: lane-operation slots (a transcendental takes four)
+    if cfg == 6 and "lstm_encoder" in ksum:
+        # per unit and step: 5 exp2 + 5 reciprocals (4 slots each) and 16 plain operations (scalings, sums,
+        # cell update, packing); 128 units (two layers of 64) per scenario and step
+        slots = float(S) * w.L * 128 * (10 * 4 + 16)
+        t_ms = ksum["lstm_encoder"]["avg_ms"]
+        peak = 256 * 4 * 16 * 2.4e9            # CUs x SIMDs x lanes per clock x clock: non-packed fp32 issue slots
+        out["encoder_roofline"] = {"bound": "alu", "kernel": "lstm_encoder",
+                                   "achieved": round(slots / (t_ms * 1e-3) / 1e12, 3),
+                                   "peak": round(peak / 1e12, 3), "unit": "T lane-operations/s",
+                                   "frac": round(slots / (t_ms * 1e-3) / peak, 4), "traffic": None,
+                                   "avg_launch_ms": round(t_ms, 5),
+                                   "scenario_steps_per_s": round(float(S) * w.L / (t_ms * 1e-3), 1)}
+    if not primary:
+        return out
+    out["kernels"] = kernels
+
+    # ---- the same pass with a grid of its own for every scenario (a repeated copy of the shared one)
+    if cfg in (2, 3, 5):
+        part_s = part.repeat(S, 1).contiguous()
+        cred_s = cred.repeat(S, 1).contiguous()
+        idx_s = torch.empty_like(idx)
+
+        def grid_step():
+            ab.ab_score_candidates(d, prm, dyn, scal, part_s, cred_s, scores, idx_s, best, ws)
+
+        ms_grid, _ = timed_steps(torch, grid_step, 3, 2)
+        out["per_scenario_grids"] = {"ms_per_step": round(ms_grid, 4),
+                                     "same_choice_as_shared_grid": float((idx_s == idx).float().mean().item())}
+        step()                       # leave the shared-grid results in place for what follows
+        torch.cuda.synchronize()
+
+    # ---- CPU oracle on a bounded sample of the same workload, same box
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        # sized for 10-20 s of CPU work on 16 cores; first and last scenarios, both sides of every border between two
+        # chunks of 2^20 candidate rows, seeded random ones in between
+        n_first, n_last, n_mid = {1: (1, 0, 0), 2: (256, 256, 256), 3: (128, 128, 256), 5: (400, 400, 400),
+                                  6: (400, 400, 400)}[cfg]
+        rows = wl.sample_scenarios(w.S, n_first, n_last, n_mid, max(1, (1 << 20) // w.C), seed=cfg)
+        sub = w.subset(rows)
+        n_s = len(rows)
+        reps = 2000 if cfg == 1 else 1                # the tiny workload is repeated to get a measurable time
+        om = oracle_model(orc, np, sub)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            ref = orc.score(om, sub.dyn, sub.scal, sub.part, sub.cred)
+            ridx, rbest, rsecond = orc.select(ref)
+        dt = time.perf_counter() - t0
+        cpu = {"value": reps * n_s * w.C / dt, "unit": "candidates/s", "cores": orc.num_threads(), "kind": "oracle",
+               "sample": "%d scenarios (first %d, last %d, %d on chunk borders and seeded in between) x all %d "
+                         "candidates%s, fp64, unfactorised (%.1f s)"
+                         % (n_s, n_first, n_last, n_s - n_first - n_last, w.C, ", %d times" % reps if reps > 1 else "", dt)}
+        # parity on this sample, in the parity tests' measures
+        rows_t = torch.from_numpy(rows).to(dev)
+        got_idx = idx[rows_t].cpu().numpy()
+        rms = np.sqrt(np.mean(ref ** 2))
+        scale = np.maximum(np.abs(ref).max(axis=1), rms)
+        tol = 1e-4 if dtype == "f32" else 2e-2
+        exact = (rbest - rsecond) / scale > tol
+        cpu["choice_equals_oracle_where_margin_exceeds_tol"] = bool((got_idx[exact] == ridx[exact]).all())
+        cpu["exact_index_rule_active_frac"] = float(exact.mean())
+        cpu["choice_equals_oracle_frac"] = float((got_idx == ridx).mean())
+        chosen = ref[np.arange(n_s), np.maximum(got_idx, 0)]
+        cpu["choice_within_tol_of_oracle_best"] = bool(((rbest - chosen) <= tol * scale).all())
+        if want_scores:
+            got = scores[rows_t].cpu().numpy().astype(np.float64)
+            cpu["gpu_vs_oracle_err_per_tensor"] = float(np.abs(got - ref).max() / np.abs(ref).max())
+            cpu["gpu_vs_oracle_err_strict_per_scenario"] = float((np.abs(got - ref) / scale[:, None]).max())
+            if dtype == "bf16":
+                om.round_stored_bf16 = True            # what bf16 storage alone does to the same scenarios
+                refq = orc.score(om, sub.dyn, sub.scal, sub.part, sub.cred)
+                cpu["rounding_alone_err_strict_per_scenario"] = float((np.abs(refq - ref) / scale[:, None]).max())
+                scale_q = np.maximum(np.abs(refq).max(axis=1), np.sqrt(np.mean(refq ** 2)))
+                cpu["gpu_vs_rounding_matched_oracle_err_strict"] = float((np.abs(got - refq) / scale_q[:, None]).max())
+        out["cpu_baseline"] = cpu
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "lstm"])
+    ap.add_argument("--workload", default="cfg3", choices=ALL_WORKLOADS)
     ap.add_argument("--scenarios", type=int, default=None, help="override the scenario count (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", action="store_true", help="run the primary workload alone (no legs of the other configurations)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a reference dispatch for HBM byte counters)")
     args = ap.parse_args()
@@ -65,69 +414,7 @@ def main():
     ab.load()
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    cfg = 6 if args.workload == "lstm" else int(args.workload[3:])   # "lstm": cfg5's shape behind the LSTM encoder
-    t_gen = time.time()
-
-    if cfg == 4:
-        u = wl.make_update()
-        d = ab.desc_from_workload(u)
-        prm = ab.Params(u.W, u.b, u.dtype, dev, trainable=True)
-        ws = ab.alloc_workspace(d, B=u.batch, device=dev)
-        loss = torch.zeros(1, dtype=torch.float32, device=dev)
-        xall, yall = torch.from_numpy(u.x_raw).to(dev), torch.from_numpy(u.target).to(dev)
-        batches = []
-        for s in range(16):
-            idx = torch.from_numpy(u.batch_indices(s)).to(dev)
-            batches.append((xall[idx].contiguous(), yall[idx].contiguous()))
-        counter = [0]
-
-        def step():
-            x, y = batches[counter[0] % 16]
-            counter[0] += 1
-            ab.ab_online_update(d, prm, x, y, loss_out=loss, workspace=ws)
-
-        units_per_step = u.batch
-        metric, unit = "online-update samples/sec", "samples/s"
-        dtype = u.dtype
-        steps = args.steps if args.steps is not None else 1000
-        warmup = args.warmup if args.warmup is not None else 20
-        widths = [u.F] + list(u.hidden) + [1]
-        flops_per_unit = sum(6.0 * widths[i] * widths[i + 1] for i in range(len(widths) - 1)) - 2.0 * widths[0] * widths[1]
-        dominant = None
-        workload_desc = {"workload": "cfg4: online adaptation, minibatch 4096, 390->512->512->512->1, "
-                                     "bf16 GEMMs, fp32 masters, Adam lr 1e-3", "batch": u.batch}
-    else:
-        w = wl.make_config(cfg, S=args.scenarios)
-        d = ab.desc_from_workload(w)
-        prm = ab.Params.from_workload(w, dev)
-        S, Cn = w.S, w.C
-        ws = ab.alloc_workspace(d, S, Cn, device=dev)
-        dyn, scal = torch.from_numpy(w.dyn).to(dev), torch.from_numpy(w.scal).to(dev)
-        part, cred = torch.from_numpy(w.part).to(dev), torch.from_numpy(w.cred).to(dev)
-        want_scores = cfg in (1, 3)
-        scores = torch.empty(S, Cn, dtype=torch.float32, device=dev) if want_scores else None
-        idx = torch.empty(S, dtype=torch.int32, device=dev)
-        best = torch.empty(S, dtype=torch.float32, device=dev)
-
-        def step():
-            ab.ab_score_candidates(d, prm, dyn, scal, part, cred, scores, idx, best, ws)
-
-        units_per_step = S * Cn
-        metric, unit = "candidate configs scored/sec (meta-net fwd+argmax)", "candidates/s"
-        dtype = w.dtype
-        steps = args.steps if args.steps is not None else {1: 500, 3: 10}.get(cfg, 20)
-        warmup = args.warmup if args.warmup is not None else 2
-        H = list(w.hidden)
-        flops_per_unit = H[0] + sum(2.0 * H[i] * H[i + 1] for i in range(len(H) - 1)) + 2.0 * H[-1]
-        workload_desc = {"workload": "%s: %d scenarios x %d candidates, scorer %d->%s->1%s, %s"
-                                     % (args.workload, S, Cn, w.F, "->".join(map(str, H)),
-                                        (", embedding 4->32 + two-layer LSTM (64 units) over %d tensors" % w.L
-                                         if w.te_kind == "lstm" else
-                                         ", tensor encoder 4->128->128 mean-pooled over %d tensors" % w.L)
-                                        if w.te_hidden else "", dtype),
-                         "scenarios": S, "candidates_per_scenario": Cn,
-                         "outputs": "scores+argmax" if want_scores else "argmax"}
-    t_gen = time.time() - t_gen
+    mods = (np, torch, ab, wl)
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -137,219 +424,24 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # ---- timed region: W warm-up steps, then exactly K steps between two device syncs
-    for _ in range(warmup):
-        step()
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record()
-    for _ in range(steps):
-        step()
-    e1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = max(e0.elapsed_time(e1), 0.0) / steps
-    ms_wall = wall * 1e3 / steps
-    value = units_per_step / (ms_per_step * 1e-3)
-
-    # ---- per-kernel device time: events around every launch, on the launching stream
-    trace_steps = 2 if cfg != 4 else 20
-    with ab.KernelTimer() as kt:
-        for _ in range(trace_steps):
-            step()
-        ksum = kt.summary()
-    kernels = {}
-    for name, r in sorted(ksum.items(), key=lambda kv: -kv[1]["total_ms"]):
-        rate = r["work"] / (r["total_ms"] * 1e-3) if r["total_ms"] > 0 else 0.0
-        kernels[name] = {"launches_per_step": r["launches"] / trace_steps, "avg_ms": round(r["avg_ms"], 5),
-                         "ms_per_step": round(r["total_ms"] / trace_steps, 5),
-                         ("GB/s" if r["is_bytes"] else "TFLOP/s"): round(rate / (1e9 if r["is_bytes"] else 1e12), 3)}
-    gemm_names = [n for n in ksum if n.startswith("gemm_hidden") or n.startswith("upd_gemm")]
-    if gemm_names:
-        tot_ms = sum(ksum[n]["total_ms"] for n in gemm_names)
-        tot_work = sum(ksum[n]["work"] for n in gemm_names)
-        launches = sum(ksum[n]["launches"] for n in gemm_names)
-        achieved = tot_work / (tot_ms * 1e-3)
-        roofline = {"bound": "mfma", "kernel": "hidden-layer GEMM launches (" + ", ".join(sorted(gemm_names)) + ")",
-                    "achieved": round(achieved / 1e12, 3), "peak": PEAK[dtype] / 1e12, "unit": "TFLOP/s",
-                    "frac": round(achieved / PEAK[dtype], 4),
-                    "traffic": TRAFFIC.get((args.workload, ab.ab_version())),
-                    "flop_per_launch": tot_work / launches, "avg_launch_ms": round(tot_ms / launches, 5),
-                    "share_of_step_time": round(tot_ms / trace_steps / ms_per_step, 3)}
-    else:
-        roofline = None
-
-    # ---- the memory-bound stages against the HBM peak: the feature transform as it ran inside the pass, and the
-    # stand-alone argmax over the stored score matrix
-    hbm_stages = None
-    if cfg != 4:
-        hbm_stages = {"peak_GB/s": 8000.0}
-        if "encode_stats" in ksum:
-            r = ksum["encode_stats"]
-            rate = r["work"] / (r["total_ms"] * 1e-3)
-            hbm_stages["encode_stats"] = {"bytes_per_launch": r["work"] / r["launches"], "avg_us": round(r["avg_ms"] * 1e3, 2),
-                                          "GB/s": round(rate / 1e9, 1), "frac": round(rate / 8e12, 4)}
-        if want_scores and S * Cn >= (1 << 20):
-            idx2, best2 = torch.empty_like(idx), torch.empty_like(best)
-            for _ in range(3):
-                ab.ab_select_best(scores, idx2, best2)
-            with ab.KernelTimer() as kt2:
-                for _ in range(20):
-                    ab.ab_select_best(scores, idx2, best2)
-                r = kt2.summary()["select_best"]
-            rate = r["work"] / (r["total_ms"] * 1e-3)
-            hbm_stages["select_best"] = {"bytes_per_launch": r["work"] / r["launches"], "avg_us": round(r["avg_ms"] * 1e3, 2),
-                                         "GB/s": round(rate / 1e9, 1), "frac": round(rate / 8e12, 4),
-                                         "same_choice_as_fused": bool(torch.equal(idx2, idx))}
-
-    # ---- the same pass with a grid of its own for every scenario (a repeated copy of the shared one)
-    grid_variant = None
-    if cfg in (2, 3, 5):
-        part_s = part.repeat(S, 1).contiguous()
-        cred_s = cred.repeat(S, 1).contiguous()
-        idx_s = torch.empty_like(idx)
-        for _ in range(2):
-            ab.ab_score_candidates(d, prm, dyn, scal, part_s, cred_s, scores, idx_s, best, ws)
-        torch.cuda.synchronize()
-        f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        f0.record()
-        for _ in range(3):
-            ab.ab_score_candidates(d, prm, dyn, scal, part_s, cred_s, scores, idx_s, best, ws)
-        f1.record()
-        torch.cuda.synchronize()
-        grid_variant = {"ms_per_step": round(f0.elapsed_time(f1) / 3, 4),
-                        "same_choice_as_shared_grid": float((idx_s == idx).float().mean().item())}
-        step()                       # leave the shared-grid results in place for what follows
-
-    # ---- transfer-learning form of the update and the minibatch assembly, timed next to the full step (cfg4 only)
-    transfer = None
-    if cfg == 4:
-        transfer = {}
-        D = len(u.hidden)
-        for k0 in (D - 1, D):
-            for _ in range(20):
-                ab.ab_online_update_tail(d, prm, batches[0][0], batches[0][1], k0, loss_out=loss, workspace=ws)
-            torch.cuda.synchronize()
-            f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            f0.record()
-            for i in range(200):
-                ab.ab_online_update_tail(d, prm, batches[i % 16][0], batches[i % 16][1], k0, loss_out=loss, workspace=ws)
-            f1.record()
-            torch.cuda.synchronize()
-            transfer["first_trainable_%d_us_per_step" % k0] = round(f0.elapsed_time(f1) * 1e3 / 200, 2)
-        pick = torch.randint(-u.x_raw.shape[0], 4096, (u.batch,), dtype=torch.int32, device=dev)
-        xo, to = torch.empty_like(batches[0][0]), torch.empty_like(batches[0][1])
-        for _ in range(10):
-            ab.ab_replay_mix(batches[1][0], batches[1][1], xall, yall, pick, xo, to)
-        torch.cuda.synchronize()
-        f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        f0.record()
-        for _ in range(200):
-            ab.ab_replay_mix(batches[1][0], batches[1][1], xall, yall, pick, xo, to)
-        f1.record()
-        torch.cuda.synchronize()
-        us = f0.elapsed_time(f1) * 1e3 / 200
-        transfer["replay_mix_us"] = round(us, 2)
-        transfer["replay_mix_GB/s"] = round(u.batch * (u.F + 1) * 8.0 / (us * 1e-6) / 1e9, 1)
-        # the same network with one output per worker (eight workers) and the unsquared L2 loss of Eq. 2
-        uw = wl.make_update(N=4096 * 4, n_workers=8, loss_kind="l2norm")
-        dw = ab.desc_from_workload(uw)
-        pw = ab.Params(uw.W, uw.b, uw.dtype, dev, trainable=True)
-        wsw = ab.alloc_workspace(dw, B=uw.batch, device=dev)
-        xw, yw = torch.from_numpy(uw.x_raw).to(dev), torch.from_numpy(uw.target).to(dev)
-        bw = [(xw[i * 4096:(i + 1) * 4096].contiguous(), yw[i * 4096:(i + 1) * 4096].contiguous()) for i in range(4)]
-        for i in range(20):
-            ab.ab_online_update(dw, pw, bw[i % 4][0], bw[i % 4][1], loss_out=loss, workspace=wsw)
-        torch.cuda.synchronize()
-        f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        f0.record()
-        for i in range(200):
-            ab.ab_online_update(dw, pw, bw[i % 4][0], bw[i % 4][1], loss_out=loss, workspace=wsw)
-        f1.record()
-        torch.cuda.synchronize()
-        transfer["eight_workers_norm_loss_us_per_step"] = round(f0.elapsed_time(f1) * 1e3 / 200, 2)
-        transfer["note"] = ("first_trainable = D-1 trains the last hidden layer and the output unit, D the output "
-                            "unit alone; replay_mix gathers one 4096-row minibatch from a 4096-row and a 65536-row pool")
-
-    # ---- the temporal encoder is bound by the vector ALUs: lane-operation slots (a transcendental takes four)
-    encoder_roofline = None
-    if cfg == 6 and "lstm_encoder" in ksum:
-        # per unit and step: 5 exp2 + 5 reciprocals (4 slots each) and 16 plain operations (scalings, sums,
-        # cell update, packing); 128 units (two layers of 64) per scenario and step
-        slots = float(S) * w.L * 128 * (10 * 4 + 16)
-        t_ms = ksum["lstm_encoder"]["avg_ms"]
-        peak = 256 * 4 * 16 * 2.4e9            # CUs x SIMDs x lanes per clock x clock: non-packed fp32 issue slots
-        encoder_roofline = {"bound": "alu", "kernel": "lstm_encoder", "achieved": round(slots / (t_ms * 1e-3) / 1e12, 3),
-                            "peak": round(peak / 1e12, 3), "unit": "T lane-operations/s",
-                            "frac": round(slots / (t_ms * 1e-3) / peak, 4), "traffic": None,
-                            "avg_launch_ms": round(t_ms, 5),
-                            "scenario_steps_per_s": round(float(S) * w.L / (t_ms * 1e-3), 1)}
-
-    # ---- launch floor of the update step: the same number of back-to-back trivial dependent launches
-    launch_floor = None
-    if cfg == 4:
-        n_launch = int(round(sum(r["launches"] for r in ksum.values()) / trace_steps))
-        tiny = torch.zeros(64, dtype=torch.float32, device=dev)
-        for _ in range(50):
-            tiny.add_(1.0)
-        torch.cuda.synchronize()
-        f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        f0.record()
-        for _ in range(100 * n_launch):
-            tiny.add_(1.0)
-        f1.record()
-        torch.cuda.synchronize()
-        launch_floor = {"launches_per_step": n_launch,
-                        "us_per_step_of_trivial_launches": round(f0.elapsed_time(f1) * 10.0, 2),
-                        "note": "the step is a chain of short dependent launches (16.2 GFLOP in all); replaying it "
-                                "from a captured HIP graph gave the same time, so the gaps are on the device side"}
-
-    # ---- CPU oracle on a bounded sample of the same workload, same box
-    cpu = None
-    if not args.no_cpu_baseline:
-        from oracle import oracle as orc
-        if cfg == 4:
-            n_steps = 32                                  # whole minibatches: about ten seconds of CPU work
-            st = orc.TrainState.fresh(u.W, u.b)
-            om = oracle_model(orc, np, u)
-            t0 = time.perf_counter()
-            for k in range(n_steps):
-                rows = u.batch_indices(k)
-                orc.update(om, st, u.x_raw[rows], u.target[rows], want_grads=False)
-            dt = time.perf_counter() - t0
-            cpu = {"value": n_steps * u.batch / dt, "unit": unit, "cores": orc.num_threads(), "kind": "oracle",
-                   "sample": "%d fp64 steps on the first %d minibatches of %d rows (%.1f s)" % (n_steps, n_steps, u.batch, dt)}
-        else:
-            n_s = {1: 1, 2: 768, 3: 512, 5: 1200, 6: 1200}[cfg]       # sized for 10-20 s of CPU work on 16 cores
-            n_s = min(n_s, w.S)
-            sub = w.subset(np.arange(n_s))
-            reps = 2000 if cfg == 1 else 1                # the tiny workload is repeated to get a measurable time
-            om = oracle_model(orc, np, sub)
-            t0 = time.perf_counter()
-            for _ in range(reps):
-                ref = orc.score(om, sub.dyn, sub.scal, sub.part, sub.cred)
-                ridx, _, _ = orc.select(ref)
-            dt = time.perf_counter() - t0
-            cpu = {"value": reps * n_s * w.C / dt, "unit": unit, "cores": orc.num_threads(), "kind": "oracle",
-                   "sample": "first %d scenarios x all %d candidates%s, fp64, unfactorised (%.1f s)"
-                             % (n_s, w.C, ", %d times" % reps if reps > 1 else "", dt)}
-            if want_scores:
-                # the parity tests' two measures on this sample: per-tensor (the bar: 1e-4 fp32, 2e-2 bf16) and the
-                # strict per-scenario one (bf16 is held to 5e-2 there)
-                got = scores[:n_s].cpu().numpy().astype(np.float64)
-                scale = np.maximum(np.abs(ref).max(axis=1, keepdims=True), np.sqrt(np.mean(ref ** 2)))
-                cpu["gpu_vs_oracle_err_per_tensor"] = float(np.abs(got - ref).max() / np.abs(ref).max())
-                cpu["gpu_vs_oracle_err_strict_per_scenario"] = float((np.abs(got - ref) / scale).max())
-
-    out = {"metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": steps, "warmup": warmup,
-           "ms_per_step": ms_per_step, "ms_per_step_wall": ms_wall, "higher_is_better": True, "scaling": "weak",
-           "vs_baseline": None, "dtype": dtype, "data": "synthetic (seeded, shaped like the paper's workloads)",
-           "config": workload_desc,
-           "algorithmic_flop_per_unit": flops_per_unit,
-           "whole_step_TFLOP/s": round(units_per_step * flops_per_unit / (ms_per_step * 1e-3) / 1e12, 3),
-           "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "launch_floor": launch_floor, "encoder_roofline": encoder_roofline, "hbm_stages": hbm_stages, "per_scenario_grids": grid_variant, "transfer_learning": transfer,
-           "input_generation_s": round(t_gen, 2)}
+    run = lambda name, primary: (run_update(mods, args, primary) if name == "cfg4"
+                                 else run_scoring(mods, args, name, primary))
+    res = run(args.workload, True)
+    out = {"metric": res.pop("metric"), "value": res.pop("value"), "unit": res.pop("unit"), "n_gpus": 1,
+           "steps": res.pop("steps"), "warmup": res.pop("warmup"), "ms_per_step": res.pop("ms_per_step"),
+           "ms_per_step_wall": res.pop("ms_per_step_wall"), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": res.pop("dtype"),
+           "data": "synthetic (seeded, shaped like the paper's workloads)", "config": res.pop("config"),
+           "roofline": res.pop("roofline"), "cpu_baseline": res.pop("cpu_baseline", None)}
+    out.update(res)
+    if not args.only:
+        others = {}
+        for name in ("cfg4", "cfg2", "cfg5", "cfg1", "cfg3"):
+            if name == args.workload:
+                continue
+            torch.cuda.empty_cache()
+            others[name] = run(name, False)
+        out["other_workloads"] = others
     print(json.dumps(out))
 
 

@@ -366,6 +366,22 @@ def make_config(cfg: int, S: Optional[int] = None, seed: Optional[int] = None) -
     raise ValueError("scoring configurations are 1, 2, 3, 5 and 6 (4 is the update workload)")
 
 
+def sample_scenarios(S: int, n_first: int, n_last: int, n_mid: int, edge: int, seed: int) -> np.ndarray:
+    """Scenario indices for a reference sample of a full-size run: the first ``n_first``, the last ``n_last``
+    and ``n_mid`` in between, of which as many as fit sit on both sides of a multiple of ``edge`` (the number
+    of scenarios one chunk of the launch sequence holds, so the last tile of one chunk and the first of the
+    next are both looked at); the rest are seeded random draws.  Sorted, without repeats."""
+    rng = np.random.default_rng(seed)
+    borders = np.arange(edge, S, edge, dtype=np.int64)
+    mid = np.concatenate([borders - 1, borders])
+    if mid.size > n_mid:
+        mid = rng.choice(mid, n_mid, replace=False)
+    lo, hi = min(n_first, S), max(min(n_first, S) + 1, S - n_last)
+    extra = rng.integers(lo, hi, max(0, n_mid - mid.size)) if hi > lo else np.zeros(0, dtype=np.int64)
+    rows = np.concatenate([np.arange(min(n_first, S)), np.arange(max(0, S - n_last), S), mid, extra])
+    return np.unique(rows[(rows >= 0) & (rows < S)].astype(np.int64))
+
+
 # --------------------------------------------------------------------------------------------
 # online-adaptation workload
 # --------------------------------------------------------------------------------------------

@@ -87,19 +87,9 @@ def frob_error(got, ref):
 
 
 def full_size_sample(S, n_first, n_last, n_mid, edge, seed):
-    """Scenario indices for an oracle sample of a full-size run: the first ``n_first``, the last ``n_last``
-    and ``n_mid`` in between, of which as many as fit sit on both sides of a multiple of ``edge`` (the number
-    of scenarios one chunk of the launch sequence holds, so the last tile of one chunk and the first of the
-    next are both looked at); the rest are seeded random draws."""
-    rng = np.random.default_rng(seed)
-    borders = np.arange(edge, S, edge, dtype=np.int64)
-    mid = np.concatenate([borders - 1, borders])
-    if mid.size > n_mid:
-        mid = rng.choice(mid, n_mid, replace=False)
-    lo, hi = min(n_first, S), max(min(n_first, S) + 1, S - n_last)
-    extra = rng.integers(lo, hi, max(0, n_mid - mid.size)) if hi > lo else np.zeros(0, dtype=np.int64)
-    rows = np.concatenate([np.arange(min(n_first, S)), np.arange(max(0, S - n_last), S), mid, extra])
-    return np.unique(rows[(rows >= 0) & (rows < S)].astype(np.int64))
+    """Scenario indices for an oracle sample of a full-size run (see ``workloads.sample_scenarios``)."""
+    from paper_2112_13509_amd import workloads as wl
+    return wl.sample_scenarios(S, n_first, n_last, n_mid, edge, seed)
 
 
 def check_against_matched(got, refq, tolq):
