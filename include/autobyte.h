@@ -54,7 +54,9 @@
 extern "C" {
 #endif
 
-#define AB_MAX_STATS   8    /* statistics per layer (K)                    */
+#define AB_MAX_STATS   16   /* statistics per layer (K): Table 1's T has one backward time per layer and worker;
+                               the two encoders take at most AB_MAX_ENCODER_STATS of them                   */
+#define AB_MAX_ENCODER_STATS 8
 #define AB_MAX_SCALARS 40   /* scalar features per scenario (Table 1: n, l, type vectors, B_d and B_u per worker) */
 #define AB_MAX_HIDDEN  8    /* hidden layers of the scorer                 */
 #define AB_MAX_OUTPUTS 16   /* entries of the predicted speed V            */
@@ -81,7 +83,8 @@ typedef struct { int32_t kind; float shift; float scale; } ab_enc;
 
 /*
  * Model description (HOST, plain data, read during the call).
- *   n_layers, n_stats      L and K of the statistics tensor dyn[S, L, K]
+ *   n_layers, n_stats      L and K of the statistics tensor dyn[S, L, K]; K <= AB_MAX_STATS for the flat layout,
+ *                          K <= AB_MAX_ENCODER_STATS with an encoder (more is AB_ERR_UNSUPPORTED)
  *   n_scalars              scalar features per scenario (worker count, bandwidth, type one-hots ...)
  *   enc_*                  transform of each statistic kind, each scalar, the partition size and the
  *                          credit multiple
@@ -190,6 +193,19 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
                               void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * ab_score_candidates that also returns the predicted speed vector itself for the chosen candidate (Table 1: V has
+ * one entry per worker; Eq. 1 returns V, of which ab_score_candidates only reports the mean it ranks by).
+ *   v_best      DEVICE [S, n_outputs] fp32: V of candidate best_idx[s] (NaN where best_idx[s] = -1), or NULL;
+ *               needs best_idx.  mean_o v_best[s, o] equals best_score[s] up to fp32 summation order.
+ * Everything else as ab_score_candidates (same workspace size).  With v_best given the hidden chain runs once
+ * more on one row per scenario (1/C of the scoring work) and the output layer is applied unit by unit.
+ */
+ab_status ab_score_candidates_v(const ab_model_desc *desc, const ab_params *params,
+                                const ab_stats *stats, const ab_grid *grid,
+                                float *scores, int32_t *best_idx, float *best_score, float *v_best,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * ab_score_candidates for callers that cannot allocate device memory or hand over a workspace: code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The workspace is a fixed array of
  * AB_STATIC_SCRATCH_BYTES inside the library's code object (every device the library runs on holds its own
@@ -267,14 +283,15 @@ ab_status ab_online_update_tail(const ab_model_desc *desc, ab_params *params,
  * Minibatch assembly for online adaptation (Section 3.2: the newly observed samples also extend the
  * dataset the model was trained on, so a step mixes both): output row i is row pick[i] of the new pool
  * if pick[i] >= 0, else row -pick[i] - 1 of the old pool; the targets follow.  Which rows to mix is the
- * caller's draw.  An index outside its pool yields a NaN row and a NaN target (no memory is read).
- *   x_new [n_new, F], target_new [n_new], x_old [n_old, F], target_old [n_old]   DEVICE fp32 raw rows
- *   pick [B] DEVICE int32;  x_out [B, F], target_out [B] DEVICE fp32 (must not overlap the pools)
- * A pool of size 0 may be NULL.
+ * caller's draw.  An index outside its pool yields a NaN row and NaN targets (no memory is read).
+ *   x_new [n_new, F], target_new [n_new, n_outputs], x_old [n_old, F], target_old [n_old, n_outputs]  DEVICE fp32
+ *   pick [B] DEVICE int32;  x_out [B, F], target_out [B, n_outputs] DEVICE fp32 (must not overlap the pools)
+ * n_outputs >= 1 is the number of observed speeds per row (one, or one per worker as ab_online_update takes them),
+ * at most AB_MAX_OUTPUTS.  A pool of size 0 may be NULL.
  */
 ab_status ab_replay_mix(const float *x_new, const float *target_new, int64_t n_new,
                         const float *x_old, const float *target_old, int64_t n_old,
-                        const int32_t *pick, int64_t B, int32_t F,
+                        const int32_t *pick, int64_t B, int32_t F, int32_t n_outputs,
                         float *x_out, float *target_out, void *stream);
 
 const char *ab_status_string(ab_status status);

@@ -262,8 +262,9 @@ static void orc_scenario_features(const orc_model *m, const double *dyn_s, const
     if (m->round_stored_bf16) for (int j = 0; j < off + m->Ns; ++j) xs[j] = orc_round_bf16(xs[j]);
 }
 
-/* Scorer MLP on one full input vector x[F]; buf holds 2*maxwidth doubles. */
-static double orc_mlp_forward(const orc_model *m, const double *x, int F, double *buf, int maxw)
+/* Scorer MLP on one full input vector x[F]; buf holds 2*maxwidth doubles.  Returns the score (mean of V);
+ * v_out, if given, receives the n_out entries of V themselves. */
+static double orc_mlp_forward_v(const orc_model *m, const double *x, int F, double *buf, int maxw, double *v_out)
 {
     const double *cur = x;
     int n_in = F;
@@ -277,11 +278,17 @@ static double orc_mlp_forward(const orc_model *m, const double *x, int F, double
         n_in = m->hidden[k];
     }
     /* V has n_out entries; the configuration's score is their mean */
-    double v[64], score = 0.0;
+    double v_local[64], score = 0.0;
+    double *v = v_out ? v_out : v_local;
     const int no = orc_n_out(m);
     orc_dense(m->W[m->n_hidden], m->b[m->n_hidden], no, n_in, cur, v, 0);
     for (int w = 0; w < no; ++w) score += v[w];
     return score / (double)no;
+}
+
+static double orc_mlp_forward(const orc_model *m, const double *x, int F, double *buf, int maxw)
+{
+    return orc_mlp_forward_v(m, x, F, buf, maxw, NULL);
 }
 
 /*
@@ -329,6 +336,44 @@ int orc_score_grids(const orc_model *m, const double *dyn, const double *scal, i
         }
     }
     return err ? ORC_ERR_MEM : ORC_OK;
+}
+
+/*
+ * The predicted speed vector V itself (Table 1: one entry per worker; Eq. 1 returns V) for ONE candidate per
+ * scenario: cand[s] = p*Q + q, e.g. the chosen one.  V is [S, n_out]; a scenario with cand[s] outside [0, P*Q)
+ * (no valid choice) gets NaN.  Same steps as orc_score_grids, nothing folded: the output layer is applied unit
+ * by unit.
+ */
+int orc_predict_v(const orc_model *m, const double *dyn, const double *scal, int64_t S,
+                  const int32_t *layers_of, const double *part, int P, const double *cred, int Q,
+                  int grid_per_scenario, const int32_t *cand, double *V)
+{
+    if (!m || !V || !cand || S < 0 || P <= 0 || Q <= 0 || orc_n_out(m) > 64) return ORC_ERR_ARG;
+    if (layers_of && !m->tensor_encoder) return ORC_ERR_ARG;
+    const int Fs = orc_stats_width(m), F = Fs + 2, no = orc_n_out(m);
+    int maxw = 1;
+    for (int k = 0; k < m->n_hidden; ++k) if (m->hidden[k] > maxw) maxw = m->hidden[k];
+    const int tmpw = orc_feature_scratch(m);
+    double *x = (double *)malloc(sizeof(double) * (size_t)(F + 2 * maxw + tmpw));
+    if (!x) return ORC_ERR_MEM;
+    double *buf = x + F, *tmp = buf + 2 * maxw;
+    for (int64_t s = 0; s < S; ++s) {
+        double *v = V + (size_t)s * no;
+        if (cand[s] < 0 || cand[s] >= P * Q) {
+            for (int w = 0; w < no; ++w) v[w] = NAN;
+            continue;
+        }
+        const int p = cand[s] / Q, q = cand[s] % Q;
+        orc_scenario_features(m, dyn + (size_t)s * m->L * m->K, scal + (size_t)s * m->Ns,
+                              orc_layers_of(m, layers_of, s), x, tmp);
+        const double *part_s = grid_per_scenario ? part + (size_t)s * P : part;
+        const double *cred_s = grid_per_scenario ? cred + (size_t)s * Q : cred;
+        x[Fs]     = orc_phi(part_s[p], m->cfg_kind[0], m->cfg_shift[0], m->cfg_scale[0]);
+        x[Fs + 1] = orc_phi(cred_s[q], m->cfg_kind[1], m->cfg_shift[1], m->cfg_scale[1]);
+        (void)orc_mlp_forward_v(m, x, F, buf, maxw, v);
+    }
+    free(x);
+    return ORC_OK;
 }
 
 int orc_score_layers(const orc_model *m, const double *dyn, const double *scal, int64_t S,

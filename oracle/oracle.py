@@ -210,6 +210,28 @@ def score(model: Model, dyn, scal, part, cred, layers_of=None) -> np.ndarray:
     return out
 
 
+def predict_v(model: Model, dyn, scal, part, cred, cand, layers_of=None) -> np.ndarray:
+    """The predicted speed vector V (one entry per output unit, Table 1) of candidate ``cand[s]`` = p*Q + q for
+    every scenario: float64 [S, n_out]; NaN where cand[s] is not a valid candidate index."""
+    lib = _load()
+    dyn, scal, part, cred = _f64(dyn), _f64(scal), _f64(part), _f64(cred)
+    S = dyn.shape[0]
+    assert dyn.shape == (S, model.L, model.K) and scal.shape == (S, model.Ns)
+    per_scenario = part.ndim == 2
+    P, Q = part.shape[-1], cred.shape[-1]
+    cand = np.ascontiguousarray(cand, dtype=np.int32)
+    assert cand.shape == (S,)
+    out = np.empty((S, model.n_out), dtype=np.float64)
+    cm = model._c()
+    lo = None if layers_of is None else np.ascontiguousarray(layers_of, dtype=np.int32)
+    _check(lib.orc_predict_v(C.byref(cm), dyn.ctypes.data_as(_dp), scal.ctypes.data_as(_dp), C.c_int64(S),
+                             None if lo is None else lo.ctypes.data_as(_ip),
+                             part.ctypes.data_as(_dp), C.c_int(P), cred.ctypes.data_as(_dp), C.c_int(Q),
+                             C.c_int(1 if per_scenario else 0), cand.ctypes.data_as(_ip),
+                             out.ctypes.data_as(_dp)), "predict_v")
+    return out
+
+
 def lstm_encode(model: Model, dyn, layers_of=None) -> np.ndarray:
     """The LSTM temporal encoder alone (Section 3.1): last hidden state of the second layer, float64 [S, H]."""
     lib = _load()
@@ -350,12 +372,14 @@ def update(model: Model, state: TrainState, x_raw, target, lr=1e-3, beta1=0.9, b
 def replay_mix(x_new, t_new, x_old, t_old, pick):
     """Minibatch assembled from freshly observed rows and the offline set (Section 3.2: online
     adaptation refreshes the offline-trained model and extends its dataset with the new samples): entry i of ``pick`` >= 0 takes new row pick[i], entry < 0 takes
-    old row -pick[i] - 1; an index outside its pool gives a NaN row.  Returns (x [B, F], target [B])."""
+    old row -pick[i] - 1; an index outside its pool gives a NaN row.  Targets are [n] or [n, n_out] (one observed
+    speed per worker).  Returns (x [B, F], target [B] or [B, n_out])."""
     x_new, t_new, x_old, t_old = _f64(x_new), _f64(t_new), _f64(x_old), _f64(t_old)
     pick = np.asarray(pick, dtype=np.int64)
     F = x_new.shape[1] if x_new.size else x_old.shape[1]
+    t_ref = t_new if t_new.size else t_old
     x = np.full((pick.shape[0], F), np.nan)
-    t = np.full(pick.shape[0], np.nan)
+    t = np.full((pick.shape[0],) + t_ref.shape[1:], np.nan)
     for i, p in enumerate(pick):
         if 0 <= p < x_new.shape[0]:
             x[i], t[i] = x_new[p], t_new[p]

@@ -14,7 +14,7 @@ import torch
 
 AB_F32, AB_BF16 = 0, 1
 AB_ENC_LINEAR, AB_ENC_LOG = 0, 1
-AB_MAX_STATS, AB_MAX_SCALARS, AB_MAX_HIDDEN, AB_MAX_LAYERS = 8, 40, 8, 12
+AB_MAX_STATS, AB_MAX_SCALARS, AB_MAX_HIDDEN, AB_MAX_LAYERS = 16, 40, 8, 12
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libautobyte.so")
 _lib = None
@@ -80,6 +80,10 @@ def load():
         lib.ab_score_candidates.argtypes = [C.POINTER(ab_model_desc), C.POINTER(ab_params),
                                             C.POINTER(ab_stats), C.POINTER(ab_grid),
                                             _vp, _vp, _vp, _vp, C.c_size_t, _vp]
+        lib.ab_score_candidates_v.restype = C.c_int32
+        lib.ab_score_candidates_v.argtypes = [C.POINTER(ab_model_desc), C.POINTER(ab_params),
+                                              C.POINTER(ab_stats), C.POINTER(ab_grid),
+                                              _vp, _vp, _vp, _vp, _vp, C.c_size_t, _vp]
         lib.ab_static_scratch_bytes.restype = C.c_size_t
         lib.ab_static_scratch_bytes.argtypes = []
         lib.ab_score_candidates_static.restype = C.c_int32
@@ -100,7 +104,7 @@ def load():
                                               C.c_int64, C.c_int32, C.c_float, C.c_float, C.c_float, C.c_float,
                                               _vp, _vp, C.c_size_t, _vp]
         lib.ab_replay_mix.restype = C.c_int32
-        lib.ab_replay_mix.argtypes = [_vp, _vp, C.c_int64, _vp, _vp, C.c_int64, _vp, C.c_int64, C.c_int32,
+        lib.ab_replay_mix.argtypes = [_vp, _vp, C.c_int64, _vp, _vp, C.c_int64, _vp, C.c_int64, C.c_int32, C.c_int32,
                                       _vp, _vp, _vp]
         _lib = lib
     return _lib
@@ -282,8 +286,9 @@ def ab_score_candidates(desc: ab_model_desc, params: Params, dyn: torch.Tensor, 
                         scores: Optional[torch.Tensor] = None, best_idx: Optional[torch.Tensor] = None,
                         best_score: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
                         stream=None, check: bool = True, layers_of: Optional[torch.Tensor] = None,
-                        static_scratch: bool = False) -> int:
+                        static_scratch: bool = False, v_best: Optional[torch.Tensor] = None) -> int:
     """Enqueue scoring of every (scenario, candidate); outputs are written into the given tensors.
+    ``v_best`` [S, n_outputs] (needs ``best_idx``): the predicted speed vector of the chosen candidate.
     ``layers_of`` (int32 [S], encoder models only): how many of the L padded layers each scenario really has.
     ``partition_bytes`` [P] and ``credit_mult`` [Q] are shared by all scenarios; given as [S, P] and [S, Q]
     every scenario brings its own grid."""
@@ -304,9 +309,12 @@ def ab_score_candidates(desc: ab_model_desc, params: Params, dyn: torch.Tensor, 
     for t, n, what in ((scores, S * P * Q, "scores"), (best_idx, S, "best_idx"), (best_score, S, "best_score")):
         if t is not None and t.numel() != n:
             raise ValueError("%s has %d elements, expected %d" % (what, t.numel(), n))
+    n_out = max(1, int(desc.n_outputs))
+    if v_best is not None and v_best.numel() != S * n_out:
+        raise ValueError("v_best has %d elements, expected %d" % (v_best.numel(), S * n_out))
     if static_scratch:
-        if workspace is not None:
-            raise ValueError("the static-scratch form takes no workspace")
+        if workspace is not None or v_best is not None:
+            raise ValueError("the static-scratch form takes neither a workspace nor v_best")
         rc = lib.ab_score_candidates_static(C.byref(desc), C.byref(params.c), C.byref(st), C.byref(gr),
                                             _ptr(scores, torch.float32, "scores"),
                                             _ptr(best_idx, torch.int32, "best_idx"),
@@ -315,6 +323,15 @@ def ab_score_candidates(desc: ab_model_desc, params: Params, dyn: torch.Tensor, 
             raise AutoByteError(rc, "ab_score_candidates_static")
         return rc
     ws_ptr = _ptr(workspace, torch.uint8, "workspace")
+    if v_best is not None:
+        rc = lib.ab_score_candidates_v(C.byref(desc), C.byref(params.c), C.byref(st), C.byref(gr),
+                                       _ptr(scores, torch.float32, "scores"), _ptr(best_idx, torch.int32, "best_idx"),
+                                       _ptr(best_score, torch.float32, "best_score"),
+                                       _ptr(v_best, torch.float32, "v_best"), ws_ptr,
+                                       0 if workspace is None else workspace.numel(), _stream_handle(stream))
+        if check and rc != 0:
+            raise AutoByteError(rc, "ab_score_candidates_v")
+        return rc
     rc = lib.ab_score_candidates(C.byref(desc), C.byref(params.c), C.byref(st), C.byref(gr),
                                  _ptr(scores, torch.float32, "scores"), _ptr(best_idx, torch.int32, "best_idx"),
                                  _ptr(best_score, torch.float32, "best_score"), ws_ptr,
@@ -439,11 +456,15 @@ def ab_replay_mix(x_new: Optional[torch.Tensor], target_new: Optional[torch.Tens
     for t_ in (x_new, x_old):
         if t_ is not None and int(t_.shape[1]) != F:
             raise ValueError("pools and output must have the same row width")
-    if pick.numel() != B or target_out.numel() != B:
-        raise ValueError("pick and target_out must have one entry per output row")
+    if pick.numel() != B or target_out.numel() % B != 0:
+        raise ValueError("pick must have one entry and target_out n_outputs entries per output row")
+    n_out = target_out.numel() // B
+    for t_, n_ in ((target_new, n_new), (target_old, n_old)):
+        if t_ is not None and t_.numel() != n_ * n_out:
+            raise ValueError("pool targets must have %d entries per row" % n_out)
     rc = lib.ab_replay_mix(_ptr(x_new, torch.float32, "x_new"), _ptr(target_new, torch.float32, "target_new"), n_new,
                            _ptr(x_old, torch.float32, "x_old"), _ptr(target_old, torch.float32, "target_old"), n_old,
-                           _ptr(pick, torch.int32, "pick"), B, F, _ptr(x_out, torch.float32, "x_out"),
+                           _ptr(pick, torch.int32, "pick"), B, F, n_out, _ptr(x_out, torch.float32, "x_out"),
                            _ptr(target_out, torch.float32, "target_out"), _stream_handle(stream))
     if check and rc != 0:
         raise AutoByteError(rc, "ab_replay_mix")

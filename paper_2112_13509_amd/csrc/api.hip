@@ -42,6 +42,7 @@ static ab_status check_desc(const ab_model_desc *d)
     if (d->tensor_encoder < 0 || d->tensor_encoder > 2) return AB_ERR_SHAPE;
     if (d->tensor_encoder) {
         if (d->enc_hidden[0] <= 0 || d->enc_hidden[1] <= 0) return AB_ERR_SHAPE;
+        if (d->n_stats > AB_MAX_ENCODER_STATS) return AB_ERR_UNSUPPORTED;
         if (d->tensor_encoder == 1 && (d->enc_hidden[0] != 128 || d->enc_hidden[1] != 128)) return AB_ERR_UNSUPPORTED;
         if (d->tensor_encoder == 2 && (d->enc_hidden[0] != 32 || d->enc_hidden[1] != 64)) return AB_ERR_UNSUPPORTED;
         if (d->compute_dtype != AB_BF16) return AB_ERR_UNSUPPORTED;
@@ -60,9 +61,14 @@ struct ScorePlan {
     int nt_last;
     int64_t chunk_scen, chunk_rows;
     size_t off_xs, off_w1s, off_aterm, off_bterm, off_cfgv, off_wout, off_xrow, off_partial, off_act0, off_act1, total;
+    // second pass for the chosen candidate's prediction vector: one row per scenario, kVChunk scenarios at a time
+    int64_t v_chunk;
+    int v_tile[AB_MAX_HIDDEN];
+    size_t off_vx, off_vact0, off_vact1, off_vlast;
 };
 
 static const int64_t kTargetChunkRows = 1 << 20;
+static const int64_t kVChunk = 4096;
 
 static ab_status plan_scoring(const ab_model_desc *d, int64_t S, int32_t C, ScorePlan *p)
 {
@@ -108,6 +114,13 @@ static ab_status plan_scoring(const ab_model_desc *d, int64_t S, int32_t C, Scor
     p->off_act0 = p->off_act1 = 0;
     if (p->D >= 3) p->off_act0 = take((size_t)p->chunk_rows * hmax * es);
     if (p->D >= 4) p->off_act1 = take((size_t)p->chunk_rows * hmax * es);
+    p->v_chunk = S < kVChunk ? (S > 0 ? S : 1) : kVChunk;
+    for (int k = 1; k < p->D; ++k) p->v_tile[k] = pick_tile(p->v_chunk, p->H[k]);
+    p->off_vx = take((size_t)p->v_chunk * 2 * 4);
+    p->off_vact0 = p->off_vact1 = p->off_vlast = 0;
+    if (p->D >= 2) p->off_vlast = take((size_t)p->v_chunk * p->H[p->D - 1] * 4);
+    if (p->D >= 3) p->off_vact0 = take((size_t)p->v_chunk * hmax * es);
+    if (p->D >= 4) p->off_vact1 = take((size_t)p->v_chunk * hmax * es);
     p->total = off;
     return AB_OK;
 }
@@ -120,7 +133,7 @@ static inline bool misaligned(const void *p, size_t a) { return ((uintptr_t)p % 
 size_t update_workspace_bytes(const ab_model_desc *d, int64_t B);
 hipError_t launch_replay_mix(const float *x_new, const float *t_new, int64_t n_new, const float *x_old,
                              const float *t_old, int64_t n_old, const int32_t *pick, int64_t B, int32_t F,
-                             float *x_out, float *t_out, hipStream_t st);
+                             int32_t n_out, float *x_out, float *t_out, hipStream_t st);
 ab_status online_update(const ab_model_desc *d, ab_params *params, const float *x_raw, const float *target,
                         int64_t B, float lr, float beta1, float beta2, float eps, float *loss_out,
                         void *workspace, size_t ws_bytes, int first_trainable, hipStream_t st);
@@ -172,7 +185,7 @@ size_t ab_workspace_bytes(const ab_model_desc *desc, int64_t S, int32_t C, int64
 // Scoring with the workspace given by address: the body of both scoring entry points.
 static ab_status score_candidates_in(const ab_model_desc *desc, const ab_params *params,
                                      const ab_stats *stats, const ab_grid *grid,
-                                     float *scores, int32_t *best_idx, float *best_score,
+                                     float *scores, int32_t *best_idx, float *best_score, float *v_best,
                                      void *workspace, size_t workspace_bytes, void *stream)
 {
     ab_status rc = check_desc(desc);
@@ -181,6 +194,7 @@ static ab_status score_candidates_in(const ab_model_desc *desc, const ab_params 
     if (stats->S == 0) return AB_OK;      // nothing to score: valid no-op, no pointer is looked at
     if (!scores && !best_idx) return AB_ERR_NULL;
     if (best_score && !best_idx) return AB_ERR_NULL;
+    if (v_best && !best_idx) return AB_ERR_NULL;
     if (stats->S < 0 || grid->P <= 0 || grid->Q <= 0) return AB_ERR_SHAPE;
     if ((int64_t)grid->P * grid->Q > (1 << 24)) return AB_ERR_SHAPE;
     if (!grid->partition_bytes || !grid->credit_mult) return AB_ERR_NULL;
@@ -200,13 +214,13 @@ static ab_status score_candidates_in(const ab_model_desc *desc, const ab_params 
         if (misaligned(params->W[k], 16) || misaligned(params->b[k], 4)) return AB_ERR_ALIGN;
     }
     if (misaligned(stats->dyn, 4) || misaligned(stats->scalars, 4) || misaligned(scores, 4) ||
-        misaligned(best_idx, 4) || misaligned(best_score, 4)) return AB_ERR_ALIGN;
+        misaligned(best_idx, 4) || misaligned(best_score, 4) || misaligned(v_best, 4)) return AB_ERR_ALIGN;
     if (!workspace || workspace_bytes < p.total) return AB_ERR_WORKSPACE;
     if (misaligned(workspace, 256)) return AB_ERR_ALIGN;
     if (S == 0) return AB_OK;
 
     hipStream_t st = (hipStream_t)stream;
-    if (score_tiny_supported(desc, S, C)) {
+    if (!v_best && score_tiny_supported(desc, S, C)) {
         // the paper's own operating point (a job, tens of candidates, a small scorer): one launch does everything
         double fl = (double)p.H[0] * p.Fs * 2.0 * S;
         for (int k = 0; k < p.D; ++k) fl += 2.0 * S * C * p.H[k] * (k ? p.H[k - 1] : 3);
@@ -320,6 +334,42 @@ static ab_status score_candidates_in(const ab_model_desc *desc, const ab_params 
                                     best_idx ? best_idx + s0 : nullptr,
                                     best_score ? best_score + s0 : nullptr, ns, C, st));
     }
+    // 5. the chosen candidate's prediction vector: the hidden chain once more on one row per scenario (the row's
+    // candidate values are those of best_idx), then the output layer unit by unit
+    if (v_best) {
+        const int n_out = desc->n_outputs > 0 ? desc->n_outputs : 1;
+        float *xp_sel = (float *)(ws + p.off_vx), *xc_sel = xp_sel + p.v_chunk;
+        float *h_last = (float *)(ws + p.off_vlast);
+        void *vact[2] = {ws + p.off_vact0, ws + p.off_vact1};
+        for (int64_t s0 = 0; s0 < S; s0 += p.v_chunk) {
+            const int64_t ns = (S - s0 < p.v_chunk) ? S - s0 : p.v_chunk;
+            ab_grid gsub = *grid;
+            if (per_scenario) { gsub.partition_bytes += s0 * grid->P; gsub.credit_mult += s0 * grid->Q; }
+            {
+                TraceScope ts("chosen_pair", (double)ns * 20.0, 1, st);
+                AB_HIP(launch_chosen_pair(desc, &gsub, best_idx + s0, xp_sel, xc_sel, ns, st));
+            }
+            for (int k = 1; k < p.D; ++k) {
+                GemmArgs g;
+                memset(&g, 0, sizeof(g));
+                if (k == 1) {
+                    g.a_term = a_term + s0 * p.H[0]; g.ldt = p.H[0]; g.C = 1;
+                    g.wp = cfg_vec; g.wc = cfg_vec + p.H[0]; g.xp = xp_sel; g.xc = xc_sel; g.x_per_row = 1;
+                } else { g.A = vact[k & 1]; g.lda = p.H[k - 1]; }
+                g.B = params->W[p.base + k]; g.ldb = p.H[k - 1];
+                g.M = ns; g.N = p.H[k]; g.K = p.H[k - 1];
+                g.bias = params->b[p.base + k]; g.relu = 1;
+                if (k == p.D - 1) { g.out = h_last; g.ldo = p.H[k]; g.out_f32 = 1; }
+                else { g.out = vact[(k + 1) & 1]; g.ldo = p.H[k]; }
+                TraceScope ts("gemm_chosen_rows", 2.0 * ns * p.H[k] * p.H[k - 1], 0, st);
+                AB_HIP(launch_gemm(dt, p.v_tile[k], k == 1 ? AMODE_GENV : AMODE_LOAD, EPI_STORE, g, st));
+            }
+            TraceScope ts("output_v", (double)ns * (p.H[p.D - 1] * 4.0 + n_out * 4.0), 1, st);
+            AB_HIP(launch_output_v(dt, p.D >= 2 ? h_last : nullptr, a_term + s0 * p.H[0], cfg_vec, cfg_vec + p.H[0],
+                                   xp_sel, xc_sel, params->W[p.base + p.D], params->b[p.base + p.D], p.H[p.D - 1],
+                                   n_out, best_idx + s0, v_best + s0 * n_out, ns, st));
+        }
+    }
     return AB_OK;
 }
 
@@ -353,7 +403,16 @@ ab_status ab_score_candidates(const ab_model_desc *desc, const ab_params *params
                               float *scores, int32_t *best_idx, float *best_score,
                               void *workspace, size_t workspace_bytes, void *stream)
 {
-    return score_candidates_in(desc, params, stats, grid, scores, best_idx, best_score,
+    return score_candidates_in(desc, params, stats, grid, scores, best_idx, best_score, nullptr,
+                               workspace, workspace_bytes, stream);
+}
+
+ab_status ab_score_candidates_v(const ab_model_desc *desc, const ab_params *params,
+                                const ab_stats *stats, const ab_grid *grid,
+                                float *scores, int32_t *best_idx, float *best_score, float *v_best,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    return score_candidates_in(desc, params, stats, grid, scores, best_idx, best_score, v_best,
                                workspace, workspace_bytes, stream);
 }
 
@@ -376,7 +435,7 @@ ab_status ab_score_candidates_static(const ab_model_desc *desc, const ab_params 
     void *ptr = nullptr;
     rc = static_scratch(&ptr);
     if (rc != AB_OK) return rc;
-    return score_candidates_in(desc, params, stats, grid, scores, best_idx, best_score,
+    return score_candidates_in(desc, params, stats, grid, scores, best_idx, best_score, nullptr,
                                ptr, AB_STATIC_SCRATCH_BYTES, stream);
 }
 
@@ -448,10 +507,10 @@ ab_status ab_online_update_tail(const ab_model_desc *desc, ab_params *params,
 
 ab_status ab_replay_mix(const float *x_new, const float *target_new, int64_t n_new,
                         const float *x_old, const float *target_old, int64_t n_old,
-                        const int32_t *pick, int64_t B, int32_t F,
+                        const int32_t *pick, int64_t B, int32_t F, int32_t n_outputs,
                         float *x_out, float *target_out, void *stream)
 {
-    if (n_new < 0 || n_old < 0 || B < 0 || F <= 0) return AB_ERR_SHAPE;
+    if (n_new < 0 || n_old < 0 || B < 0 || F <= 0 || n_outputs < 1 || n_outputs > AB_MAX_OUTPUTS) return AB_ERR_SHAPE;
     if (B == 0) return AB_OK;
     if (!pick || !x_out || !target_out) return AB_ERR_NULL;
     if ((n_new > 0 && (!x_new || !target_new)) || (n_old > 0 && (!x_old || !target_old))) return AB_ERR_NULL;
@@ -459,8 +518,9 @@ ab_status ab_replay_mix(const float *x_new, const float *target_new, int64_t n_n
     if (misaligned(x_new, 4) || misaligned(x_old, 4) || misaligned(x_out, 4) || misaligned(pick, 4) ||
         misaligned(target_new, 4) || misaligned(target_old, 4) || misaligned(target_out, 4)) return AB_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
-    TraceScope ts("replay_mix", (double)B * (F + 1) * 8.0 + (double)B * 4.0, 1, st);
-    AB_HIP(launch_replay_mix(x_new, target_new, n_new, x_old, target_old, n_old, pick, B, F, x_out, target_out, st));
+    TraceScope ts("replay_mix", (double)B * (F + n_outputs) * 8.0 + (double)B * 4.0, 1, st);
+    AB_HIP(launch_replay_mix(x_new, target_new, n_new, x_old, target_old, n_old, pick, B, F, n_outputs, x_out,
+                             target_out, st));
     return AB_OK;
 }
 

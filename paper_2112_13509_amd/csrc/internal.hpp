@@ -53,6 +53,11 @@ hipError_t launch_score_single_hidden(const float *a_term, const float *b_term, 
                                       const float *xp_row, const float *xc_row, hipStream_t st);
 hipError_t launch_grid_rows(const ab_model_desc *d, const float *part, const float *cred, int P, int Q,
                             float *xp_row, float *xc_row, int64_t rows, hipStream_t st);
+hipError_t launch_chosen_pair(const ab_model_desc *d, const ab_grid *grid, const int32_t *best_idx,
+                              float *xp_sel, float *xc_sel, int64_t S, hipStream_t st);
+hipError_t launch_output_v(int dtype, const float *h_last, const float *a_term, const float *wp, const float *wc,
+                           const float *xp_sel, const float *xc_sel, const void *W, const float *b, int H, int n_out,
+                           const int32_t *best_idx, float *V, int64_t S, hipStream_t st);
 bool score_tiny_supported(const ab_model_desc *d, int64_t S, int32_t C);
 hipError_t launch_score_tiny(int dtype, const ab_model_desc *d, const ab_params *prm, const float *dyn,
                              const float *scal, const float *part, const float *cred, int32_t P, int32_t Q,

@@ -224,6 +224,92 @@ hipError_t launch_grid_rows(const ab_model_desc *d, const float *part, const flo
 }
 
 // ------------------------------------------------------------------------------------------------
+// The predicted speed vector V of the chosen candidate (Table 1: V has one entry per worker; Eq. 1 returns V).
+// Scoring ranks candidates by the mean of V through a folded output unit; for the one chosen candidate per
+// scenario the hidden chain is run once more (one row per scenario) and the output layer applied unit by unit.
+// ------------------------------------------------------------------------------------------------
+// The chosen candidate's transformed pair (phi(S_p), phi(S_c)) per scenario; NaN where nothing was chosen.
+struct ChosenArgs { const float *part, *cred; int32_t P, Q, per_scenario; ab_enc enc_part, enc_cred;
+                    const int32_t *best_idx; float *xp_sel, *xc_sel; int64_t S; };
+__global__ __launch_bounds__(256) void chosen_pair_kernel(const ChosenArgs a)
+{
+    const int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (s >= a.S) return;
+    const int c = a.best_idx[s];
+    float xp = __builtin_nanf(""), xc = __builtin_nanf("");
+    if (c >= 0 && c < a.P * a.Q) {
+        const int p = c / a.Q, q = c - p * a.Q;
+        xp = phi(a.part[(a.per_scenario ? s * a.P : 0) + p], a.enc_part);
+        xc = phi(a.cred[(a.per_scenario ? s * a.Q : 0) + q], a.enc_cred);
+    }
+    a.xp_sel[s] = xp;
+    a.xc_sel[s] = xc;
+}
+
+hipError_t launch_chosen_pair(const ab_model_desc *d, const ab_grid *grid, const int32_t *best_idx,
+                              float *xp_sel, float *xc_sel, int64_t S, hipStream_t st)
+{
+    if (S == 0) return hipSuccess;
+    ChosenArgs a{grid->partition_bytes, grid->credit_mult, grid->P, grid->Q, grid->per_scenario,
+                 d->enc_partition, d->enc_credit, best_idx, xp_sel, xc_sel, S};
+    chosen_pair_kernel<<<(unsigned)((S + 255) / 256), 256, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+// V[s, o] = b[o] + sum_j W[o, j] * h[s, j]: a wavefront per scenario, lanes over j, up to AB_MAX_OUTPUTS sums.
+// h is the last hidden activation in fp32 (h_last), or, for a scorer with one hidden layer, generated here as
+// relu(a_term[s, j] + wp[j] * xp[s] + wc[j] * xc[s]).  A scenario without a choice (best_idx < 0) gets NaN.
+struct OutputVArgs { const float *h_last; const float *a_term, *wp, *wc, *xp_sel, *xc_sel;
+                     const void *W; const float *b; int32_t H, n_out; const int32_t *best_idx; float *V; int64_t S; };
+template <typename T>
+__global__ __launch_bounds__(256) void output_v_kernel(const OutputVArgs a)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t s = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (s >= a.S) return;
+    float acc[AB_MAX_OUTPUTS];
+#pragma unroll
+    for (int o = 0; o < AB_MAX_OUTPUTS; ++o) acc[o] = 0.f;
+    const float xp = a.h_last ? 0.f : a.xp_sel[s], xc = a.h_last ? 0.f : a.xc_sel[s];
+    for (int j = lane; j < a.H; j += 64) {
+        float h;
+        if (a.h_last) h = a.h_last[s * a.H + j];
+        else {
+            h = relu_keep_nan(fmaf(a.wc[j], xc, fmaf(a.wp[j], xp, a.a_term[s * a.H + j])));   // (the last hidden
+        }                                                       // activation stays fp32 in the scoring pass too)
+#pragma unroll
+        for (int o = 0; o < AB_MAX_OUTPUTS; ++o) {
+            if (o < a.n_out) {
+                float w;
+                if constexpr (sizeof(T) == 2) w = bf16_bits_to_f32(((const uint16_t *)a.W)[(int64_t)o * a.H + j]);
+                else w = ((const float *)a.W)[(int64_t)o * a.H + j];
+                acc[o] = fmaf(w, h, acc[o]);
+            }
+        }
+    }
+    const bool none = a.best_idx[s] < 0;
+#pragma unroll
+    for (int o = 0; o < AB_MAX_OUTPUTS; ++o) {
+        if (o < a.n_out) {
+            const float v = wave_sum(acc[o]) + a.b[o];
+            if (lane == 0) a.V[s * a.n_out + o] = none ? __builtin_nanf("") : v;
+        }
+    }
+}
+
+hipError_t launch_output_v(int dtype, const float *h_last, const float *a_term, const float *wp, const float *wc,
+                           const float *xp_sel, const float *xc_sel, const void *W, const float *b, int H, int n_out,
+                           const int32_t *best_idx, float *V, int64_t S, hipStream_t st)
+{
+    if (S == 0) return hipSuccess;
+    OutputVArgs a{h_last, a_term, wp, wc, xp_sel, xc_sel, W, b, H, n_out, best_idx, V, S};
+    const unsigned blocks = (unsigned)((S + 3) / 4);
+    if (dtype == AB_BF16) output_v_kernel<bf16_t><<<blocks, 256, 0, st>>>(a);
+    else                  output_v_kernel<float><<<blocks, 256, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
 // Argmax helpers: (value, index) pairs, larger value wins, lower index wins ties, NaN never wins.
 // "Nothing yet" is (-inf, INT_MAX).
 // ------------------------------------------------------------------------------------------------
@@ -652,7 +738,7 @@ struct TensorEncArgs {
     void *xs; int32_t ld;                // scenario rows; columns [0,128) written here
     const int32_t *layers_of;            // [S] or NULL: layers the scenario really has (clamped to [1, L])
     int64_t S;
-    ab_enc enc_stat[AB_MAX_STATS];
+    ab_enc enc_stat[AB_MAX_ENCODER_STATS];
 };
 
 template <typename T>
@@ -661,8 +747,8 @@ __global__ __launch_bounds__(256) void tensor_encoder_kernel(const TensorEncArgs
     constexpr int H = 128;
     __shared__ __attribute__((aligned(16))) unsigned char wb_s[H * 256];        // W_b, bf16, swizzled rows
     __shared__ __attribute__((aligned(16))) unsigned char hbuf[4][32 * 256];    // per wavefront: 32 tensors x 128 bf16
-    __shared__ __attribute__((aligned(16))) float xin[4][32 * AB_MAX_STATS];    // per wavefront: transformed statistics
-    __shared__ __attribute__((aligned(16))) float wa_s[H * AB_MAX_STATS];       // [unit][AB_MAX_STATS], zero padded
+    __shared__ __attribute__((aligned(16))) float xin[4][32 * AB_MAX_ENCODER_STATS];    // per wavefront: transformed statistics
+    __shared__ __attribute__((aligned(16))) float wa_s[H * AB_MAX_ENCODER_STATS];       // [unit][AB_MAX_ENCODER_STATS], zero padded
     __shared__ float ba_s[H];
     __shared__ float red[4][H];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, half = lane >> 5, l31 = lane & 31;
@@ -672,8 +758,8 @@ __global__ __launch_bounds__(256) void tensor_encoder_kernel(const TensorEncArgs
         return n;
     };
 
-    for (int i = t; i < H * AB_MAX_STATS; i += 256) {
-        const int o = i / AB_MAX_STATS, k = i % AB_MAX_STATS;
+    for (int i = t; i < H * AB_MAX_ENCODER_STATS; i += 256) {
+        const int o = i / AB_MAX_ENCODER_STATS, k = i % AB_MAX_ENCODER_STATS;
         wa_s[i] = (k < a.K) ? load_as_f32<T>(a.Wa, o * a.K + k) : 0.f;
     }
     if (t < H) ba_s[t] = a.ba[t];
@@ -696,17 +782,17 @@ __global__ __launch_bounds__(256) void tensor_encoder_kernel(const TensorEncArgs
     for (int jn = 0; jn < 4; ++jn) bb[jn] = a.bb[jn * 32 + l31];
     unsigned char *hb = hbuf[wave];
     float *xw = xin[wave];
-    float wa0[AB_MAX_STATS], wa1[AB_MAX_STATS];             // first layer: rows 2*lane and 2*lane+1 of W_a
+    float wa0[AB_MAX_ENCODER_STATS], wa1[AB_MAX_ENCODER_STATS];             // first layer: rows 2*lane and 2*lane+1 of W_a
 #pragma unroll
-    for (int k = 0; k < AB_MAX_STATS; ++k) {
-        wa0[k] = wa_s[(2 * lane) * AB_MAX_STATS + k];
-        wa1[k] = wa_s[(2 * lane + 1) * AB_MAX_STATS + k];
+    for (int k = 0; k < AB_MAX_ENCODER_STATS; ++k) {
+        wa0[k] = wa_s[(2 * lane) * AB_MAX_ENCODER_STATS + k];
+        wa1[k] = wa_s[(2 * lane + 1) * AB_MAX_ENCODER_STATS + k];
     }
     const float ba0 = ba_s[2 * lane], ba1 = ba_s[2 * lane + 1];
 
-    // this lane's slots of a block's statistics: element i = lane + 64 j of [32 tensors][AB_MAX_STATS], i.e.
+    // this lane's slots of a block's statistics: element i = lane + 64 j of [32 tensors][AB_MAX_ENCODER_STATS], i.e.
     // tensor (lane >> 3) + 8 j, statistic lane & 7 (the same statistic for all four: one transform)
-    const int my_k = lane & (AB_MAX_STATS - 1);
+    const int my_k = lane & (AB_MAX_ENCODER_STATS - 1);
     const ab_enc my_enc = a.enc_stat[my_k];
     auto fetch_raw = [&](int64_t sc, int n_layers, int l0, float (&raw)[4]) {
         const float *dyn = a.dyn + sc * (int64_t)a.L * a.K;
@@ -746,11 +832,11 @@ __global__ __launch_bounds__(256) void tensor_encoder_kernel(const TensorEncArgs
         // a tensor's statistics are one broadcast LDS read, its two results one packed 4-byte write
 #pragma unroll 8
         for (int r = 0; r < 32; ++r) {
-            const f32x4 x0 = *(const f32x4 *)(xw + r * AB_MAX_STATS);
+            const f32x4 x0 = *(const f32x4 *)(xw + r * AB_MAX_ENCODER_STATS);
             float h0 = fmaf(wa0[3], x0.w, fmaf(wa0[2], x0.z, fmaf(wa0[1], x0.y, fmaf(wa0[0], x0.x, ba0))));
             float h1 = fmaf(wa1[3], x0.w, fmaf(wa1[2], x0.z, fmaf(wa1[1], x0.y, fmaf(wa1[0], x0.x, ba1))));
             if (a.K > 4) {
-                const f32x4 x1 = *(const f32x4 *)(xw + r * AB_MAX_STATS + 4);
+                const f32x4 x1 = *(const f32x4 *)(xw + r * AB_MAX_ENCODER_STATS + 4);
                 h0 = fmaf(wa0[7], x1.w, fmaf(wa0[6], x1.z, fmaf(wa0[5], x1.y, fmaf(wa0[4], x1.x, h0))));
                 h1 = fmaf(wa1[7], x1.w, fmaf(wa1[6], x1.z, fmaf(wa1[5], x1.y, fmaf(wa1[4], x1.x, h1))));
             }
@@ -974,7 +1060,7 @@ struct LstmEncArgs {
     const void *W2; const float *b2;      // [256, 64 + 64]
     void *xs; int32_t ld;                 // scenario rows; columns [0, 64) written here
     const int32_t *layers_of;             // [S] or NULL: layers the scenario really has (clamped to [1, L])
-    ab_enc enc_stat[AB_MAX_STATS];
+    ab_enc enc_stat[AB_MAX_ENCODER_STATS];
 };
 
 __device__ __forceinline__ float fast_sigmoid(float x)
@@ -992,7 +1078,7 @@ __global__ __launch_bounds__(512) void lstm_encoder_kernel(const LstmEncArgs a)
     constexpr int STRIDE = 336;                    // bytes per row: (32 + 64 + 64) bf16 + 16 (bank spread)
     constexpr int COL_H1 = E, COL_H2 = E + H;
     __shared__ __attribute__((aligned(16))) unsigned char act[2][R * STRIDE];
-    __shared__ __attribute__((aligned(16))) float stat[2][R][TC][AB_MAX_STATS];
+    __shared__ __attribute__((aligned(16))) float stat[2][R][TC][AB_MAX_ENCODER_STATS];
 
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -1025,16 +1111,16 @@ __global__ __launch_bounds__(512) void lstm_encoder_kernel(const LstmEncArgs a)
     }
     // ---- embedding (the second layer's wavefronts do it): thread -> row te >> 3, outputs 4 (te & 7) .. + 3
     // (W_e and b_e sit in LDS: 33 values per output would crowd the registers that hold the gate weights)
-    __shared__ __attribute__((aligned(16))) float we_s[E][AB_MAX_STATS];
+    __shared__ __attribute__((aligned(16))) float we_s[E][AB_MAX_ENCODER_STATS];
     __shared__ float be_s[E];
     const int te = t & 255, erow = te >> 3, ej = (te & 7) * 4;
-    if (t < E * AB_MAX_STATS) {
-        const int o = t / AB_MAX_STATS, k = t % AB_MAX_STATS;
+    if (t < E * AB_MAX_ENCODER_STATS) {
+        const int o = t / AB_MAX_ENCODER_STATS, k = t % AB_MAX_ENCODER_STATS;
         we_s[o][k] = k < K ? bf16_bits_to_f32(((const uint16_t *)a.We)[o * K + k]) : 0.f;
     }
     if (t < E) be_s[t] = a.be[t];
     // ---- statistics chunks: 32 rows x TC steps x K values, element idx = t + 512 i
-    constexpr int PRE = R * TC * AB_MAX_STATS / 512;     // 8 registers at K = 8
+    constexpr int PRE = R * TC * AB_MAX_ENCODER_STATS / 512;     // 8 registers at K = 8
     float pre[PRE];
     const int per_row = TC * K;
     auto fetch_chunk = [&](int n) {
@@ -1067,7 +1153,7 @@ __global__ __launch_bounds__(512) void lstm_encoder_kernel(const LstmEncArgs a)
         const float *sp = &stat[(step / TC) & 1][erow][step % TC][0];
         float e[4] = {be_s[ej], be_s[ej + 1], be_s[ej + 2], be_s[ej + 3]};
 #pragma unroll
-        for (int k = 0; k < AB_MAX_STATS; ++k)
+        for (int k = 0; k < AB_MAX_ENCODER_STATS; ++k)
             if (k < K) {
                 const float x = sp[k];
 #pragma unroll
@@ -1184,7 +1270,7 @@ hipError_t launch_lstm_encoder(const ab_model_desc *d, const float *dyn, const v
     a.layers_of = layers_of;
     a.dyn = dyn; a.L = d->n_layers; a.K = d->n_stats; a.S = S;
     a.We = We; a.be = be; a.W1 = W1; a.b1 = b1; a.W2 = W2; a.b2 = b2; a.xs = xs; a.ld = ld;
-    for (int i = 0; i < AB_MAX_STATS; ++i) a.enc_stat[i] = d->enc_stat[i];
+    for (int i = 0; i < AB_MAX_ENCODER_STATS; ++i) a.enc_stat[i] = d->enc_stat[i];
     const int64_t blocks = (S + 31) / 32;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     lstm_encoder_kernel<<<(unsigned)blocks, 512, 0, st>>>(a);
@@ -1200,7 +1286,7 @@ hipError_t launch_tensor_encoder(int dtype, const ab_model_desc *d, const float 
     a.layers_of = layers_of;
     a.dyn = dyn; a.L = d->n_layers; a.K = d->n_stats; a.Wa = Wa; a.ba = ba; a.Wb = Wb; a.bb = bb;
     a.xs = xs; a.ld = ld; a.S = S;
-    for (int i = 0; i < AB_MAX_STATS; ++i) a.enc_stat[i] = d->enc_stat[i];
+    for (int i = 0; i < AB_MAX_ENCODER_STATS; ++i) a.enc_stat[i] = d->enc_stat[i];
     int dev = 0, cus = 0;
     hipError_t e;
     if ((e = hipGetDevice(&dev)) != hipSuccess) return e;

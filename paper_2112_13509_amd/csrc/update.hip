@@ -757,7 +757,7 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
 // output row, 16-byte pieces where the row width allows.  An index outside its pool gives a NaN row.
 struct ReplayMixArgs {
     const float *x_new, *t_new, *x_old, *t_old; const int32_t *pick;
-    float *x_out, *t_out; int64_t n_new, n_old, B; int32_t F;
+    float *x_out, *t_out; int64_t n_new, n_old, B; int32_t F, n_out;
 };
 __global__ __launch_bounds__(256) void replay_mix_kernel(const ReplayMixArgs a)
 {
@@ -766,8 +766,8 @@ __global__ __launch_bounds__(256) void replay_mix_kernel(const ReplayMixArgs a)
     const int lane = threadIdx.x & 63;
     const int64_t pk = a.pick[row];
     const float *src = nullptr, *ts = nullptr;
-    if (pk >= 0) { if (pk < a.n_new) { src = a.x_new + pk * a.F; ts = a.t_new + pk; } }
-    else { const int64_t o = -pk - 1; if (o < a.n_old) { src = a.x_old + o * a.F; ts = a.t_old + o; } }
+    if (pk >= 0) { if (pk < a.n_new) { src = a.x_new + pk * a.F; ts = a.t_new + pk * a.n_out; } }
+    else { const int64_t o = -pk - 1; if (o < a.n_old) { src = a.x_old + o * a.F; ts = a.t_old + o * a.n_out; } }
     float *dst = a.x_out + row * a.F;
     const float nanv = __uint_as_float(0x7fc00000u);
     if ((a.F & 3) == 0 && src && (((uintptr_t)src | (uintptr_t)dst) & 15) == 0) {
@@ -775,15 +775,15 @@ __global__ __launch_bounds__(256) void replay_mix_kernel(const ReplayMixArgs a)
     } else {
         for (int j = lane; j < a.F; j += 64) dst[j] = src ? src[j] : nanv;
     }
-    if (lane == 0) a.t_out[row] = ts ? *ts : nanv;
+    if (lane < a.n_out) a.t_out[row * a.n_out + lane] = ts ? ts[lane] : nanv;
 }
 
 hipError_t launch_replay_mix(const float *x_new, const float *t_new, int64_t n_new, const float *x_old,
                              const float *t_old, int64_t n_old, const int32_t *pick, int64_t B, int32_t F,
-                             float *x_out, float *t_out, hipStream_t st)
+                             int32_t n_out, float *x_out, float *t_out, hipStream_t st)
 {
     if (B == 0) return hipSuccess;
-    ReplayMixArgs a{x_new, t_new, x_old, t_old, pick, x_out, t_out, n_new, n_old, B, F};
+    ReplayMixArgs a{x_new, t_new, x_old, t_old, pick, x_out, t_out, n_new, n_old, B, F, n_out};
     replay_mix_kernel<<<(unsigned)((B + 3) / 4), 256, 0, st>>>(a);
     return hipGetLastError();
 }
@@ -795,6 +795,9 @@ ab_status online_update(const ab_model_desc *d, ab_params *prm, const float *x_r
     if (B > (1 << 24)) return AB_ERR_UNSUPPORTED;
     UpdatePlan p;
     plan_update(d, B, &p);
+    // the Adam launch numbers a tensor's elements with 32 bits: the first layer's weight matrix must stay below 2^32
+    if ((int64_t)d->hidden[0] * ((int64_t)d->n_layers * d->n_stats + d->n_scalars + 2) >= (1LL << 32))
+        return AB_ERR_UNSUPPORTED;
     if (first_trainable < 0 || first_trainable > p.D) return AB_ERR_SHAPE;
     if (!prm->step) return AB_ERR_NULL;
     for (int k = 0; k <= p.D; ++k) {

@@ -20,22 +20,31 @@ class Scorer:
         self.params = ab.Params.from_workload(w, DEV)
         self.part, self.cred = to_dev(w.part), to_dev(w.cred)
 
-    def run(self, dyn=None, scal=None, want_scores=True, want_best=True, layers_of=None):
+    def run(self, dyn=None, scal=None, want_scores=True, want_best=True, layers_of=None, want_v=False,
+            part=None, cred=None):
+        """Scores, choice and best score (and, with ``want_v``, the chosen candidate's prediction vector as a fourth
+        result); ``part`` / ``cred`` replace the workload's grid (two-dimensional: a grid per scenario)."""
         w = self.w
         dyn = w.dyn if dyn is None else dyn
         scal = w.scal if scal is None else scal
         S, Cn = dyn.shape[0], w.C
         d_dyn = dyn if isinstance(dyn, torch.Tensor) else to_dev(dyn)
         d_scal = scal if isinstance(scal, torch.Tensor) else to_dev(scal)
+        d_part = self.part if part is None else to_dev(part)
+        d_cred = self.cred if cred is None else to_dev(cred)
         scores = torch.full((S, Cn), float("nan"), dtype=torch.float32, device=DEV) if want_scores else None
         idx = torch.full((S,), -7, dtype=torch.int32, device=DEV) if want_best else None
         best = torch.full((S,), float("nan"), dtype=torch.float32, device=DEV) if want_best else None
+        n_out = max(1, int(self.desc.n_outputs))
+        v = torch.full((S, n_out), 12345.0, dtype=torch.float32, device=DEV) if want_v else None
         ws = ab.alloc_workspace(self.desc, S, Cn, device=DEV)
         lo = None if layers_of is None else to_dev(np.asarray(layers_of, dtype=np.int32))
-        ab.ab_score_candidates(self.desc, self.params, d_dyn, d_scal, self.part, self.cred,
-                               scores, idx, best, ws, layers_of=lo)
+        ab.ab_score_candidates(self.desc, self.params, d_dyn, d_scal, d_part, d_cred,
+                               scores, idx, best, ws, layers_of=lo, v_best=v)
         torch.cuda.synchronize()
         out = lambda t: None if t is None else t.cpu().numpy()
+        if want_v:
+            return out(scores), out(idx), out(best), out(v)
         return out(scores), out(idx), out(best)
 
 

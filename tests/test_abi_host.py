@@ -34,9 +34,9 @@ def test_exports_every_declared_symbol(lib):
 
 
 def test_struct_layout_matches_header_sizes():
-    # ab_enc = 12 bytes; desc = 3 ints + 26 encs + int + 8 ints + int + 2 ints + int + 2 ints
+    # ab_enc = 12 bytes; desc = 3 ints + 58 encs (16 + 40 + 2) + int + 8 ints + int + 2 ints + int + 2 ints
     assert C.sizeof(ab.ab_enc) == 12
-    assert C.sizeof(ab.ab_model_desc) == 4 * 3 + 12 * (8 + 40 + 2) + 4 + 4 * 8 + 4 + 8 + 4 + 8
+    assert C.sizeof(ab.ab_model_desc) == 4 * 3 + 12 * (16 + 40 + 2) + 4 + 4 * 8 + 4 + 8 + 4 + 8
     assert C.sizeof(ab.ab_params) == 8 * (12 * 7 + 1)
     assert C.sizeof(ab.ab_stats) == 32 and C.sizeof(ab.ab_grid) == 32
 
@@ -164,6 +164,10 @@ def test_select_and_update_argument_errors(lib):
     assert call(full, B=0) == -2
     assert call(full, ws=None) == -5
     assert call(full, n=10) == -5
+    # a first layer of 2^32 weights or more is refused (the Adam launch numbers a tensor's elements with 32 bits)
+    wide = ab.make_desc(1 << 16, 16, [(0, 0.0, 1.0)] * 16, [], (1, 12.0, 0.5), (1, 2.0, 0.5), (4096,), "bf16")
+    assert lib.ab_online_update(C.byref(wide), C.byref(full), 0x1000, 0x2000, 64, f(1e-3), f(0.9), f(0.999),
+                                f(1e-8), None, 0x100000, 1 << 60, None) == -6
     dte = ab.desc_from_workload(wl.make_config(5, S=1))
     assert lib.ab_online_update(C.byref(dte), C.byref(full), 0x1000, 0x2000, 64, f(1e-3), f(0.9), f(0.999),
                                 f(1e-8), None, 0x100000, 1 << 40, None) == -6
@@ -187,9 +191,10 @@ def test_transfer_learning_argument_errors(lib):
     q.W_master[2] = q.adam_mW[2] = q.adam_vW[2] = q.adam_mb[2] = q.adam_vb[2] = 0xa0000
     assert lib.ab_online_update_tail(C.byref(d), C.byref(q), 0x1000, 0x2000, 64, 2, f(1e-3), f(0.9), f(0.999), f(1e-8),
                                      None, 0x100000, 16, None) == -5     # everything present: the workspace is too small
-    mix = lambda xn=0x1000, tn=0x2000, nn=4, xo=0x3000, to=0x4000, no=4, pick=0x5000, B=8, F=6, xout=0x6000, tout=0x7000: \
-        lib.ab_replay_mix(xn, tn, nn, xo, to, no, pick, B, F, xout, tout, None)
+    mix = lambda xn=0x1000, tn=0x2000, nn=4, xo=0x3000, to=0x4000, no=4, pick=0x5000, B=8, F=6, xout=0x6000, tout=0x7000, n_out=1: \
+        lib.ab_replay_mix(xn, tn, nn, xo, to, no, pick, B, F, n_out, xout, tout, None)
     assert mix(F=0) == -2 and mix(nn=-1) == -2 and mix(B=-1) == -2
+    assert mix(n_out=0) == -2 and mix(n_out=17) == -2
     assert mix(pick=None) == -1 and mix(xout=None) == -1 and mix(xn=None) == -1 and mix(to=None) == -1
     assert mix(xout=0x6001) == -4
     assert mix(B=0) == 0
@@ -221,3 +226,33 @@ def test_static_scratch_form_checks_its_arguments_on_the_host(lib):
     bad = ab.make_desc(128, 3, [(1, 0.7, 2.0)] * 3, [(0, 0.0, 1.0)] * 4, (1, 12.0, 0.5), (1, 2.0, 0.5),
                        (1000,), "bf16")
     assert call(bad, p, ab.ab_stats(0x3000, 0x4000, 4), ab.ab_grid(0x5000, 16, 0x6000, 16)) == -6
+
+
+def test_statistics_per_layer_limits(lib):
+    """Sixteen statistics per layer (one backward time per worker of a sixteen-worker job, Table 1) are taken by
+    the flat layout; the two encoders take eight and refuse more."""
+    enc = [(1, 0.7, 2.0)] * 16
+    flat = ab.make_desc(4, 16, enc, [(0, 0.0, 1.0)] * 38, (1, 12.0, 0.5), (1, 2.0, 0.5), (64, 64), "bf16")
+    assert ab.ab_workspace_bytes(flat, 8, 16) > 0
+    with pytest.raises(ValueError):
+        ab.make_desc(4, 17, enc + [(1, 0.7, 2.0)], [], (1, 12.0, 0.5), (1, 2.0, 0.5), (64,), "bf16")
+    flat.n_stats = 17
+    assert ab.ab_workspace_bytes(flat, 8, 16) == 0
+    for kind in ("mlp", "lstm"):
+        te = ab.make_desc(4, 9, enc[:9], [(0, 0.0, 1.0)] * 2, (1, 12.0, 0.5), (1, 2.0, 0.5), (64, 64), "bf16",
+                          te_hidden=(128, 128) if kind == "mlp" else (32, 64), te_kind=kind)
+        assert ab.ab_workspace_bytes(te, 8, 16) == 0
+        assert _call_score(lib, te, params=_fake_params(6)) == -6
+        te.n_stats = 8
+        assert ab.ab_workspace_bytes(te, 8, 16) > 0
+
+
+def test_prediction_vector_form_checks_its_arguments(lib):
+    w = wl.make_config(1)
+    d = ab.desc_from_workload(w)
+    p = _fake_params(3)
+    call = lambda idx, v: lib.ab_score_candidates_v(C.byref(d), C.byref(p), C.byref(ab.ab_stats(0x3000, 0x4000, 4)),
+                                                    C.byref(ab.ab_grid(0x5000, 2, 0x6000, 2)), 0x7000, idx, None, v,
+                                                    0x100000, 1 << 40, None)
+    assert call(None, 0x9000) == -1            # the vector is that of the chosen candidate: needs best_idx
+    assert call(0x8000, 0x9002) == -4

@@ -108,18 +108,20 @@ def test_output_layer_only_training_at_configuration_4_shape_lowers_the_loss():
 
 def test_replay_mix_matches_the_oracle_bit_for_bit():
     rng = np.random.default_rng(3)
-    for F, n_new, n_old, B in ((392, 300, 5000, 4096), (7, 5, 3, 40), (64, 0, 10, 33), (12, 9, 0, 17)):
-        xn, tn = rng.standard_normal((n_new, F)).astype(np.float32), rng.standard_normal(n_new).astype(np.float32)
-        xo, to = rng.standard_normal((n_old, F)).astype(np.float32), rng.standard_normal(n_old).astype(np.float32)
+    for F, n_new, n_old, B, n_out in ((392, 300, 5000, 4096, 0), (7, 5, 3, 40, 0), (64, 0, 10, 33, 0), (12, 9, 0, 17, 0),
+                                      (392, 300, 5000, 4096, 8), (9, 6, 7, 50, 16), (5, 0, 4, 9, 3)):
+        tshape = lambda n: (n,) if n_out == 0 else (n, n_out)        # one observed speed per row, or one per worker
+        xn, tn = rng.standard_normal((n_new, F)).astype(np.float32), rng.standard_normal(tshape(n_new)).astype(np.float32)
+        xo, to = rng.standard_normal((n_old, F)).astype(np.float32), rng.standard_normal(tshape(n_old)).astype(np.float32)
         pick = rng.integers(-n_old - 1, n_new + 1, B).astype(np.int32)        # a few entries outside both pools
         t = lambda a: torch.from_numpy(a).to(DEV) if a.shape[0] else None
         x_out = torch.full((B, F), 7.0, dtype=torch.float32, device=DEV)
-        t_out = torch.full((B,), 7.0, dtype=torch.float32, device=DEV)
+        t_out = torch.full(tshape(B), 7.0, dtype=torch.float32, device=DEV)
         ab.ab_replay_mix(t(xn), t(tn), t(xo), t(to), torch.from_numpy(pick).to(DEV), x_out, t_out)
         torch.cuda.synchronize()
         rx, rt = orc.replay_mix(xn, tn, xo, to, pick)
         gx, gt = x_out.cpu().numpy(), t_out.cpu().numpy()
         assert np.array_equal(np.isnan(gx), np.isnan(rx)) and np.array_equal(np.isnan(gt), np.isnan(rt))
-        ok = ~np.isnan(rt)
+        ok = ~np.isnan(rt.reshape(B, -1)[:, 0])
         assert np.array_equal(gx[ok], rx[ok].astype(np.float32)) and np.array_equal(gt[ok], rt[ok].astype(np.float32))
         assert (~ok).sum() > 0 or B == 0

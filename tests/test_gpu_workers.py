@@ -124,7 +124,82 @@ def test_integer_network_with_per_worker_outputs_is_reproduced_exactly(dtype, hi
         m.round_stored_bf16 = True
         assert (orc.score(m, w.dyn, w.scal, w.part, w.cred) == ref).all()
     assert (ref * n_workers == np.round(ref * n_workers)).all() and len(np.unique(ref)) > 8
-    scores, idx, best = Scorer(w).run()
+    sc = Scorer(w)
+    scores, idx, best = sc.run()
     ridx, rbest, _ = orc.select(ref)
     assert (scores == ref.astype(np.float32)).all()
     assert (idx == ridx).all() and (best == rbest.astype(np.float32)).all()
+    # the chosen candidate's prediction vector, unfolded: integers, so equal to the oracle's bit for bit
+    _, idx_v, best_v, V = sc.run(want_scores=False, want_v=True)
+    assert (idx_v == ridx).all() and (best_v == best).all()
+    assert (V == orc.predict_v(oracle_model(w), w.dyn, w.scal, w.part, w.cred, ridx).astype(np.float32)).all()
+    assert len(np.unique(V)) > 4 and (V.mean(axis=1, dtype=np.float64) == rbest).all()
+
+
+@pytest.mark.parametrize("dtype,hidden,S,P,Q,n_workers,per_scenario", [
+    ("f32", [64, 64], 3, 8, 8, 4, False),              # a size the single-launch path would take without the vector
+    ("f32", [128], 33, 5, 7, 3, False),                # one hidden layer: the vector comes straight from the scenario term
+    ("bf16", [64], 20, 4, 4, 16, True),
+    ("bf16", [256, 256, 256], 70, 16, 16, 8, False),   # 256 x 256 streaming kernels in the scoring pass
+    ("bf16", [512, 512], 40, 32, 32, 16, True),        # a grid of its own per scenario
+    ("bf16", [128, 256, 128, 64], 9, 6, 6, 1, False),  # one output: the vector is the best score itself
+    ("bf16", [1024] * 4, 4100, 16, 16, 8, False),      # more scenarios than one chunk of the second pass holds
+])
+def test_prediction_vector_of_the_chosen_candidate(dtype, hidden, S, P, Q, n_workers, per_scenario):
+    """ab_score_candidates_v: V (one entry per worker, Table 1; Eq. 1) of the candidate the pass chose, against the
+    oracle's unfolded forward pass for that same candidate."""
+    w = wl.make_scoring("v-best", S, 6, hidden, P, Q, 16e3, 64e6, 1.0, 16.0, False, dtype, seed=S * 3 + n_workers)
+    w = with_worker_outputs(w, n_workers, seed=n_workers + 1)
+    part, cred = w.part, w.cred
+    if per_scenario:
+        rng = np.random.default_rng(S)
+        part = np.exp(rng.uniform(np.log(16e3), np.log(64e6), (S, P))).astype(np.float32)
+        cred = rng.uniform(1.0, 16.0, (S, Q)).astype(np.float32)
+    sc = Scorer(w)
+    scores, idx, best, V = sc.run(want_v=True, part=part, cred=cred)
+    assert V.shape == (S, n_workers) and np.isfinite(V).all()
+    m = oracle_model(w)
+    ref = orc.predict_v(m, w.dyn, w.scal, part, cred, idx)            # the candidate the GPU chose
+    scale = np.abs(ref).max()
+    err = np.abs(V - ref).max() / scale
+    mean_gap = np.abs(V.mean(axis=1, dtype=np.float64) - best).max() / max(np.abs(best).max(), 1e-30)
+    msg = "V of the chosen candidate %s %s: max err %.3g of max |V|, |mean V - best score| %.3g" % (dtype, hidden, err, mean_gap)
+    if dtype == "bf16":
+        m.round_stored_bf16 = True
+        errq = np.abs(V - orc.predict_v(m, w.dyn, w.scal, part, cred, idx)).max() / scale
+        msg += ", vs rounding-matched oracle %.3g" % errq
+        assert errq <= (2e-3 if len(hidden) <= 2 else 1e-2), msg
+    print(msg)
+    assert err <= TOL[dtype], msg
+    assert mean_gap <= (1e-5 if dtype == "f32" else 1e-2), msg
+    # same choice and scores as the plain entry point
+    s2, i2, b2 = sc.run(part=part, cred=cred)
+    if not (dtype == "f32" and S * P * Q <= 16384 and max(hidden) <= 128):     # (the single-launch path sums differently)
+        assert np.array_equal(s2, scores) and np.array_equal(i2, idx) and np.array_equal(b2, best)
+
+
+def test_prediction_vector_is_nan_where_nothing_could_be_chosen():
+    w = wl.make_scoring("v-nan", 6, 8, [64, 64], 4, 4, 16e3, 64e6, 1.0, 16.0, False, "f32", seed=5)
+    w = with_worker_outputs(w, 3, seed=2)
+    w.dyn[2, 1, 0] = np.nan
+    _, idx, best, V = Scorer(w).run(want_v=True)
+    assert idx[2] == -1 and np.isnan(V[2]).all()
+    ok = [0, 1, 3, 4, 5]
+    ref = orc.predict_v(oracle_model(w), w.dyn, w.scal, w.part, w.cred, idx)
+    assert np.isnan(ref[2]).all() and np.abs(V[ok] - ref[ok]).max() <= 1e-4 * np.abs(ref[ok]).max()
+
+
+@pytest.mark.parametrize("dtype,S,L,hidden", [("f32", 40, 12, [128, 64]), ("bf16", 300, 48, [256, 256, 256])])
+def test_table1_record_of_a_sixteen_worker_job(dtype, S, L, hidden):
+    """Sixteen workers: T is L x 16 (sixteen statistics per layer), B_d and B_u have sixteen entries each (38
+    scalars), V has sixteen entries; scores, choice and the chosen candidate's V against the oracle."""
+    w = wl.make_per_worker("table1-16", S, L, 16, hidden, 16, 16, dtype, seed=S + L + 16)
+    sc = Scorer(w)
+    assert sc.desc.n_stats == 16 and sc.desc.n_scalars == 38 and sc.desc.n_outputs == 16
+    scores, idx, best, V = sc.run(want_v=True)
+    ref = orc.score(oracle_model(w), w.dyn, w.scal, w.part, w.cred)
+    err, frac = check_scores(dtype, scores, idx, ref, matched_scores(w) if dtype == "bf16" else None)
+    refv = orc.predict_v(oracle_model(w), w.dyn, w.scal, w.part, w.cred, idx)
+    errv = np.abs(V - refv).max() / np.abs(refv).max()
+    print("Table 1 record, 16 workers, %s: score err %.3g, exact-argmax fraction %.2f, V err %.3g" % (dtype, err, frac, errv))
+    assert errv <= TOL[dtype]
