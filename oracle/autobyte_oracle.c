@@ -411,8 +411,8 @@ int orc_materialise_inputs(const orc_model *m, const double *dyn, const double *
 }
 
 /*
- * Pick the candidate with the largest predicted V per scenario (Section 3, "select the optimal
- * pair with the maximum training speedup").  Sequential scan: the lowest index wins exact ties.
+ * Pick the candidate with the largest predicted V per scenario (Section 3, introduction: of all candidate
+ * pairs the one whose predicted speed is highest is applied).  Sequential scan: the lowest index wins exact ties.
  * NaN never wins; a scenario whose scores are all NaN gets index -1 and a NaN best score.
  * second[s] is the runner-up value (-inf if C == 1 or no second non-NaN score).
  */

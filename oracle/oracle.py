@@ -37,10 +37,24 @@ def build(force: bool = False) -> str:
 _lib = None
 
 
+def build_sanitized() -> str:
+    """The same source compiled with AddressSanitizer and UndefinedBehaviorSanitizer (gcc, -O1), as
+    ``liborc_san.so``; a process that loads it needs gcc's ASan runtime preloaded.  Returns the library path."""
+    out = os.path.join(_HERE, "liborc_san.so")
+    if not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
+        tmp = out + ".tmp%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O1", "-g", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+                               "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                               "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, out)
+    return out
+
+
 def _load():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build())
+        # AUTOBYTE_ORACLE_LIB: an already built variant of this library (the sanitizer run of the tests uses it)
+        _lib = C.CDLL(os.environ.get("AUTOBYTE_ORACLE_LIB") or build())
         _lib.orc_encode_value.restype = C.c_double
         _lib.orc_encode_value.argtypes = [C.c_double, C.c_int, C.c_double, C.c_double]
         _lib.orc_round_bf16_value.restype = C.c_double

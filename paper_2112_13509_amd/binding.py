@@ -16,7 +16,8 @@ AB_F32, AB_BF16 = 0, 1
 AB_ENC_LINEAR, AB_ENC_LOG = 0, 1
 AB_MAX_STATS, AB_MAX_SCALARS, AB_MAX_HIDDEN, AB_MAX_LAYERS = 16, 40, 8, 12
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libautobyte.so")
+# AUTOBYTE_LIB: an already built variant of the library (the host-sanitizer run of the argument-check tests uses it)
+_LIB_PATH = os.environ.get("AUTOBYTE_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libautobyte.so")
 _lib = None
 
 

@@ -242,6 +242,7 @@ static ab_status score_candidates_in(const ab_model_desc *desc, const ab_params 
 
     // 1. scenario rows: transformed statistics (or pooled tensor embedding) + scalars, K-padded
     const double es = (double)elem_size(dt);
+    bool prep_done = false;
     if (desc->tensor_encoder == 2) {
         {
             // per scenario and layer: two gate products (256 x 96 and 256 x 128) and the K -> 32 embedding
@@ -263,11 +264,17 @@ static ab_status score_candidates_in(const ab_model_desc *desc, const ab_params 
         AB_HIP(launch_encode_stats(dt, desc, stats->dyn, stats->scalars, xs, S, p.Kp,
                                    desc->enc_hidden[1], 0, st));
     } else {
-        TraceScope ts("encode_stats", (double)S * (p.Fs * 4.0 + p.Kp * es), 1, st);
-        AB_HIP(launch_encode_stats(dt, desc, stats->dyn, stats->scalars, xs, S, p.Kp, 0, 1, st));
+        // flat statistics: transform and layer-1 preparation (step 2) share one launch where the layout allows
+        const double prep_bytes = (double)p.H[0] * (p.F * es + p.Kp * es) + (double)C * p.H[0] * 4.0;
+        TraceScope ts("encode_and_prep", (double)S * (p.Fs * 4.0 + p.Kp * es) + prep_bytes, 1, st);
+        AB_HIP(launch_encode_and_prep(dt, desc, stats->dyn, stats->scalars, xs, S, p.Kp, params->W[p.base],
+                                      params->b[p.base], p.F, p.Fs, p.H[0], w1s, grid, b_term, cfg_vec,
+                                      params->W[p.base + p.D], params->b[p.base + p.D], p.H[p.D - 1], w_out_f,
+                                      &prep_done, st));
+        if (!prep_done) AB_HIP(launch_encode_stats(dt, desc, stats->dyn, stats->scalars, xs, S, p.Kp, 0, 1, st));
     }
     // 2. layer-1 split: packed statistics columns of W1, candidate term B[c], fp32 output weights
-    {
+    if (!prep_done) {
         TraceScope ts("prep_layer1", (double)p.H[0] * (p.F * es + p.Kp * es) + (double)C * p.H[0] * 4.0, 1, st);
         AB_HIP(launch_prep_layer1(dt, desc, params->W[p.base], params->b[p.base], p.F, p.Fs, p.H[0], p.Kp, w1s,
                                   grid, b_term, cfg_vec, params->W[p.base + p.D], params->b[p.base + p.D],

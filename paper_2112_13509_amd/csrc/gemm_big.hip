@@ -1121,11 +1121,11 @@ static hipError_t launch_stream_gen_impl(const GemmArgs &g, hipStream_t st)
 {
     constexpr int smem = 4 * 256 * 128 + 20480 + (COL_REGS ? 8192 : 0);
     auto kern = gemm_stream_gen_kernel<EPI, COL_REGS>;
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    static DeviceOnce once;
+    hipError_t e = ensure_dynamic_lds((const void *)kern, smem, once);
     if (e != hipSuccess) return e;
-    int dev = 0, cus = 0;
-    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
-    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+    int cus = 0;
+    if ((e = compute_units(&cus)) != hipSuccess) return e;
     const int64_t ids = (g.m_tiles + 7) / 8 * 8 * g.n_tiles;
     if (ids <= 0) return hipSuccess;
     if (ids > 0x7fffffffLL) return hipErrorInvalidValue;
@@ -1156,11 +1156,11 @@ static hipError_t launch_stream_one_impl(const GemmArgs &g, hipStream_t st)
 {
     constexpr int smem = 5 * 256 * 128;
     auto kern = gemm_stream_kernel<EPI, COL_REGS>;
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    static DeviceOnce once;
+    hipError_t e = ensure_dynamic_lds((const void *)kern, smem, once);
     if (e != hipSuccess) return e;
-    int dev = 0, cus = 0;
-    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
-    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+    int cus = 0;
+    if ((e = compute_units(&cus)) != hipSuccess) return e;
     const int64_t ids = (g.m_tiles + 7) / 8 * 8 * g.n_tiles;
     if (ids <= 0) return hipSuccess;
     if (ids > 0x7fffffffLL) return hipErrorInvalidValue;
@@ -1176,7 +1176,8 @@ static hipError_t launch_big_one(const GemmArgs &g, hipStream_t st)
 {
     constexpr int smem = 5 * 256 * 128;   // 163840: three A slabs + two W slabs; the staged output tile (135168) reuses them
     auto kern = gemm_big_kernel<AMODE, EPI>;
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    static DeviceOnce once;
+    hipError_t e = ensure_dynamic_lds((const void *)kern, smem, once);
     if (e != hipSuccess) return e;
     const int64_t blocks = (g.m_tiles + 7) / 8 * 8 * g.n_tiles;
     if (blocks <= 0) return hipSuccess;

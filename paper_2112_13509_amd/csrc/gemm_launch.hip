@@ -10,7 +10,8 @@ static hipError_t launch_one(const GemmArgs &g, hipStream_t st)
     constexpr int smem = 2 * (BM + BN) * 128;
     auto kern = gemm_tn_kernel<T, WB, WB, AMODE, EPI>;
     if (smem > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        static DeviceOnce once;
+        hipError_t e = ensure_dynamic_lds((const void *)kern, smem, once);
         if (e != hipSuccess) return e;
     }
     const int64_t m_pad = (g.m_tiles + 7) / 8 * 8;

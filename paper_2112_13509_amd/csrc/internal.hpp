@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 #include "../../include/autobyte.h"
 #include "gemm_core.hpp"
 
@@ -24,6 +25,36 @@ __device__ __forceinline__ float phi(float x, const ab_enc &e)
     return (gx - e.shift) * e.scale;
 }
 
+// Launch attributes that do not change while the process lives are looked up once per device: a kernel's
+// dynamic-LDS limit (one DeviceOnce per kernel instantiation, a function-local static of its launcher) and the
+// device's compute-unit count.  Devices beyond 63 are simply set up at every launch.
+struct DeviceOnce { std::atomic<uint64_t> done{0}; };
+inline hipError_t ensure_dynamic_lds(const void *kern, int bytes, DeviceOnce &once)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = (dev >= 0 && dev < 64) ? (1ull << dev) : 0;
+    if (bit && (once.done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+    e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && bit) once.done.fetch_or(bit, std::memory_order_release);
+    return e;
+}
+inline hipError_t compute_units(int *cus)
+{
+    static std::atomic<int> cached[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64) {
+        const int c = cached[dev].load(std::memory_order_relaxed);
+        if (c > 0) { *cus = c; return hipSuccess; }
+    }
+    e = hipDeviceGetAttribute(cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e == hipSuccess && dev >= 0 && dev < 64) cached[dev].store(*cus, std::memory_order_relaxed);
+    return e;
+}
+
 enum { TILE_SMALL = 0, TILE_MID = 1, TILE_BIG = 2 };   // 64x64, 128x128, 256x256 work-group tiles
 
 static inline int tile_edge(int tile) { return 64 << tile; }
@@ -42,6 +73,10 @@ hipError_t launch_encode_stats(int dtype, const ab_model_desc *d, const float *d
 hipError_t launch_prep_layer1(int dtype, const ab_model_desc *d, const void *W1, const float *b1, int F, int Fs,
                               int H1, int ld, void *w1s, const ab_grid *grid, float *b_term, float *cfg_vec,
                               const void *Wout, const float *b_out, int H_last, float *w_out_f, hipStream_t st);
+hipError_t launch_encode_and_prep(int dtype, const ab_model_desc *d, const float *dyn, const float *scal, void *xs,
+                                  int64_t S, int ld, const void *W1, const float *b1, int F, int Fs, int H1, void *w1s,
+                                  const ab_grid *grid, float *b_term, float *cfg_vec, const void *Wout,
+                                  const float *b_out, int H_last, float *w_out_f, bool *done, hipStream_t st);
 hipError_t launch_finish_select(const float *partial, int nt, int64_t row_stride, const float *b_out,
                                 float *scores, int64_t score_stride, int32_t *best_idx, float *best_score,
                                 int64_t S, int C, hipStream_t st);

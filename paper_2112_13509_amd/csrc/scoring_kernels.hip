@@ -75,7 +75,7 @@ __device__ __forceinline__ void store_quad(void *xs, int64_t o, const float (&v)
 struct QuadSplit { int q4s, q4t; uint32_t magic_q4s, magic_q4t, magic_k; int rpb; };
 
 template <typename T>
-__global__ __launch_bounds__(256) void encode_stats_quad_kernel(const EncodeArgs a, const QuadSplit g)
+__device__ __forceinline__ void encode_stats_quad_block(const EncodeArgs &a, const QuadSplit &g, unsigned block)
 {
     __shared__ f32x4 tab[AB_MAX_STATS + AB_MAX_SCALARS];     // statistics first, then the scalars
     if (threadIdx.x < AB_MAX_STATS + AB_MAX_SCALARS) {
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void encode_stats_quad_kernel(const EncodeArgs
         tab[i] = f32x4{e->kind == AB_ENC_LOG ? 1.f : 0.f, e->shift, e->scale, 0.f};
     }
     __syncthreads();
-    const int64_t row0 = (int64_t)blockIdx.x * g.rpb;
+    const int64_t row0 = (int64_t)block * g.rpb;
     const int rows = (int)((a.S - row0 < g.rpb) ? a.S - row0 : g.rpb);
 
     // the statistics columns: q4s quads a row, a thread's four loads issued before the first value is used
@@ -130,6 +130,12 @@ __global__ __launch_bounds__(256) void encode_stats_quad_kernel(const EncodeArgs
     }
 }
 
+template <typename T>
+__global__ __launch_bounds__(256) void encode_stats_quad_kernel(const EncodeArgs a, const QuadSplit g)
+{
+    encode_stats_quad_block<T>(a, g, blockIdx.x);
+}
+
 // ------------------------------------------------------------------------------------------------
 // Layer-1 preparation.  The first dense layer acts on [statistics | S_p | S_c]; its statistics
 // columns are shared by all candidates of a scenario and its two configuration columns by all
@@ -158,9 +164,9 @@ __device__ __forceinline__ float load_as_f32(const void *p, int64_t i)
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void prep_layer1_kernel(const PrepArgs a)
+__device__ __forceinline__ void prep_layer1_block(const PrepArgs &a, unsigned block)
 {
-    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t gid = (int64_t)block * 256 + threadIdx.x;
     const int64_t n_pack = (int64_t)a.H1 * a.ld;
     const int64_t n_bt = (int64_t)a.P * a.Q * a.H1;
     if (gid < n_pack) {
@@ -198,6 +204,23 @@ __global__ __launch_bounds__(256) void prep_layer1_kernel(const PrepArgs a)
         a.xp_f[c] = phi(a.part[c / a.Q], a.enc_part);
         a.xc_f[c] = phi(a.cred[c % a.Q], a.enc_cred);
     }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void prep_layer1_kernel(const PrepArgs a)
+{
+    prep_layer1_block<T>(a, blockIdx.x);
+}
+
+// The two launches that open a scoring pass of the flat model are independent of each other (the transform reads
+// the statistics, the preparation reads the model and the grid), so they share one launch: the first
+// `prep_blocks` work-groups do the layer-1 preparation, the others the feature transform.
+template <typename T>
+__global__ __launch_bounds__(256) void encode_and_prep_kernel(const EncodeArgs a, const QuadSplit g, const PrepArgs p,
+                                                              unsigned prep_blocks)
+{
+    if (blockIdx.x < prep_blocks) prep_layer1_block<T>(p, blockIdx.x);
+    else encode_stats_quad_block<T>(a, g, blockIdx.x - prep_blocks);
 }
 
 // Per-scenario candidate grids: the transformed pair (phi(S_p), phi(S_c)) of every (scenario, candidate) row
@@ -902,25 +925,41 @@ __global__ __launch_bounds__(256) void tensor_encoder_kernel(const TensorEncArgs
 // ------------------------------------------------------------------------------------------------
 static inline unsigned blocks_for(int64_t n) { return (unsigned)((n + 255) / 256); }
 
-hipError_t launch_encode_stats(int dtype, const ab_model_desc *d, const float *dyn, const float *scal,
-                               void *xs, int64_t S, int ld, int col0, int with_stats, hipStream_t st)
+static void fill_encode_args(EncodeArgs &a, const ab_model_desc *d, const float *dyn, const float *scal,
+                             void *xs, int64_t S, int ld, int col0, int with_stats)
 {
-    if (S == 0) return hipSuccess;
-    EncodeArgs a;
     a.dyn = dyn; a.scal = scal; a.xs = xs; a.S = S; a.ld = ld; a.col0 = col0;
     a.n_stat = with_stats ? d->n_layers * d->n_stats : 0;
     a.n_stats_per_layer = d->n_stats; a.n_scal = d->n_scalars;
     for (int i = 0; i < AB_MAX_STATS; ++i) a.enc_stat[i] = d->enc_stat[i];
     for (int i = 0; i < AB_MAX_SCALARS; ++i) a.enc_scal[i] = d->enc_scalar[i];
+}
+
+// Whether the four-columns-per-thread form of the transform takes this layout; fills its index constants.
+static bool quad_split(int dtype, const ab_model_desc *d, const EncodeArgs &a, QuadSplit &g)
+{
+    const int width = a.ld - a.col0;
+    if (!(width % 4 == 0 && a.col0 % 4 == 0 && a.n_stat % 4 == 0 && a.n_stat != 4 && width - a.n_stat >= 8 &&
+          width / 4 < 65536 && ((uintptr_t)a.dyn & 15) == 0 && ((uintptr_t)a.xs & 15) == 0 &&
+          (a.ld * elem_size(dtype)) % 16 == 0))
+        return false;
+    // magic = floor(2^32 / n) + 1 turns index / n into a multiply-high, exact while index * n < 2^32
+    auto magic = [](int n) { return n >= 2 ? (uint32_t)(0x100000000ull / (uint32_t)n) + 1u : 0u; };
+    g.q4s = a.n_stat / 4; g.q4t = (width - a.n_stat) / 4;
+    g.rpb = width / 4 >= 2048 ? 1 : 2048 / (width / 4);      // about two thousand quads per work-group
+    g.magic_q4s = magic(g.q4s); g.magic_q4t = magic(g.q4t); g.magic_k = magic(d->n_stats);
+    return true;
+}
+
+hipError_t launch_encode_stats(int dtype, const ab_model_desc *d, const float *dyn, const float *scal,
+                               void *xs, int64_t S, int ld, int col0, int with_stats, hipStream_t st)
+{
+    if (S == 0) return hipSuccess;
+    EncodeArgs a;
+    fill_encode_args(a, d, dyn, scal, xs, S, ld, col0, with_stats);
     const int width = ld - col0;
-    if (width % 4 == 0 && col0 % 4 == 0 && a.n_stat % 4 == 0 && a.n_stat != 4 && width - a.n_stat >= 8 && width / 4 < 65536 &&
-        ((uintptr_t)dyn & 15) == 0 && ((uintptr_t)xs & 15) == 0 && (ld * elem_size(dtype)) % 16 == 0) {
-        // magic = floor(2^32 / n) + 1 turns index / n into a multiply-high, exact while index * n < 2^32
-        auto magic = [](int n) { return n >= 2 ? (uint32_t)(0x100000000ull / (uint32_t)n) + 1u : 0u; };
-        QuadSplit g;
-        g.q4s = a.n_stat / 4; g.q4t = (width - a.n_stat) / 4;
-        g.rpb = width / 4 >= 2048 ? 1 : 2048 / (width / 4);      // about two thousand quads per work-group
-        g.magic_q4s = magic(g.q4s); g.magic_q4t = magic(g.q4t); g.magic_k = magic(d->n_stats);
+    QuadSplit g;
+    if (quad_split(dtype, d, a, g)) {
         const unsigned blocks = (unsigned)((S + g.rpb - 1) / g.rpb);
         if (dtype == AB_BF16) encode_stats_quad_kernel<bf16_t><<<blocks, 256, 0, st>>>(a, g);
         else encode_stats_quad_kernel<float><<<blocks, 256, 0, st>>>(a, g);
@@ -932,21 +971,57 @@ hipError_t launch_encode_stats(int dtype, const ab_model_desc *d, const float *d
     return hipGetLastError();
 }
 
+static int64_t fill_prep_args(PrepArgs &a, const ab_model_desc *d, const void *W1, const float *b1, int F, int Fs,
+                              int H1, int ld, void *w1s, const ab_grid *grid, float *b_term, float *cfg_vec,
+                              const void *Wout, const float *b_out, int H_last, float *w_out_f);
+
 hipError_t launch_prep_layer1(int dtype, const ab_model_desc *d, const void *W1, const float *b1, int F, int Fs,
                               int H1, int ld, void *w1s, const ab_grid *grid, float *b_term, float *cfg_vec,
                               const void *Wout, const float *b_out, int H_last, float *w_out_f, hipStream_t st)
 {
     PrepArgs a;
+    const int64_t n = fill_prep_args(a, d, W1, b1, F, Fs, H1, ld, w1s, grid, b_term, cfg_vec, Wout, b_out, H_last, w_out_f);
+    if (dtype == AB_BF16) prep_layer1_kernel<bf16_t><<<blocks_for(n), 256, 0, st>>>(a);
+    else prep_layer1_kernel<float><<<blocks_for(n), 256, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+// Transform of the flat model's statistics and layer-1 preparation in one launch.  *done = false (and nothing
+// launched) when the layout needs the general form of the transform; the caller then makes the two launches.
+hipError_t launch_encode_and_prep(int dtype, const ab_model_desc *d, const float *dyn, const float *scal, void *xs,
+                                  int64_t S, int ld, const void *W1, const float *b1, int F, int Fs, int H1, void *w1s,
+                                  const ab_grid *grid, float *b_term, float *cfg_vec, const void *Wout,
+                                  const float *b_out, int H_last, float *w_out_f, bool *done, hipStream_t st)
+{
+    *done = false;
+    if (S == 0) return hipSuccess;
+    EncodeArgs a;
+    fill_encode_args(a, d, dyn, scal, xs, S, ld, 0, 1);
+    QuadSplit g;
+    if (!quad_split(dtype, d, a, g)) return hipSuccess;
+    PrepArgs p;
+    const int64_t n = fill_prep_args(p, d, W1, b1, F, Fs, H1, ld, w1s, grid, b_term, cfg_vec, Wout, b_out, H_last, w_out_f);
+    const int64_t enc_blocks = (S + g.rpb - 1) / g.rpb, prep_blocks = (n + 255) / 256;
+    if (enc_blocks + prep_blocks > 0x7fffffffLL) return hipSuccess;
+    *done = true;
+    if (dtype == AB_BF16)
+        encode_and_prep_kernel<bf16_t><<<(unsigned)(enc_blocks + prep_blocks), 256, 0, st>>>(a, g, p, (unsigned)prep_blocks);
+    else
+        encode_and_prep_kernel<float><<<(unsigned)(enc_blocks + prep_blocks), 256, 0, st>>>(a, g, p, (unsigned)prep_blocks);
+    return hipGetLastError();
+}
+
+static int64_t fill_prep_args(PrepArgs &a, const ab_model_desc *d, const void *W1, const float *b1, int F, int Fs,
+                              int H1, int ld, void *w1s, const ab_grid *grid, float *b_term, float *cfg_vec,
+                              const void *Wout, const float *b_out, int H_last, float *w_out_f)
+{
     a.W1 = W1; a.F = F; a.Fs = Fs; a.H1 = H1; a.ld = ld; a.w1s = w1s; a.b1 = b1;
     a.part = grid->partition_bytes; a.cred = grid->credit_mult; a.P = grid->P; a.Q = grid->Q;
     a.enc_part = d->enc_partition; a.enc_cred = d->enc_credit; a.b_term = b_term;
     const int Cn = grid->P * grid->Q;
     a.wp_f = cfg_vec; a.wc_f = cfg_vec + H1; a.xp_f = cfg_vec + 2 * H1; a.xc_f = cfg_vec + 2 * H1 + Cn;
     a.Wout = Wout; a.b_out = b_out; a.H_last = H_last; a.n_out = d->n_outputs > 1 ? d->n_outputs : 1; a.w_out_f = w_out_f;
-    const int64_t n = (int64_t)H1 * ld + (int64_t)Cn * H1 + H_last + H1 + Cn;
-    if (dtype == AB_BF16) prep_layer1_kernel<bf16_t><<<blocks_for(n), 256, 0, st>>>(a);
-    else prep_layer1_kernel<float><<<blocks_for(n), 256, 0, st>>>(a);
-    return hipGetLastError();
+    return (int64_t)H1 * ld + (int64_t)Cn * H1 + H_last + H1 + Cn;
 }
 
 hipError_t launch_finish_select(const float *partial, int nt, int64_t row_stride, const float *b_out,
@@ -1002,11 +1077,13 @@ hipError_t launch_score_tiny(int dtype, const ab_model_desc *d, const ab_params 
     constexpr int smem = (2 * 64 * 132 + 128 * 128) * 4;       // activation buffers + one weight matrix as fp32
     hipError_t e;
     if (dtype == AB_BF16) {
-        e = hipFuncSetAttribute((const void *)score_tiny_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        static DeviceOnce once;
+        e = ensure_dynamic_lds((const void *)score_tiny_kernel<bf16_t>, smem, once);
         if (e != hipSuccess) return e;
         score_tiny_kernel<bf16_t><<<(unsigned)S, 1024, smem, st>>>(a);
     } else {
-        e = hipFuncSetAttribute((const void *)score_tiny_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        static DeviceOnce once;
+        e = ensure_dynamic_lds((const void *)score_tiny_kernel<float>, smem, once);
         if (e != hipSuccess) return e;
         score_tiny_kernel<float><<<(unsigned)S, 1024, smem, st>>>(a);
     }
@@ -1287,10 +1364,9 @@ hipError_t launch_tensor_encoder(int dtype, const ab_model_desc *d, const float 
     a.dyn = dyn; a.L = d->n_layers; a.K = d->n_stats; a.Wa = Wa; a.ba = ba; a.Wb = Wb; a.bb = bb;
     a.xs = xs; a.ld = ld; a.S = S;
     for (int i = 0; i < AB_MAX_ENCODER_STATS; ++i) a.enc_stat[i] = d->enc_stat[i];
-    int dev = 0, cus = 0;
+    int cus = 0;
     hipError_t e;
-    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
-    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+    if ((e = compute_units(&cus)) != hipSuccess) return e;
     const int64_t grid = S < 2 * (int64_t)cus ? S : 2 * (int64_t)cus;      // two work-groups fit a CU's LDS
     if (dtype == AB_BF16) tensor_encoder_kernel<bf16_t><<<(unsigned)grid, 256, 0, st>>>(a);
     else tensor_encoder_kernel<float><<<(unsigned)grid, 256, 0, st>>>(a);

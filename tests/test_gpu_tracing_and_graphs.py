@@ -43,8 +43,9 @@ def test_trace_hook_brackets_every_launch():
         ab.ab_set_trace(None)
     torch.cuda.synchronize()
     names = [e[0] for e in events if e[1] == 0]
-    assert names[:3] == ["encode_stats", "prep_layer1", "gemm_scenario_term"]
-    assert names[3:] == ["gemm_hidden_first", "gemm_hidden_mid", "gemm_hidden_last", "finish_select"]
+    # (the feature transform and the layer-1 preparation share the first launch)
+    assert names == ["encode_and_prep", "gemm_scenario_term", "gemm_hidden_first", "gemm_hidden_mid",
+                     "gemm_hidden_last", "finish_select"]
     # phases alternate 0, 1 with the same name and work
     for a, b in zip(events[0::2], events[1::2]):
         assert a[1] == 0 and b[1] == 1 and a[0] == b[0] and a[2] == b[2]
