@@ -88,8 +88,9 @@ typedef struct { int32_t kind; float shift; float scale; } ab_enc;
  *   n_scalars              scalar features per scenario (worker count, bandwidth, type one-hots ...)
  *   enc_*                  transform of each statistic kind, each scalar, the partition size and the
  *                          credit multiple
- *   n_hidden, hidden[]     scorer hidden widths.  Supported: 1 <= n_hidden <= 8, every width a multiple
- *                          of 64 and <= 4096
+ *   n_hidden, hidden[]     scorer hidden widths.  Supported: 0 <= n_hidden <= 8, every width a multiple
+ *                          of 64 and <= 4096.  n_hidden = 0 is the linear scorer V = W x + b (flat statistics
+ *                          only; one launch, no workspace needed beyond the 256 bytes ab_workspace_bytes reports)
  *   tensor_encoder         0: flat statistics block (width L*K); 1: shared per-layer MLP
  *                          K -> enc_hidden[0] -> enc_hidden[1] (ReLU after both), mean over the L layers
  *                          (width enc_hidden[1]).  Supported: enc_hidden = {128, 128};

@@ -28,7 +28,7 @@ static ab_status check_desc(const ab_model_desc *d)
     if (d->n_layers <= 0 || d->n_stats <= 0 || d->n_stats > AB_MAX_STATS) return AB_ERR_SHAPE;
     if (d->n_scalars < 0 || d->n_scalars > AB_MAX_SCALARS) return AB_ERR_SHAPE;
     if (d->n_hidden < 0 || d->n_hidden > AB_MAX_HIDDEN) return AB_ERR_SHAPE;
-    if (d->n_hidden == 0) return AB_ERR_UNSUPPORTED;
+    if (d->n_hidden == 0 && d->tensor_encoder) return AB_ERR_UNSUPPORTED;   // the linear scorer takes flat statistics only
     for (int k = 0; k < d->n_hidden; ++k) {
         if (d->hidden[k] <= 0) return AB_ERR_SHAPE;
         if (d->hidden[k] % 64 != 0 || d->hidden[k] > 4096) return AB_ERR_UNSUPPORTED;
@@ -167,7 +167,9 @@ size_t ab_workspace_bytes(const ab_model_desc *desc, int64_t S, int32_t C, int64
 {
     if (check_desc(desc) != AB_OK || S < 0 || C < 0 || B < 0) return 0;
     size_t need = 0;
-    if (C > 0) {
+    if (C > 0 && desc->n_hidden == 0) {
+        need = 256;                        // the linear scorer runs in one launch and uses no workspace
+    } else if (C > 0) {
         ScorePlan p;
         if (plan_scoring(desc, S, C, &p) != AB_OK) return 0;
         need = p.total;
@@ -205,6 +207,19 @@ static ab_status score_candidates_in(const ab_model_desc *desc, const ab_params 
     if (S > 0 && (!stats->dyn || (desc->n_scalars > 0 && !stats->scalars))) return AB_ERR_NULL;
     if (stats->layers_of && !desc->tensor_encoder) return AB_ERR_UNSUPPORTED;   // the flat layout has one width
     if (misaligned(stats->layers_of, 4)) return AB_ERR_ALIGN;
+    if (desc->n_hidden == 0) {
+        // no hidden layer: V = W x + b, one launch, no workspace
+        if (!params->W[0] || !params->b[0]) return AB_ERR_NULL;
+        if (misaligned(params->W[0], 16) || misaligned(params->b[0], 4)) return AB_ERR_ALIGN;
+        if (misaligned(stats->dyn, 4) || misaligned(stats->scalars, 4) || misaligned(scores, 4) ||
+            misaligned(best_idx, 4) || misaligned(best_score, 4) || misaligned(v_best, 4)) return AB_ERR_ALIGN;
+        hipStream_t st0 = (hipStream_t)stream;
+        const double Fs0 = (double)desc->n_layers * desc->n_stats + desc->n_scalars;
+        TraceScope ts("score_linear", (double)S * (Fs0 * 4.0 + (scores ? C * 4.0 : 0.0) + 8.0), 1, st0);
+        AB_HIP(launch_score_linear(desc->compute_dtype, desc, params, stats->dyn, stats->scalars, grid, S, scores,
+                                   best_idx, best_score, v_best, st0));
+        return AB_OK;
+    }
     ScorePlan p;
     rc = plan_scoring(desc, S, C, &p);
     if (rc != AB_OK) return rc;
@@ -432,7 +447,7 @@ ab_status ab_score_candidates_static(const ab_model_desc *desc, const ab_params 
     ab_status rc = check_desc(desc);
     if (rc != AB_OK) return rc;
     if (!params || !stats || !grid) return AB_ERR_NULL;
-    if (stats->S > 0 && grid->P > 0 && grid->Q > 0 && (int64_t)grid->P * grid->Q <= (1 << 24)) {
+    if (desc->n_hidden > 0 && stats->S > 0 && grid->P > 0 && grid->Q > 0 && (int64_t)grid->P * grid->Q <= (1 << 24)) {
         // refuse what does not fit before anything else is looked at
         ScorePlan p;
         rc = plan_scoring(desc, stats->S, grid->P * grid->Q, &p);

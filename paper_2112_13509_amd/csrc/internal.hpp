@@ -93,6 +93,9 @@ hipError_t launch_chosen_pair(const ab_model_desc *d, const ab_grid *grid, const
 hipError_t launch_output_v(int dtype, const float *h_last, const float *a_term, const float *wp, const float *wc,
                            const float *xp_sel, const float *xc_sel, const void *W, const float *b, int H, int n_out,
                            const int32_t *best_idx, float *V, int64_t S, hipStream_t st);
+hipError_t launch_score_linear(int dtype, const ab_model_desc *d, const ab_params *prm, const float *dyn,
+                               const float *scal, const ab_grid *grid, int64_t S, float *scores, int32_t *best_idx,
+                               float *best_score, float *v_best, hipStream_t st);
 bool score_tiny_supported(const ab_model_desc *d, int64_t S, int32_t C);
 hipError_t launch_score_tiny(int dtype, const ab_model_desc *d, const ab_params *prm, const float *dyn,
                              const float *scal, const float *part, const float *cred, int32_t P, int32_t Q,

@@ -1050,6 +1050,108 @@ hipError_t launch_finish_select(const float *partial, int nt, int64_t row_stride
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------
+// A scorer without hidden layers (Section 3.1 leaves the depth open; with none the network is the linear map
+// V = W x + b): a candidate's score is  mean_o W[o, :Fs] . x_s + mean_o b[o]  +  wp phi(S_p) + wc phi(S_c),
+// wp / wc the means of W's two configuration columns.  One work-group per scenario: its wavefronts share the
+// dot product over the transformed statistics (values kept as the compute type keeps them), then every thread
+// takes candidates.  With v_out the per-output dot products of the chosen candidate are written as well.
+// ------------------------------------------------------------------------------------------------
+struct LinearArgs {
+    const float *dyn, *scal, *part, *cred; int32_t part_stride, cred_stride;
+    int32_t n_stat, K, Ns, Q, C, F, n_out;
+    const void *W; const float *b;
+    ab_enc enc_stat[AB_MAX_STATS], enc_scalar[AB_MAX_SCALARS], enc_part, enc_cred;
+    float *scores; int32_t *best_idx; float *best_score; float *v_best;
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void score_linear_kernel(const LinearArgs a)
+{
+    __shared__ float red[4][AB_MAX_OUTPUTS + 2];
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    const int64_t s = blockIdx.x;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int Fs = a.n_stat + a.Ns;
+    // per output: the dot product over the statistics block and the scalars
+    float acc[AB_MAX_OUTPUTS];
+#pragma unroll
+    for (int o = 0; o < AB_MAX_OUTPUTS; ++o) acc[o] = 0.f;
+    for (int j = t; j < Fs; j += 256) {
+        float x = j < a.n_stat ? phi(a.dyn[s * a.n_stat + j], a.enc_stat[j % a.K])
+                               : phi(a.scal[s * a.Ns + (j - a.n_stat)], a.enc_scalar[j - a.n_stat]);
+        x = as_stored<T>(x);
+#pragma unroll
+        for (int o = 0; o < AB_MAX_OUTPUTS; ++o)
+            if (o < a.n_out) acc[o] = fmaf(load_as_f32<T>(a.W, (int64_t)o * a.F + j), x, acc[o]);
+    }
+#pragma unroll
+    for (int o = 0; o < AB_MAX_OUTPUTS; ++o) {
+        if (o < a.n_out) {
+            const float v = wave_sum(acc[o]);
+            if (lane == 0) red[wave][o] = v;
+        }
+    }
+    __syncthreads();
+    float a0 = 0.f, wp = 0.f, wc = 0.f;                    // folded over the outputs: mean of the rows, mean of the biases
+    for (int o = 0; o < a.n_out; ++o) {
+        a0 += ((red[0][o] + red[1][o]) + (red[2][o] + red[3][o])) + a.b[o];
+        wp += load_as_f32<T>(a.W, (int64_t)o * a.F + Fs);
+        wc += load_as_f32<T>(a.W, (int64_t)o * a.F + Fs + 1);
+    }
+    const float inv = 1.f / (float)a.n_out;
+    a0 *= inv; wp *= inv; wc *= inv;
+    const float *part = a.part + s * a.part_stride, *cred = a.cred + s * a.cred_stride;
+    float bv = -INFINITY;
+    int bi = AB_NONE;
+    for (int c = t; c < a.C; c += 256) {
+        const float xp = phi(part[c / a.Q], a.enc_part), xc = phi(cred[c % a.Q], a.enc_cred);
+        const float v = fmaf(wc, xc, fmaf(wp, xp, a0));
+        if (a.scores) a.scores[s * a.C + c] = v;
+        amax_take(bv, bi, v, c);
+    }
+    if (!a.best_idx) return;
+    amax_wave(bv, bi);
+    if (lane == 0) { sv[wave] = bv; si[wave] = bi; }
+    __syncthreads();
+    for (int w = 0; w < 4; ++w) if (w != wave) amax_take(bv, bi, sv[w], si[w]);     // every thread ends with the block's choice
+    if (t == 0) {
+        a.best_idx[s] = (bi == AB_NONE) ? -1 : bi;
+        if (a.best_score) a.best_score[s] = (bi == AB_NONE) ? __uint_as_float(0x7fc00000u) : bv;
+    }
+    if (a.v_best && t < a.n_out) {
+        float v = __uint_as_float(0x7fc00000u);
+        if (bi != AB_NONE) {
+            const float xp = phi(part[bi / a.Q], a.enc_part), xc = phi(cred[bi % a.Q], a.enc_cred);
+            const float d = ((red[0][t] + red[1][t]) + (red[2][t] + red[3][t])) + a.b[t];
+            v = fmaf(load_as_f32<T>(a.W, (int64_t)t * a.F + Fs + 1), xc, fmaf(load_as_f32<T>(a.W, (int64_t)t * a.F + Fs), xp, d));
+        }
+        a.v_best[s * a.n_out + t] = v;
+    }
+}
+
+hipError_t launch_score_linear(int dtype, const ab_model_desc *d, const ab_params *prm, const float *dyn,
+                               const float *scal, const ab_grid *grid, int64_t S, float *scores, int32_t *best_idx,
+                               float *best_score, float *v_best, hipStream_t st)
+{
+    if (S == 0) return hipSuccess;
+    if (S > 0x7fffffffLL) return hipErrorInvalidValue;
+    LinearArgs a = {};
+    a.dyn = dyn; a.scal = scal; a.part = grid->partition_bytes; a.cred = grid->credit_mult;
+    a.part_stride = grid->per_scenario ? grid->P : 0; a.cred_stride = grid->per_scenario ? grid->Q : 0;
+    a.n_stat = d->n_layers * d->n_stats; a.K = d->n_stats; a.Ns = d->n_scalars; a.Q = grid->Q; a.C = grid->P * grid->Q;
+    a.F = a.n_stat + a.Ns + 2; a.n_out = d->n_outputs > 1 ? d->n_outputs : 1;
+    a.W = prm->W[0]; a.b = prm->b[0];
+    for (int i = 0; i < AB_MAX_STATS; ++i) a.enc_stat[i] = d->enc_stat[i];
+    for (int i = 0; i < AB_MAX_SCALARS; ++i) a.enc_scalar[i] = d->enc_scalar[i];
+    a.enc_part = d->enc_partition; a.enc_cred = d->enc_credit;
+    a.scores = scores; a.best_idx = best_idx; a.best_score = best_score; a.v_best = v_best;
+    if (dtype == AB_BF16) score_linear_kernel<bf16_t><<<(unsigned)S, 256, 0, st>>>(a);
+    else                  score_linear_kernel<float><<<(unsigned)S, 256, 0, st>>>(a);
+    return hipGetLastError();
+}
+
 bool score_tiny_supported(const ab_model_desc *d, int64_t S, int32_t C)
 {
     if (d->tensor_encoder || d->n_hidden < 1 || d->n_outputs > 1) return false;

@@ -72,14 +72,14 @@ static void plan_update(const ab_model_desc *d, int64_t B, UpdatePlan *p)
         p->off_gw[k] = take((size_t)s * p->H[k] * p->in_w[k] * 4);
         p->off_gb[k] = take((size_t)p->H[k] * 4);
     }
-    p->off_gwout = take((size_t)p->n_out * p->H[p->D - 1] * 4);
+    p->off_gwout = take((size_t)p->n_out * (p->D > 0 ? p->H[p->D - 1] : p->F) * 4);   // no hidden layer: the output layer reads x
     p->off_gbout = take((size_t)AB_MAX_OUTPUTS * 4);
     p->total = off;
 }
 
 size_t update_workspace_bytes(const ab_model_desc *d, int64_t B)
 {
-    if (d->tensor_encoder || d->n_hidden < 1) return 0;
+    if (d->tensor_encoder || d->n_hidden < 0) return 0;
     UpdatePlan p;
     plan_update(d, B, &p);
     return p.total;
@@ -245,6 +245,47 @@ __global__ __launch_bounds__(256) void output_forward_kernel(const OutFwdArgs a)
     }
 }
 
+// The scorer without hidden layers: yhat = W x + b on the transformed rows x[B, ld] (W is [n_out, F], F <= ld),
+// the loss terms and the output deltas as in output_forward_kernel; a wavefront per sample.
+struct LinFwdArgs {
+    const void *x; const void *w; const float *b; const float *target;
+    float *yhat; float *dout; float *lossrow; int64_t B; int32_t ld, F, n_out, loss_kind;
+};
+template <typename T>
+__global__ __launch_bounds__(256) void linear_forward_kernel(const LinFwdArgs a)
+{
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= a.B) return;
+    const int lane = threadIdx.x & 63;
+    float dv[AB_MAX_OUTPUTS];
+#pragma unroll
+    for (int w = 0; w < AB_MAX_OUTPUTS; ++w) dv[w] = 0.f;
+    for (int j = lane; j < a.F; j += 64) {
+        const float xv = ld_f32<T>(a.x, r * a.ld + j);
+#pragma unroll
+        for (int w = 0; w < AB_MAX_OUTPUTS; ++w)
+            if (w < a.n_out) dv[w] = fmaf(xv, ld_f32<T>(a.w, (int64_t)w * a.F + j), dv[w]);
+    }
+    float sq = 0.f;
+#pragma unroll
+    for (int w = 0; w < AB_MAX_OUTPUTS; ++w) {
+        if (w < a.n_out) {
+            const float yh = wave_sum(dv[w]) + a.b[w];
+            if (lane == 0) a.yhat[r * a.n_out + w] = yh;
+            dv[w] = yh - a.target[r * a.n_out + w];
+            sq += dv[w] * dv[w];
+        }
+    }
+    const float nrm = sqrtf(sq);
+    const float f = a.loss_kind == AB_LOSS_L2NORM ? (nrm > 0.f ? 1.f / (nrm * (float)a.B) : 0.f) : 2.f / (float)a.B;
+    if (lane == 0) {
+        a.lossrow[r] = a.loss_kind == AB_LOSS_L2NORM ? nrm : sq;
+#pragma unroll
+        for (int w = 0; w < AB_MAX_OUTPUTS; ++w)
+            if (w < a.n_out) a.dout[r * a.n_out + w] = dv[w] * f;
+    }
+}
+
 // Output layer gradients: block c < H handles column c of the last hidden layer:
 //   gw_out[w, c] = sum_r dout[r, w] h[r, c]  and  d^T[c, r] = (sum_w dout[r, w] W_out[w, c]) [h^T[c, r] > 0];
 // block H + w (w < n_out) reduces the bias gradient sum_r dout[r, w], block H + n_out the loss.
@@ -319,9 +360,11 @@ __device__ __forceinline__ void output_grad_block(const OutGradArgs &a, unsigned
                     }
                 }
             }
+            if (a.dt) {                  // (no layer below the output layer: nothing to hand down)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) ds[e] = hv[e] > 0.f ? ds[e] : 0.f;
-            store8<T>(a.dt, (int64_t)c * a.Bp + r0, ds);
+                for (int e = 0; e < 8; ++e) ds[e] = hv[e] > 0.f ? ds[e] : 0.f;
+                store8<T>(a.dt, (int64_t)c * a.Bp + r0, ds);
+            }
         }
 #pragma unroll
         for (int w = 0; w < AB_MAX_OUTPUTS; ++w) {
@@ -602,6 +645,42 @@ static ab_status run_update(const ab_model_desc *d, ab_params *prm, const Update
         TraceScope ts("upd_encode_prep", (double)B * (p.F * 4.0 + 2.0 * p.Kp * esz) + 2.0 * (double)start * esz, 1, st);
         update_first_kernel<T><<<enc_blocks + prep_blocks, 256, 0, st>>>(e, a, enc_blocks);
         AB_HIP(hipGetLastError());
+    }
+    if (D == 0) {
+        // no hidden layer: the output layer acts on the transformed rows themselves.  Forward + deltas, then the
+        // weight and bias gradients from x^T (one work-group per input column), then Adam: four launches in all.
+        {
+            LinFwdArgs a{x, prm->W[0], prm->b[0], target, yhat, dout, (float *)(ws + p.off_lossrow), B, p.Kp, p.F, p.n_out,
+                         d->loss_kind};
+            TraceScope ts("upd_output_forward", (double)B * p.Kp * esz, 1, st);
+            linear_forward_kernel<T><<<(unsigned)((B + 3) / 4), 256, 0, st>>>(a);
+            AB_HIP(hipGetLastError());
+        }
+        {
+            GroupArgs ga;
+            memset(&ga, 0, sizeof(ga));
+            ga.kind[2] = UJ_OUT_GRAD;
+            ga.og = OutGradArgs{xt, prm->W[0], dout, (const float *)(ws + p.off_lossrow), nullptr, gw_out, gb_out, loss_out,
+                                B, Bp, p.F, p.n_out, d->loss_kind};
+            ga.start[3] = (unsigned)p.F + (unsigned)p.n_out + 1;
+            TraceScope ts("upd_output_grad", (double)B * p.Kp * esz, 1, st);
+            update_group_kernel<T><<<ga.start[3], 256, 2 * 128 * 128, st>>>(ga);
+            AB_HIP(hipGetLastError());
+        }
+        AdamArgs a;
+        memset(&a, 0, sizeof(a));
+        auto add = [&](float *w, float *m, float *v, void *wc, const float *g, int rows, int cols, int64_t start) {
+            AdamArgs::Tn &t = a.tn[a.n++];
+            t.w = w; t.m = m; t.v = v; t.w_compute = wc; t.g = g; t.rows = rows; t.cols = cols; t.ldg = cols;
+            t.splits = 1; t.split_stride = 0; t.vw = 1; t.start = start;
+        };
+        add(prm->W_master[0], prm->adam_mW[0], prm->adam_vW[0], (void *)prm->W[0], gw_out, p.n_out, p.F, 0);
+        add(prm->b[0], prm->adam_mb[0], prm->adam_vb[0], nullptr, gb_out, 1, p.n_out, (int64_t)p.n_out * p.F);
+        a.total = (int64_t)p.n_out * p.F + p.n_out; a.scal = scal; a.lr = lr; a.beta1 = beta1; a.beta2 = beta2; a.eps = eps;
+        TraceScope ts("upd_adam", (double)a.total * (28.0 + esz), 1, st);
+        adam_kernel<T><<<(unsigned)((a.total + 255) / 256), 256, 0, st>>>(a);
+        AB_HIP(hipGetLastError());
+        return AB_OK;
     }
     // forward
     for (int k = 0; k < D; ++k) {

@@ -119,8 +119,12 @@ def test_score_argument_errors(lib):
     d3.hidden[0] = 100
     assert _call_score(lib, d3, p) == -6                                       # width not a multiple of 64
     d4 = _desc(2)
-    d4.n_hidden = 0
-    assert _call_score(lib, d4, p) == -6
+    d4.n_hidden = 0                                                            # no hidden layer: the linear scorer
+    assert ab.ab_workspace_bytes(d4, 16, 4) == 256                             # (one launch, no workspace of its own)
+    assert _call_score(lib, d4, ab.ab_params()) == -1                          # its one weight matrix is missing
+    d4.tensor_encoder = 1
+    d4.enc_hidden[0] = d4.enc_hidden[1] = 128
+    assert _call_score(lib, d4, p) == -6 and ab.ab_workspace_bytes(d4, 16, 4) == 0   # ... takes flat statistics only
     d5 = _desc(2)
     d5.n_stats = 99
     assert _call_score(lib, d5, p) == -2
