@@ -214,13 +214,14 @@ __global__ __launch_bounds__(256) void prep_layer1_kernel(const PrepArgs a)
 
 // The two launches that open a scoring pass of the flat model are independent of each other (the transform reads
 // the statistics, the preparation reads the model and the grid), so they share one launch: the first
-// `prep_blocks` work-groups do the layer-1 preparation, the others the feature transform.
+// `enc_blocks` work-groups do the feature transform (the long, memory-bound part starts at once), the short
+// work-groups of the layer-1 preparation fill in behind them.
 template <typename T>
 __global__ __launch_bounds__(256) void encode_and_prep_kernel(const EncodeArgs a, const QuadSplit g, const PrepArgs p,
-                                                              unsigned prep_blocks)
+                                                              unsigned enc_blocks)
 {
-    if (blockIdx.x < prep_blocks) prep_layer1_block<T>(p, blockIdx.x);
-    else encode_stats_quad_block<T>(a, g, blockIdx.x - prep_blocks);
+    if (blockIdx.x < enc_blocks) encode_stats_quad_block<T>(a, g, blockIdx.x);
+    else prep_layer1_block<T>(p, blockIdx.x - enc_blocks);
 }
 
 // Per-scenario candidate grids: the transformed pair (phi(S_p), phi(S_c)) of every (scenario, candidate) row
@@ -1005,9 +1006,9 @@ hipError_t launch_encode_and_prep(int dtype, const ab_model_desc *d, const float
     if (enc_blocks + prep_blocks > 0x7fffffffLL) return hipSuccess;
     *done = true;
     if (dtype == AB_BF16)
-        encode_and_prep_kernel<bf16_t><<<(unsigned)(enc_blocks + prep_blocks), 256, 0, st>>>(a, g, p, (unsigned)prep_blocks);
+        encode_and_prep_kernel<bf16_t><<<(unsigned)(enc_blocks + prep_blocks), 256, 0, st>>>(a, g, p, (unsigned)enc_blocks);
     else
-        encode_and_prep_kernel<float><<<(unsigned)(enc_blocks + prep_blocks), 256, 0, st>>>(a, g, p, (unsigned)prep_blocks);
+        encode_and_prep_kernel<float><<<(unsigned)(enc_blocks + prep_blocks), 256, 0, st>>>(a, g, p, (unsigned)enc_blocks);
     return hipGetLastError();
 }
 
