@@ -279,6 +279,28 @@ def run_scoring(mods, args, name, primary):
     if cfg == 1:
         out["us_per_call"] = round(ms_per_step * 1e3, 2)
         out["launches_per_call"] = int(round(sum(r["launches"] for r in ksum.values()) / trace_steps))
+        # the loop above is bound by the interpreter (one ctypes call per launch), so two more figures: the device
+        # side alone, 64 calls recorded into a HIP graph and replayed, and what a caller waits for one decision
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(64):
+                step()
+        g.replay()
+        torch.cuda.synchronize()
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g0.record()
+        for _ in range(20):
+            g.replay()
+        g1.record()
+        torch.cuda.synchronize()
+        out["us_per_call_in_replayed_graph"] = round(g0.elapsed_time(g1) * 1e3 / (20 * 64), 2)
+        waits = []
+        for _ in range(300):
+            t0 = time.perf_counter()
+            step()
+            torch.cuda.synchronize()
+            waits.append(time.perf_counter() - t0)
+        out["us_call_and_wait_median"] = round(sorted(waits)[len(waits) // 2] * 1e6, 2)
 
     # ---- the memory-bound stages against the HBM peak: the feature transform as it ran inside the pass (time
     # between events around the launch, which includes the launch itself; profiles/ has the kernel time), and the

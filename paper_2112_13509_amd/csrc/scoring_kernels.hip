@@ -342,14 +342,26 @@ __device__ __forceinline__ void amax_take(float &bv, int &bi, float v, int i)
 {
     if (!(v != v) && (v > bv || (v == bv && i < bi))) { bv = v; bi = i; }
 }
+// Over the 64 lanes of a wavefront, result in every lane: the exchanges of wave_sum (no LDS round trips); a lane
+// that an exchange does not reach takes "nothing yet", which changes nothing.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ void amax_dpp(float &bv, int &bi)
+{
+    const float ov = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp((int)0xff800000u, __builtin_bit_cast(int, bv),
+                                                                           CTRL, ROW_MASK, 0xF, false));
+    const int oi = __builtin_amdgcn_update_dpp(AB_NONE, bi, CTRL, ROW_MASK, 0xF, false);
+    amax_take(bv, bi, ov, oi);
+}
 __device__ __forceinline__ void amax_wave(float &bv, int &bi)
 {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) {
-        const float ov = __shfl_xor(bv, m, 64);
-        const int oi = __shfl_xor(bi, m, 64);
-        amax_take(bv, bi, ov, oi);
-    }
+    amax_dpp<0xB1>(bv, bi);
+    amax_dpp<0x4E>(bv, bi);
+    amax_dpp<0x141>(bv, bi);
+    amax_dpp<0x140>(bv, bi);
+    amax_dpp<0x142, 0xA>(bv, bi);    // row_bcast:15
+    amax_dpp<0x143, 0xC>(bv, bi);    // row_bcast:31
+    bv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, bv), 63));
+    bi = __builtin_amdgcn_readlane(bi, 63);
 }
 
 // One work-group per scenario.  score[c] = b_out + sum_t partial[(row0 + c)*nt + t]  (nt = 1 and
@@ -457,14 +469,6 @@ __global__ __launch_bounds__(256) void finish_select_wave_kernel(const FinishArg
 // Plain argmax over stored rows (C <= 1024, a multiple of 4, 16-byte aligned rows): sixteen lanes per
 // scenario, four scenarios per wavefront, all of a lane's 16-byte loads issued up front; the lanes of a
 // row of sixteen combine through four DPP exchanges (no LDS).
-template <int CTRL>
-__device__ __forceinline__ void amax_dpp(float &bv, int &bi)
-{
-    const float ov = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, bv), CTRL, 0xf, 0xf, false));
-    const int oi = __builtin_amdgcn_update_dpp(0, bi, CTRL, 0xf, 0xf, false);
-    amax_take(bv, bi, ov, oi);
-}
-
 template <int NLOAD>
 __global__ __launch_bounds__(256) void select_rows16_kernel(const FinishArgs a, int64_t S)
 {
@@ -521,25 +525,6 @@ struct TinyArgs {
     float *scores; int32_t *best_idx; float *best_score;
 };
 
-// One dense layer for 64 candidates (one per lane): this wavefront's outputs [j0, j0 + nj) from the
-// candidate's HIN inputs held in registers and the layer's weights staged in LDS as fp32 (every lane of a
-// wavefront reads the same weight: broadcast reads).  f(j, value) consumes an output.
-template <int HIN, typename F>
-__device__ __forceinline__ void tiny_dense(const float *w_lds, const float *bias, int j0, int nj, const float (&h)[HIN], F &&f)
-{
-    for (int jj = 0; jj < nj; ++jj) {
-        const int j = j0 + jj;
-        const float *wr = w_lds + j * HIN;
-        float acc = bias[j];
-#pragma unroll
-        for (int i = 0; i < HIN; i += 4) {
-            const f32x4 w = *(const f32x4 *)(wr + i);
-            acc = fmaf(w.w, h[i + 3], fmaf(w.z, h[i + 2], fmaf(w.y, h[i + 1], fmaf(w.x, h[i], acc))));
-        }
-        f(j, acc);
-    }
-}
-
 template <typename T>
 __device__ __forceinline__ float as_stored(float v)        // what a value becomes when kept in the compute type
 {
@@ -547,43 +532,111 @@ __device__ __forceinline__ float as_stored(float v)        // what a value becom
     else return v;
 }
 
+// One work-group = one scenario = one CU, so the kernel is a chain of short stages and its time is the sum of
+// their latencies.  What does not depend on an earlier stage is done at the start (transformed grid values,
+// hidden biases and the output unit -> LDS, each by a thread of its own instead of once per wavefront), and
+// the hidden layers run on the matrix cores in fp32: 16 x 16 output blocks (outputs x candidates), one or two
+// per wavefront, operands read from LDS as 16-byte pieces with one K order for both sides (piece q of a lane
+// holds k = 16q + 4 (lane / 16) + e for the e-th instruction of the piece).
 template <typename T>
 __global__ __launch_bounds__(1024) void score_tiny_kernel(const TinyArgs a)
 {
-    constexpr int HM = 128, G = 64, STR = HM + 4, FS_MAX = 2048, NW = 16;   // sixteen wavefronts
+    constexpr int HM = 128, G = 64, STR = HM + 4, FS_MAX = 2048, NW = 16, CM = 256;   // sixteen wavefronts
     __shared__ float xs[FS_MAX];
     __shared__ float A1[HM], wp[HM], wc[HM];
+    __shared__ __attribute__((aligned(16))) float b_s[AB_MAX_HIDDEN - 1][HM];   // biases of the hidden layers after the first
+    __shared__ float wo_s[HM + 1];                                        // output unit: weights, then its bias
+    __shared__ float xp_s[CM], xc_s[CM];                                  // transformed grid values per candidate
     __shared__ float red[NW][G];
     extern __shared__ __attribute__((aligned(16))) float tiny_dyn[];      // two activation buffers, one weight matrix
     float (*hb)[G * STR] = (float (*)[G * STR])tiny_dyn;
-    float *w_lds = tiny_dyn + 2 * G * STR;
+    float *w_lds = tiny_dyn + 2 * G * STR;                                // rows of hin + 4 floats
     const int64_t s = blockIdx.x;
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int hl = a.H[a.D - 1];
 
-    // transformed statistics and scalars of the scenario
+    auto load_w4 = [&](const void *W, int e) {                 // four adjacent weights as fp32
+        if constexpr (sizeof(T) == 2) {
+            const uint2 r = *(const uint2 *)((const uint16_t *)W + e);
+            return f32x4{__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xffff0000u),
+                         __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xffff0000u)};
+        } else {
+            return *(const f32x4 *)((const float *)W + e);
+        }
+    };
+    auto park_w4 = [&](int hin, int e, f32x4 w) {              // ... to their place in the padded LDS rows
+        const int j = hin == 64 ? e >> 6 : e >> 7;
+        *(f32x4 *)(w_lds + j * (hin + 4) + (e & (hin - 1))) = w;
+    };
+
+    // transformed statistics and scalars of the scenario (threads from the front), everything else that only
+    // depends on the arguments (threads from the back); the raw statistics are requested first, the second
+    // layer's weights and this wavefront's first layer-1 rows right behind them
     const int n_stat = a.L * a.K;
-    for (int i = t; i < a.Fs; i += 64 * NW)
+    const int H1 = a.H[0];
+    const bool first_x = t < a.Fs;
+    float raw0 = 0.f;
+    if (first_x) raw0 = t < n_stat ? a.dyn[s * n_stat + t] : a.scal[s * a.Ns + (t - n_stat)];
+    const int n_w1 = a.D > 1 ? a.H[1] * H1 : 0;
+    f32x4 w_pre[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+        if (t * 4 + u * 4096 < n_w1) w_pre[u] = load_w4(a.W[1], t * 4 + u * 4096);
+    float w0_pre[4] = {0.f, 0.f, 0.f, 0.f};
+    if (wave * 4 < H1 && lane < a.Fs) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) w0_pre[u] = load_as_f32<T>(a.W[0], (int64_t)(wave * 4 + u) * a.F + lane);
+    }
+    if (first_x) xs[t] = as_stored<T>(phi(raw0, t < n_stat ? a.enc_stat[t % a.K] : a.enc_scalar[t - n_stat]));
+    for (int i = t + 64 * NW; i < a.Fs; i += 64 * NW)
         xs[i] = as_stored<T>(i < n_stat ? phi(a.dyn[s * n_stat + i], a.enc_stat[i % a.K])
                                         : phi(a.scal[s * a.Ns + (i - n_stat)], a.enc_scalar[i - n_stat]));
+    {
+        const int r = 64 * NW - 1 - t;
+        if (r < a.C) xp_s[r] = phi(a.part[(int64_t)blockIdx.x * a.part_stride + r / a.Q], a.enc_part);
+        else if (r >= CM && r - CM < a.C) xc_s[r - CM] = phi(a.cred[(int64_t)blockIdx.x * a.cred_stride + (r - CM) % a.Q], a.enc_cred);
+        else if (r >= 2 * CM && r - 2 * CM <= hl)
+            wo_s[r - 2 * CM] = r - 2 * CM < hl ? load_as_f32<T>(a.W[a.D], r - 2 * CM) : a.b[a.D][0];
+        for (int q = t; q < (a.D - 1) * HM; q += 64 * NW) {
+            const int k = 1 + q / HM, jx = q % HM;
+            if (jx < a.H[k]) b_s[k - 1][jx] = a.b[k][jx];
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+        if (t * 4 + u * 4096 < n_w1) park_w4(H1, t * 4 + u * 4096, w_pre[u]);
     __syncthreads();
     // scenario term of layer 1 and its two configuration columns
-    const int H1 = a.H[0];
     for (int j0 = wave * 4; j0 < H1; j0 += 4 * NW) {           // four outputs at a time: four loads in flight
         float acc[4] = {0.f, 0.f, 0.f, 0.f};
-        for (int i = lane; i < a.Fs; i += 64) {
+        int i_from = lane;
+        if (j0 == wave * 4 && lane < a.Fs) {                    // (the piece requested at the start)
+            const float x = xs[lane];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc[u] = w0_pre[u] * x;
+            i_from = lane + 64;
+        }
+        for (int i = i_from; i < a.Fs; i += 64) {
             const float x = xs[i];
 #pragma unroll
             for (int u = 0; u < 4; ++u) acc[u] = fmaf(load_as_f32<T>(a.W[0], (int64_t)(j0 + u) * a.F + i), x, acc[u]);
+        }
+        float mine = 0.f, mp = 0.f, mc = 0.f;                  // (requested before the sums are formed)
+        if (lane < 4) {
+            const int j = j0 + lane;
+            mine = a.b[0][j];
+            mp = load_as_f32<T>(a.W[0], (int64_t)j * a.F + a.Fs);
+            mc = load_as_f32<T>(a.W[0], (int64_t)j * a.F + a.Fs + 1);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) acc[u] = wave_sum(acc[u]);
         if (lane < 4) {
             const int j = j0 + lane;
             const float av = lane == 0 ? acc[0] : lane == 1 ? acc[1] : lane == 2 ? acc[2] : acc[3];
-            A1[j] = av + a.b[0][j];
-            wp[j] = load_as_f32<T>(a.W[0], (int64_t)j * a.F + a.Fs);
-            wc[j] = load_as_f32<T>(a.W[0], (int64_t)j * a.F + a.Fs + 1);
+            A1[j] = av + mine;
+            wp[j] = mp;
+            wc[j] = mc;
         }
     }
     __syncthreads();
@@ -593,10 +646,9 @@ __global__ __launch_bounds__(1024) void score_tiny_kernel(const TinyArgs a)
     for (int c0 = 0; c0 < a.C; c0 += G) {
         const int c = c0 + lane;
         const int cc = c < a.C ? c : a.C - 1;
-        const float xp = phi(a.part[(int64_t)blockIdx.x * a.part_stride + cc / a.Q], a.enc_part);
-        const float xc = phi(a.cred[(int64_t)blockIdx.x * a.cred_stride + cc % a.Q], a.enc_cred);
-        float *mine = &hb[0][lane * STR];
+        const float xp = xp_s[cc], xc = xc_s[cc];
         {
+            float *mine = &hb[0][lane * STR];
             const int hq = H1 / NW;
             for (int jj = 0; jj < hq; ++jj) {
                 const int j = wave * hq + jj;
@@ -604,64 +656,62 @@ __global__ __launch_bounds__(1024) void score_tiny_kernel(const TinyArgs a)
                 mine[j] = a.D > 1 ? as_stored<T>(h) : h;
             }
         }
-        __syncthreads();
         int cur = 0;
         for (int k = 1; k < a.D; ++k) {
-            const int hin = a.H[k - 1], hq = a.H[k] / NW;
-            // the layer's weights -> LDS as fp32 (the previous layer's readers are past the barrier above)
-            for (int e = t * 4; e < a.H[k] * hin; e += 256 * NW) {
-                f32x4 w;
-                if constexpr (sizeof(T) == 2) {
-                    const uint2 r = *(const uint2 *)((const uint16_t *)a.W[k] + e);
-                    w = f32x4{__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xffff0000u),
-                              __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xffff0000u)};
-                } else {
-                    w = *(const f32x4 *)((const float *)a.W[k] + e);
+            const int hin = a.H[k - 1], hout = a.H[k], ws = hin + 4;
+            // the layer's weights -> LDS as fp32, once the layer before has read its own (the last layer of the
+            // group before is behind the output unit's barriers); the second layer's are there from the start
+            // and, being the only ones, stay for every group of candidates
+            if (k > 1) __syncthreads();
+            if (!(k == 1 && (c0 == 0 || a.D == 2))) {           // (the second layer's were parked at the start)
+                for (int e = t * 4; e < hout * hin; e += 256 * NW) park_w4(hin, e, load_w4(a.W[k], e));
+            }
+            __syncthreads();                                    // weights and the layer's inputs are in place
+            const bool keep = k == a.D - 1;                     // the last hidden layer is not kept in the compute type
+            for (int blk = wave; blk < 4 * (hout >> 4); blk += NW) {
+                const int cb = blk & 3, ob = blk >> 2;
+                const int row = lane & 15, kq = (lane >> 4) * 4;
+                const float *pw = w_lds + (16 * ob + row) * ws + kq;
+                const float *ph = &hb[cur][(16 * cb + row) * STR + kq];
+                f32x4 acc = *(const f32x4 *)&b_s[k - 1][16 * ob + kq];     // lane: outputs 16 ob + kq .. + 3 of candidate 16 cb + row
+                for (int q = 0; q < hin; q += 16) {
+                    const f32x4 wv = *(const f32x4 *)(pw + q), hv = *(const f32x4 *)(ph + q);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wv.x, hv.x, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wv.y, hv.y, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wv.z, hv.z, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wv.w, hv.w, acc, 0, 0, 0);
                 }
-                *(f32x4 *)(w_lds + e) = w;
-            }
-            const float *src = &hb[cur][lane * STR];
-            float *dst = &hb[cur ^ 1][lane * STR];
-            const bool keep = k == a.D - 1;                 // the last hidden layer is not kept in the compute type
-            auto put = [&](int j, float v) { v = relu_keep_nan(v); dst[j] = keep ? v : as_stored<T>(v); };
-            if (hin == 64) {
-                float h[64];
 #pragma unroll
-                for (int i = 0; i < 64; i += 4) *(f32x4 *)&h[i] = *(const f32x4 *)(src + i);
-                __syncthreads();
-                tiny_dense<64>(w_lds, a.b[k], wave * hq, hq, h, put);
-            } else {
-                float h[128];
-#pragma unroll
-                for (int i = 0; i < 128; i += 4) *(f32x4 *)&h[i] = *(const f32x4 *)(src + i);
-                __syncthreads();
-                tiny_dense<128>(w_lds, a.b[k], wave * hq, hq, h, put);
+                for (int e = 0; e < 4; ++e) {
+                    const float v = relu_keep_nan(acc[e]);
+                    acc[e] = keep ? v : as_stored<T>(v);
+                }
+                *(f32x4 *)&hb[cur ^ 1][(16 * cb + row) * STR + 16 * ob + kq] = acc;
             }
-            __syncthreads();
             cur ^= 1;
         }
+        __syncthreads();
         {   // output unit: each wavefront its share of the dot product
-            const int hl = a.H[a.D - 1], hq = hl / NW;
+            const int hq = hl / NW;
             const float *src = &hb[cur][lane * STR + wave * hq];
+            const float *wo = wo_s + wave * hq;
             float acc = 0.f;
             for (int i = 0; i < hq; i += 4) {
                 const f32x4 h = *(const f32x4 *)(src + i);
-                acc = fmaf(load_as_f32<T>(a.W[a.D], wave * hq + i + 3), h.w,
-                           fmaf(load_as_f32<T>(a.W[a.D], wave * hq + i + 2), h.z,
-                                fmaf(load_as_f32<T>(a.W[a.D], wave * hq + i + 1), h.y,
-                                     fmaf(load_as_f32<T>(a.W[a.D], wave * hq + i), h.x, acc))));
+                acc = fmaf(wo[i + 3], h.w, fmaf(wo[i + 2], h.z, fmaf(wo[i + 1], h.y, fmaf(wo[i], h.x, acc))));
             }
             red[wave][lane] = acc;
         }
         __syncthreads();
         if (wave == 0 && c < a.C) {
-            float v = a.b[a.D][0];
+            float v = wo_s[hl];
 #pragma unroll
             for (int w = 0; w < NW; ++w) v += red[w][lane];
             if (a.scores) a.scores[s * a.C + c] = v;
             amax_take(bv, bi, v, c);
         }
-        __syncthreads();                                    // red and the activation buffers are reused
+        // (the next group's first writes go to hb[0]: its last readers, the first hidden layer's matrix
+        // instructions or the output unit, are behind a barrier; red is rewritten two barriers later)
     }
     if (wave == 0 && a.best_idx) {
         amax_wave(bv, bi);
@@ -1177,7 +1227,7 @@ hipError_t launch_score_tiny(int dtype, const ab_model_desc *d, const ab_params 
     for (int i = 0; i < AB_MAX_SCALARS; ++i) a.enc_scalar[i] = d->enc_scalar[i];
     a.enc_part = d->enc_partition; a.enc_cred = d->enc_credit;
     a.scores = scores; a.best_idx = best_idx; a.best_score = best_score;
-    constexpr int smem = (2 * 64 * 132 + 128 * 128) * 4;       // activation buffers + one weight matrix as fp32
+    constexpr int smem = (2 * 64 * 132 + 128 * 132) * 4;       // activation buffers + one weight matrix as fp32, padded rows
     hipError_t e;
     if (dtype == AB_BF16) {
         static DeviceOnce once;

@@ -93,6 +93,8 @@ def test_config1_tiny_fp32():
     (3, 5, [64], 3, 5),
     (7, 16, [64, 64], 8, 8),
     (70, 9, [128, 64], 5, 7),
+    (4, 6, [128, 128, 64], 16, 16),            # single launch: four groups of 64 candidates, weights restaged per group
+    (3, 7, [64, 128, 128, 64], 9, 9),          # single launch: four hidden layers, a ragged second group
     (5, 40, [192, 128, 64], 4, 9),
     (33, 128, [256, 256], 16, 16),
     (9, 128, [128, 256, 128, 64, 64], 6, 6),
@@ -236,6 +238,8 @@ def test_more_than_2_pow_32_candidates():
     ("bf16", [64], 9, 3, 4, 4),                # one hidden layer
     ("f32", [256, 256], 9, 128, 64, 64),       # fp32 256 x 256 tiles
     ("f32", [64, 64], 1, 16, 8, 8),            # single-launch path
+    ("f32", [128, 128, 64], 2, 16, 16, 16),    # single-launch path: three hidden layers, 256 candidates
+    ("bf16", [64, 128], 3, 8, 10, 10),         # single-launch path in bf16, 100 candidates
 ])
 def test_integer_network_is_reproduced_exactly(dtype, hidden, S, L, P, Q):
     """A network in small integers (inputs 0..2 under the identity transform, sixteen +-1 weights per row, biases
