@@ -114,6 +114,32 @@ def gemm_roofline(ab, workload, ksum, dtype, trace_steps, ms_per_step):
     return out
 
 
+def library_gemm_same_shape(torch, dev, dtype, rows, width):
+    """Context for the roofline figure, not a code path of the library: the image's BLAS (through torch.addmm) on
+    one hidden layer's shape, out[rows, width] = bias + a[rows, width] w[width, width]^T with post-ReLU-like data,
+    without the ReLU, the generated operand or the fused output unit that the kernels here carry."""
+    tt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(5)
+    a = torch.relu(torch.randn(rows, width, device=dev, generator=gen)).to(tt)
+    w = (torch.randn(width, width, device=dev, generator=gen) / width ** 0.5).to(tt)
+    b = torch.randn(width, device=dev, generator=gen).to(tt)
+    out = torch.empty(rows, width, device=dev, dtype=tt)
+    for _ in range(3):
+        torch.addmm(b, a, w.t(), out=out)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        torch.addmm(b, a, w.t(), out=out)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / 10
+    rate = 2.0 * rows * width * width / (ms * 1e-3)
+    return {"what": "torch.addmm (the image's BLAS), bias GEMM [%d, %d] x [%d, %d]^T, %s, no ReLU" % (rows, width, width, width, dtype),
+            "ms": round(ms, 4), "TFLOP/s": round(rate / 1e12, 1), "frac": round(rate / PEAK[dtype], 4)}
+
+
 def launch_floor_of(torch, dev, n_launch):
     """The same number of back-to-back trivial dependent launches as one update step makes."""
     tiny = torch.zeros(64, dtype=torch.float32, device=dev)
@@ -276,6 +302,8 @@ def run_scoring(mods, args, name, primary):
            "whole_step_TFLOP/s": round(S * Cn * flops_per_unit / (ms_per_step * 1e-3) / 1e12, 3),
            "roofline": gemm_roofline(ab, name, ksum, dtype, trace_steps, ms_per_step),
            "input_generation_s": round(t_gen, 2)}
+    if primary and out["roofline"] and len(H) >= 2 and H[-1] == H[-2]:
+        out["roofline"]["library_gemm_same_shape"] = library_gemm_same_shape(torch, dev, dtype, min(S * Cn, 1 << 20), H[-1])
     if cfg == 1:
         out["us_per_call"] = round(ms_per_step * 1e3, 2)
         out["launches_per_call"] = int(round(sum(r["launches"] for r in ksum.values()) / trace_steps))
@@ -301,6 +329,7 @@ def run_scoring(mods, args, name, primary):
             torch.cuda.synchronize()
             waits.append(time.perf_counter() - t0)
         out["us_call_and_wait_median"] = round(sorted(waits)[len(waits) // 2] * 1e6, 2)
+        out["us_per_trivial_launch"] = launch_floor_of(torch, dev, 1)["us_per_step_of_trivial_launches"]
 
     # ---- the memory-bound stages against the HBM peak: the feature transform as it ran inside the pass (time
     # between events around the launch, which includes the launch itself; profiles/ has the kernel time), and the
