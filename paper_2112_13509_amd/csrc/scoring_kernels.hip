@@ -997,7 +997,8 @@ static bool quad_split(int dtype, const ab_model_desc *d, const EncodeArgs &a, Q
     // magic = floor(2^32 / n) + 1 turns index / n into a multiply-high, exact while index * n < 2^32
     auto magic = [](int n) { return n >= 2 ? (uint32_t)(0x100000000ull / (uint32_t)n) + 1u : 0u; };
     g.q4s = a.n_stat / 4; g.q4t = (width - a.n_stat) / 4;
-    g.rpb = width / 4 >= 2048 ? 1 : 2048 / (width / 4);      // about two thousand quads per work-group
+    g.rpb = width / 4 >= 1792 ? 1 : 1792 / (width / 4);      // seven quads per thread (measured: 1000-2000 quads per
+                                                             // work-group are alike, more are slower)
     g.magic_q4s = magic(g.q4s); g.magic_q4t = magic(g.q4t); g.magic_k = magic(d->n_stats);
     return true;
 }
