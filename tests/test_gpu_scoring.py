@@ -95,6 +95,8 @@ def test_config1_tiny_fp32():
     (70, 9, [128, 64], 5, 7),
     (4, 6, [128, 128, 64], 16, 16),            # single launch: four groups of 64 candidates, weights restaged per group
     (3, 7, [64, 128, 128, 64], 9, 9),          # single launch: four hidden layers, a ragged second group
+    (2, 3, [64, 128, 64, 64, 128, 128, 64, 64], 5, 4),      # single launch: the deepest scorer the ABI takes
+    (300, 3, [64, 128, 64, 64, 128, 128, 64, 64], 8, 8),    # the same depth on the batched path
     (5, 40, [192, 128, 64], 4, 9),
     (33, 128, [256, 256], 16, 16),
     (9, 128, [128, 256, 128, 64, 64], 6, 6),
@@ -240,6 +242,8 @@ def test_more_than_2_pow_32_candidates():
     ("f32", [64, 64], 1, 16, 8, 8),            # single-launch path
     ("f32", [128, 128, 64], 2, 16, 16, 16),    # single-launch path: three hidden layers, 256 candidates
     ("bf16", [64, 128], 3, 8, 10, 10),         # single-launch path in bf16, 100 candidates
+    ("f32", [128] * 8, 2, 4, 6, 6),            # eight hidden layers on the single-launch path
+    ("bf16", [256] * 8, 40, 8, 16, 16),        # eight hidden layers on the 256 x 256 streaming kernels
 ])
 def test_integer_network_is_reproduced_exactly(dtype, hidden, S, L, P, Q):
     """A network in small integers (inputs 0..2 under the identity transform, sixteen +-1 weights per row, biases
@@ -248,7 +252,9 @@ def test_integer_network_is_reproduced_exactly(dtype, hidden, S, L, P, Q):
     must equal the oracle's exactly -- with integer scores most candidates tie, so the lowest-index rule decides
     nearly every scenario."""
     from gpu_helpers import Scorer
-    w = wl.make_integer_scoring("int", S, L, hidden, P, Q, dtype, 1000 + S + L, nonzeros=16)
+    # (sixteen non-zeros per weight row; four in the deep networks, whose activations would otherwise outgrow
+    # the integers that bf16 holds exactly)
+    w = wl.make_integer_scoring("int", S, L, hidden, P, Q, dtype, 1000 + S + L, nonzeros=16 if len(hidden) <= 4 else 4)
     m = oracle_model(w)
     ref = orc.score(m, w.dyn, w.scal, w.part, w.cred)
     if dtype == "bf16":
