@@ -110,9 +110,14 @@ def test_ragged_shapes(dtype, case):
     compare(w, *Scorer(w).run(), label=str(case))
 
 
-def test_outputs_optional_and_deterministic():
+@pytest.mark.parametrize("S,hidden", [(40, [128, 128]),        # single-launch path
+                                      (300, [128, 128]),       # batched path, generic tiles
+                                      (70, [256, 256, 256]),   # batched path, 256 x 256 kernels
+                                      (50, [192])])            # one hidden layer
+def test_outputs_optional_and_deterministic(S, hidden):
     from gpu_helpers import Scorer
-    w = wl.make_scoring("opt", 40, 16, [128, 128], 8, 8, 16 * wl.KIB, 64 * wl.MIB, 1.0, 64.0, False, "bf16", 77)
+    w = wl.make_scoring("opt", S, 16, hidden, 8, 8 if len(hidden) < 3 else 32, 16 * wl.KIB, 64 * wl.MIB, 1.0, 64.0,
+                        False, "bf16", 77)
     sc = Scorer(w)
     s1, i1, b1 = sc.run()
     s2, i2, b2 = sc.run()
