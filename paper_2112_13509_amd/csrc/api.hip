@@ -144,7 +144,7 @@ using namespace ab;
 
 extern "C" {
 
-int32_t ab_version(void) { return 106; }
+int32_t ab_version(void) { return 107; }
 
 void ab_set_trace(ab_trace_fn fn, void *user) { g_trace_fn = fn; g_trace_user = user; }
 
@@ -330,6 +330,7 @@ static ab_status score_candidates_in(const ab_model_desc *desc, const ab_params 
                     g.a_term = a_chunk; g.b_term = b_term; g.ldt = p.H[0]; g.C = C;
                     g.wp = cfg_vec; g.wc = cfg_vec + p.H[0]; g.xp = cfg_vec + 2 * p.H[0]; g.xc = cfg_vec + 2 * p.H[0] + C;
                     if (per_scenario) { g.xp = xp_row; g.xc = xc_row; g.x_per_row = 1; }
+                    g.xp_runs4 = grid->Q % 4 == 0;          // (row = s C + p Q + q and 4 | Q: four adjacent rows, one p)
                 }
                 else { g.A = act[k & 1]; g.lda = p.H[k - 1]; }
                 g.B = params->W[p.base + k]; g.ldb = p.H[k - 1];

@@ -749,7 +749,7 @@ __device__ __forceinline__ void dma4(const void *gsrc, void *lds_uniform_dst)   
     __builtin_amdgcn_global_load_lds((global_void *)gsrc, (lds_void *)lds_uniform_dst, 4, 0, 0);
 }
 
-template <int EPI, bool COL_REGS>
+template <int EPI, bool COL_REGS, bool SHARE>
 __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
 {
     constexpr int BM = 256, BK = 64;
@@ -824,16 +824,17 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
         }
     };
 
-    // ---- generation: thread -> k chunk t & 7 of rows (t >> 3) + 64 i
-    const int gcc = t & 7, grow = t >> 3;
-    const int gen_st0 = grow * 128 + ((gcc ^ ((grow >> 1) & 7)) << 4);       // (+ 64 i rows: same swizzle)
-    float gxp[4], gxc[4];
-    auto load_xpc = [&](int b) {
+    // ---- generation: thread -> k chunk t & 7 of the four adjacent rows 4 (t >> 3) + i.  With SHARE (the rows of
+    // such a group take the same xp, GemmArgs::xp_runs4) the inner term wp * xp + a_term is formed once for the
+    // four rows: 5 instead of 8 fused multiply-adds per row chunk, the same values bit for bit.
+    const int gcc = t & 7, grow4 = (t >> 3) * 4;
+    int gen_st[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            gxp[i] = *(const float *)(smem + V_XP + b * 2048 + (grow + 64 * i) * 4);
-            gxc[i] = *(const float *)(smem + V_XP + b * 2048 + 1024 + (grow + 64 * i) * 4);
-        }
+    for (int i = 0; i < 4; ++i) gen_st[i] = (grow4 + i) * 128 + ((gcc ^ (((grow4 + i) >> 1) & 7)) << 4);
+    f32x4 gxp, gxc;
+    auto load_xpc = [&](int b) {
+        gxp = *(const f32x4 *)(smem + V_XP + b * 2048 + grow4 * 4);
+        gxc = *(const f32x4 *)(smem + V_XP + b * 2048 + 1024 + grow4 * 4);
     };
     f32x4 va[2], vp[2], vc[2];
     auto load_slices = [&](int b, int gk) {
@@ -846,7 +847,7 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
         vc[1] = *(const f32x4 *)(smem + V_WC + o + 16);
     };
     auto gen_chunk = [&](int slot, int i) {
-        const float xp = gxp[i], xc = gxc[i];
+        const float xp = SHARE ? gxp[0] : gxp[i], xc = gxc[i];
         float h[8];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -858,7 +859,7 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
         v.y = (int)pack_bf16x2(h[2], h[3]);
         v.z = (int)pack_bf16x2(h[4], h[5]);
         v.w = (int)pack_bf16x2(h[6], h[7]);
-        lds_write16(smem + slot * SLAB + gen_st0 + i * 8192, v);
+        lds_write16(smem + slot * SLAB + gen_st[i], v);
     };
 
     // ---- fragment read offsets
@@ -1107,20 +1108,22 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // no DMA may still target LDS when the group ends
 }
 
-template <int EPI, bool COL_REGS>
+template <int EPI, bool COL_REGS, bool SHARE>
 static hipError_t launch_stream_gen_impl(const GemmArgs &g, hipStream_t st);
 template <int EPI>
 static hipError_t launch_stream_gen(const GemmArgs &g, hipStream_t st)
 {
     // at most four column tiles: bias and output weights sit in LDS tables (8 KB behind the vector area); otherwise
     // they come by scalar loads
-    return g.n_tiles <= 4 ? launch_stream_gen_impl<EPI, true>(g, st) : launch_stream_gen_impl<EPI, false>(g, st);
+    if (g.xp_runs4)
+        return g.n_tiles <= 4 ? launch_stream_gen_impl<EPI, true, true>(g, st) : launch_stream_gen_impl<EPI, false, true>(g, st);
+    return g.n_tiles <= 4 ? launch_stream_gen_impl<EPI, true, false>(g, st) : launch_stream_gen_impl<EPI, false, false>(g, st);
 }
-template <int EPI, bool COL_REGS>
+template <int EPI, bool COL_REGS, bool SHARE>
 static hipError_t launch_stream_gen_impl(const GemmArgs &g, hipStream_t st)
 {
     constexpr int smem = 4 * 256 * 128 + 20480 + (COL_REGS ? 8192 : 0);
-    auto kern = gemm_stream_gen_kernel<EPI, COL_REGS>;
+    auto kern = gemm_stream_gen_kernel<EPI, COL_REGS, SHARE>;
     static DeviceOnce once;
     hipError_t e = ensure_dynamic_lds((const void *)kern, smem, once);
     if (e != hipSuccess) return e;

@@ -54,6 +54,8 @@ struct GemmArgs {
     // with x_per_row the two candidate vectors are indexed by the row r instead (xp[r], xc[r]: every scenario
     // has its own candidate values).  AMODE_GENV: the generic tiles' form of the factored operand
     const float *wp, *wc, *xp, *xc; int32_t x_per_row;
+    int32_t xp_runs4;                         // rows 4j .. 4j+3 of the product take the same xp (the grid's credit
+                                              // count is a multiple of 4): lets a thread share wp*xp + a_term over them
     // B operand: B[N, K], leading dimension ldb
     const void *B; int64_t ldb;
     int64_t M; int32_t N; int32_t K;          // K is a multiple of the K-slab; N a multiple of the tile width

@@ -239,6 +239,8 @@ def test_more_than_2_pow_32_candidates():
 @pytest.mark.parametrize("dtype,hidden,S,L,P,Q", [
     ("bf16", [1024] * 4, 130, 128, 16, 16),    # 256 x 256 streaming kernels: generated, stored and fused-output forms
     ("bf16", [512, 512], 70, 44, 32, 32),      # generated operand feeding the output unit directly
+    ("bf16", [512, 512, 512], 40, 9, 128, 2),  # streaming kernels with a credit count that is no multiple of four
+                                               # (adjacent rows then differ in both candidate values)
     ("bf16", [256, 256, 256], 33, 20, 16, 16),
     ("bf16", [2048, 2048], 3, 8, 16, 16),      # K above the streaming kernel's range: one tile per work-group
     ("bf16", [128, 64], 40, 5, 5, 7),          # generic tiles
