@@ -572,10 +572,17 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
     unsigned q = 0;
     // One slab.  A tile's first slab is its own copy of the code (its first matrix instructions take the bias
     // as their addend, its wait knows of the stores in front), so that no branch sits inside a quarter.
+    // Wave priority by progress: among equal priorities a SIMD serves its older wavefront first, so of the two
+    // wavefronts of a SIMD the older one would run through its three quarters at full rate, wait at the barrier for
+    // about 900 cycles of a 2400-cycle slab (measured with clock stamps around the barrier) while the younger one
+    // runs alone, and each would expose its own fragment-read latencies.  With the priority falling from quarter
+    // to quarter the wavefront that is behind wins, the two stay within one quarter of each other (the wait falls
+    // to about 400 cycles) and fill each other's gaps.
     auto slab = [&](auto first_tag) {
         constexpr bool FIRST = decltype(first_tag)::value;
         const int pa = a_slot == 0 ? 2 : a_slot - 1;       // the A stage retired one slab ago
         AB_FENCE();
+        __builtin_amdgcn_s_setprio(2);
         load_frags(a_slot, w_slot, 1, 1);
         dma_a_rows(pa, 0);
         dma_a_rows(pa, 2);
@@ -584,10 +591,12 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
         AB_FENCE();
         advance_a();
         AB_FENCE();
+        __builtin_amdgcn_s_setprio(1);
         load_frags(a_slot, w_slot, 2, 0);
         mma(1);
         AB_INTERLEAVE_6();
         AB_FENCE();
+        __builtin_amdgcn_s_setprio(0);
         load_frags(a_slot, w_slot, 3, 1);
         mma(0);
         AB_INTERLEAVE_6();
@@ -606,6 +615,7 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         AB_FENCE();
+        __builtin_amdgcn_s_setprio(3);
         const int na = a_slot == 2 ? 0 : a_slot + 1, nw = w_slot ^ 1;
         load_frags(na, nw, 0, 0);
         dma_w_rows(w_slot, 0);
