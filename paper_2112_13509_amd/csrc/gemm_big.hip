@@ -740,8 +740,8 @@ __global__ __launch_bounds__(512) void gemm_stream_kernel(const GemmArgs g)
 // A[r, k] = relu(a_term[s, k] + wp[k] * xp[c] + wc[k] * xc[c]) for row r = (scenario s, candidate c), one
 // scenario per 256-row tile.  Same walk over the tiles and same W ring as gemm_stream_kernel; differences:
 //   - the A ring has two stages; while slab j is multiplied, slab j+1 is generated into the other
-//     stage by the vector ALUs (a thread owns one 8-wide k chunk of four rows: two row chunks in the
-//     first quarter, one in each of the next two), next to the matrix instructions;
+//     stage by the vector ALUs (a thread owns one 8-wide k chunk of four adjacent rows: two row chunks
+//     in the first quarter, one in each of the next two), next to the matrix instructions;
 //   - everything the generation reads comes from LDS: wp and wc (whole, fetched once), the scenario's
 //     a_term row and the tile's xp / xc slices (double-buffered per tile, fetched one tile ahead by
 //     DMA, 3 requests per wavefront), 20 KB behind the rings.  No ordinary vector load is in flight
