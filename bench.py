@@ -31,7 +31,7 @@ PEAK = {"bf16": 2.5e15, "f32": 157.3e12}     # dense MFMA peaks of MI355X, flop/
 HBM_PEAK = 8.0e12
 # HBM bytes per hidden-GEMM launch from the FETCH_SIZE / WRITE_SIZE counter runs recorded under profiles/.
 # They describe the kernels of ONE library version; any other version reports null and says why.
-TRAFFIC = {"cfg3": {"library_version": 108, "read_bytes": 1.544e9, "written_bytes": 1.437e9,
+TRAFFIC = {"cfg3": {"library_version": 109, "read_bytes": 1.553e9, "written_bytes": 1.437e9,
                     "source": "profiles/gemm_stream_cfg3.md"}}
 ALL_WORKLOADS = ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "lstm"]
 ROLE_OF = {"gemm_hidden_first": "first", "gemm_hidden_mid": "middle", "gemm_hidden_last": "last",

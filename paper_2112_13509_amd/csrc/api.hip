@@ -144,7 +144,7 @@ using namespace ab;
 
 extern "C" {
 
-int32_t ab_version(void) { return 108; }
+int32_t ab_version(void) { return 109; }
 
 void ab_set_trace(ab_trace_fn fn, void *user) { g_trace_fn = fn; g_trace_user = user; }
 

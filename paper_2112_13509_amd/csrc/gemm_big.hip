@@ -981,6 +981,10 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
     unsigned q = 0;
     // One slab (kt = its place in the tile).  A tile's first slab is its own copy of the code, so that no
     // branch sits inside a quarter.
+    // Wave priority: here the older wavefront of a SIMD does not expose latencies when it runs ahead (its vector
+    // work fills them), so taking turns by progress as in the stored-operand kernel changes nothing; what the clock
+    // stamps show is the younger wavefront held up in the first quarter, the one with two row chunks to generate
+    // (990 cycles against 510).  It goes first there (3 against 0), after that the priority falls with progress.
     auto slab = [&](auto first_tag, int kt) {
         constexpr bool FIRST = decltype(first_tag)::value;
         const int nxt = a_slot ^ 1;                        // retired one slab ago: slab j+1 is generated there
@@ -988,17 +992,20 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
         if (gk == KT) { gk = 0; gpar ^= 1; load_xpc(gpar); }
         load_slices(gpar, gk);
         AB_FENCE();
+        if (wave_m) __builtin_amdgcn_s_setprio(3); else __builtin_amdgcn_s_setprio(0);
         load_frags(a_slot, w_slot, 1, 1);
         gen_chunk(nxt, 0);
         gen_chunk(nxt, 1);
         if constexpr (FIRST) mma_first(0); else mma(0);
         AB_INTERLEAVE_6();
         AB_FENCE();
+        __builtin_amdgcn_s_setprio(1);
         load_frags(a_slot, w_slot, 2, 0);
         gen_chunk(nxt, 2);
         mma(1);
         AB_INTERLEAVE_6();
         AB_FENCE();
+        __builtin_amdgcn_s_setprio(0);
         load_frags(a_slot, w_slot, 3, 1);
         gen_chunk(nxt, 3);
         mma(0);
@@ -1017,6 +1024,7 @@ __global__ __launch_bounds__(512) void gemm_stream_gen_kernel(const GemmArgs g)
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         AB_FENCE();
+        __builtin_amdgcn_s_setprio(2);
         const int nw = w_slot ^ 1;
         load_frags(nxt, nw, 0, 0);
         dma_w_rows(w_slot, 0);
