@@ -1314,6 +1314,9 @@ __global__ __launch_bounds__(512) void lstm_encoder_kernel(const LstmEncArgs a)
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int role = wave >> 2, wu = wave & 3;     // role 0: first LSTM layer, 1: second; wu: which 16 units
+    // Of the two wavefronts of a SIMD the one of the second layer has more to do per step (eight k steps against six,
+    // and the next step's embedding) and, being the younger one, would be served last: it gets the higher priority.
+    if (role) __builtin_amdgcn_s_setprio(2);
     const int l31 = lane & 31, hf = lane >> 5;
     const int64_t s0 = (int64_t)blockIdx.x * R;
     const int L = a.L, K = a.K;
